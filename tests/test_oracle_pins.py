@@ -1,0 +1,462 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these compares the oracle with itself: each uses a closed form, a brute
+force written independently in this file, a statistical law the paper states, or
+a hand-derived fixture under tests/golden/.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import qaq_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+F16, F32 = np.float16, np.float32
+
+
+def _golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, *v = line.split()
+            out[k] = np.array([float(t) for t in v])
+    return out
+
+
+# ------------------------------------------------------------------ attention
+def _attention_loops(q, K, V):
+    """Section 2.1 written as python loops in exact-ish arithmetic (math.fsum)."""
+    T, D = len(K), len(q)
+    a = [math.fsum(q[d] * K[t][d] for d in range(D)) / math.sqrt(D) for t in range(T)]
+    m = max(a)
+    e = [math.exp(v - m) for v in a]
+    z = math.fsum(e)
+    S = [v / z for v in e]
+    X = [math.fsum(S[t] * V[t][d] for t in range(T)) for d in range(D)]
+    return X, S
+
+
+def test_attention_brute_force_tiny():
+    rng = np.random.default_rng(1)
+    for T, D in [(1, 2), (3, 4), (8, 8), (5, 3)]:
+        q, K, V = rng.standard_normal(D), rng.standard_normal((T, D)), rng.standard_normal((T, D))
+        X, S = O.attention(q, K, V)
+        Xb, Sb = _attention_loops(q.tolist(), K.tolist(), V.tolist())
+        np.testing.assert_allclose(X, Xb, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(S, Sb, rtol=1e-13, atol=1e-15)
+        assert abs(S.sum() - 1) < 1e-14
+
+
+def test_attention_special_cases():
+    rng = np.random.default_rng(2)
+    D = 8
+    q = rng.standard_normal(D)
+    V = rng.standard_normal((6, D))
+    # one token: X is that token's value whatever the query
+    X, S = O.attention(q, rng.standard_normal((1, D)), V[:1])
+    np.testing.assert_allclose(X, V[0], rtol=0, atol=1e-15)
+    assert S.tolist() == [1.0]
+    # identical keys: uniform scores, X is the mean value
+    X, S = O.attention(q, np.tile(rng.standard_normal(D), (6, 1)), V)
+    np.testing.assert_allclose(S, np.full(6, 1 / 6), rtol=1e-14)
+    np.testing.assert_allclose(X, V.mean(0), rtol=1e-13, atol=1e-15)
+    # a transposed operand or a missing 1/sqrt(D) would break this one:
+    K = np.zeros((2, 4)); K[1, 0] = 2.0
+    X, S = O.attention(np.array([3.0, 0, 0, 0]), K, np.eye(2, 4))
+    # logits (0, 3*2/sqrt(4)) = (0, 3)
+    np.testing.assert_allclose(S[1] / S[0], math.exp(3.0), rtol=1e-13)
+
+
+def test_attention_sensitivities_finite_difference():
+    """Section 3.1: dX_j/dV_ti = S_t [i == j];  dX_j/dK_ti = S_t Q_i (V_tj - X_j),
+    times the 1/sqrt(D) the paper leaves out of the key derivative."""
+    rng = np.random.default_rng(3)
+    T, D = 5, 4
+    q, K, V = rng.standard_normal(D), rng.standard_normal((T, D)), rng.standard_normal((T, D))
+    X, S = O.attention(q, K, V)
+    h = 1e-6
+    for t in range(T):
+        for i in range(D):
+            Vp = V.copy(); Vp[t, i] += h
+            Vm = V.copy(); Vm[t, i] -= h
+            dV = (O.attention(q, K, Vp)[0] - O.attention(q, K, Vm)[0]) / (2 * h)
+            want = np.zeros(D); want[i] = S[t]
+            np.testing.assert_allclose(dV, want, atol=1e-8)
+            Kp = K.copy(); Kp[t, i] += h
+            Km = K.copy(); Km[t, i] -= h
+            dK = (O.attention(q, Kp, V)[0] - O.attention(q, Km, V)[0]) / (2 * h)
+            want = S[t] * q[i] * (V[t] - X) / math.sqrt(D)
+            np.testing.assert_allclose(dK, want, atol=1e-8)
+
+
+# ------------------------------------------------------------------ quantizer
+def test_quantizer_golden_worked_example():
+    g = _golden("midpoint_quantizer_worked_example.txt")
+    x = g["x"].astype(F16)[None]
+    mn, mx = O.token_range(x, np.zeros_like(x, bool))
+    assert float(mn[0]) == 0.0 and float(mx[0]) == 3.0
+    for B in (1, 2):
+        c = O.encode(x, mn, mx, np.array([B]))
+        assert c[0].tolist() == g[f"B{B}_codes"].astype(int).tolist()
+        xh = O.decode(c, mn, mx, np.array([B]))
+        np.testing.assert_array_equal(xh[0], g[f"B{B}_mid"].astype(F32))
+
+
+def _textbook_uniform(x, B):
+    """Per-row min/max uniform quantizer with midpoint reconstruction, in double."""
+    x = x.astype(np.float64)
+    lo, hi = x.min(1, keepdims=True), x.max(1, keepdims=True)
+    w = (hi - lo) / 2 ** B
+    c = np.minimum(np.floor((x - lo) / w), 2 ** B - 1)
+    return c, lo + (c + 0.5) * w
+
+
+@pytest.mark.parametrize("B", [2, 3, 4, 8])
+def test_uniform_special_case_matches_textbook(B):
+    """alpha = 0 and one width for all tokens is the paper's "uniform" comparison
+    method (Section 5.3): an ordinary per-row min/max quantizer."""
+    rng = np.random.default_rng(10 + B)
+    x = (rng.standard_normal((200, 64)) * 3).astype(F16)
+    om = O.outlier_split(x, 0)
+    assert not om.any()
+    mn, mx = O.token_range(x, om)
+    bits = np.full(200, B)
+    c = O.encode(x, mn, mx, bits)
+    ct, xt = _textbook_uniform(x, B)
+    # identical except where the double-precision quotient sits within fp32
+    # rounding of a segment border
+    xd = x.astype(np.float64)
+    pos = (xd - xd.min(1, keepdims=True)) / ((xd.max(1, keepdims=True) - xd.min(1, keepdims=True)) / 2 ** B)
+    safe = np.abs(pos - np.round(pos)) > 1e-4
+    assert safe.mean() > 0.9
+    np.testing.assert_array_equal(c[safe], ct[safe].astype(np.uint8))
+    xh = O.decode(c, mn, mx, bits)
+    np.testing.assert_allclose(xh[safe], xt[safe], rtol=2e-6, atol=2e-6)
+
+
+@pytest.mark.parametrize("B", [2, 3, 4, 8])
+def test_error_bound_and_uniform_error_law(B):
+    """|x - x^| <= Delta = range / 2^(B+1), and on dense data the error is uniform
+    on [-Delta, Delta], std Delta/sqrt(3) (Section 4.1)."""
+    rng = np.random.default_rng(20 + B)
+    N, D = 64, 4096
+    x = rng.uniform(-4, 4, size=(N, D)).astype(F16)
+    om = O.outlier_split(x, 2)
+    mn, mx = O.token_range(x, om)
+    bits = np.full(N, B)
+    c = O.encode(x, mn, mx, bits)
+    xh = O.dequantize(c, mn, mx, bits, om, x)
+    err = xh.astype(np.float64) - x.astype(np.float64)
+    rng_t = O.range_f32(mn, mx).astype(np.float64)
+    delta = rng_t / 2 ** (B + 1)
+    assert (np.abs(err) <= delta[:, None] * (1 + 1e-6) + 1e-7).all()
+    assert (err[om] == 0).all()                       # outliers restored exactly
+    ratio = err[~om].std() / (delta.mean() / math.sqrt(3))
+    tol = 0.03 if B < 8 else 0.08                      # at 8 bits fp16 granularity shows
+    assert abs(ratio - 1) < tol
+    # more bits never loosen the bound
+    if B > 2:
+        assert (delta < rng_t / 2 ** B).all()
+
+
+def test_error_bound_halves_per_bit():
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((300, 128)) * 2).astype(F16)
+    om = O.outlier_split(x, 1)
+    mn, mx = O.token_range(x, om)
+    prev = None
+    for B in (2, 3, 4, 8):
+        bits = np.full(300, B)
+        xh = O.dequantize(O.encode(x, mn, mx, bits), mn, mx, bits, om, x)
+        worst = np.abs(xh - x.astype(F32)).max(1) / O.range_f32(mn, mx)
+        assert (worst <= 2.0 ** -(B + 1) * (1 + 1e-5)).all()
+        if prev is not None:
+            assert worst.mean() < prev
+        prev = worst.mean()
+
+
+def test_degenerate_rows():
+    # all-equal vector: range 0, codes 0, reconstruction exact
+    x = np.full((2, 64), 1.5, F16)
+    om = O.outlier_split(x, 1)
+    # ties -> lower channel first: channel 0 is the top outlier, channel 1 the bottom one
+    assert np.nonzero(om[0])[0].tolist() == [0, 1]
+    mn, mx = O.token_range(x, om)
+    c = O.encode(x, mn, mx, np.array([2, 8]))
+    assert (c == 0).all()
+    assert (O.dequantize(c, mn, mx, np.array([2, 8]), om, x) == 1.5).all()
+    # x == max sits in the last segment; top outlier clamps to 2^B-1, bottom to 0
+    x = np.array([[0, 1, 2, 3, 100, -50, 2.5, 0.1]], F16)
+    om = O.outlier_split(x, 1)
+    assert np.nonzero(om[0])[0].tolist() == [4, 5]
+    mn, mx = O.token_range(x, om)
+    assert (float(mn[0]), float(mx[0])) == (0.0, 3.0)
+    c = O.encode(x, mn, mx, np.array([3]))
+    assert c[0, 4] == 7 and c[0, 5] == 0 and c[0, 3] == 7 and c[0, 0] == 0
+
+
+# ------------------------------------------------------------------- outliers
+def _outliers_brute(row, n_o):
+    D = len(row)
+    idx = list(range(D))
+    top = sorted(idx, key=lambda d: (-float(row[d]), d))[:n_o]
+    rest = [d for d in idx if d not in top]
+    bot = sorted(rest, key=lambda d: (float(row[d]), d))[:n_o]
+    return sorted(top + bot)
+
+
+def test_outlier_split_brute_force_and_ties():
+    rng = np.random.default_rng(7)
+    for D, n_o in [(8, 1), (8, 2), (16, 3), (6, 2)]:
+        # few distinct values -> many ties
+        x = rng.integers(-2, 3, size=(200, D)).astype(F16)
+        x[::7] = 0.0
+        x[3, :] = np.where(rng.random(D) < 0.5, F16(0.0), F16(-0.0))   # signed zeros compare equal
+        om = O.outlier_split(x, n_o)
+        for r in range(x.shape[0]):
+            assert np.nonzero(om[r])[0].tolist() == _outliers_brute(x[r], n_o)
+        assert (om.sum(1) == 2 * n_o).all()
+
+
+def test_outliers_shrink_range_and_restore_exactly():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((500, 128)).astype(np.float32)
+    x[rng.random(x.shape) < 0.01] *= 15
+    x = x.astype(F16)
+    om0 = O.outlier_split(x, 0)
+    om1 = O.outlier_split(x, 1)
+    r0 = O.range_f32(*O.token_range(x, om0))
+    r1 = O.range_f32(*O.token_range(x, om1))
+    assert (r1 <= r0).all() and (r1 < r0).mean() > 0.99
+    mn, mx = O.token_range(x, om1)
+    bits = np.full(500, 2)
+    xh = O.dequantize(O.encode(x, mn, mx, bits), mn, mx, bits, om1, x)
+    assert (xh[om1] == x.astype(F32)[om1]).all()
+    assert O.outliers_per_side(0.01, 128) == 1 and O.outliers_per_side(0.01, 64) == 1
+    assert O.outliers_per_side(0.0, 128) == 0 and O.outliers_per_side(0.05, 128) == 4
+
+
+# ----------------------------------------------------------------- requantize
+def test_requantize_down_equals_direct_quantization():
+    """Section 4.2: lower widths are reached from higher ones without the
+    original; the nested midpoint grids make that identical to quantizing the
+    original directly."""
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal((400, 128)) * rng.uniform(0.1, 8, size=(400, 1))).astype(F16)
+    # adversarial rows: values on segment borders, x == max, zero range
+    x[0] = np.linspace(0, 4, 128).astype(F16)
+    x[1] = 2.0
+    x[2, :] = np.repeat(np.arange(16), 8) * 0.25
+    om = O.outlier_split(x, 1)
+    mn, mx = O.token_range(x, om)
+    N = x.shape[0]
+    for hi in (8, 4, 3):
+        ch = O.encode(x, mn, mx, np.full(N, hi))
+        for lo in (4, 3, 2):
+            if lo >= hi:
+                continue
+            direct = O.encode(x, mn, mx, np.full(N, lo))
+            shifted = O.requantize_codes(ch, np.full(N, hi), np.full(N, lo))
+            np.testing.assert_array_equal(shifted, direct)
+
+
+def test_headcache_requantize_up_needs_original():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((10, 64)).astype(F16)
+    hc = O.HeadCache(64, 1)
+    hc.append(x, np.full(10, 2, np.uint8))
+    want = np.array([2, 3, 4, 8, 2, 2, 8, 3, 2, 4], np.uint8)
+    assert hc.requantize(want, None) == int((want > 2).sum())
+    assert (hc.bits == 2).all()
+    assert hc.requantize(want, x) == 0
+    ref = O.HeadCache(64, 1)
+    ref.append(x, want)
+    np.testing.assert_array_equal(hc.codes, ref.codes)
+    np.testing.assert_array_equal(hc.bits, want)
+
+
+# ----------------------------------------------------- thresholds and bit rule
+def test_key_bound_inverts_the_variance_model():
+    for T in (2, 5, 64, 4096, 32768):
+        for s in (1e-6, 1e-4, 3e-3, 0.05):
+            for qn in (0.003, 0.01, 1.0):
+                v = O.key_variance_bound(T, s, qn)
+                assert math.isclose(O.score_variance_model(T, v, qn), s * s, rel_tol=1e-11)
+    # monotone increasing in T (T >= 2) and in sigma; small-argument series
+    vals = [O.key_variance_bound(T, 1e-3, 0.01) for T in range(2, 400)]
+    assert all(b > a for a, b in zip(vals, vals[1:]))
+    assert O.key_variance_bound(100, 2e-3, 0.01) > O.key_variance_bound(100, 1e-3, 0.01)
+    T, s, qn = 3, 1e-7, 0.5
+    assert math.isclose(O.key_variance_bound(T, s, qn), T ** 3 / (T - 1) * s * s / qn, rel_tol=1e-10)
+    assert O.key_variance_bound(1, 1e-3, 0.01) == math.inf
+
+
+def test_bits_by_compare_equals_printed_ceil_log2():
+    rng = np.random.default_rng(12)
+    rngs = np.exp(rng.uniform(np.log(1e-3), np.log(64), 20000)).astype(F32)
+    T, sx, ss, qn = 777, 0.02, 2e-3, 0.011
+    # key rule
+    tau = O.key_threshold(T, ss, qn)
+    sigma_k = math.sqrt(O.key_variance_bound(T, ss, qn))
+    raw = O.bits_formula_f64(rngs, sigma_k)
+    ratio = rngs.astype(np.float64) / (2 * math.sqrt(3) * sigma_k)
+    safe = np.abs(np.log2(ratio) - np.round(np.log2(ratio))) > 1e-5
+    got_all = O.snap_bits_from_compare(rngs, tau, range(-30, 31))   # un-snapped: every integer allowed
+    np.testing.assert_array_equal(got_all[safe].astype(np.int8), raw[safe].astype(np.int8))
+    # snapping into {2,3,4,8}: up to the next allowed width, clipped at both ends
+    snapped = O.select_bits_key(rngs, tau)
+    def snap(b):
+        for a in (2, 3, 4, 8):
+            if b <= a:
+                return a
+        return 8
+    want = np.array([snap(b) for b in raw])
+    np.testing.assert_array_equal(snapped[safe], want[safe])
+    # value rule
+    S = np.exp(rng.uniform(np.log(1e-6), 0, 20000)).astype(F32)
+    cv = O.value_threshold(T, sx)
+    sigma_v = sx / (math.sqrt(T) * S.astype(np.float64))
+    raw = O.bits_formula_f64(rngs, sigma_v)
+    ratio = rngs.astype(np.float64) / (2 * math.sqrt(3) * sigma_v)
+    safe = np.abs(np.log2(ratio) - np.round(np.log2(ratio))) > 1e-5
+    got = O.select_bits_value(rngs, S, cv)
+    want = np.array([snap(b) for b in raw])
+    np.testing.assert_array_equal(got[safe], want[safe])
+    assert safe.mean() > 0.99
+
+
+def test_value_bits_monotone():
+    r = np.full(100, 3.0, F32)
+    S = np.linspace(1e-5, 1, 100).astype(F32)
+    b = O.select_bits_value(r, S, O.value_threshold(512, 0.01)).astype(int)
+    assert (np.diff(b) >= 0).all() and b[0] == 2 and b[-1] == 8
+    b2 = O.select_bits_value(np.linspace(0, 50, 100).astype(F32), np.full(100, 0.01, F32), O.value_threshold(512, 0.01)).astype(int)
+    assert (np.diff(b2) >= 0).all()
+    looser = O.select_bits_value(r, S, O.value_threshold(512, 0.1)).astype(int)
+    assert (looser <= b).all()
+
+
+def test_value_rule_variance_budget_monte_carlo():
+    """Section 4.1 "Value cache quantization": with per-token noise of std
+    sigma_t = sigma_Xmax/(sqrt(T) S_t), Var[X^_d] = sum_t S_t^2 sigma_t^2 = sigma_Xmax^2.
+    Realised with the oracle's own quantizer at the (un-snapped) widths the rule
+    gives: the error variance of X must stay below the budget."""
+    rng = np.random.default_rng(13)
+    T, D, sx = 256, 2048, 0.05
+    V = rng.uniform(-2, 2, (T, D)).astype(F16)
+    a = rng.standard_normal(T) * 1.5
+    S = np.exp(a - a.max()); S /= S.sum()
+    om = O.outlier_split(V, 0)
+    mn, mx = O.token_range(V, om)
+    cv = O.value_threshold(T, sx)
+    bits = O.snap_bits_from_compare((O.range_f32(mn, mx) * S.astype(F32)).astype(F32), cv, range(1, 9))
+    Vh = O.decode(O.encode(V, mn, mx, bits), mn, mx, bits).astype(np.float64)
+    errX = S @ (Vh - V.astype(np.float64))
+    # predicted variance with the realised widths: sum S^2 Delta^2/3  <= sigma_Xmax^2
+    delta = O.range_f32(mn, mx).astype(np.float64) / 2.0 ** (bits.astype(int) + 1)
+    pred = (S ** 2 * delta ** 2 / 3).sum()
+    assert pred <= sx ** 2 * (1 + 1e-6)
+    assert abs(errX.var() / pred - 1) < 0.15
+    assert bits.max() > bits.min()
+
+
+# --------------------------------------------------------------------- window
+def test_window():
+    rng = np.random.default_rng(14)
+    rows = [rng.random(10).astype(F32), rng.random(11).astype(F32), rng.random(12).astype(F32)]
+    # n = 1: the current scores only (the paper's "no window" setting)
+    np.testing.assert_array_equal(O.window_predict(rows, 1, 12), rows[-1])
+    p = O.window_predict(rows, 2, 12)
+    np.testing.assert_array_equal(p[:11], np.maximum(rows[1], rows[2][:11]))
+    assert p[11] == rows[2][11]
+    p = O.window_predict(rows, 5, 13)
+    assert p[12] == 0 and p[3] == max(r[3] for r in rows)
+    # constant history: window size does not matter
+    c = [rows[0]] * 5
+    for n in (1, 2, 5):
+        np.testing.assert_array_equal(O.window_predict(c, n, 10), rows[0])
+    # GQA: max over the heads of a group
+    sq = rng.random((8, 6)).astype(F32)
+    g = O.gqa_reduce(sq, 2)
+    np.testing.assert_array_equal(g[1], sq[4:].max(0))
+
+
+# ----------------------------------------------------------------- accounting
+def test_accounting_and_canonical_pack():
+    g = _golden("opt175b_sizing.txt")
+    assert round(float(g["kv_gb"][0] / g["weights_gb"][0]), 2) == float(g["ratio"][0])
+    cfg = O.Config(1, 2, 2, 64, qnorm2=np.ones(2))
+    oc = O.OracleCache(cfg)
+    rng = np.random.default_rng(15)
+    k = rng.standard_normal((1, 2, 9, 64)).astype(F16)
+    bits = rng.choice([2, 3, 4, 8], size=(1, 2, 9)).astype(np.uint8)
+    oc.append(k, k, bits, bits)
+    assert oc.code_bytes() == 2 * int(bits.sum()) * 64 // 8
+    assert sum(len(oc.K[0][h].packed(t)) for h in range(2) for t in range(9)) * 2 == oc.code_bytes()
+    oc2 = O.OracleCache(cfg)
+    two = np.full((1, 2, 9), 2, np.uint8)
+    oc2.append(k, k, two, two)
+    assert oc2.ratio_codes() == 8.0
+    assert oc2.ratio_all() < 8.0
+    # canonical pack: LSB-first bit string, channel d at bits [dB, (d+1)B)
+    codes = np.array([5, 2, 7, 0, 1, 6, 3, 4], np.uint8)
+    packed = O.pack_canonical(codes, 3)
+    val = sum(int(c) << (3 * d) for d, c in enumerate(codes))
+    assert packed.tobytes() == val.to_bytes(3, "little")
+    assert O.pack_canonical(np.array([1, 2, 3, 0], np.uint8), 2).tolist() == [0b00111001]
+    assert O.pack_canonical(np.array([200, 7], np.uint8), 8).tolist() == [200, 7]
+
+
+def test_query_norm_statistic():
+    rng = np.random.default_rng(16)
+    q = rng.standard_normal((4000, 128)) / math.sqrt(128)
+    s = O.query_norm_statistic(q, 128)
+    n2 = np.sort((q ** 2).sum(1))
+    assert n2[int(0.89 * 4000)] / 128 < s < n2[int(0.91 * 4000)] / 128
+    assert (n2 / 128 <= s).mean() == pytest.approx(0.9, abs=0.002)
+
+
+# ------------------------------------------------------- end-to-end oracle chain
+def test_oracle_chain_consistency():
+    """The stateful wrapper does what its parts do: attention over the dequantized
+    cache plus the unquantized new token, bits from the window, shift-requantize."""
+    from paper_2403_04643_amd import workloads as W
+    sh = W.shape(1, context=96)
+    K, V = W.make_kv(1, sh)
+    q = W.make_queries(1, sh, n=3)
+    cfg = O.Config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, window=2,
+                   sigma_s_max=2e-4, sigma_x_max=0.02,
+                   qnorm2=np.full(sh.n_kv_heads, O.query_norm_statistic(q, sh.head_dim)))
+    oc = O.OracleCache(cfg)
+    oc.append(K, V)
+    assert oc.T == 96 and (oc.K[0][0].bits == 8).all()
+    kn, vn = W.make_new_token(1, sh)
+    X, S = oc.decode_attention(q[0], kn, vn)
+    assert S.shape == (1, 8, 97) and np.allclose(S.sum(-1), 1)
+    # by hand for one head
+    Kd, Vd = oc.dequantize()
+    Kc = np.concatenate([Kd[0, 3], kn[0, 3].astype(F32)[None]])
+    Vc = np.concatenate([Vd[0, 3], vn[0, 3].astype(F32)[None]])
+    Xb, Sb = _attention_loops(q[0, 0, 3].astype(float).tolist(), Kc.astype(float).tolist(), Vc.astype(float).tolist())
+    np.testing.assert_allclose(X[0, 3], Xb, rtol=1e-12, atol=1e-14)
+    # 8-bit cache is close to the fp16 one
+    Xf, _ = O.attention(q[0, 0, 3], np.concatenate([K[0, 3], kn[0, 3][None]]), np.concatenate([V[0, 3], vn[0, 3][None]]))
+    assert np.abs(X[0, 3] - Xf).max() < 0.02 * np.abs(Xf).max() + 1e-3
+    oc.append(kn[:, :, None], vn[:, :, None])
+    oc.observe(S.astype(F32))
+    bk, bv = oc.select_bits()
+    assert set(np.unique(bk)) <= {2, 3, 4, 8} and set(np.unique(bv)) <= {2, 3, 4, 8}
+    assert len(np.unique(bv)) > 1
+    before = oc.code_bytes()
+    oc.requantize(bk, bv)
+    assert oc.refused == 0 and oc.code_bytes() < before
+    np.testing.assert_array_equal(oc.K[0][0].bits, bk[0, 0])
+    # same result as quantizing the originals directly at those widths
+    ref = O.OracleCache(cfg)
+    Kall = np.concatenate([K, kn[:, :, None]], 2); Vall = np.concatenate([V, vn[:, :, None]], 2)
+    ref.append(Kall, Vall, bk, bv)
+    np.testing.assert_array_equal(ref.V[0][5].codes, oc.V[0][5].codes)
