@@ -1,0 +1,189 @@
+/*
+ * libqaq -- quality-adaptive quantization of an LLM KV cache and the decode-step
+ * attention that reads it, for AMD MI355X (gfx950).
+ *
+ * Method: "QAQ: Quality Adaptive Quantization for LLM KV Cache" (arXiv 2403.04643).
+ * Section / equation references below are to that paper.
+ *
+ * Conventions for every entry point
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers
+ *     are ordinary host memory.  The library never frees or keeps caller tensors
+ *     beyond the call, except the arena given to qaq_create, which it uses until
+ *     qaq_destroy (and never frees).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue kernels on it and return; they do not synchronise, and after
+ *     qaq_create they allocate nothing.  (qaq_create and qaq_stats do synchronise.)
+ *   - Tensors are row-major with the head dimension D innermost.  fp16 is IEEE
+ *     binary16.  All sequences of the batch have the same length.
+ *   - Return value: QAQ_OK (0) or a negative qaq_status.  Arguments are validated on
+ *     the host without reading device memory; nothing crosses the ABI as an
+ *     exception or abort.  qaq_last_error() gives a thread-local description.
+ *   - Not checked: that inputs are finite, and that width arrays only hold members
+ *     of the configured bit set.
+ *   - Calls on one cache must be ordered by the caller (same stream, or events).
+ */
+#ifndef QAQ_H
+#define QAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QAQ_OK = 0,
+  QAQ_ERR_INVALID_ARG = -1,
+  QAQ_ERR_CAPACITY = -2,     /* more tokens than max_tokens, or arena too small */
+  QAQ_ERR_HIP = -3,          /* a HIP runtime call failed */
+  QAQ_ERR_NEED_ORIGINAL = -4 /* reserved: widening without the unquantized copy is
+                                refused per token and counted in qaq_stats, not failed */
+} qaq_status;
+
+typedef struct qaq_cache qaq_cache; /* opaque host-side descriptor */
+
+typedef struct {
+  int32_t batch;          /* B, number of sequences                                   */
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                             */
+  int32_t n_kv_heads;     /* Hkv                                                      */
+  int32_t head_dim;       /* D: 64 or 128                                             */
+  int32_t max_tokens;     /* capacity per sequence (rounded up to a tile of 256)      */
+  int32_t bit_set[4];     /* allowed code widths, ascending, a subset of {2,3,4,8}    */
+  int32_t n_bits;         /* how many entries of bit_set are used (1..4)              */
+  float   outlier_frac;   /* alpha, total over both ends (Section 4.2 "Outliers");
+                             the paper's experiments use 0.01                        */
+  int32_t n_outlier_per_side; /* <0: ceil(outlier_frac/2 * D); 0: none; at most 4     */
+  int32_t window;         /* n of the attention window (Section 3.2); 1..8; paper: 5  */
+  double  sigma_s_max;    /* bound on the std of a score   (Section 4.1, key rule)    */
+  double  sigma_x_max;    /* bound on the std of an output (Section 4.1, value rule)  */
+  const float* qnorm2;    /* host [n_kv_heads]: statistic of sum_d Q_d^2 used by the key
+                             rule (the paper takes the upper-10% quantile), with the
+                             query already carrying the softmax's 1/sqrt(D), i.e.
+                             quantile(|q|^2) / D.  Copied by qaq_create.              */
+} qaq_config;
+
+typedef struct {
+  int64_t tokens;            /* cached positions per sequence                         */
+  int64_t hist_k[4];         /* token-heads per width, in bit_set {2,3,4,8} order     */
+  int64_t hist_v[4];
+  int64_t code_bytes;        /* sum over token-heads of D*(bK+bV)/8 (Section 2.1:
+                                memory "calculated by the quantized bit")             */
+  int64_t layout_code_bytes; /* bytes the device layout actually reads for codes      */
+  int64_t meta_bytes;        /* min/max, order bytes, outlier side store              */
+  int64_t fp16_bytes;        /* the same tokens as an fp16 cache                      */
+  int64_t refused_upgrades;  /* widenings asked for without an unquantized copy       */
+} qaq_stats_t;
+
+/* Bytes of device memory the cache needs for this configuration (worst case: every
+ * token at the widest code).  0 if the configuration is invalid. */
+size_t qaq_arena_bytes(const qaq_config* cfg);
+
+/* Creates an empty cache inside `dev_arena` (at least qaq_arena_bytes, 256-byte
+ * aligned).  Clears the arena's bookkeeping on the default stream and waits for it. */
+int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_cache** out);
+int qaq_destroy(qaq_cache* c);
+
+/* Forget all tokens and the score window (host bookkeeping only). */
+int qaq_reset(qaq_cache* c);
+
+/* Number of cached positions per sequence. */
+int qaq_length(const qaq_cache* c, int32_t* host_len);
+
+/* Change the two hyper-parameters of Section 4.1 between calls. */
+int qaq_set_sigmas(qaq_cache* c, double sigma_s_max, double sigma_x_max);
+
+/* The fp32 thresholds qaq_select_bits compares against when T tokens are attended:
+ * tau_k[h] = 2*sqrt(3)*sigma_K(T, h) with sigma_K^2 = log(T^3/(T-1)*sigma_Smax^2 + 1)/qnorm2[h]
+ * (last display of "Key cache quantization"), and c_v = 2*sqrt(3)*sigma_Xmax/sqrt(T)
+ * (display of "Value cache quantization" combined with the bit formula of "Determining
+ * quantization bits").  Computed in double, rounded once.  host_tau_k: [n_kv_heads]. */
+int qaq_thresholds(const qaq_cache* c, int32_t T, float* host_tau_k, float* host_c_v);
+
+/* Section 4.2 "Outliers" + Section 4.1 "Determining quantization bits": append n_new
+ * tokens per sequence.  For every token vector the n_o largest and n_o smallest
+ * entries go to the fp16 side store, [min,max] is taken over the rest, and all D
+ * entries are coded with 2^B equal segments.
+ *   dev_k, dev_v       fp16 [B, Hkv, n_new, D]
+ *   dev_k_bits/v_bits  uint8 [B, Hkv, n_new] widths, or NULL = widest of the bit set
+ * QAQ_ERR_CAPACITY if the cache would exceed max_tokens. */
+int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
+                        const uint8_t* dev_k_bits, const uint8_t* dev_v_bits, void* stream);
+
+/* Section 4.1 bit rules + Section 4.2 "Attention score prediction": record one row of
+ * attention scores in the window and compute the width of every cached token.
+ *   dev_scores  fp32 [B, Hq, T] normalised scores of the last decode step over the T
+ *               cached tokens (T = qaq_length), or NULL = use the window as it is.
+ *               For grouped queries the maximum over the heads of a KV head is kept.
+ *   dev_k_bits, dev_v_bits  out, uint8 [B, Hkv, T].
+ * The predicted score of a token is the maximum over the last `window` rows that
+ * cover it.  Widths: the smallest b of the bit set with range_K <= 2^b*tau_k, resp.
+ * range_V * score <= 2^b*c_v (the printed ceil(log2(.)) written as comparisons),
+ * the widest if none qualifies. */
+int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits,
+                    uint8_t* dev_v_bits, void* stream);
+
+/* Section 4.2 "Integration in text generation process": move every cached token to
+ * the requested width.  Narrowing drops low code bits in place.  Widening re-encodes
+ * from the caller's unquantized copy with the stored [min,max] and outlier set.
+ *   dev_k_bits, dev_v_bits  uint8 [B, Hkv, T] (either may be NULL = leave that side)
+ *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, T, D] unquantized copies, or NULL: tokens
+ *                           asked to widen then keep their width and are counted. */
+int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v_bits,
+                   const void* dev_k_orig, const void* dev_v_orig, void* stream);
+
+/* Section 2.1 attention over the quantized cache for one new query per head:
+ * S = softmax(q K^^T / sqrt(D)), X = S V^, with K^, V^ the midpoint reconstruction and
+ * outlier channels at their stored fp16 value.  If dev_k_new/dev_v_new are given, that
+ * token takes part unquantized as position T (Section 4.2: the new token "combined
+ * with the quantized KV cache of previous tokens"); it is not appended.
+ *   dev_q       fp16 [B, Hq, D]
+ *   dev_k_new, dev_v_new  fp16 [B, Hkv, D], both or neither
+ *   dev_out     [B, Hq, D], fp32 if out_is_fp32 else fp16
+ *   dev_scores_out  fp32 [B, Hq, T(+1)] normalised scores, or NULL
+ * QAQ_ERR_INVALID_ARG if the cache is empty and no new token is given. */
+int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
+                         const void* dev_v_new, void* dev_out, int32_t out_is_fp32,
+                         float* dev_scores_out, void* stream);
+
+/* Midpoint reconstruction of positions [t0, t1) with outliers restored exactly
+ * (Section 4.1 / 4.2), rounded to fp16.  dev_k_out/dev_v_out: fp16 [B, Hkv, t1-t0, D],
+ * either may be NULL. */
+int qaq_dequantize(qaq_cache* c, int32_t t0, int32_t t1, void* dev_k_out, void* dev_v_out,
+                   void* stream);
+
+/* Layout-independent view of one side (side 0 = keys, 1 = values) for tests and
+ * export, by position:
+ *   dev_bits   uint8 [B, Hkv, T]
+ *   dev_minmax fp16  [B, Hkv, T, 2]
+ *   dev_oidx   uint8 [B, Hkv, T, 2*n_o] outlier channels, ascending
+ *   dev_oval   fp16  [B, Hkv, T, 2*n_o]
+ *   dev_codes  uint8 [B, Hkv, T, D]: the first D*B/8 bytes of a row are the token's
+ *              codes as a little-endian bit string (channel d at bits [d*B,(d+1)*B)),
+ *              the rest of the row is zero.
+ * Any output pointer may be NULL. */
+int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* dev_minmax,
+                         uint8_t* dev_oidx, void* dev_oval, uint8_t* dev_codes, void* stream);
+
+/* Width histogram and byte accounting.  Runs a small kernel on `stream` and waits. */
+int qaq_stats(qaq_cache* c, qaq_stats_t* host_out, void* stream);
+
+/* Number of outliers kept per end of a token vector for this configuration. */
+int qaq_outliers_per_side(const qaq_config* cfg);
+
+const char* qaq_last_error(void);
+
+/* Host-only helpers for layout tests (no device access): where the device layout keeps
+ * the bf-bit field (bf = 1, 2, 4, 8) of token `idx` of its width region, channel d, for
+ * a tile side with the given class counts: byte offset of the 32-bit word from the start
+ * of the tile side, bit position inside it, and the end of the last region.  And the
+ * bytes reserved per tile side. */
+int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8,
+                    int32_t bf, int32_t idx, int32_t d, uint32_t* byte_off, int32_t* shift,
+                    uint32_t* region_end);
+uint32_t qaq_debug_tile_capacity(int32_t side, int32_t D);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QAQ_H */

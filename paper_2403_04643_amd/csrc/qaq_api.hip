@@ -1,0 +1,353 @@
+// Host side of libqaq: argument checking, cache bookkeeping, thresholds, launches.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "qaq_internal.h"
+
+struct qaq_cache {
+  qaq_config cfg;
+  std::vector<float> qnorm2;
+  QaqDims dims;
+  QaqArena arena;
+  QaqView view;
+  int len;                         // cached positions per sequence
+  int n_o;
+  int ring_next;                   // ring row that the next score row goes to
+  int row_len[QAQ_MAX_WINDOW];     // tokens covered by each ring row (0 = empty)
+  double sigma_s, sigma_x;
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(QAQ_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int outliers_per_side(const qaq_config* cfg) {
+  if (cfg->n_outlier_per_side >= 0) return cfg->n_outlier_per_side;
+  if (!(cfg->outlier_frac > 0.0f)) return 0;
+  return (int)std::ceil((double)cfg->outlier_frac / 2.0 * cfg->head_dim - 1e-12);
+}
+
+bool valid_config(const qaq_config* c, QaqDims* d) {
+  if (!c) { fail(QAQ_ERR_INVALID_ARG, "config is NULL"); return false; }
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads) {
+    fail(QAQ_ERR_INVALID_ARG, "bad batch/head counts (%d, %d, %d)", c->batch, c->n_q_heads, c->n_kv_heads); return false; }
+  if (c->n_kv_heads > QAQ_MAX_KV_HEADS) { fail(QAQ_ERR_INVALID_ARG, "at most %d KV heads", QAQ_MAX_KV_HEADS); return false; }
+  if (c->head_dim != 64 && c->head_dim != 128) { fail(QAQ_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", c->head_dim); return false; }
+  if (c->max_tokens < 1) { fail(QAQ_ERR_INVALID_ARG, "max_tokens must be positive"); return false; }
+  if (c->n_bits < 1 || c->n_bits > 4) { fail(QAQ_ERR_INVALID_ARG, "n_bits must be 1..4"); return false; }
+  for (int i = 0; i < c->n_bits; ++i) {
+    const int b = c->bit_set[i];
+    if (!(b == 2 || b == 3 || b == 4 || b == 8) || (i && b <= c->bit_set[i - 1])) {
+      fail(QAQ_ERR_INVALID_ARG, "bit_set must be an ascending subset of {2,3,4,8}"); return false; }
+  }
+  if (c->window < 1 || c->window > QAQ_MAX_WINDOW) { fail(QAQ_ERR_INVALID_ARG, "window must be 1..%d", QAQ_MAX_WINDOW); return false; }
+  const int no = outliers_per_side(c);
+  if (no < 0 || 2 * no > QAQ_MAX_NO2 || c->head_dim - 2 * no < 2) { fail(QAQ_ERR_INVALID_ARG, "unsupported outlier count %d per side", no); return false; }
+  if (!(c->sigma_s_max > 0.0) || !(c->sigma_x_max > 0.0)) { fail(QAQ_ERR_INVALID_ARG, "sigma bounds must be positive"); return false; }
+  if (!c->qnorm2) { fail(QAQ_ERR_INVALID_ARG, "qnorm2 is NULL"); return false; }
+  for (int h = 0; h < c->n_kv_heads; ++h)
+    if (!(c->qnorm2[h] > 0.0f)) { fail(QAQ_ERR_INVALID_ARG, "qnorm2[%d] must be positive", h); return false; }
+  d->B = c->batch; d->Hq = c->n_q_heads; d->Hkv = c->n_kv_heads; d->D = c->head_dim;
+  d->NT = (c->max_tokens + QAQ_TT - 1) / QAQ_TT;
+  d->Tmax = d->NT * QAQ_TT;
+  d->no2 = 2 * no;
+  d->window = c->window;
+  return true;
+}
+
+void thresholds(const qaq_cache* c, int T, float* tau_k, float* c_v) {
+  for (int h = 0; h < c->dims.Hkv; ++h) {
+    if (T < 2) { tau_k[h] = INFINITY; continue; }
+    const double var_k = std::log1p((double)T * T * T / (T - 1.0) * c->sigma_s * c->sigma_s) / (double)c->qnorm2[h];
+    tau_k[h] = (float)(2.0 * std::sqrt(3.0) * std::sqrt(var_k));
+  }
+  *c_v = (float)(2.0 * std::sqrt(3.0) * c->sigma_x / std::sqrt((double)(T < 1 ? 1 : T)));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* qaq_last_error(void) { return g_err; }
+
+int qaq_outliers_per_side(const qaq_config* cfg) {
+  QaqDims d;
+  if (!valid_config(cfg, &d)) return QAQ_ERR_INVALID_ARG;
+  return d.no2 / 2;
+}
+
+size_t qaq_arena_bytes(const qaq_config* cfg) {
+  QaqDims d;
+  if (!valid_config(cfg, &d)) return 0;
+  return qaq_carve(d).total;
+}
+
+int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_cache** out) {
+  QaqDims d;
+  if (!out) return fail(QAQ_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  if (!valid_config(cfg, &d)) return QAQ_ERR_INVALID_ARG;
+  if (!dev_arena || ((uintptr_t)dev_arena & 255)) return fail(QAQ_ERR_INVALID_ARG, "arena must be non-NULL and 256-byte aligned");
+  const QaqArena a = qaq_carve(d);
+  if (arena_bytes < a.total) return fail(QAQ_ERR_CAPACITY, "arena has %zu bytes, %zu needed", arena_bytes, a.total);
+  qaq_cache* c = new (std::nothrow) qaq_cache();
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "out of host memory");
+  c->cfg = *cfg;
+  c->qnorm2.assign(cfg->qnorm2, cfg->qnorm2 + cfg->n_kv_heads);
+  c->cfg.qnorm2 = c->qnorm2.data();
+  c->dims = d;
+  c->arena = a;
+  c->n_o = d.no2 / 2;
+  c->len = 0;
+  c->ring_next = 0;
+  std::memset(c->row_len, 0, sizeof(c->row_len));
+  c->sigma_s = cfg->sigma_s_max;
+  c->sigma_x = cfg->sigma_x_max;
+  uint8_t* base = (uint8_t*)dev_arena;
+  QaqView& v = c->view;
+  for (int s = 0; s < 2; ++s) {
+    v.codes[s] = base + a.codes[s];
+    v.mm[s] = (uint32_t*)(base + a.mm[s]);
+    v.perm[s] = base + a.perm[s];
+    v.oidx[s] = base + a.oidx[s];
+    v.oval[s] = (uint16_t*)(base + a.oval[s]);
+    v.tags[s] = base + a.tags[s];
+  }
+  v.counts = (uint16_t*)(base + a.counts);
+  v.ring = (float*)(base + a.ring);
+  v.partial = (float*)(base + a.partial);
+  v.statbuf = (long long*)(base + a.statbuf);
+  v.refused = (unsigned int*)(base + a.refused);
+  v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
+  v.cap[0] = qaq_k_cap(d.D);
+  v.cap[1] = qaq_v_cap(d.D);
+  hipError_t e = qaq_launch_init(v, nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e != hipSuccess) { delete c; return hip_fail(e, "qaq_create: init"); }
+  *out = c;
+  return QAQ_OK;
+}
+
+int qaq_destroy(qaq_cache* c) {
+  delete c;
+  return QAQ_OK;
+}
+
+int qaq_reset(qaq_cache* c) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  c->len = 0;
+  c->ring_next = 0;
+  std::memset(c->row_len, 0, sizeof(c->row_len));
+  return QAQ_OK;
+}
+
+int qaq_length(const qaq_cache* c, int32_t* host_len) {
+  if (!c || !host_len) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  *host_len = c->len;
+  return QAQ_OK;
+}
+
+int qaq_set_sigmas(qaq_cache* c, double sigma_s_max, double sigma_x_max) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (!(sigma_s_max > 0.0) || !(sigma_x_max > 0.0)) return fail(QAQ_ERR_INVALID_ARG, "sigma bounds must be positive");
+  c->sigma_s = sigma_s_max;
+  c->sigma_x = sigma_x_max;
+  return QAQ_OK;
+}
+
+int qaq_thresholds(const qaq_cache* c, int32_t T, float* host_tau_k, float* host_c_v) {
+  if (!c || !host_tau_k || !host_c_v) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if (T < 1) return fail(QAQ_ERR_INVALID_ARG, "T must be positive");
+  thresholds(c, T, host_tau_k, host_c_v);
+  return QAQ_OK;
+}
+
+int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
+                        const uint8_t* dev_k_bits, const uint8_t* dev_v_bits, void* stream) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (n_new < 0) return fail(QAQ_ERR_INVALID_ARG, "n_new is negative");
+  if (n_new == 0) return QAQ_OK;
+  if (!dev_k || !dev_v) return fail(QAQ_ERR_INVALID_ARG, "K/V input is NULL");
+  if (((uintptr_t)dev_k & 15) || ((uintptr_t)dev_v & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
+  if ((long long)c->len + n_new > c->cfg.max_tokens)
+    return fail(QAQ_ERR_CAPACITY, "%d cached + %d new tokens exceed max_tokens %d", c->len, n_new, c->cfg.max_tokens);
+  QaqBuildArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.mode = 0;
+  a.len_before = c->len;
+  a.len_after = c->len + n_new;
+  a.tile0 = c->len / QAQ_TT;
+  a.n_new = n_new;
+  a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
+  a.newx[0] = (const __half*)dev_k; a.newx[1] = (const __half*)dev_v;
+  a.newbits[0] = dev_k_bits; a.newbits[1] = dev_v_bits;
+  const int tile_last = (a.len_after - 1) / QAQ_TT;
+  hipError_t e = qaq_launch_build(a, tile_last - a.tile0 + 1, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_quantize_append");
+  c->len = a.len_after;
+  return QAQ_OK;
+}
+
+int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream) {
+  if (!c || !dev_k_bits || !dev_v_bits) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if (c->len == 0) return QAQ_OK;
+  QaqSelectArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.len = c->len;
+  a.G = c->dims.Hq / c->dims.Hkv;
+  a.scores = dev_scores;
+  a.new_row = c->ring_next;
+  if (dev_scores) {
+    c->row_len[c->ring_next] = c->len;
+    c->ring_next = (c->ring_next + 1) % c->dims.window;
+  }
+  for (int r = 0; r < QAQ_MAX_WINDOW; ++r) a.row_len[r] = r < c->dims.window ? c->row_len[r] : 0;
+  a.nbits = c->cfg.n_bits;
+  for (int i = 0; i < 4; ++i) a.bit_set[i] = c->cfg.bit_set[i < a.nbits ? i : a.nbits - 1];
+  thresholds(c, c->len, a.tau_k, &a.c_v);
+  a.out_bits[0] = dev_k_bits; a.out_bits[1] = dev_v_bits;
+  hipError_t e = qaq_launch_select(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_select_bits");
+  return QAQ_OK;
+}
+
+int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v_bits,
+                   const void* dev_k_orig, const void* dev_v_orig, void* stream) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (c->len == 0 || (!dev_k_bits && !dev_v_bits)) return QAQ_OK;
+  if (((uintptr_t)dev_k_orig & 15) || ((uintptr_t)dev_v_orig & 15)) return fail(QAQ_ERR_INVALID_ARG, "originals must be 16-byte aligned");
+  QaqBuildArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.mode = 1;
+  a.len_before = a.len_after = c->len;
+  a.tile0 = 0;
+  a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
+  a.newbits[0] = dev_k_bits; a.newbits[1] = dev_v_bits;
+  a.orig[0] = (const __half*)dev_k_orig; a.orig[1] = (const __half*)dev_v_orig;
+  hipError_t e = qaq_launch_build(a, (c->len + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_requantize");
+  return QAQ_OK;
+}
+
+int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
+                         void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
+  if (!c || !dev_q || !dev_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if ((dev_k_new == nullptr) != (dev_v_new == nullptr)) return fail(QAQ_ERR_INVALID_ARG, "k_new and v_new must be given together");
+  if (c->len == 0 && !dev_k_new) return fail(QAQ_ERR_INVALID_ARG, "empty cache and no new token");
+  QaqAttnArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.len = c->len;
+  a.G = c->dims.Hq / c->dims.Hkv;
+  a.q = (const __half*)dev_q;
+  a.k_new = (const __half*)dev_k_new;
+  a.v_new = (const __half*)dev_v_new;
+  a.out = dev_out;
+  a.out_is_fp32 = out_is_fp32;
+  a.scores = dev_scores_out;
+  a.score_stride = c->len + (dev_k_new ? 1 : 0);
+  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
+  return QAQ_OK;
+}
+
+int qaq_dequantize(qaq_cache* c, int32_t t0, int32_t t1, void* dev_k_out, void* dev_v_out, void* stream) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (t0 < 0 || t1 < t0 || t1 > c->len) return fail(QAQ_ERR_INVALID_ARG, "bad range [%d, %d) for %d tokens", t0, t1, c->len);
+  if (t1 == t0 || (!dev_k_out && !dev_v_out)) return QAQ_OK;
+  QaqDequantArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.len = c->len; a.t0 = t0; a.t1 = t1;
+  a.out[0] = (__half*)dev_k_out; a.out[1] = (__half*)dev_v_out;
+  hipError_t e = qaq_launch_dequant(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_dequantize");
+  return QAQ_OK;
+}
+
+int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* dev_minmax, uint8_t* dev_oidx,
+                         void* dev_oval, uint8_t* dev_codes, void* stream) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (side != 0 && side != 1) return fail(QAQ_ERR_INVALID_ARG, "side must be 0 (keys) or 1 (values)");
+  if (c->len == 0) return QAQ_OK;
+  QaqExportArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.len = c->len; a.side = side;
+  a.bits = dev_bits; a.minmax = (uint16_t*)dev_minmax; a.oidx = dev_oidx; a.oval = (uint16_t*)dev_oval; a.codes = dev_codes;
+  hipError_t e = qaq_launch_export(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_export_canonical");
+  return QAQ_OK;
+}
+
+int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
+  if (!c || !out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  std::memset(out, 0, sizeof(*out));
+  out->tokens = c->len;
+  long long buf[16] = {0};
+  unsigned int refused = 0;
+  hipError_t e = qaq_launch_stats(c->view, c->len, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(buf, c->view.statbuf, sizeof(buf), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(&refused, c->view.refused, sizeof(refused), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_stats");
+  static const int widths[4] = {2, 3, 4, 8};
+  const long long D = c->dims.D;
+  for (int i = 0; i < 4; ++i) {
+    out->hist_k[i] = buf[i];
+    out->hist_v[i] = buf[4 + i];
+    out->code_bytes += (buf[i] + buf[4 + i]) * D * widths[i] / 8;
+  }
+  out->layout_code_bytes = buf[8];
+  out->meta_bytes = buf[9];
+  out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
+  out->refused_upgrades = refused;
+  return QAQ_OK;
+}
+
+// Host-only view of the code layout, for layout tests: where the field of width
+// `bf` (1, 2, 4 or 8) of token `idx` of its region, channel d, is stored, relative to the
+// start of the tile side; the region offsets follow from the class counts.
+int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8, int32_t bf,
+                    int32_t idx, int32_t d, uint32_t* byte_off, int32_t* shift, uint32_t* region_end) {
+  if ((D != 64 && D != 128) || d < 0 || d >= D || idx < 0) return fail(QAQ_ERR_INVALID_ARG, "bad layout query");
+  QaqCounts c; c.n3 = n3; c.n2 = n2; c.n4 = n4; c.n8 = n8;
+  QaqFieldPos p;
+  if (side == 0) {
+    const QaqKRegions r = qaq_k_regions(c, D);
+    const uint32_t ro = bf == 2 ? r.r2 : bf == 1 ? r.r1 : bf == 4 ? r.r4 : r.r8;
+    p = qaq_k_field(ro, bf, idx, d, D);
+    *region_end = r.end;
+  } else {
+    const QaqVRegions r = qaq_v_regions(c, D);
+    if (bf == 8) { p.byte_off = (r.r8 + (uint32_t)idx * D + d) & ~3u; p.shift = 8 * (d & 3); }
+    else p = qaq_v_field(bf == 2 ? r.r2 : bf == 1 ? r.r1 : r.r4, bf, idx, d, D);
+    *region_end = r.end;
+  }
+  *byte_off = p.byte_off;
+  *shift = p.shift;
+  return QAQ_OK;
+}
+
+uint32_t qaq_debug_tile_capacity(int32_t side, int32_t D) { return side == 0 ? qaq_k_cap(D) : qaq_v_cap(D); }
+
+}  // extern "C"

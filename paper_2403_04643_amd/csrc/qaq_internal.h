@@ -1,0 +1,102 @@
+// Internal declarations shared by the host API and the kernel files of libqaq.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/qaq.h"
+#include "qaq_layout.h"
+
+#define QAQ_MAX_KV_HEADS 128
+#define QAQ_MAX_WINDOW 8
+
+// What every kernel sees of a cache: raw pointers into the arena plus the shape.
+struct QaqView {
+  uint8_t* codes[2];
+  uint32_t* mm[2];
+  uint8_t* perm[2];
+  uint8_t* oidx[2];
+  uint16_t* oval[2];
+  uint8_t* tags[2];
+  uint16_t* counts;
+  float* ring;
+  float* partial;
+  long long* statbuf;
+  unsigned int* refused;
+  int B, Hq, Hkv, D, Tmax, NT, no2, window;
+  uint32_t cap[2];
+};
+
+__host__ __device__ __forceinline__ size_t qaq_bh(const QaqView& v, int b, int h) { return (size_t)b * v.Hkv + h; }
+__device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, int b, int h, int tile) {
+  return v.codes[side] + ((qaq_bh(v, b, h) * v.NT + tile) * (size_t)v.cap[side]);
+}
+__device__ __forceinline__ size_t qaq_slot_index(const QaqView& v, int b, int h, int tile, int slot) {
+  return qaq_bh(v, b, h) * v.Tmax + (size_t)tile * QAQ_TT + slot;
+}
+__device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side, int b, int h, int tile) {
+  const uint16_t* p = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
+  QaqCounts c;
+  c.n3 = p[QC3]; c.n2 = p[QC2]; c.n4 = p[QC4]; c.n8 = p[QC8];
+  return c;
+}
+
+struct QaqBuildArgs {
+  QaqView v;
+  int mode;          // 0 = append, 1 = requantize
+  int len_before, len_after, tile0, n_new, widest;
+  const __half* newx[2];       // append: [B,Hkv,n_new,D]
+  const uint8_t* newbits[2];   // append: [B,Hkv,n_new] or null; requantize: [B,Hkv,len] or null
+  const __half* orig[2];       // requantize: [B,Hkv,len,D] or null
+};
+
+struct QaqSelectArgs {
+  QaqView v;
+  int len;                 // tokens to select for
+  int G;                   // query heads per KV head
+  const float* scores;     // [B,Hq,len] or null
+  int new_row;             // ring row that receives `scores` (ignored if null)
+  int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
+  int nbits;
+  int bit_set[4];
+  float tau_k[QAQ_MAX_KV_HEADS];
+  float c_v;
+  uint8_t* out_bits[2];    // [B,Hkv,len]
+};
+
+struct QaqAttnArgs {
+  QaqView v;
+  int len, G;
+  const __half* q;        // [B,Hq,D]
+  const __half* k_new;    // [B,Hkv,D] or null
+  const __half* v_new;
+  void* out;              // [B,Hq,D]
+  int out_is_fp32;
+  float* scores;          // [B,Hq,len(+1)] or null
+  int score_stride;       // len (+1)
+};
+
+struct QaqExportArgs {
+  QaqView v;
+  int len, side;
+  uint8_t* bits;
+  uint16_t* minmax;
+  uint8_t* oidx;
+  uint16_t* oval;
+  uint8_t* codes;
+};
+
+struct QaqDequantArgs {
+  QaqView v;
+  int len, t0, t1;
+  __half* out[2];
+};
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t qaq_launch_init(const QaqView& v, hipStream_t s);
+hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
+hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
+hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s);
+hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
+hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);
+hipError_t qaq_launch_stats(const QaqView& v, int len, hipStream_t s);

@@ -1,0 +1,557 @@
+// Quantization side of libqaq: tile build (append / requantize), width selection,
+// canonical export, dequantization, accounting.  Compiled with FP contraction off:
+// the fp32 operation order of the encoder and decoder is part of the contract
+// (one rounding per operation, round to nearest even).
+#include "qaq_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int D>
+struct TileLds {
+  uint8_t stage[QAQ_TT][D];            // one code per (position, channel), at the token's width
+  uint32_t mm[QAQ_TT];                 // fp16 min | fp16 max << 16, by position
+  uint8_t oidx[QAQ_TT][QAQ_MAX_NO2];   // outlier channels, by position
+  uint16_t oval[QAQ_TT][QAQ_MAX_NO2];  // outlier fp16 values
+  uint8_t bits_old[QAQ_TT];
+  uint8_t bits_new[QAQ_TT];
+  uint16_t slot_of_pos[QAQ_TT];
+  uint16_t pos_of_slot[QAQ_TT];
+  int wave_cnt[4][4];
+  int flag;
+};
+
+__device__ __forceinline__ float h2f(uint16_t b) { return __half2float(__ushort_as_half(b)); }
+__device__ __forceinline__ uint16_t f2h(float f) { return __half_as_ushort(__float2half_rn(f)); }
+
+__device__ __forceinline__ uint32_t rd_field(const uint8_t* base, QaqFieldPos p, uint32_t mask) {
+  return (*(const uint32_t*)(base + p.byte_off) >> p.shift) & mask;
+}
+
+// Code of (slot, channel d) as stored for this tile side.
+template <int D>
+__device__ __forceinline__ uint32_t load_code(int side, const uint8_t* base, const QaqCounts& c, uint32_t r2,
+                                              uint32_t r1, uint32_t r4, uint32_t r8, int slot, int d) {
+  const int n32 = c.n32();
+  if (slot < n32) {
+    uint32_t f = side == 0 ? rd_field(base, qaq_k_field(r2, 2, slot, d, D), 3u)
+                           : rd_field(base, qaq_v_field(r2, 2, slot, d, D), 3u);
+    if (slot < c.n3) {
+      uint32_t lo = side == 0 ? rd_field(base, qaq_k_field(r1, 1, slot, d, D), 1u)
+                              : rd_field(base, qaq_v_field(r1, 1, slot, d, D), 1u);
+      return f * 2u + lo;
+    }
+    return f;
+  }
+  if (slot < n32 + c.n4) {
+    int i4 = slot - n32;
+    return side == 0 ? rd_field(base, qaq_k_field(r4, 4, i4, d, D), 15u)
+                     : rd_field(base, qaq_v_field(r4, 4, i4, d, D), 15u);
+  }
+  int i8 = slot - n32 - c.n4;
+  if (side == 0) return rd_field(base, qaq_k_field(r8, 8, i8, d, D), 255u) ^ 0x80u;
+  return base[r8 + (uint32_t)i8 * D + d];
+}
+
+// Bring a stored tile side into LDS, indexed by position.
+template <int D>
+__device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, int n_tok, TileLds<D>& L) {
+  const int tid = threadIdx.x;
+  const QaqCounts c = qaq_load_counts(v, side, b, h, tile);
+  uint32_t r2, r1, r4, r8;
+  if (side == 0) { QaqKRegions r = qaq_k_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; }
+  else { QaqVRegions r = qaq_v_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; }
+  if (tid < n_tok) {
+    const int s = tid;
+    const size_t gi = qaq_slot_index(v, b, h, tile, s);
+    const int pos = v.perm[side][gi];
+    L.mm[pos] = v.mm[side][gi];
+    L.slot_of_pos[pos] = (uint16_t)s;
+    L.bits_old[pos] = (uint8_t)c.bits_of_slot(s);
+    for (int k = 0; k < v.no2; ++k) {
+      L.oidx[pos][k] = v.oidx[side][gi * v.no2 + k];
+      L.oval[pos][k] = v.oval[side][gi * v.no2 + k];
+    }
+  }
+  __syncthreads();
+  const uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
+  for (int e = tid; e < n_tok * D; e += kThreads) {
+    const int pos = e / D, d = e % D;
+    L.stage[pos][d] = (uint8_t)load_code<D>(side, base, c, r2, r1, r4, r8, L.slot_of_pos[pos], d);
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------
+// Encoder for one token vector, run by a group of D/8 consecutive lanes (8 channels
+// per lane).  Outliers: the n_o largest, then the n_o smallest of the rest, ties to
+// the lower channel; [min,max] over what remains; code = clamp(floor((x-min)*inv)).
+// ---------------------------------------------------------------------------------
+template <int D>
+__device__ void encode_token(const __half* src, int gl, bool fresh, int bits, int n_o, uint32_t* mm_pos,
+                             uint8_t* oidx_row, uint16_t* oval_row, uint8_t* stage_row) {
+  constexpr int LPT = D / 8;
+  const uint4 raw = ((const uint4*)src)[gl];
+  const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+  float x[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] = h2f((uint16_t)(rw[j >> 1] >> (16 * (j & 1))));
+  float mn, mx;
+  if (fresh) {
+    uint32_t marked = 0;
+    for (int k = 0; k < 2 * n_o; ++k) {
+      const bool top = k < n_o;
+      float best = top ? -INFINITY : INFINITY;
+      int bidx = 1 << 20;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        // the first free element of the lane always enters, later ones only if
+        // strictly better: equal values keep the lower channel
+        const bool free_ = !((marked >> j) & 1u);
+        const bool better = top ? (x[j] > best) : (x[j] < best);
+        if (free_ && (bidx == (1 << 20) || better)) { best = x[j]; bidx = gl * 8 + j; }
+      }
+#pragma unroll
+      for (int off = LPT / 2; off >= 1; off >>= 1) {
+        const float ob = __shfl_xor(best, off);
+        const int oi = __shfl_xor(bidx, off);
+        const bool take = (oi < (1 << 20)) &&
+                          (bidx == (1 << 20) || (top ? (ob > best) : (ob < best)) || (ob == best && oi < bidx));
+        if (take) { best = ob; bidx = oi; }
+      }
+      if ((bidx >> 3) == gl) marked |= 1u << (bidx & 7);
+      if (gl == 0) { oidx_row[k] = (uint8_t)bidx; oval_row[k] = f2h(best); }
+    }
+    mn = INFINITY; mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (!((marked >> j) & 1u)) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
+#pragma unroll
+    for (int off = LPT / 2; off >= 1; off >>= 1) {
+      mn = fminf(mn, __shfl_xor(mn, off));
+      mx = fmaxf(mx, __shfl_xor(mx, off));
+    }
+    if (gl == 0) *mm_pos = (uint32_t)f2h(mn) | ((uint32_t)f2h(mx) << 16);
+  } else {
+    const uint32_t m = *mm_pos;
+    mn = h2f((uint16_t)(m & 0xffffu));
+    mx = h2f((uint16_t)(m >> 16));
+  }
+  const float range = mx - mn;
+  const float levels = (float)(1 << bits);
+  const float inv = levels / range;
+  const float top_code = levels - 1.0f;
+  uint32_t lo = 0, hi = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float diff = x[j] - mn;
+    const float prod = diff * inv;
+    float c = floorf(prod);
+    c = fminf(fmaxf(c, 0.0f), top_code);
+    if (!(range > 0.0f)) c = 0.0f;
+    const uint32_t ci = (uint32_t)c;
+    if (j < 4) lo |= ci << (8 * j); else hi |= ci << (8 * (j - 4));
+  }
+  uint2* dst = (uint2*)(stage_row + gl * 8);
+  *dst = make_uint2(lo, hi);
+}
+
+// ---------------------------------------------------------------------------------
+// Tile build: append new tokens and / or move cached tokens to other widths, then
+// write the tile side back in class order.
+// ---------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  TileLds<D>& L = *reinterpret_cast<TileLds<D>*>(smem_raw);
+  uint32_t* outb = reinterpret_cast<uint32_t*>(smem_raw + ((sizeof(TileLds<D>) + 15) & ~(size_t)15));
+  constexpr int OUTB = QAQ_TT * D / 2 + 12 * D;   // bytes: every region but the 8-bit one
+
+  const QaqView& v = a.v;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = a.tile0 + blockIdx.x;
+  const int bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
+  const int side = blockIdx.z;
+  const int t0 = tile * QAQ_TT;
+  const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
+  const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
+  if (n_after == 0) return;
+  const int n_o = v.no2 / 2;
+
+  if (a.mode == 1) {
+    // requantize: nothing to do for this side, or no token of the tile changes
+    if (a.newbits[side] == nullptr) return;
+    bool changed = false;
+    if (tid < n_before) {
+      const int oldb = v.tags[side][qaq_slot_index(v, b, h, tile, tid)];
+      const int req = a.newbits[side][(size_t)bh * a.len_before + t0 + tid];
+      if (req < oldb) changed = true;
+      else if (req > oldb) {
+        if (a.orig[side]) changed = true;
+        else atomicAdd(v.refused, 1u);
+      }
+    }
+    if (!__syncthreads_or(changed ? 1 : 0)) return;
+  }
+
+  if (n_before > 0) tile_load<D>(v, side, b, h, tile, n_before, L);
+
+  // final width of every position
+  if (tid < n_after) {
+    int nb;
+    if (tid < n_before) {
+      const int oldb = L.bits_old[tid];
+      nb = oldb;
+      if (a.mode == 1) {
+        const int req = a.newbits[side][(size_t)bh * a.len_before + t0 + tid];
+        if (req < oldb || (req > oldb && a.orig[side])) nb = req;
+      }
+    } else {
+      const int r = t0 + tid - a.len_before;
+      nb = a.newbits[side] ? a.newbits[side][(size_t)bh * a.n_new + r] : a.widest;
+      L.bits_old[tid] = (uint8_t)nb;
+    }
+    L.bits_new[tid] = (uint8_t)nb;
+  }
+  __syncthreads();
+
+  // encode: new tokens, and cached tokens that widen (from the unquantized copy)
+  {
+    constexpr int LPT = D / 8;
+    constexpr int TPP = kThreads / LPT;   // tokens per pass
+    const int gl = tid % LPT, gt = tid / LPT;
+    for (int p0 = 0; p0 < n_after; p0 += TPP) {
+      const int p = p0 + gt;
+      if (p >= n_after) continue;          // whole lane groups drop out together
+      const bool fresh = p >= n_before;
+      const bool widen = !fresh && L.bits_new[p] > L.bits_old[p];
+      if (!fresh && !widen) continue;
+      const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
+                                : a.orig[side] + ((size_t)bh * a.len_before + (t0 + p)) * D;
+      encode_token<D>(src, gl, fresh, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], L.stage[p]);
+    }
+  }
+  __syncthreads();
+
+  // narrowing: drop low code bits (the coarser grid's segments contain the finer one's);
+  // side store of fresh tokens: order by channel
+  for (int e = tid; e < n_before * D; e += kThreads) {
+    const int pos = e / D, d = e % D;
+    const int sh = (int)L.bits_old[pos] - (int)L.bits_new[pos];
+    if (sh > 0) L.stage[pos][d] = L.stage[pos][d] >> sh;
+  }
+  if (tid >= n_before && tid < n_after && v.no2 > 1) {
+    for (int i = 1; i < v.no2; ++i) {
+      const uint8_t ki = L.oidx[tid][i];
+      const uint16_t vi = L.oval[tid][i];
+      int j = i - 1;
+      while (j >= 0 && L.oidx[tid][j] > ki) {
+        L.oidx[tid][j + 1] = L.oidx[tid][j];
+        L.oval[tid][j + 1] = L.oval[tid][j];
+        --j;
+      }
+      L.oidx[tid][j + 1] = ki;
+      L.oval[tid][j + 1] = vi;
+    }
+  }
+
+  // stable counting sort of the positions by class (3, 2, 4, 8)
+  const int cls = tid < n_after ? qaq_class_of_bits(L.bits_new[tid]) : -1;
+  int my_rank = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const unsigned long long bal = __ballot(cls == c);
+    if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
+    if (cls == c) my_rank = __popcll(bal & ((1ull << lane) - 1ull));
+  }
+  __syncthreads();
+  QaqCounts cn;
+  {
+    int n[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
+    cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8];
+  }
+  if (cls >= 0) {
+    int s = cn.start(cls) + my_rank;
+    for (int w = 0; w < wave; ++w) s += L.wave_cnt[cls][w];
+    L.slot_of_pos[tid] = (uint16_t)s;
+    L.pos_of_slot[s] = (uint16_t)tid;
+  }
+  uint32_t r2, r1, r4, r8, rend;
+  if (side == 0) { QaqKRegions r = qaq_k_regions(cn, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; rend = r.end; }
+  else { QaqVRegions r = qaq_v_regions(cn, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; rend = r.end; }
+  for (int i = tid; i < OUTB / 4; i += kThreads) outb[i] = 0u;
+  __syncthreads();
+
+  // metadata in slot order, widths by position, class counts
+  if (tid < n_after) {
+    const int s = L.slot_of_pos[tid];
+    const size_t gi = qaq_slot_index(v, b, h, tile, s);
+    v.mm[side][gi] = L.mm[tid];
+    v.perm[side][gi] = (uint8_t)tid;
+    for (int k = 0; k < v.no2; ++k) {
+      v.oidx[side][gi * v.no2 + k] = L.oidx[tid][k];
+      v.oval[side][gi * v.no2 + k] = L.oval[tid][k];
+    }
+    v.tags[side][qaq_slot_index(v, b, h, tile, tid)] = L.bits_new[tid];
+  }
+  if (tid == 0) {
+    uint16_t* cp = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
+    cp[QC3] = (uint16_t)cn.n3; cp[QC2] = (uint16_t)cn.n2; cp[QC4] = (uint16_t)cn.n4; cp[QC8] = (uint16_t)cn.n8;
+  }
+
+  // scatter the sub-byte fields into the output image
+  const int n32 = cn.n32();
+  for (int e = tid; e < n_after * D; e += kThreads) {
+    const int pos = e / D, d = e % D;
+    const int s = L.slot_of_pos[pos];
+    const uint32_t c = L.stage[pos][d];
+    if (s < n32) {
+      const bool three = s < cn.n3;
+      const uint32_t f2 = three ? (c >> 1) : c;
+      const QaqFieldPos p = side == 0 ? qaq_k_field(r2, 2, s, d, D) : qaq_v_field(r2, 2, s, d, D);
+      if (f2) atomicOr(&outb[p.byte_off >> 2], f2 << p.shift);
+      if (three && (c & 1u)) {
+        const QaqFieldPos p1 = side == 0 ? qaq_k_field(r1, 1, s, d, D) : qaq_v_field(r1, 1, s, d, D);
+        atomicOr(&outb[p1.byte_off >> 2], 1u << p1.shift);
+      }
+    } else if (s < n32 + cn.n4) {
+      const QaqFieldPos p = side == 0 ? qaq_k_field(r4, 4, s - n32, d, D) : qaq_v_field(r4, 4, s - n32, d, D);
+      if (c) atomicOr(&outb[p.byte_off >> 2], c << p.shift);
+    }
+  }
+  __syncthreads();
+
+  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
+  for (uint32_t i = tid; i < r8 / 16; i += kThreads) ((uint4*)base)[i] = ((const uint4*)outb)[i];
+  // 8-bit class: one byte per channel, straight from the stage
+  const int first8 = n32 + cn.n4;
+  for (int e = tid; e < cn.n8 * (D / 4); e += kThreads) {
+    const int i8 = e / (D / 4), dq = e % (D / 4);
+    const int pos = L.pos_of_slot[first8 + i8];
+    uint32_t w;
+    if (side == 0) {
+      constexpr int KS = D / 64;
+      const int q = dq >> 2, vv = dq & 3, g = q / KS, ks = q % KS;
+      w = *(const uint32_t*)&L.stage[pos][64 * ks + 16 * g + 4 * vv] ^ 0x80808080u;
+    } else {
+      w = *(const uint32_t*)&L.stage[pos][4 * dq];
+    }
+    *(uint32_t*)(base + r8 + (uint32_t)i8 * D + 4u * dq) = w;
+  }
+  (void)rend;
+}
+
+template <int D>
+constexpr size_t build_smem() {
+  return ((sizeof(TileLds<D>) + 15) & ~(size_t)15) + (QAQ_TT * D / 2 + 12 * D);
+}
+
+// ---------------------------------------------------------------------------------
+// Width selection (Section 4.1 bit rules written as comparisons, Section 4.2 window).
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
+  __shared__ float rk[QAQ_TT], rv[QAQ_TT];
+  const QaqView& v = a.v;
+  const int tid = threadIdx.x;
+  const int tile = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
+  const int t0 = tile * QAQ_TT;
+  const int n_tok = min(a.len - t0, QAQ_TT);
+  if (n_tok <= 0) return;
+  if (tid < n_tok) {
+    const size_t gi = qaq_slot_index(v, b, h, tile, tid);
+    {
+      const uint32_t m = v.mm[0][gi];
+      rk[v.perm[0][gi]] = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
+    }
+    {
+      const uint32_t m = v.mm[1][gi];
+      rv[v.perm[1][gi]] = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
+    }
+  }
+  __syncthreads();
+  if (tid >= n_tok) return;
+  const int t = t0 + tid;
+  const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
+  const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
+  float pred = 0.0f;
+  if (a.scores) {
+    float s = 0.0f;
+    for (int g = 0; g < a.G; ++g) s = fmaxf(s, a.scores[((size_t)b * v.Hq + (h * a.G + g)) * a.len + t]);
+    v.ring[(size_t)a.new_row * ring_row + ri] = s;
+    pred = s;
+  }
+  for (int r = 0; r < v.window; ++r) {
+    if (a.scores && r == a.new_row) continue;
+    if (t < a.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
+  }
+  const float tau = a.tau_k[h];
+  const float lhs_v = rv[tid] * pred;
+  int bk = a.bit_set[a.nbits - 1], bv = a.bit_set[a.nbits - 1];
+  for (int i = a.nbits - 1; i >= 0; --i) {
+    const int bb = a.bit_set[i];
+    if (rk[tid] <= ldexpf(tau, bb)) bk = bb;
+    if (lhs_v <= ldexpf(a.c_v, bb)) bv = bb;
+  }
+  a.out_bits[0][(size_t)bh * a.len + t] = (uint8_t)bk;
+  a.out_bits[1][(size_t)bh * a.len + t] = (uint8_t)bv;
+}
+
+// ---------------------------------------------------------------------------------
+// Canonical export and dequantization (tests, export; not on the decode path).
+// ---------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads) void k_export(QaqExportArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  TileLds<D>& L = *reinterpret_cast<TileLds<D>*>(smem_raw);
+  const QaqView& v = a.v;
+  const int tid = threadIdx.x;
+  const int tile = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
+  const int t0 = tile * QAQ_TT;
+  const int n_tok = min(a.len - t0, QAQ_TT);
+  if (n_tok <= 0) return;
+  tile_load<D>(v, a.side, b, h, tile, n_tok, L);
+  if (tid < n_tok) {
+    const size_t o = (size_t)bh * a.len + t0 + tid;
+    if (a.bits) a.bits[o] = L.bits_old[tid];
+    if (a.minmax) { a.minmax[2 * o] = (uint16_t)(L.mm[tid] & 0xffffu); a.minmax[2 * o + 1] = (uint16_t)(L.mm[tid] >> 16); }
+    for (int k = 0; k < v.no2; ++k) {
+      if (a.oidx) a.oidx[o * v.no2 + k] = L.oidx[tid][k];
+      if (a.oval) a.oval[o * v.no2 + k] = L.oval[tid][k];
+    }
+  }
+  if (a.codes) {
+    for (int e = tid; e < n_tok * D; e += kThreads) {
+      const int pos = e / D, k = e % D;
+      const int bits = L.bits_old[pos];
+      uint32_t byte = 0;
+      if (k < D * bits / 8) {
+        for (int j = 0; j < 8; ++j) {
+          const int gb = 8 * k + j;
+          const int d = gb / bits, bit = gb % bits;
+          byte |= ((L.stage[pos][d] >> bit) & 1u) << j;
+        }
+      }
+      a.codes[((size_t)bh * a.len + t0 + pos) * D + k] = (uint8_t)byte;
+    }
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void k_dequant(QaqDequantArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  TileLds<D>& L = *reinterpret_cast<TileLds<D>*>(smem_raw);
+  const QaqView& v = a.v;
+  const int tid = threadIdx.x;
+  const int tile = a.t0 / QAQ_TT + blockIdx.x;
+  const int bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
+  const int side = blockIdx.z;
+  if (a.out[side] == nullptr) return;
+  const int t0 = tile * QAQ_TT;
+  const int n_tok = min(a.len - t0, QAQ_TT);
+  if (n_tok <= 0) return;
+  tile_load<D>(v, side, b, h, tile, n_tok, L);
+  const int nt = a.t1 - a.t0;
+  for (int e = tid; e < n_tok * D; e += kThreads) {
+    const int pos = e / D, d = e % D;
+    const int t = t0 + pos;
+    if (t < a.t0 || t >= a.t1) continue;
+    const int bits = L.bits_old[pos];
+    const float mn = h2f((uint16_t)(L.mm[pos] & 0xffffu)), mx = h2f((uint16_t)(L.mm[pos] >> 16));
+    const float range = mx - mn;
+    const float scale = ldexpf(range, -bits);
+    const float half_c = (float)L.stage[pos][d] + 0.5f;
+    const float prod = half_c * scale;
+    float xh = prod + mn;
+    uint16_t hb = f2h(xh);
+    for (int k = 0; k < v.no2; ++k)
+      if (L.oidx[pos][k] == d) hb = L.oval[pos][k];
+    a.out[side][((size_t)bh * nt + (t - a.t0)) * D + d] = __ushort_as_half(hb);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Accounting.
+// statbuf: [0..3] hist K (2,3,4,8), [4..7] hist V, [8] layout code bytes, [9] meta bytes
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
+  __shared__ unsigned long long acc[10];
+  const int tid = threadIdx.x;
+  if (tid < 10) acc[tid] = 0;
+  __syncthreads();
+  const int ntile = (len + QAQ_TT - 1) / QAQ_TT;
+  const long long total = (long long)v.B * v.Hkv * ntile * 2;
+  unsigned long long loc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  for (long long i = (long long)blockIdx.x * kThreads + tid; i < total; i += (long long)gridDim.x * kThreads) {
+    const int side = (int)(i & 1);
+    const long long j = i >> 1;
+    const int tile = (int)(j % ntile);
+    const int bh = (int)(j / ntile);
+    const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile);
+    loc[side * 4 + 0] += c.n2; loc[side * 4 + 1] += c.n3; loc[side * 4 + 2] += c.n4; loc[side * 4 + 3] += c.n8;
+    loc[8] += side == 0 ? qaq_k_regions(c, v.D).end : qaq_v_regions(c, v.D).end;
+    loc[9] += (unsigned long long)c.total() * (4 + 1 + 3 * v.no2);
+  }
+  for (int k = 0; k < 10; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
+  __syncthreads();
+  if (tid < 10 && acc[tid]) atomicAdd((unsigned long long*)&v.statbuf[tid], acc[tid]);
+}
+
+__global__ void k_init(QaqView v) {
+  const size_t n = (size_t)v.B * v.Hkv * v.NT * 2 * 4;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) v.counts[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 32) v.statbuf[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 4) v.refused[threadIdx.x] = 0;
+}
+
+__global__ void k_clear_stats(QaqView v) {
+  if (threadIdx.x < 32) v.statbuf[threadIdx.x] = 0;
+}
+
+}  // namespace
+
+hipError_t qaq_launch_init(const QaqView& v, hipStream_t s) {
+  hipLaunchKernelGGL(k_init, dim3(64), dim3(256), 0, s, v);
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  dim3 grid(ntiles, a.v.B * a.v.Hkv, 2);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_build<128>, grid, dim3(kThreads), build_smem<128>(), s, a);
+  else hipLaunchKernelGGL(k_build<64>, grid, dim3(kThreads), build_smem<64>(), s, a);
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s) {
+  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  if (ntile <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_select, dim3(ntile, a.v.B * a.v.Hkv), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s) {
+  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  if (ntile <= 0) return hipSuccess;
+  dim3 grid(ntile, a.v.B * a.v.Hkv);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_export<128>, grid, dim3(kThreads), sizeof(TileLds<128>), s, a);
+  else hipLaunchKernelGGL(k_export<64>, grid, dim3(kThreads), sizeof(TileLds<64>), s, a);
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s) {
+  if (a.t1 <= a.t0) return hipSuccess;
+  const int tile_lo = a.t0 / QAQ_TT, tile_hi = (a.t1 - 1) / QAQ_TT;
+  dim3 grid(tile_hi - tile_lo + 1, a.v.B * a.v.Hkv, 2);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_dequant<128>, grid, dim3(kThreads), sizeof(TileLds<128>), s, a);
+  else hipLaunchKernelGGL(k_dequant<64>, grid, dim3(kThreads), sizeof(TileLds<64>), s, a);
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_stats(const QaqView& v, int len, hipStream_t s) {
+  hipLaunchKernelGGL(k_clear_stats, dim3(1), dim3(64), 0, s, v);
+  hipLaunchKernelGGL(k_stats, dim3(64), dim3(kThreads), 0, s, v, len);
+  return hipGetLastError();
+}

@@ -1,0 +1,258 @@
+"""ctypes binding over libqaq.so: argument marshalling only.
+
+Every step of the method runs inside the library's HIP kernels; PyTorch is used
+here for device memory (torch tensors own every buffer, including the cache
+arena) and for the stream the kernels are enqueued on.  There is no CPU
+fallback: `load()` raises if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqaq.so")
+TILE = 256
+
+OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_HIP, ERR_NEED_ORIGINAL = 0, -1, -2, -3, -4
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("max_tokens", C.c_int32),
+        ("bit_set", C.c_int32 * 4), ("n_bits", C.c_int32),
+        ("outlier_frac", C.c_float), ("n_outlier_per_side", C.c_int32),
+        ("window", C.c_int32),
+        ("sigma_s_max", C.c_double), ("sigma_x_max", C.c_double),
+        ("qnorm2", C.POINTER(C.c_float)),
+    ]
+
+
+class Stats(C.Structure):
+    _fields_ = [
+        ("tokens", C.c_int64), ("hist_k", C.c_int64 * 4), ("hist_v", C.c_int64 * 4),
+        ("code_bytes", C.c_int64), ("layout_code_bytes", C.c_int64), ("meta_bytes", C.c_int64),
+        ("fp16_bytes", C.c_int64), ("refused_upgrades", C.c_int64),
+    ]
+
+
+# name -> (restype, argtypes); the names are those declared in include/qaq.h
+_vp, _i32, _u8p, _f32p = C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p
+SIGNATURES = {
+    "qaq_arena_bytes": (C.c_size_t, [C.POINTER(Config)]),
+    "qaq_create": (C.c_int, [C.POINTER(Config), _vp, C.c_size_t, C.POINTER(_vp)]),
+    "qaq_destroy": (C.c_int, [_vp]),
+    "qaq_reset": (C.c_int, [_vp]),
+    "qaq_length": (C.c_int, [_vp, C.POINTER(C.c_int32)]),
+    "qaq_set_sigmas": (C.c_int, [_vp, C.c_double, C.c_double]),
+    "qaq_thresholds": (C.c_int, [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
+    "qaq_quantize_append": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
+    "qaq_select_bits": (C.c_int, [_vp, _f32p, _u8p, _u8p, _vp]),
+    "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _vp]),
+    "qaq_decode_attention": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _f32p, _vp]),
+    "qaq_dequantize": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp]),
+    "qaq_export_canonical": (C.c_int, [_vp, _i32, _u8p, _vp, _u8p, _vp, _u8p, _vp]),
+    "qaq_stats": (C.c_int, [_vp, C.POINTER(Stats), _vp]),
+    "qaq_outliers_per_side": (C.c_int, [C.POINTER(Config)]),
+    "qaq_last_error": (C.c_char_p, []),
+    "qaq_debug_field": (C.c_int, [_i32] * 9 + [C.POINTER(C.c_uint32), C.POINTER(C.c_int32), C.POINTER(C.c_uint32)]),
+    "qaq_debug_tile_capacity": (C.c_uint32, [_i32, _i32]),
+}
+
+_lib = None
+
+
+class QaqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libqaq error {code}: {msg}")
+        self.code = code
+
+
+def load() -> C.CDLL:
+    """Load libqaq.so (built by __graft_entry__.build()).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python __graft_entry__.py`; "
+                               "there is no fallback path")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise QaqError(rc, load().qaq_last_error().decode())
+
+
+def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequence[float],
+                bit_set=(2, 3, 4, 8), outlier_frac=0.01, n_outlier_per_side=-1, window=5,
+                sigma_s_max=1e-3, sigma_x_max=1e-2):
+    cfg = Config()
+    cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens = batch, n_q_heads, n_kv_heads, head_dim, max_tokens
+    for i, b in enumerate(bit_set):
+        cfg.bit_set[i] = int(b)
+    cfg.n_bits = len(bit_set)
+    cfg.outlier_frac = outlier_frac
+    cfg.n_outlier_per_side = n_outlier_per_side
+    cfg.window = window
+    cfg.sigma_s_max, cfg.sigma_x_max = sigma_s_max, sigma_x_max
+    arr = (C.c_float * len(qnorm2))(*[float(x) for x in qnorm2])
+    cfg.qnorm2 = C.cast(arr, C.POINTER(C.c_float))
+    cfg._keepalive = arr
+    return cfg
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Cache:
+    """A quantized KV cache of one layer.  Methods mirror the C entry points."""
+
+    def __init__(self, cfg: Config, device="cuda:0"):
+        import torch
+        self.lib = load()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        n = self.lib.qaq_arena_bytes(C.byref(cfg))
+        if n == 0:
+            raise QaqError(ERR_INVALID_ARG, self.lib.qaq_last_error().decode())
+        self.arena = torch.empty(n + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.arena.data_ptr()) % 256
+        self.arena_bytes = n
+        self._base = self.arena.data_ptr() + off
+        h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.qaq_create(C.byref(cfg), self._base, n, C.byref(h)))
+        self.h = h
+        self.n_o = self.lib.qaq_outliers_per_side(C.byref(cfg))
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.qaq_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- bookkeeping ---------------------------------------------------------------
+    def length(self) -> int:
+        n = C.c_int32()
+        _check(self.lib.qaq_length(self.h, C.byref(n)))
+        return n.value
+
+    def reset(self):
+        _check(self.lib.qaq_reset(self.h))
+
+    def set_sigmas(self, sigma_s_max: float, sigma_x_max: float):
+        _check(self.lib.qaq_set_sigmas(self.h, sigma_s_max, sigma_x_max))
+
+    def thresholds(self, T: int):
+        tau = (C.c_float * self.cfg.n_kv_heads)()
+        cv = C.c_float()
+        _check(self.lib.qaq_thresholds(self.h, T, tau, C.byref(cv)))
+        return list(tau), cv.value
+
+    # -- the five calls of the hot path -----------------------------------------------
+    def quantize_append(self, k, v, k_bits=None, v_bits=None):
+        """k, v: fp16 [B, Hkv, n_new, D]; bits: uint8 [B, Hkv, n_new] or None (= widest)."""
+        n_new = k.shape[2]
+        _check(self.lib.qaq_quantize_append(self.h, _ptr(k), _ptr(v), n_new, _ptr(k_bits), _ptr(v_bits), _stream()))
+
+    def select_bits(self, scores=None):
+        """scores: fp32 [B, Hq, T] or None.  Returns (k_bits, v_bits) uint8 [B, Hkv, T]."""
+        import torch
+        T = self.length()
+        shape = (self.cfg.batch, self.cfg.n_kv_heads, T)
+        kb = torch.empty(shape, dtype=torch.uint8, device=self.device)
+        vb = torch.empty(shape, dtype=torch.uint8, device=self.device)
+        if scores is not None:
+            assert tuple(scores.shape) == (self.cfg.batch, self.cfg.n_q_heads, T), "scores must be [B, Hq, T]"
+        _check(self.lib.qaq_select_bits(self.h, _ptr(scores), _ptr(kb), _ptr(vb), _stream()))
+        return kb, vb
+
+    def select_bits_into(self, scores, kb, vb):
+        _check(self.lib.qaq_select_bits(self.h, _ptr(scores), _ptr(kb), _ptr(vb), _stream()))
+
+    def requantize(self, k_bits, v_bits, k_orig=None, v_orig=None):
+        _check(self.lib.qaq_requantize(self.h, _ptr(k_bits), _ptr(v_bits), _ptr(k_orig), _ptr(v_orig), _stream()))
+
+    def decode_attention(self, q, k_new=None, v_new=None, out=None, scores_out=None, want_scores=False, out_fp32=True):
+        """q: fp16 [B, Hq, D]; k_new, v_new: fp16 [B, Hkv, D] or None.
+        Returns (X [B, Hq, D], scores [B, Hq, T(+1)] or None)."""
+        import torch
+        cfg = self.cfg
+        if out is None:
+            out = torch.empty((cfg.batch, cfg.n_q_heads, cfg.head_dim),
+                              dtype=torch.float32 if out_fp32 else torch.float16, device=self.device)
+        if scores_out is None and want_scores:
+            scores_out = torch.empty((cfg.batch, cfg.n_q_heads, self.length() + (k_new is not None)),
+                                     dtype=torch.float32, device=self.device)
+        _check(self.lib.qaq_decode_attention(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                             1 if out.dtype == torch.float32 else 0, _ptr(scores_out), _stream()))
+        return out, scores_out
+
+    def dequantize(self, t0=0, t1=None, want_k=True, want_v=True):
+        import torch
+        cfg = self.cfg
+        t1 = self.length() if t1 is None else t1
+        shape = (cfg.batch, cfg.n_kv_heads, t1 - t0, cfg.head_dim)
+        k = torch.empty(shape, dtype=torch.float16, device=self.device) if want_k else None
+        v = torch.empty(shape, dtype=torch.float16, device=self.device) if want_v else None
+        _check(self.lib.qaq_dequantize(self.h, t0, t1, _ptr(k), _ptr(v), _stream()))
+        return k, v
+
+    # -- observability ---------------------------------------------------------------
+    def export_canonical(self, side: int):
+        """Returns dict(bits, minmax, oidx, oval, codes) of device tensors, by position."""
+        import torch
+        cfg = self.cfg
+        T = self.length()
+        B, H, D, k = cfg.batch, cfg.n_kv_heads, cfg.head_dim, 2 * self.n_o
+        dev = self.device
+        out = dict(
+            bits=torch.empty((B, H, T), dtype=torch.uint8, device=dev),
+            minmax=torch.empty((B, H, T, 2), dtype=torch.float16, device=dev),
+            oidx=torch.empty((B, H, T, max(k, 1)), dtype=torch.uint8, device=dev),
+            oval=torch.empty((B, H, T, max(k, 1)), dtype=torch.float16, device=dev),
+            codes=torch.empty((B, H, T, D), dtype=torch.uint8, device=dev),
+        )
+        _check(self.lib.qaq_export_canonical(self.h, side, _ptr(out["bits"]), _ptr(out["minmax"]),
+                                             _ptr(out["oidx"]) if k else None, _ptr(out["oval"]) if k else None,
+                                             _ptr(out["codes"]), _stream()))
+        if k == 0:
+            out["oidx"] = out["oidx"][..., :0]
+            out["oval"] = out["oval"][..., :0]
+        return out
+
+    def stats(self) -> Stats:
+        st = Stats()
+        _check(self.lib.qaq_stats(self.h, C.byref(st), _stream()))
+        return st
+
+
+def debug_field(side, D, counts, bf, idx, d):
+    """Host-only layout query: (byte offset of the 32-bit word, bit shift, end of regions)."""
+    lib = load()
+    off, sh, end = C.c_uint32(), C.c_int32(), C.c_uint32()
+    n3, n2, n4, n8 = counts
+    _check(lib.qaq_debug_field(side, D, n3, n2, n4, n8, bf, idx, d, C.byref(off), C.byref(sh), C.byref(end)))
+    return off.value, sh.value, end.value

@@ -1,0 +1,62 @@
+"""Helpers shared by the GPU parity tests: run the same seeded inputs through the CPU
+oracle and through libqaq, and compare the layout-independent views."""
+import numpy as np
+
+from oracle import qaq_oracle as O
+from paper_2403_04643_amd import qaq
+
+F16, F32 = np.float16, np.float32
+
+
+def dev(a, dtype=None):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def make_pair(sh, qnorm2, max_tokens=None, **kw):
+    """(oracle cache, GPU cache) with identical hyper-parameters."""
+    qn = np.full(sh.n_kv_heads, qnorm2, F32) if np.isscalar(qnorm2) else np.asarray(qnorm2, F32)
+    okw = dict(window=kw.get("window", 5), sigma_s_max=kw.get("sigma_s_max", 1e-3),
+               sigma_x_max=kw.get("sigma_x_max", 1e-2), outlier_frac=kw.get("outlier_frac", 0.01),
+               n_outlier_per_side=kw.get("n_outlier_per_side", -1), bit_set=tuple(kw.get("bit_set", (2, 3, 4, 8))))
+    ocfg = O.Config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, qnorm2=qn, **okw)
+    gcfg = qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
+                           max_tokens or sh.context, qn.tolist(), **okw)
+    return O.OracleCache(ocfg), qaq.Cache(gcfg)
+
+
+def compare_canonical(oc, gc, what=""):
+    """Bit-exact comparison of widths, [min,max], outlier lists and packed codes."""
+    cfg = oc.cfg
+    D = cfg.head_dim
+    for side, heads in ((0, oc.K), (1, oc.V)):
+        ex = {k: v.cpu().numpy() for k, v in gc.export_canonical(side).items()}
+        for b in range(cfg.batch):
+            for h in range(cfg.n_kv_heads):
+                hc = heads[b][h]
+                tag = f"{what} side={side} b={b} h={h}"
+                np.testing.assert_array_equal(ex["bits"][b, h], hc.bits, err_msg=tag + " bits")
+                # min/max compared by value (the sign of a zero is not part of the contract)
+                np.testing.assert_array_equal(ex["minmax"][b, h, :, 0].astype(F32), hc.mn.astype(F32), err_msg=tag + " min")
+                np.testing.assert_array_equal(ex["minmax"][b, h, :, 1].astype(F32), hc.mx.astype(F32), err_msg=tag + " max")
+                if cfg.n_o():
+                    idx, val = hc.outlier_lists()
+                    np.testing.assert_array_equal(ex["oidx"][b, h], idx, err_msg=tag + " outlier idx")
+                    np.testing.assert_array_equal(ex["oval"][b, h].view(np.uint16), val.view(np.uint16), err_msg=tag + " outlier val")
+                want = np.zeros((hc.T, D), np.uint8)
+                for t in range(hc.T):
+                    p = hc.packed(t)
+                    want[t, : len(p)] = p
+                np.testing.assert_array_equal(ex["codes"][b, h], want, err_msg=tag + " packed codes")
+
+
+def attention_errors(X_gpu, S_gpu, X_ref, S_ref):
+    """Per (b, q-head): max_d |X - X_ref| / max_d |X_ref| and max_t |S - S_ref| / max_t S_ref."""
+    ex = np.abs(X_gpu.astype(np.float64) - X_ref).max(-1) / np.abs(X_ref).max(-1)
+    es = None
+    if S_gpu is not None:
+        es = np.abs(S_gpu.astype(np.float64) - S_ref).max(-1) / S_ref.max(-1)
+    return ex, es

@@ -1,0 +1,295 @@
+"""GPU parity: libqaq (through the C ABI) against the CPU oracle on the same seeded
+inputs.  Widths, packed codes, [min,max] and outlier lists are compared bit for bit;
+attention outputs within 2e-3 (max-norm relative error per head), the tolerance the
+task states for fp32 attention over an exactly matching cache."""
+import numpy as np
+import pytest
+
+from oracle import qaq_oracle as O
+from paper_2403_04643_amd import workloads as W
+from tests.parity_util import F16, F32, attention_errors, compare_canonical, dev, make_pair
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def _rand_bits(rng, shape, p=(0.4, 0.3, 0.2, 0.1)):
+    return rng.choice(np.array([2, 3, 4, 8], np.uint8), size=shape, p=p)
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ quantize / append
+@pytest.mark.parametrize("cfgno,shape_kw,chunks", [
+    (1, dict(), [512]),                                     # config 1 as stated: D=64, two full tiles
+    (2, dict(batch=2, n_q_heads=3, n_kv_heads=3, context=300), [300]),   # D=128, ragged tail
+    (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=531), [100, 1, 199, 1, 230]),  # appends across tiles
+    (5, dict(batch=1, n_q_heads=8, n_kv_heads=2, context=77), [77]),
+])
+def test_quantize_append_matches_oracle(cfgno, shape_kw, chunks):
+    sh = W.shape(cfgno, **shape_kw)
+    _log(f"quantize_append cfg={cfgno} shape={sh} chunks={chunks}")
+    K, V = W.make_kv(cfgno, sh)
+    rng = np.random.default_rng(100 + cfgno)
+    bk = _rand_bits(rng, K.shape[:3]); bv = _rand_bits(rng, K.shape[:3], p=(0.7, 0.1, 0.1, 0.1))
+    oc, gc = make_pair(sh, 0.01)
+    t = 0
+    for n in chunks:
+        sl = slice(t, t + n)
+        oc.append(K[:, :, sl], V[:, :, sl], bk[:, :, sl], bv[:, :, sl])
+        gc.quantize_append(dev(K[:, :, sl]), dev(V[:, :, sl]), dev(bk[:, :, sl]), dev(bv[:, :, sl]))
+        t += n
+    assert gc.length() == sh.context
+    compare_canonical(oc, gc, f"cfg{cfgno}")
+    # dequantize: fp16 rounding of the oracle's fp32 reconstruction, outliers exact
+    Kd, Vd = gc.dequantize()
+    Ko, Vo = oc.dequantize()
+    np.testing.assert_array_equal(Kd.cpu().numpy().view(np.uint16), Ko.astype(F16).view(np.uint16))
+    np.testing.assert_array_equal(Vd.cpu().numpy().view(np.uint16), Vo.astype(F16).view(np.uint16))
+    # a sub-range that starts and ends inside tiles
+    t0, t1 = 5, min(sh.context, 290)
+    Kp, _ = gc.dequantize(t0, t1, want_v=False)
+    np.testing.assert_array_equal(Kp.cpu().numpy().view(np.uint16), Ko[:, :, t0:t1].astype(F16).view(np.uint16))
+    st = gc.stats()
+    assert st.code_bytes == oc.code_bytes()
+    assert st.tokens == sh.context and st.fp16_bytes == K.size * 4
+    assert st.layout_code_bytes >= st.code_bytes
+
+
+def test_default_width_and_outlier_variants():
+    sh = W.shape(1, context=70)
+    K, V = W.make_kv(1, sh)
+    for kw in (dict(outlier_frac=0.0), dict(n_outlier_per_side=2), dict(n_outlier_per_side=4), dict(bit_set=(2, 4))):
+        _log(f"variant {kw}")
+        oc, gc = make_pair(sh, 0.02, **kw)
+        oc.append(K, V)                      # widths None -> widest of the set
+        gc.quantize_append(dev(K), dev(V))
+        compare_canonical(oc, gc, str(kw))
+        assert int(gc.export_canonical(0)["bits"].max()) == max(kw.get("bit_set", (8,)))
+
+
+def test_degenerate_tokens():
+    """All-equal vectors (range 0), ties between outlier candidates, a single token."""
+    sh = W.shape(1, batch=1, n_q_heads=2, n_kv_heads=2, context=9)
+    rng = np.random.default_rng(5)
+    K = rng.integers(-1, 2, size=(1, 2, 9, 64)).astype(F16)
+    K[0, 0, 0] = 2.5
+    K[0, 1, 3] = 0.0
+    K[0, 1, 4, ::2] = -0.0
+    V = np.round(rng.standard_normal((1, 2, 9, 64)) * 2).astype(F16)
+    bits = _rand_bits(rng, (1, 2, 9))
+    oc, gc = make_pair(sh, 0.02)
+    oc.append(K[:, :, :1], V[:, :, :1], bits[:, :, :1], bits[:, :, :1])
+    gc.quantize_append(dev(K[:, :, :1]), dev(V[:, :, :1]), dev(bits[:, :, :1]), dev(bits[:, :, :1]))
+    compare_canonical(oc, gc, "T=1")
+    q = W.make_queries(1, sh)[0]
+    X, S = gc.decode_attention(dev(q), want_scores=True)
+    Xo, So = oc.decode_attention(q)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    assert ex.max() < TOL and es.max() < TOL
+    oc.append(K[:, :, 1:], V[:, :, 1:], bits[:, :, 1:], bits[:, :, 1:])
+    gc.quantize_append(dev(K[:, :, 1:]), dev(V[:, :, 1:]), dev(bits[:, :, 1:]), dev(bits[:, :, 1:]))
+    compare_canonical(oc, gc, "degenerate")
+    X, S = gc.decode_attention(dev(q), want_scores=True)
+    Xo, So = oc.decode_attention(q)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    assert ex.max() < TOL and es.max() < TOL
+
+
+def test_capacity_and_argument_errors():
+    from paper_2403_04643_amd import qaq
+    sh = W.shape(1, context=300)
+    K, V = W.make_kv(1, sh)
+    _, gc = make_pair(sh, 0.02, max_tokens=256)
+    gc.quantize_append(dev(K[:, :, :200]), dev(V[:, :, :200]))
+    with pytest.raises(qaq.QaqError) as e:
+        gc.quantize_append(dev(K[:, :, 200:]), dev(V[:, :, 200:]))
+    assert e.value.code == qaq.ERR_CAPACITY and gc.length() == 200
+    with pytest.raises(qaq.QaqError):
+        gc.dequantize(0, 201)
+    q = W.make_queries(1, sh)[0]
+    with pytest.raises(qaq.QaqError):
+        gc.decode_attention(dev(q), k_new=dev(K[:, :, 0]), v_new=None)
+    gc.reset()
+    assert gc.length() == 0
+    with pytest.raises(qaq.QaqError):
+        gc.decode_attention(dev(q))
+
+
+# ------------------------------------------------------------------------ select bits
+@pytest.mark.parametrize("cfgno,shape_kw,window", [
+    (1, dict(), 1),
+    (2, dict(batch=2, n_q_heads=4, n_kv_heads=4, context=700), 5),
+    (5, dict(batch=2, n_q_heads=16, n_kv_heads=2, context=300), 3),     # grouped queries
+])
+def test_select_bits_matches_oracle(cfgno, shape_kw, window):
+    sh = W.shape(cfgno, **shape_kw)
+    _log(f"select_bits cfg={cfgno} shape={sh} window={window}")
+    K, V = W.make_kv(cfgno, sh)
+    qn = np.linspace(0.005, 0.02, sh.n_kv_heads).astype(F32)   # the ABI carries qnorm2 as fp32
+    oc, gc = make_pair(sh, qn, max_tokens=sh.context + 8, window=window, sigma_s_max=3e-4, sigma_x_max=0.01)
+    T0 = sh.context - 4
+    oc.append(K[:, :, :T0], V[:, :, :T0]); gc.quantize_append(dev(K[:, :, :T0]), dev(V[:, :, :T0]))
+    # thresholds agree with the oracle's double-precision formulas rounded once
+    tau, cv = gc.thresholds(T0)
+    assert cv == float(O.value_threshold(T0, 0.01))
+    assert tau == [float(O.key_threshold(T0, 3e-4, float(qn[h]))) for h in range(sh.n_kv_heads)]
+    seen = set()
+    for step in range(window + 2):             # more rows than the window holds; T grows meanwhile
+        T = oc.T
+        S = W.random_score_rows(sh, T, 1, seed=step, peaky=3.0)[0]
+        oc.observe(S)
+        bk_o, bv_o = oc.select_bits()
+        bk_g, bv_g = gc.select_bits(dev(S))
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o, err_msg=f"K bits step {step}")
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o, err_msg=f"V bits step {step}")
+        seen |= set(np.unique(bv_o).tolist())
+        # scores NULL: the window as it is gives the same answer again
+        bk2, bv2 = gc.select_bits(None)
+        np.testing.assert_array_equal(bv2.cpu().numpy(), bv_o)
+        if step < 4:
+            sl = slice(T, T + 1)
+            oc.append(K[:, :, sl], V[:, :, sl]); gc.quantize_append(dev(K[:, :, sl]), dev(V[:, :, sl]))
+    assert len(seen) >= 3, seen
+
+
+# ------------------------------------------------------------------------- requantize
+def test_requantize_matches_oracle():
+    sh = W.shape(2, batch=2, n_q_heads=3, n_kv_heads=3, context=600)
+    K, V = W.make_kv(2, sh)
+    rng = np.random.default_rng(7)
+    oc, gc = make_pair(sh, 0.01)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    # narrow everything (8 -> mixed), no originals needed
+    b1k, b1v = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3], p=(0.6, 0.2, 0.1, 0.1))
+    oc.requantize(b1k, b1v); gc.requantize(dev(b1k), dev(b1v))
+    compare_canonical(oc, gc, "narrow")
+    assert oc.refused == 0 and gc.stats().refused_upgrades == 0
+    # equals direct quantization of the originals at those widths
+    ref, _ = make_pair(sh, 0.01)
+    ref.append(K, V, b1k, b1v)
+    for b in range(sh.batch):
+        for h in range(sh.n_kv_heads):
+            np.testing.assert_array_equal(ref.K[b][h].codes, oc.K[b][h].codes)
+    # mixed moves without the unquantized copy: widenings are refused and counted
+    b2k, b2v = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3])
+    oc.requantize(b2k, b2v); gc.requantize(dev(b2k), dev(b2v))
+    compare_canonical(oc, gc, "mixed, no originals")
+    assert gc.stats().refused_upgrades == oc.refused > 0
+    # with the copy: every token reaches the requested width
+    b3k, b3v = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3])
+    oc.requantize(b3k, b3v, K, V); gc.requantize(dev(b3k), dev(b3v), dev(K), dev(V))
+    compare_canonical(oc, gc, "mixed, with originals")
+    np.testing.assert_array_equal(gc.export_canonical(1)["bits"].cpu().numpy(), b3v)
+    # one side only
+    b4v = _rand_bits(rng, K.shape[:3], p=(0.9, 0.1, 0.0, 0.0))
+    oc.requantize(oc_bits(oc, 0), b4v); gc.requantize(None, dev(b4v))
+    compare_canonical(oc, gc, "values only")
+
+
+def oc_bits(oc, side):
+    heads = oc.K if side == 0 else oc.V
+    return np.stack([np.stack([hc.bits for hc in row]) for row in heads])
+
+
+# ------------------------------------------------------------------- decode attention
+@pytest.mark.parametrize("cfgno,shape_kw,p_bits", [
+    (1, dict(), (0.4, 0.3, 0.2, 0.1)),
+    (1, dict(), (1.0, 0.0, 0.0, 0.0)),
+    (2, dict(batch=2, n_q_heads=4, n_kv_heads=4, context=1000), (0.5, 0.3, 0.15, 0.05)),
+    (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=257), (0.0, 0.0, 0.0, 1.0)),
+    (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=256), (0.0, 1.0, 0.0, 0.0)),
+    (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=40), (0.0, 0.0, 1.0, 0.0)),
+    (5, dict(batch=2, n_q_heads=16, n_kv_heads=2, context=333), (0.4, 0.3, 0.2, 0.1)),
+])
+def test_decode_attention_matches_oracle(cfgno, shape_kw, p_bits):
+    sh = W.shape(cfgno, **shape_kw)
+    _log(f"decode_attention cfg={cfgno} shape={sh} p={p_bits}")
+    K, V = W.make_kv(cfgno, sh)
+    rng = np.random.default_rng(31 + cfgno)
+    bk, bv = _rand_bits(rng, K.shape[:3], p_bits), _rand_bits(rng, K.shape[:3], p_bits)
+    oc, gc = make_pair(sh, 0.01)
+    oc.append(K, V, bk, bv); gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    qs = W.make_queries(cfgno, sh, n=2)
+    kn, vn = W.make_new_token(cfgno, sh)
+    # cache only
+    X, S = gc.decode_attention(dev(qs[0]), want_scores=True)
+    Xo, So = oc.decode_attention(qs[0])
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    _log(f"  cache only: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+    assert ex.max() < TOL and es.max() < TOL
+    np.testing.assert_allclose(S.cpu().numpy().sum(-1), 1.0, rtol=1e-5)
+    # with the unquantized new token, fp16 output, no scores
+    X, S = gc.decode_attention(dev(qs[1]), dev(kn), dev(vn), want_scores=True)
+    Xo, So = oc.decode_attention(qs[1], kn, vn)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    _log(f"  with new token: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+    assert ex.max() < TOL and es.max() < TOL
+    assert S.shape[-1] == sh.context + 1
+    Xh, none = gc.decode_attention(dev(qs[1]), dev(kn), dev(vn), out_fp32=False)
+    assert none is None
+    exh, _ = attention_errors(Xh.float().cpu().numpy(), None, Xo, None)
+    assert exh.max() < TOL + 1e-3        # plus fp16 rounding of the output
+
+
+def test_attention_with_peaked_scores():
+    """A query aligned with one key: the softmax is dominated by a single token."""
+    sh = W.shape(2, batch=1, n_q_heads=4, n_kv_heads=4, context=600)
+    K, V = W.make_kv(2, sh)
+    rng = np.random.default_rng(3)
+    bk, bv = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3])
+    oc, gc = make_pair(sh, 0.01)
+    oc.append(K, V, bk, bv); gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = (K[:, :, 321, :].astype(F32) * 0.5).astype(F16)
+    X, S = gc.decode_attention(dev(q), want_scores=True)
+    Xo, So = oc.decode_attention(q)
+    assert So.max() > 0.5
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    assert ex.max() < TOL and es.max() < TOL
+    # all-zero query: uniform scores, X = mean of the reconstructed values
+    q0 = np.zeros_like(q)
+    X, S = gc.decode_attention(dev(q0), want_scores=True)
+    Xo, So = oc.decode_attention(q0)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    assert ex.max() < TOL and es.max() < TOL
+
+
+# ------------------------------------------------------- the per-step procedure, chained
+def test_decode_steps_chain():
+    """Config 3's loop at reduced size: attention with the new token, append, observe the
+    scores, select widths, requantize (with the unquantized copy) -- the oracle follows the
+    GPU's emitted scores for width selection (they are an input of that step), while those
+    scores themselves are checked against the oracle's."""
+    sh = W.shape(3, batch=2, n_q_heads=4, n_kv_heads=4, context=500)
+    steps = 8
+    K, V = W.make_kv(3, sh)
+    qcal = W.make_queries(3, sh, n=64, seed_offset=9)
+    qn = O.query_norm_statistic(qcal, sh.head_dim)
+    oc, gc = make_pair(sh, qn, max_tokens=sh.context + steps, window=3, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    widths = set()
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Xo, So = oc.decode_attention(qs[s], kn, vn)
+        ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+        _log(f"  step {s}: T={oc.T} err X {ex.max():.2e} S {es.max():.2e} ratio_codes {oc.ratio_codes():.2f}")
+        assert ex.max() < TOL and es.max() < TOL
+        oc.append(kn[:, :, None], vn[:, :, None]); gc.quantize_append(dev(kn[:, :, None]), dev(vn[:, :, None]))
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        Sg = S.cpu().numpy()
+        oc.observe(Sg)
+        bk_o, bv_o = oc.select_bits()
+        bk_g, bv_g = gc.select_bits(S)
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+        oc.requantize(bk_o, bv_o, Korig, Vorig)
+        gc.requantize(bk_g, bv_g, dev(Korig), dev(Vorig))
+        widths |= set(np.unique(bv_o).tolist()) | set(np.unique(bk_o).tolist())
+    compare_canonical(oc, gc, "after chain")
+    assert len(widths) >= 3
+    assert oc.ratio_codes() > 2.0

@@ -1,0 +1,94 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header
+declares, rejects bad arguments, and its code layout is a bijection."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2403_04643_amd import qaq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "qaq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qaq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = qaq.load()
+    names = _declared()
+    assert {"qaq_select_bits", "qaq_quantize_append", "qaq_requantize", "qaq_decode_attention",
+            "qaq_dequantize"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+        assert n in qaq.SIGNATURES, f"binding lacks {n}"
+    assert sorted(qaq.SIGNATURES) == names
+
+
+def test_config_validation_without_gpu():
+    lib = qaq.load()
+    good = qaq.make_config(2, 8, 8, 128, 1000, [0.01] * 8)
+    n = lib.qaq_arena_bytes(C.byref(good))
+    assert n > 2 * 2 * 8 * 1024 * 128          # at least the 8-bit codes of K and V
+    assert lib.qaq_outliers_per_side(C.byref(good)) == 1
+    for kw in (dict(head_dim=96), dict(bit_set=(2, 5)), dict(bit_set=(3, 2)), dict(window=0),
+               dict(n_outlier_per_side=5), dict(sigma_s_max=0.0), dict(n_q_heads=7)):
+        args = dict(batch=2, n_q_heads=8, n_kv_heads=8, head_dim=128, max_tokens=1000, qnorm2=[0.01] * 8)
+        args.update(kw)
+        bad = qaq.make_config(**args)
+        assert lib.qaq_arena_bytes(C.byref(bad)) == 0
+        assert lib.qaq_last_error()
+    h = C.c_void_p()
+    assert lib.qaq_create(C.byref(good), None, n, C.byref(h)) == qaq.ERR_INVALID_ARG
+    assert lib.qaq_create(C.byref(good), 256, n - 1, C.byref(h)) == qaq.ERR_CAPACITY
+    assert lib.qaq_create(C.byref(good), 257, n, C.byref(h)) == qaq.ERR_INVALID_ARG
+    assert lib.qaq_reset(None) == qaq.ERR_INVALID_ARG
+    assert b"NULL" in lib.qaq_last_error()
+    no_out = qaq.make_config(1, 4, 4, 64, 10, [1.0] * 4, outlier_frac=0.0)
+    assert lib.qaq_outliers_per_side(C.byref(no_out)) == 0
+    four = qaq.make_config(1, 4, 4, 128, 10, [1.0] * 4, outlier_frac=0.05)
+    assert lib.qaq_outliers_per_side(C.byref(four)) == 4
+
+
+@pytest.mark.parametrize("side", [0, 1])
+@pytest.mark.parametrize("D", [64, 128])
+def test_layout_is_a_bijection(side, D):
+    """Every code bit of every token lands on its own bit of the tile image, inside the
+    region bounds and the reserved capacity; the image has no other holes than the
+    documented padding."""
+    rng = np.random.default_rng(D + side)
+    cap = qaq.load().qaq_debug_tile_capacity(side, D)
+    cases = [(256, 0, 0, 0), (0, 256, 0, 0), (0, 0, 256, 0), (0, 0, 0, 256), (1, 1, 1, 1), (17, 9, 3, 33)]
+    for _ in range(4):
+        cut = np.sort(rng.integers(0, 257, 3))
+        cases.append((cut[0], cut[1] - cut[0], cut[2] - cut[1], 256 - cut[2]))
+    for n3, n2, n4, n8 in cases:
+        counts = (int(n3), int(n2), int(n4), int(n8))
+        used = np.zeros(cap * 8, dtype=np.uint8)
+        end = None
+        def mark(bf, idx, width_mask_bits):
+            nonlocal end
+            for d in range(D):
+                off, sh, end = qaq.debug_field(side, D, counts, bf, idx, d)
+                assert off % 4 == 0 and sh + width_mask_bits <= 32
+                lo = off * 8 + sh
+                assert lo + width_mask_bits <= end * 8 <= cap * 8
+                assert not used[lo:lo + width_mask_bits].any(), (counts, bf, idx, d)
+                used[lo:lo + width_mask_bits] = 1
+        for s in range(n3 + n2):
+            mark(2, s, 2)
+        for s in range(n3):
+            mark(1, s, 1)
+        for s in range(n4):
+            mark(4, s, 4)
+        for s in range(n8):
+            mark(8, s, 8)
+        total_bits = D * (3 * n3 + 2 * n2 + 4 * n4 + 8 * n8)
+        assert used.sum() == total_bits
+        if end is not None:
+            pad = end * 8 - total_bits
+            assert pad <= 8 * (12 * D)       # at most one partial unit per region
