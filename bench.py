@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the QAQ hot path on one MI355X.
+
+Workload: benchmark configs[1] -- one LLaMA-7B layer (batch 8, 32 heads, head
+dim 128, context 4096, fp16 K/V with per-channel scale and heavy-tailed channels),
+held as `--layers` independent cache instances that the timed steps rotate over so
+that the packed caches (together several times the 256 MB last-level cache) are
+streamed from HBM.  One step = one pass of the whole per-token procedure of the
+paper's Section 4.2: decode attention over the quantized cache plus the unquantized
+new token, append of that token, width selection from the emitted scores, and
+requantization (with the unquantized copies resident in HBM).
+
+Prints ONE JSON line.  `value` is the decode-attention rate: algorithmic bytes of a
+qaq_decode_attention call over its measured duration (HIP events recorded by the
+library on the launch stream around its kernels inside the timed steps).
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+OPERATING_POINTS = {"A": (2.5, 2.1), "B": (4.0, 3.0)}   # target mean key / value widths
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--layers", type=int, default=4, help="independent cache instances rotated over")
+    ap.add_argument("--op", choices=sorted(OPERATING_POINTS), default="A")
+    ap.add_argument("--context", type=int, default=None, help="override the context length (debugging)")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def calibrate(cache, target_k, target_v, torch):
+    """Bisect the two hyper-parameters of the bit rules (the paper sweeps them, it prints
+    no values) until the mean widths of this cache hit the operating point."""
+    def mean_bits(ss, sx):
+        cache.set_sigmas(ss, sx)
+        kb, vb = cache.select_bits(None)
+        return float(kb.float().mean()), float(vb.float().mean())
+    lo, hi = 1e-9, 1e2
+    for _ in range(40):
+        mid = (lo * hi) ** 0.5
+        mk, _ = mean_bits(mid, 1.0)
+        if mk > target_k: lo = mid
+        else: hi = mid
+    ss = (lo * hi) ** 0.5
+    lo, hi = 1e-9, 1e4
+    for _ in range(40):
+        mid = (lo * hi) ** 0.5
+        _, mv = mean_bits(ss, mid)
+        if mv > target_v: lo = mid
+        else: hi = mid
+    sx = (lo * hi) ** 0.5
+    return ss, sx
+
+
+def algorithmic_bytes(st, sh, n_o, T_scores):
+    """Bytes one qaq_decode_attention call has to move: per token-head D*(bK+bV)/8 code
+    bytes + 8 (fp16 min,max of K and V) + 2 (order / width byte per side) + 12*n_o (side
+    store), plus query, output, emitted scores and the new token."""
+    th = sh.batch * sh.n_kv_heads * st.tokens
+    cache = st.code_bytes + th * (8 + 2 + 12 * n_o)
+    io = sh.batch * sh.n_q_heads * sh.head_dim * (2 + 4) + sh.batch * sh.n_q_heads * T_scores * 4 \
+        + sh.batch * sh.n_kv_heads * sh.head_dim * 4
+    return cache, io
+
+
+def cpu_baseline(sh, hist_k, hist_v, qn, n_o):
+    """The CPU oracle's decode attention on a bounded sample of the same workload:
+    sequence 0 of layer 0 (all KV heads, full context), widths drawn i.i.d. with the
+    GPU run's width histogram.  One thread."""
+    from threadpoolctl import threadpool_limits
+    from oracle import qaq_oracle as O
+    from paper_2403_04643_amd import workloads as W
+    s1 = W.shape(2, batch=1, context=sh.context, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads)
+    K, V = W.make_kv(2, s1)
+    rng = np.random.default_rng(99)
+    widths = np.array([2, 3, 4, 8], np.uint8)
+    bk = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_k) / np.sum(hist_k))
+    bv = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_v) / np.sum(hist_v))
+    oc = O.OracleCache(O.Config(1, s1.n_q_heads, s1.n_kv_heads, s1.head_dim, qnorm2=qn))
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        oc.append(K, V, bk, bv)
+        t_quant = time.perf_counter() - t0
+        q = W.make_queries(2, s1)[0]
+        kn, vn = W.make_new_token(2, s1)
+        t0 = time.perf_counter()
+        oc.decode_attention(q, kn, vn)
+        t_attn = time.perf_counter() - t0
+    th = s1.n_kv_heads * s1.context
+    nbytes = oc.code_bytes() + th * (8 + 2 + 12 * n_o)
+    return {
+        "value": nbytes / t_attn / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"decode attention of sequence 0 (1 of {sh.batch}), all {s1.n_kv_heads} heads, context {s1.context}, "
+                  f"widths i.i.d. with the GPU run's histogram; {t_attn:.2f} s",
+        "tokens_quantized_per_s": s1.context / t_quant,
+        "us_per_call_scaled_to_full_batch": t_attn * sh.batch * 1e6,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (every (sequence, KV head) "
+              "is independent, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2403_04643_amd import qaq, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    kw = {}
+    if args.context: kw["context"] = args.context
+    if args.batch: kw["batch"] = args.batch
+    sh = W.shape(2, **kw)
+    L, steps, warm = args.layers, args.steps, args.warmup
+    total_steps = steps + warm
+    per_layer = (total_steps + L - 1) // L
+    Tcap = sh.context + per_layer + 1
+    B, Hq, Hkv, D, T0 = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+
+    qcal = W.make_queries(2, sh, n=max(1, 1024 // (B * Hq)), seed_offset=7).astype(np.float64)
+    qn = np.full(Hkv, float(np.quantile((qcal ** 2).sum(-1).reshape(-1), 0.9)) / D, np.float32)
+    tk, tv = OPERATING_POINTS[args.op]
+
+    caches, origK, origV = [], [], []
+    prefill_ms = []
+    lib = qaq.load()
+    for l in range(L):
+        K, V = W.make_kv(2, sh, seed_offset=l)
+        Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+        oK = torch.zeros((B, Hkv, Tcap, D), dtype=torch.float16, device="cuda")
+        oV = torch.zeros((B, Hkv, Tcap, D), dtype=torch.float16, device="cuda")
+        oK[:, :, :T0] = Kd; oV[:, :, :T0] = Vd
+        c = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=5))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if l == 0:   # untimed first touch of the kernel
+            c.quantize_append(Kd, Vd); c.reset()
+        e0.record(); c.quantize_append(Kd, Vd); e1.record(); torch.cuda.synchronize()
+        prefill_ms.append(e0.elapsed_time(e1))
+        caches.append(c); origK.append(oK); origV.append(oV)
+        del K, V, Kd, Vd
+    # attention window: five score rows from five seeded queries
+    hq = W.make_queries(2, sh, n=5, seed_offset=3)
+    for c in caches:
+        for i in range(5):
+            _, S = c.decode_attention(torch.from_numpy(hq[i]).cuda(), want_scores=True)
+            c.select_bits(S)
+    ss, sx = calibrate(caches[0], tk, tv, torch)
+    for c in caches:
+        c.set_sigmas(ss, sx)
+        kb, vb = c.select_bits(None)
+        c.requantize(kb, vb)
+    torch.cuda.synchronize()
+    st0 = [c.stats() for c in caches]
+
+    # inputs of the timed steps, resident in HBM before timing starts
+    qs = torch.from_numpy(W.make_queries(2, sh, n=total_steps, seed_offset=1)).cuda()
+    newk, newv = [], []
+    for l in range(L):
+        ks, vs = [], []
+        for j in range(per_layer):
+            kn, vn = W.make_new_token(2, sh, step=1000 * l + j)
+            ks.append(kn); vs.append(vn)
+        nk = torch.from_numpy(np.stack(ks)).cuda(); nv = torch.from_numpy(np.stack(vs)).cuda()
+        origK[l][:, :, T0:T0 + per_layer] = nk.permute(1, 2, 0, 3); origV[l][:, :, T0:T0 + per_layer] = nv.permute(1, 2, 0, 3)
+        newk.append(nk); newv.append(nv)
+    out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
+    scores = torch.empty(B * Hq * (Tcap + 1), dtype=torch.float32, device="cuda")
+    kbits = torch.empty(B * Hkv * Tcap, dtype=torch.uint8, device="cuda")
+    vbits = torch.empty(B * Hkv * Tcap, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    P = lambda t: C.c_void_p(t.data_ptr())
+
+    def step(i):
+        l, j = i % L, i // L
+        c = caches[l]
+        rc = lib.qaq_decode_attention(c.h, P(qs[i]), P(newk[l][j]), P(newv[l][j]), P(out), 1, P(scores), stream)
+        rc |= lib.qaq_quantize_append(c.h, P(newk[l][j]), P(newv[l][j]), 1, None, None, stream)
+        rc |= lib.qaq_select_bits(c.h, P(scores), P(kbits), P(vbits), stream)
+        rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(origK[l]), P(origV[l]), Tcap, stream)
+        assert rc == 0, lib.qaq_last_error()
+
+    for i in range(warm):
+        step(i)
+    torch.cuda.synchronize()
+    for c in caches:
+        c.profile_begin(per_layer + 1)
+    t0 = time.perf_counter()
+    for i in range(warm, total_steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_main, ms_merge = [], []
+    for c in caches:
+        a, b = c.profile_read()
+        ms_main += a; ms_merge += b
+        c.profile_begin(0)
+    st1 = [c.stats() for c in caches]
+    n_o = caches[0].n_o
+    cache_b, io_b = [], []
+    for s0, s1 in zip(st0, st1):
+        for s in (s0, s1):
+            cb, ib = algorithmic_bytes(s, sh, n_o, s.tokens + 1)
+            cache_b.append(cb); io_b.append(ib)
+    bytes_call = float(np.mean(cache_b) + np.mean(io_b))
+    us_main, us_merge = 1e3 * float(np.mean(ms_main)), 1e3 * float(np.mean(ms_merge))
+    gbs_call = bytes_call / ((us_main + us_merge) * 1e-6) / 1e9
+    gbs_main = (float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * T0 * 4) / (us_main * 1e-6) / 1e9
+    s = st1[0]
+    th = B * Hkv * s.tokens
+    mean_k = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_k)) / th
+    mean_v = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_v)) / th
+    tokens_per_s = B * T0 / (float(np.mean(prefill_ms[1:] or prefill_ms)) * 1e-3)
+
+    rec = {
+        "metric": "quantized-KV decode attention HBM GB/s (% of peak) + tokens quantized/s",
+        "value": gbs_call, "unit": "GB/s", "pct_of_hbm_peak": 100.0 * gbs_call / HBM_PEAK_GBS,
+        "tokens_quantized_per_s": tokens_per_s,
+        "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8 codes x fixed-point q/w (int32 accumulate), fp32 softmax",
+        "data": "synthetic",
+        "config": {"workload": f"configs[1]: LLaMA-7B layer, batch {B}, {Hq} heads, head_dim {D}, context {T0}, "
+                               f"operating point {args.op} (mean widths K {mean_k:.2f} / V {mean_v:.2f}), "
+                               f"{L} cache instances rotated", "op": args.op, "layers": L},
+        "us_per_attention_call": us_main + us_merge, "us_tile_kernel": us_main, "us_merge_kernel": us_merge,
+        "algorithmic_bytes_per_call": bytes_call,
+        "sigma_s_max": ss, "sigma_x_max": sx,
+        "hist_k": list(s.hist_k), "hist_v": list(s.hist_v),
+        "ratio_codes": s.fp16_bytes / s.code_bytes, "ratio_all": s.fp16_bytes / (s.code_bytes + th * (10 + 12 * n_o)),
+        "layout_code_bytes_over_code_bytes": s.layout_code_bytes / s.code_bytes,
+        "refused_upgrades": int(sum(x.refused_upgrades for x in st1)),
+        "roofline": {"bound": "hbm", "kernel": "k_attn_partial", "achieved": gbs_main, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs_main / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(sh, s.hist_k, s.hist_v, qn, n_o)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,10 +127,13 @@ int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits,
  * the requested width.  Narrowing drops low code bits in place.  Widening re-encodes
  * from the caller's unquantized copy with the stored [min,max] and outlier set.
  *   dev_k_bits, dev_v_bits  uint8 [B, Hkv, T] (either may be NULL = leave that side)
- *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, T, D] unquantized copies, or NULL: tokens
- *                           asked to widen then keep their width and are counted. */
+ *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, orig_tokens, D] unquantized copies (the first T
+ *                           rows of each head are used; orig_tokens >= T lets the caller
+ *                           keep them in a buffer sized for the whole generation), or
+ *                           NULL: tokens asked to widen keep their width and are counted. */
 int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v_bits,
-                   const void* dev_k_orig, const void* dev_v_orig, void* stream);
+                   const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
+                   void* stream);
 
 /* Section 2.1 attention over the quantized cache for one new query per head:
  * S = softmax(q K^^T / sqrt(D)), X = S V^, with K^, V^ the midpoint reconstruction and
@@ -167,6 +170,13 @@ int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* de
 
 /* Width histogram and byte accounting.  Runs a small kernel on `stream` and waits. */
 int qaq_stats(qaq_cache* c, qaq_stats_t* host_out, void* stream);
+
+/* Measurement aid: after qaq_profile_begin(c, n), the next n qaq_decode_attention calls
+ * record HIP events on their stream before, between and after their two kernels (the
+ * per-tile kernel and the merge).  qaq_profile_read waits for them and returns the
+ * elapsed milliseconds of each; host arrays of at least n floats.  n = 0 switches it off. */
+int qaq_profile_begin(qaq_cache* c, int32_t max_calls);
+int qaq_profile_read(qaq_cache* c, float* host_ms_main, float* host_ms_merge, int32_t* n_calls);
 
 /* Number of outliers kept per end of a token vector for this configuration. */
 int qaq_outliers_per_side(const qaq_config* cfg);

@@ -19,6 +19,8 @@ struct qaq_cache {
   int ring_next;                   // ring row that the next score row goes to
   int row_len[QAQ_MAX_WINDOW];     // tokens covered by each ring row (0 = empty)
   double sigma_s, sigma_x;
+  std::vector<hipEvent_t> prof_ev;  // 3 events per profiled attention call
+  int prof_n;
 };
 
 namespace {
@@ -119,6 +121,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   std::memset(c->row_len, 0, sizeof(c->row_len));
   c->sigma_s = cfg->sigma_s_max;
   c->sigma_x = cfg->sigma_x_max;
+  c->prof_n = 0;
   uint8_t* base = (uint8_t*)dev_arena;
   QaqView& v = c->view;
   for (int s = 0; s < 2; ++s) {
@@ -145,6 +148,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
 }
 
 int qaq_destroy(qaq_cache* c) {
+  if (c) for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   delete c;
   return QAQ_OK;
 }
@@ -230,8 +234,10 @@ int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits, 
 }
 
 int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v_bits,
-                   const void* dev_k_orig, const void* dev_v_orig, void* stream) {
+                   const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens, void* stream) {
   if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if ((dev_k_orig || dev_v_orig) && orig_tokens < c->len)
+    return fail(QAQ_ERR_INVALID_ARG, "unquantized copies hold %d tokens, cache has %d", orig_tokens, c->len);
   if (c->len == 0 || (!dev_k_bits && !dev_v_bits)) return QAQ_OK;
   if (((uintptr_t)dev_k_orig & 15) || ((uintptr_t)dev_v_orig & 15)) return fail(QAQ_ERR_INVALID_ARG, "originals must be 16-byte aligned");
   QaqBuildArgs a;
@@ -243,6 +249,7 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
   a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
   a.newbits[0] = dev_k_bits; a.newbits[1] = dev_v_bits;
   a.orig[0] = (const __half*)dev_k_orig; a.orig[1] = (const __half*)dev_v_orig;
+  a.orig_tokens = orig_tokens;
   hipError_t e = qaq_launch_build(a, (c->len + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_requantize");
   return QAQ_OK;
@@ -265,8 +272,37 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
   a.out_is_fp32 = out_is_fp32;
   a.scores = dev_scores_out;
   a.score_stride = c->len + (dev_k_new ? 1 : 0);
-  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream);
+  hipEvent_t* ev = nullptr;
+  if (!c->prof_ev.empty() && (size_t)(3 * c->prof_n + 3) <= c->prof_ev.size()) ev = &c->prof_ev[3 * c->prof_n++];
+  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev);
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
+  return QAQ_OK;
+}
+
+int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
+  if (!c || max_calls < 0 || max_calls > 4096) return fail(QAQ_ERR_INVALID_ARG, "bad profile request");
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  c->prof_ev.clear();
+  c->prof_n = 0;
+  for (int i = 0; i < 3 * max_calls; ++i) {
+    hipEvent_t e;
+    hipError_t r = hipEventCreate(&e);
+    if (r != hipSuccess) return hip_fail(r, "qaq_profile_begin");
+    c->prof_ev.push_back(e);
+  }
+  return QAQ_OK;
+}
+
+int qaq_profile_read(qaq_cache* c, float* host_ms_main, float* host_ms_merge, int32_t* n_calls) {
+  if (!c || !host_ms_main || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  *n_calls = c->prof_n;
+  for (int i = 0; i < c->prof_n; ++i) {
+    hipError_t r = hipEventSynchronize(c->prof_ev[3 * i + 2]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_main[i], c->prof_ev[3 * i], c->prof_ev[3 * i + 1]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[3 * i + 1], c->prof_ev[3 * i + 2]);
+    if (r != hipSuccess) return hip_fail(r, "qaq_profile_read");
+  }
+  c->prof_n = 0;
   return QAQ_OK;
 }
 

@@ -471,15 +471,17 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
 
 }  // namespace
 
-hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s) {
+hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev) {
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
-  if (a.v.D == 128) {
-    if (ntile > 0) hipLaunchKernelGGL(k_attn_partial<128>, dim3(ntile, BQ), dim3(kThreads), 0, s, a);
-    hipLaunchKernelGGL(k_attn_combine<128>, dim3(BQ), dim3(kThreads), 0, s, a);
-  } else {
-    if (ntile > 0) hipLaunchKernelGGL(k_attn_partial<64>, dim3(ntile, BQ), dim3(kThreads), 0, s, a);
-    hipLaunchKernelGGL(k_attn_combine<64>, dim3(BQ), dim3(kThreads), 0, s, a);
+  if (ev) (void)hipEventRecord(ev[0], s);
+  if (ntile > 0) {
+    if (a.v.D == 128) hipLaunchKernelGGL(k_attn_partial<128>, dim3(ntile, BQ), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL(k_attn_partial<64>, dim3(ntile, BQ), dim3(kThreads), 0, s, a);
   }
+  if (ev) (void)hipEventRecord(ev[1], s);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_attn_combine<128>, dim3(BQ), dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(k_attn_combine<64>, dim3(BQ), dim3(kThreads), 0, s, a);
+  if (ev) (void)hipEventRecord(ev[2], s);
   return hipGetLastError();
 }

@@ -47,7 +47,8 @@ struct QaqBuildArgs {
   int len_before, len_after, tile0, n_new, widest;
   const __half* newx[2];       // append: [B,Hkv,n_new,D]
   const uint8_t* newbits[2];   // append: [B,Hkv,n_new] or null; requantize: [B,Hkv,len] or null
-  const __half* orig[2];       // requantize: [B,Hkv,len,D] or null
+  const __half* orig[2];       // requantize: [B,Hkv,orig_tokens,D] or null
+  int orig_tokens;             // token extent of the unquantized copies (>= len)
 };
 
 struct QaqSelectArgs {
@@ -96,7 +97,8 @@ struct QaqDequantArgs {
 hipError_t qaq_launch_init(const QaqView& v, hipStream_t s);
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
 hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
-hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s);
+// ev: NULL, or three events recorded before, between and after the two kernels
+hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev);
 hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
 hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);
 hipError_t qaq_launch_stats(const QaqView& v, int len, hipStream_t s);

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       const bool widen = !fresh && L.bits_new[p] > L.bits_old[p];
       if (!fresh && !widen) continue;
       const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
-                                : a.orig[side] + ((size_t)bh * a.len_before + (t0 + p)) * D;
+                                : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
       encode_token<D>(src, gl, fresh, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], L.stage[p]);
     }
   }

@@ -50,7 +50,9 @@ SIGNATURES = {
     "qaq_thresholds": (C.c_int, [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "qaq_quantize_append": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
     "qaq_select_bits": (C.c_int, [_vp, _f32p, _u8p, _u8p, _vp]),
-    "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _vp]),
+    "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _i32, _vp]),
+    "qaq_profile_begin": (C.c_int, [_vp, _i32]),
+    "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
     "qaq_decode_attention": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _f32p, _vp]),
     "qaq_dequantize": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp]),
     "qaq_export_canonical": (C.c_int, [_vp, _i32, _u8p, _vp, _u8p, _vp, _u8p, _vp]),
@@ -193,7 +195,24 @@ class Cache:
         _check(self.lib.qaq_select_bits(self.h, _ptr(scores), _ptr(kb), _ptr(vb), _stream()))
 
     def requantize(self, k_bits, v_bits, k_orig=None, v_orig=None):
-        _check(self.lib.qaq_requantize(self.h, _ptr(k_bits), _ptr(v_bits), _ptr(k_orig), _ptr(v_orig), _stream()))
+        """bits: uint8 [B, Hkv, T] or None; originals: fp16 [B, Hkv, >=T, D] or None."""
+        src = k_orig if k_orig is not None else v_orig
+        n_orig = src.shape[2] if src is not None else 0
+        if k_orig is not None and v_orig is not None:
+            assert k_orig.shape[2] == v_orig.shape[2]
+        _check(self.lib.qaq_requantize(self.h, _ptr(k_bits), _ptr(v_bits), _ptr(k_orig), _ptr(v_orig), n_orig, _stream()))
+
+    def profile_begin(self, max_calls: int):
+        _check(self.lib.qaq_profile_begin(self.h, max_calls))
+        self._prof_cap = max_calls
+
+    def profile_read(self):
+        """Returns (ms of the per-tile kernel, ms of the merge kernel) lists of the profiled calls."""
+        n = C.c_int32()
+        a = (C.c_float * max(self._prof_cap, 1))()
+        b = (C.c_float * max(self._prof_cap, 1))()
+        _check(self.lib.qaq_profile_read(self.h, a, b, C.byref(n)))
+        return list(a[: n.value]), list(b[: n.value])
 
     def decode_attention(self, q, k_new=None, v_new=None, out=None, scores_out=None, want_scores=False, out_fp32=True):
         """q: fp16 [B, Hq, D]; k_new, v_new: fp16 [B, Hkv, D] or None.
