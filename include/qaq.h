@@ -172,11 +172,12 @@ int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* de
 int qaq_stats(qaq_cache* c, qaq_stats_t* host_out, void* stream);
 
 /* Measurement aid: after qaq_profile_begin(c, n), the next n qaq_decode_attention calls
- * record HIP events on their stream before, between and after their two kernels (the
- * per-tile kernel and the merge).  qaq_profile_read waits for them and returns the
+ * record HIP events on their stream before, between and after their three kernels (query
+ * preparation, the per-tile kernel and the merge).  qaq_profile_read waits for them and returns the
  * elapsed milliseconds of each; host arrays of at least n floats.  n = 0 switches it off. */
 int qaq_profile_begin(qaq_cache* c, int32_t max_calls);
-int qaq_profile_read(qaq_cache* c, float* host_ms_main, float* host_ms_merge, int32_t* n_calls);
+int qaq_profile_read(qaq_cache* c, float* host_ms_prep, float* host_ms_main, float* host_ms_merge,
+                     int32_t* n_calls);
 
 /* Number of outliers kept per end of a token vector for this configuration. */
 int qaq_outliers_per_side(const qaq_config* cfg);

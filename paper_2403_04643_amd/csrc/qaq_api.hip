@@ -19,7 +19,7 @@ struct qaq_cache {
   int ring_next;                   // ring row that the next score row goes to
   int row_len[QAQ_MAX_WINDOW];     // tokens covered by each ring row (0 = empty)
   double sigma_s, sigma_x;
-  std::vector<hipEvent_t> prof_ev;  // 3 events per profiled attention call
+  std::vector<hipEvent_t> prof_ev;  // 4 events per profiled attention call
   int prof_n;
 };
 
@@ -135,6 +135,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.counts = (uint16_t*)(base + a.counts);
   v.ring = (float*)(base + a.ring);
   v.partial = (float*)(base + a.partial);
+  v.qprep = base + a.qprep;
   v.statbuf = (long long*)(base + a.statbuf);
   v.refused = (unsigned int*)(base + a.refused);
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
@@ -273,7 +274,7 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
   a.scores = dev_scores_out;
   a.score_stride = c->len + (dev_k_new ? 1 : 0);
   hipEvent_t* ev = nullptr;
-  if (!c->prof_ev.empty() && (size_t)(3 * c->prof_n + 3) <= c->prof_ev.size()) ev = &c->prof_ev[3 * c->prof_n++];
+  if (!c->prof_ev.empty() && (size_t)(4 * c->prof_n + 4) <= c->prof_ev.size()) ev = &c->prof_ev[4 * c->prof_n++];
   hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev);
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
   return QAQ_OK;
@@ -284,7 +285,7 @@ int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.clear();
   c->prof_n = 0;
-  for (int i = 0; i < 3 * max_calls; ++i) {
+  for (int i = 0; i < 4 * max_calls; ++i) {
     hipEvent_t e;
     hipError_t r = hipEventCreate(&e);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_begin");
@@ -293,13 +294,14 @@ int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   return QAQ_OK;
 }
 
-int qaq_profile_read(qaq_cache* c, float* host_ms_main, float* host_ms_merge, int32_t* n_calls) {
-  if (!c || !host_ms_main || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+int qaq_profile_read(qaq_cache* c, float* host_ms_prep, float* host_ms_main, float* host_ms_merge, int32_t* n_calls) {
+  if (!c || !host_ms_prep || !host_ms_main || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   *n_calls = c->prof_n;
   for (int i = 0; i < c->prof_n; ++i) {
-    hipError_t r = hipEventSynchronize(c->prof_ev[3 * i + 2]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_main[i], c->prof_ev[3 * i], c->prof_ev[3 * i + 1]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[3 * i + 1], c->prof_ev[3 * i + 2]);
+    hipError_t r = hipEventSynchronize(c->prof_ev[4 * i + 3]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_prep[i], c->prof_ev[4 * i], c->prof_ev[4 * i + 1]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_main[i], c->prof_ev[4 * i + 1], c->prof_ev[4 * i + 2]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[4 * i + 2], c->prof_ev[4 * i + 3]);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_read");
   }
   c->prof_n = 0;

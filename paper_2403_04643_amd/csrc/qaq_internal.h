@@ -21,6 +21,7 @@ struct QaqView {
   uint16_t* counts;
   float* ring;
   float* partial;
+  uint8_t* qprep;
   long long* statbuf;
   unsigned int* refused;
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
@@ -97,7 +98,7 @@ struct QaqDequantArgs {
 hipError_t qaq_launch_init(const QaqView& v, hipStream_t s);
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
 hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
-// ev: NULL, or three events recorded before, between and after the two kernels
+// ev: NULL, or four events recorded before, between and after the three kernels
 hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev);
 hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
 hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);
