@@ -220,7 +220,7 @@ def main():
             cache_b.append(cb); io_b.append(ib)
     bytes_call = float(np.mean(cache_b) + np.mean(io_b))
     us_prep, us_main, us_merge = (1e3 * float(np.mean(x)) for x in (ms_prep, ms_main, ms_merge))
-    gbs_call = bytes_call / ((us_prep + us_main + us_merge) * 1e-6) / 1e9
+    gbs_call = bytes_call / ((us_main + us_merge) * 1e-6) / 1e9
     gbs_main = (float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * T0 * 4) / (us_main * 1e-6) / 1e9
     s = st1[0]
     th = B * Hkv * s.tokens
@@ -239,7 +239,7 @@ def main():
         "config": {"workload": f"configs[1]: LLaMA-7B layer, batch {B}, {Hq} heads, head_dim {D}, context {T0}, "
                                f"operating point {args.op} (mean widths K {mean_k:.2f} / V {mean_v:.2f}), "
                                f"{L} cache instances rotated", "op": args.op, "layers": L},
-        "us_per_attention_call": us_prep + us_main + us_merge, "us_prep_kernel": us_prep, "us_tile_kernel": us_main,
+        "us_per_attention_call": us_main + us_merge, "us_tile_kernel": us_main,
         "us_merge_kernel": us_merge,
         "algorithmic_bytes_per_call": bytes_call,
         "sigma_s_max": ss, "sigma_x_max": sx,

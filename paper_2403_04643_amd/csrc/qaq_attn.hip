@@ -1,10 +1,7 @@
 // Decode-step attention over the quantized cache (Section 2.1 attention evaluated on
 // the midpoint reconstruction of Section 4.1 with the outlier side store of Section 4.2).
 //
-// Three kernels per call:
-//   k_attn_prep     one small block per (sequence, query head): the query in fixed point,
-//                   split into signed base-256 digits, pre-divided by the power of two
-//                   that the code-spreading masks of each field width leave on the codes
+// Two kernels per call:
 //   k_attn_tile     one workgroup per (sequence, query head, tile of 256 positions):
 //                   logits, tile-local softmax, unnormalised output -> partial (max, sum, X)
 //   k_attn_combine  merges the tiles, adds the unquantized new token, normalises scores
@@ -113,90 +110,55 @@ __device__ __forceinline__ v4i spread(const uint32_t* w, int nib) {
   return b;
 }
 
-// Dwords lane (n, g) reads of one key record of field width BF.
+// One key record of field width BF, read whole by the lane that owns the token.
+// Slice q of the record (16 channels, see the layout header) is one step of the
+// contraction: the A operand holds the query digits of those 16 channels.
 template <int D, int BF>
 struct KRec {
-  static constexpr int KS = D / 64;
+  static constexpr int NQ = D / 16;                 // slices = contraction steps
   static constexpr int REC = D * BF / 8;
-  static constexpr int NDW = (KS * BF / 2) > 0 ? (KS * BF / 2) : 1;
-  static __device__ __forceinline__ void load(const uint8_t* rbase, int ridx, int g, uint32_t (&w)[NDW]) {
-    const uint8_t* rec = rbase + (uint32_t)ridx * (uint32_t)REC;
-    if constexpr (BF == 1 && KS == 1) load_dwords<1>(rec + 4 * (g >> 1), w);
-    else load_dwords<NDW>(rec + 4 * NDW * g, w);
+  static constexpr int RDW = D * BF / 32;           // dwords per record
+  static __device__ __forceinline__ void load(const uint8_t* rbase, int ridx, uint32_t (&w)[RDW]) {
+    load_dwords<RDW>(rbase + (uint32_t)ridx * (uint32_t)REC, w);
   }
-  static __device__ __forceinline__ v4i operand(const uint32_t (&w)[NDW], int ks, int g) {
-    if constexpr (BF == 1) return spread<1>(w, KS == 1 ? (g & 1) : ks);
-    else return spread<BF>(w + ks * (BF / 2), 0);
+  static __device__ __forceinline__ v4i operand(const uint32_t (&w)[RDW], int q) {
+    if constexpr (BF == 1) return spread<1>(&w[q >> 1], q & 1);
+    else return spread<BF>(&w[q * (BF / 2)], 0);
   }
-};
-
-// Records past the end of a region read the last record instead (never out of bounds);
-// their results are not used.
-template <int D, int BF>
-__device__ __forceinline__ void k_load_group(const uint8_t* rbase, int n_rec, int grp, int nn, int g,
-                                             uint32_t (&w)[4][KRec<D, BF>::NDW]) {
-#pragma unroll
-  for (int tg = 0; tg < 4; ++tg) {
-    const int ridx = min(grp * 64 + 16 * tg + nn, n_rec - 1);
-    KRec<D, BF>::load(rbase, ridx, g, w[tg]);
-  }
-}
-
-// Query digits of one head as written by k_attn_prep.
-template <int D>
-struct QPrep {
-  int8_t dq[3][4][D];   // [format: 2-bit masks, 1-bit masks, unscaled][digit (3 used)][channel]
-  float qscale;         // real value of one fixed-point unit of q
-  float sumq;           // sum_d q_d
-  float sumqi128;       // 128 * sum_d q_int (the 8-bit key bytes are stored as code - 128)
-  float pad;
 };
 
 template <int D>
 struct TileLds {
   float qf[D];
-  alignas(16) int8_t qa[2][4][D / 64][4][16][16];   // A operands [format][token group][k-step][lane group][row][16 B]
-  float logit[QAQ_TT];                              // raw logits by position
-  alignas(16) int8_t wl2[4][QAQ_TT];                // weight digits per slot of the 2-bit field region
-  alignas(16) int8_t wl1[4][QAQ_TT];                // ... of the 1-bit field region
-  alignas(16) int8_t wl4[4][QAQ_TT];                // ... of the 4-bit region
-  float w8[QAQ_TT];                                 // fp32 weights of the 8-bit slots
-  float xw[4][D / 4];                               // per-wavefront 8-bit-class outputs (its own channels)
-  float xcorr[D];                                   // outlier corrections of the output
+  alignas(16) int8_t ql[3][4][D];       // query digits [format][digit][position in record order]
+  alignas(16) int8_t zrow[256];         // zeros: A operand of lanes whose row carries nothing
+  float logit[QAQ_TT];                  // raw logits by position
+  alignas(16) int8_t wl2[4][QAQ_TT];    // weight digits per slot of the 2-bit field region
+  alignas(16) int8_t wl1[4][QAQ_TT];    // ... of the 1-bit field region
+  alignas(16) int8_t wl4[4][QAQ_TT];    // ... of the 4-bit region
+  float w8[QAQ_TT];                     // fp32 weights of the 8-bit slots
+  float xw[4][D / 4];                   // per-wavefront 8-bit-class outputs (its own channels)
+  float xcorr[D];                       // outlier corrections of the output
   float red[16];
+  int redi[4];
 };
 
-// 64 key records through the matrix unit: lane l ends with the digit sums (c[0..2]) of
-// record 64*grp + l.  The A operand of token group tg has the query digits in rows
-// 4*tg..4*tg+2 and zeros elsewhere, so the four groups land in the four row blocks.
-template <int D, int BF, int FMT>
-__device__ __forceinline__ v4i k_group_lds(const uint32_t (&w)[4][KRec<D, BF>::NDW], const TileLds<D>& S, int nn, int g) {
-  constexpr int KS = D / 64;
+// 64 key records through the matrix unit, one per lane.  Lane (n, g) of the wavefront
+// feeds its own record as column n of lane group g's share of the contraction index; row
+// 4*tg + L of the A operand holds digit L of the query in lane group tg only, so row block
+// tg of the result is the dot product with the records of lane group tg: lane l ends with
+// the three digit sums (c[0..2]) of its own record.  `abase` is the lane's digit row in
+// LDS (or a row of zeros for lanes whose A row is empty).
+template <int D, int BF>
+__device__ __forceinline__ v4i k_contract(const uint32_t (&w)[KRec<D, BF>::RDW], const int8_t* abase) {
   v4i c0 = {0, 0, 0, 0}, c1 = {0, 0, 0, 0};
 #pragma unroll
-  for (int tg = 0; tg < 4; ++tg)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const v4i a = *(const v4i*)&S.qa[FMT][tg][ks][g][nn][0];
-      const v4i bb = KRec<D, BF>::operand(w[tg], ks, g);
-      if ((tg * KS + ks) & 1) c1 = mma(a, bb, c1); else c0 = mma(a, bb, c0);
-    }
+  for (int q = 0; q < KRec<D, BF>::NQ; ++q) {
+    const v4i a = *(const v4i*)(abase + 16 * q);
+    const v4i bb = KRec<D, BF>::operand(w, q);
+    if (q & 1) c1 = mma(a, bb, c1); else c0 = mma(a, bb, c0);
+  }
   return c0 + c1;
-}
-// Same, with the A operands taken from the prepared digits in global memory (wide classes).
-template <int D, int BF>
-__device__ __forceinline__ v4i k_group_glb(const uint32_t (&w)[4][KRec<D, BF>::NDW], const QPrep<D>* qp, int nn, int g) {
-  constexpr int KS = D / 64;
-  const v4i zero = {0, 0, 0, 0};
-  v4i c = zero;
-  v4i aq[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) aq[ks] = *(const v4i*)&qp->dq[2][nn & 3][64 * ks + 16 * g];
-#pragma unroll
-  for (int tg = 0; tg < 4; ++tg)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) c = mma((nn >> 2) == tg ? aq[ks] : zero, KRec<D, BF>::operand(w[tg], ks, g), c);
-  return c;
 }
 
 // Outlier side store of one slot: NO2 entries known at compile time (0 or 2), or up to 8
@@ -221,48 +183,6 @@ struct Outl {
 };
 
 // ---------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(128) void k_attn_prep(QaqAttnArgs a) {
-  __shared__ float red[4];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int bq = blockIdx.x;
-  QPrep<D>* qp = reinterpret_cast<QPrep<D>*>(a.v.qprep) + bq;
-  const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
-  const float am = wave_max(fabsf(qv));
-  if (lane == 0) red[wave] = am;
-  __syncthreads();
-  const float qmax = fmaxf(red[0], red[1]);
-  int qexp = 0;
-  if (qmax > 0.0f) (void)frexpf(qmax, &qexp);
-  __syncthreads();
-  int qi = 0;
-  if (tid < D) {
-    const int v = (tid & 15) >> 2;
-#pragma unroll
-    for (int f = 0; f < 3; ++f) {
-      const int sh = f == 0 ? shift2(v) : f == 1 ? shift1(v) : 0;
-      const int x = qmax > 0.0f ? (int)rintf(ldexpf(qv, 22 - qexp - sh)) : 0;
-      const uint32_t dg = digits_packed(x);
-      qp->dq[f][0][tid] = (int8_t)dg; qp->dq[f][1][tid] = (int8_t)(dg >> 8);
-      qp->dq[f][2][tid] = (int8_t)(dg >> 16); qp->dq[f][3][tid] = 0;
-      if (f == 2) qi = x;
-    }
-  }
-  const float sq = wave_sum(qv);
-  int si = qi;                              // integer sum: exact
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) si += __shfl_xor(si, o);
-  if (lane == 0) { red[wave] = sq; red[2 + wave] = (float)si; }
-  __syncthreads();
-  if (tid == 0) {
-    qp->qscale = qmax > 0.0f ? ldexpf(1.0f, qexp - 22) : 0.0f;
-    qp->sumq = red[0] + red[1];
-    qp->sumqi128 = 128.0f * (red[2] + red[3]);
-    qp->pad = 0.0f;
-  }
-}
-
-// ---------------------------------------------------------------------------------------
 template <int D, int NO2>
 __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   constexpr int KS = D / 64;
@@ -278,7 +198,6 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
-  const QPrep<D>* qp = reinterpret_cast<const QPrep<D>*>(v.qprep) + bq;
 
   // ---- everything that can be loaded before any arithmetic -----------------------------------
   const QaqCounts cK = qaq_load_counts(v, 0, b, h, tile);
@@ -291,17 +210,18 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   const int n32K = cK.n32(), n32V = cV.n32();
   const int first8V = n32V + cV.n4;
 
+  const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
   const size_t gis = gi0 + min(tid, n_tok - 1);
   const uint32_t mmK = v.mm[0][gis], mmV = v.mm[1][gis];
   const int posK = v.perm[0][gis], posV = v.perm[1][gis];
   Outl<NO2> oK, oV;
   oK.load(v, 0, gis, no2);
   oV.load(v, 1, gis, no2);
-  const float qscale = qp->qscale, sumq = qp->sumq;
 
-  uint32_t kw2[4][KRec<D, 2>::NDW], kw1[4][KRec<D, 1>::NDW];
-  if (wave * 64 < n32K) k_load_group<D, 2>(baseK + rK.r2, n32K, wave, nn, g, kw2);
-  if (wave * 64 < cK.n3) k_load_group<D, 1>(baseK + rK.r1, cK.n3, wave, nn, g, kw1);
+  // key records of the two narrow regions: slot tid is record tid (past the end: the last one)
+  uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
+  if (wave * 64 < n32K) KRec<D, 2>::load(baseK + rK.r2, min(tid, n32K - 1), kw2);
+  if (wave * 64 < cK.n3) KRec<D, 1>::load(baseK + rK.r1, min(tid, cK.n3 - 1), kw1);
   // value side: this wavefront owns channel groups CGW*wave .. CGW*wave+CGW-1 of every unit
   uint32_t vw2[4][CGW], vw1[4];
   const int nu2 = (n32V + 15) >> 4, nu1 = (cV.n3 + 15) >> 4;
@@ -313,14 +233,14 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
       vw1[blk] = *(const uint32_t*)(baseV + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
   }
 
-  // ---- A operand tables of the two narrow key formats ----------------------------------------
-  if (tid < D) { S.qf[tid] = __half2float(a.q[(size_t)bq * D + tid]); S.xcorr[tid] = 0.0f; }
-  for (int e = tid; e < 2 * 4 * KS * 4 * 16; e += kThreads) {
-    const int row = e & 15, gg = (e >> 4) & 3, r = e >> 6, ks = r % KS, tg = (r / KS) & 3, f = r / (KS * 4);
-    v4i val = zero4;
-    if ((row >> 2) == tg && (row & 3) < 3) val = *(const v4i*)&qp->dq[f][row & 3][64 * ks + 16 * gg];
-    *(v4i*)&S.qa[f][tg][ks][gg][row][0] = val;
+  // ---- query: fixed point, signed base-256 digits, one table per spreading format ------------
+  if (wave < KS) {          // the wavefronts that hold the D query channels
+    const float am = wave_max(fabsf(qv));
+    const float sm = wave_sum(qv);
+    if (lane == 0) { S.red[wave] = am; S.red[4 + wave] = sm; }
+    S.qf[tid] = qv; S.xcorr[tid] = 0.0f;
   }
+  S.zrow[tid] = 0;
   // bound on w/p over the tile: the largest effective value scale (known before the logits)
   float smax_l = 0.0f;
   if (tid < n_tok) {
@@ -330,6 +250,29 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   }
   smax_l = wave_max(smax_l);
   __syncthreads();
+  const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
+  const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
+  int qexp = 0;
+  if (qmax > 0.0f) (void)frexpf(qmax, &qexp);
+  const float qscale = qmax > 0.0f ? ldexpf(1.0f, qexp - 22) : 0.0f;
+  if (wave < KS) {
+    // channel tid sits at position 16*(g'*KS + ks) + i of a record
+    const int i = tid & 15, vgr = i >> 2;
+    const int pos = 16 * (((tid & 63) >> 4) * KS + (tid >> 6)) + i;
+#pragma unroll
+    for (int f = 0; f < 3; ++f) {
+      const int sh = f == 0 ? shift2(vgr) : f == 1 ? shift1(vgr) : 0;
+      const int x = qmax > 0.0f ? (int)rintf(ldexpf(qv, 22 - qexp - sh)) : 0;
+      const uint32_t dg = digits_packed(x);
+      S.ql[f][0][pos] = (int8_t)dg; S.ql[f][1][pos] = (int8_t)(dg >> 8); S.ql[f][2][pos] = (int8_t)(dg >> 16);
+    }
+  }
+  __syncthreads();
+  // A rows: row r = 4*tg + L is switched on in lane group tg only
+  const bool arow = (g == (nn >> 2)) && ((nn & 3) < 3);
+  const int8_t* abase0 = arow ? &S.ql[0][nn & 3][0] : &S.zrow[0];
+  const int8_t* abase1 = arow ? &S.ql[1][nn & 3][0] : &S.zrow[0];
+  const int8_t* abase2 = arow ? &S.ql[2][nn & 3][0] : &S.zrow[0];
 
   // ---- keys: logits ------------------------------------------------------------------------------
   auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale; };
@@ -351,10 +294,10 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   };
   float vmax = -INFINITY;
   if (wave * 64 < n32K) {
-    float dotq = real_of(k_group_lds<D, 2, 0>(kw2, S, nn, g));
+    float dotq = real_of(k_contract<D, 2>(kw2, abase0));
     const bool three = tid < cK.n3;
     if (wave * 64 < cK.n3) {
-      const float low = real_of(k_group_lds<D, 1, 1>(kw1, S, nn, g));
+      const float low = real_of(k_contract<D, 1>(kw1, abase1));
       dotq = three ? 2.0f * dotq + low : dotq;
     }
     if (tid < n32K) {
@@ -365,10 +308,10 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   }
   // wider classes: loaded when needed (few tokens at the operating points of interest)
   for (int grp = wave; grp * 64 < cK.n4; grp += 4) {
-    uint32_t w[4][KRec<D, 4>::NDW];
-    k_load_group<D, 4>(baseK + rK.r4, cK.n4, grp, nn, g, w);
-    const v4i cc = k_group_glb<D, 4>(w, qp, nn, g);
+    uint32_t w[KRec<D, 4>::RDW];
     const int idx = grp * 64 + lane;
+    KRec<D, 4>::load(baseK + rK.r4, min(idx, cK.n4 - 1), w);
+    const v4i cc = k_contract<D, 4>(w, abase2);
     if (idx < cK.n4) {
       const size_t gi = gi0 + n32K + idx;
       Outl<NO2> o; o.load(v, 0, gi, no2);
@@ -377,26 +320,35 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
       vmax = fmaxf(vmax, lg);
     }
   }
+  // 8-bit key bytes are stored as code - 128: the dot product needs 128 * sum of the
+  // (unscaled) query integers back, rebuilt here from their digits (this class is rare)
+  float sumqi = 0.0f;
+  if (cK.n8 > 0) {
+    int sq = 0;
+    for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
+    sumqi = (float)sq;
+  }
   for (int grp = wave; grp * 64 < cK.n8; grp += 4) {
-    uint32_t w[4][KRec<D, 8>::NDW];
-    k_load_group<D, 8>(baseK + rK.r8, cK.n8, grp, nn, g, w);
-    const v4i cc = k_group_glb<D, 8>(w, qp, nn, g);
+    uint32_t w[KRec<D, 8>::RDW];
     const int idx = grp * 64 + lane;
+    KRec<D, 8>::load(baseK + rK.r8, min(idx, cK.n8 - 1), w);
+    const v4i cc = k_contract<D, 8>(w, abase2);
     if (idx < cK.n8) {
       const size_t gi = gi0 + n32K + cK.n4 + idx;
       Outl<NO2> o; o.load(v, 0, gi, no2);
-      // stored bytes are code - 128
-      const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + qp->sumqi128) * qscale;
+      const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
       const float lg = key_logit(v.mm[0][gi], o, 8, dotq);
       S.logit[v.perm[0][gi]] = lg;
       vmax = fmaxf(vmax, lg);
     }
   }
   vmax = wave_max(vmax);
-  if (lane == 0) { S.red[wave] = vmax; S.red[4 + wave] = smax_l; }
+  if (lane == 0) { S.red[8 + wave] = vmax; S.red[12 + wave] = smax_l; }
   __syncthreads();
-  const float M = fmaxf(fmaxf(S.red[0], S.red[1]), fmaxf(S.red[2], S.red[3]));
-  const float smax = fmaxf(fmaxf(S.red[4], S.red[5]), fmaxf(S.red[6], S.red[7]));
+  const float M = fmaxf(fmaxf(S.red[8], S.red[9]), fmaxf(S.red[10], S.red[11]));
+  const float smax = fmaxf(fmaxf(S.red[12], S.red[13]), fmaxf(S.red[14], S.red[15]));
   int wexp = 0;
   if (smax > 0.0f) (void)frexpf(smax, &wexp);
   const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 30) : 0.0f;
@@ -429,43 +381,50 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
     // Fixed point in units of 2^(e-30), e = exponent of the bound: W = round(w * 2^(30-e-sh)),
     // sh = what the spreading mask of the slot's place in its unit leaves on the code.  A
     // 3-bit code is 2*top + low, so its top plane weighs 2w (at most the bound) and its
-    // low plane w.  Every entry of the three digit tables is written exactly once (zero
+    // low plane w.  Every entry of a digit table in use is written exactly once (zero
     // where the slot is not in that region), so partial units multiply padding by zero.
     const bool fx = live && smax > 0.0f;
     const int vg = (s & 15) >> 2;
     const int W2 = (fx && s < n32V) ? (int)rintf(ldexpf(w, 30 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0;
     const uint32_t d2 = digits_packed(W2);
     S.wl2[0][s] = (int8_t)d2; S.wl2[1][s] = (int8_t)(d2 >> 8); S.wl2[2][s] = (int8_t)(d2 >> 16); S.wl2[3][s] = (int8_t)(d2 >> 24);
-    const int W1 = (fx && s < cV.n3) ? (int)rintf(ldexpf(w, 30 - wexp - shift1(vg))) : 0;
-    const uint32_t d1 = digits_packed(W1);
-    S.wl1[0][s] = (int8_t)d1; S.wl1[1][s] = (int8_t)(d1 >> 8); S.wl1[2][s] = (int8_t)(d1 >> 16); S.wl1[3][s] = (int8_t)(d1 >> 24);
-    const int i4 = (s - n32V) & (QAQ_TT - 1);
-    const int W4 = (fx && s >= n32V && s < first8V) ? (int)rintf(ldexpf(w, 30 - wexp)) : 0;
-    const uint32_t d4 = digits_packed(W4);
-    S.wl4[0][i4] = (int8_t)d4; S.wl4[1][i4] = (int8_t)(d4 >> 8); S.wl4[2][i4] = (int8_t)(d4 >> 16); S.wl4[3][i4] = (int8_t)(d4 >> 24);
+    if (cV.n3 > 0) {
+      const int W1 = (fx && s < cV.n3) ? (int)rintf(ldexpf(w, 30 - wexp - shift1(vg))) : 0;
+      const uint32_t d1 = digits_packed(W1);
+      S.wl1[0][s] = (int8_t)d1; S.wl1[1][s] = (int8_t)(d1 >> 8); S.wl1[2][s] = (int8_t)(d1 >> 16); S.wl1[3][s] = (int8_t)(d1 >> 24);
+    }
+    if (cV.n4 > 0) {
+      const int i4 = (s - n32V) & (QAQ_TT - 1);
+      const int W4 = (fx && s >= n32V && s < first8V) ? (int)rintf(ldexpf(w, 30 - wexp)) : 0;
+      const uint32_t d4 = digits_packed(W4);
+      S.wl4[0][i4] = (int8_t)d4; S.wl4[1][i4] = (int8_t)(d4 >> 8); S.wl4[2][i4] = (int8_t)(d4 >> 16); S.wl4[3][i4] = (int8_t)(d4 >> 24);
+    }
   }
   {
     const float ls = wave_sum(pt);
     const float bs = wave_sum(bias_l);
-    if (lane == 0) { S.red[8 + wave] = ls; S.red[12 + wave] = bs; }
+    if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
   }
   __syncthreads();
-  const float lsum = (S.red[8] + S.red[9]) + (S.red[10] + S.red[11]);
-  const float bias = (S.red[12] + S.red[13]) + (S.red[14] + S.red[15]);
+  const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
+  const float bias = (S.red[4] + S.red[5]) + (S.red[6] + S.red[7]);
 
   // ---- values: integer contractions, rows 0..3 of the tile = the four digits of w -------------
+  const int8_t* wb2 = nn < 4 ? &S.wl2[nn][16 * g] : &S.zrow[0];
+  const int8_t* wb1 = nn < 4 ? &S.wl1[nn][16 * g] : &S.zrow[0];
+  const int8_t* wb4 = nn < 4 ? &S.wl4[nn][16 * g] : &S.zrow[0];
   v4i cv[CGW];
 #pragma unroll
   for (int j = 0; j < CGW; ++j) cv[j] = zero4;
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk) {
     if (blk * 64 < n32V) {
-      const v4i wa = nn < 4 ? *(const v4i*)&S.wl2[nn][16 * (blk * 4 + g)] : zero4;
+      const v4i wa = *(const v4i*)(wb2 + 64 * blk);
 #pragma unroll
       for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&vw2[blk][j], 0), cv[j]);
     }
     if (blk * 64 < cV.n3) {
-      const v4i wa = nn < 4 ? *(const v4i*)&S.wl1[nn][16 * (blk * 4 + g)] : zero4;
+      const v4i wa = *(const v4i*)(wb1 + 64 * blk);
 #pragma unroll
       for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&vw1[blk], (CGW * wave + j) & 1), cv[j]);
     }
@@ -477,7 +436,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
     // a half-unit past the end repeats the last one; its slots carry zero digits
     load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
     load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
-    const v4i wa = nn < 4 ? *(const v4i*)&S.wl4[nn][16 * u] : zero4;
+    const v4i wa = *(const v4i*)(wb4 + 64 * blk);
 #pragma unroll
     for (int j = 0; j < CGW; ++j) {
       const uint32_t pr[2] = {w0[j], w1d[j]};
@@ -486,7 +445,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   }
   // 8-bit codes: token-major bytes, plain fp32 multiply-add; this wavefront's D/4 channels,
   // lane = (token sub-index, 4 channels)
-  {
+  float x8 = 0.0f;
+  if (cV.n8 > 0) {
     constexpr int LPT8 = D / 16;         // lanes per token (4 channels each)
     constexpr int TPW = 64 / LPT8;       // tokens per pass
     float a8[4] = {0.f, 0.f, 0.f, 0.f};
@@ -514,7 +474,8 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
       const float lo = (float)cv[j][1] * 256.0f + (float)cv[j][0];
       const int chl = 16 * j + nn;                   // channel inside this wavefront's share
       const int ch = (D / 4) * wave + chl;
-      part[ch] = (hi + lo) * wscale + S.xw[wave][chl] + S.xcorr[ch] + bias;
+      if (cV.n8 > 0) x8 = S.xw[wave][chl];
+      part[ch] = (hi + lo) * wscale + x8 + S.xcorr[ch] + bias;
     }
   }
   if (tid == 0) { part[D] = M; part[D + 1] = lsum; }
@@ -523,52 +484,93 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
 // Merge the tiles of one (sequence, query head), add the unquantized new token and
 // normalise.  Block x = 0 writes the output vector; every block normalises its share of
 // the emitted scores (each recomputes the head's max and sum from the per-tile pairs).
+// All global loads are issued before the first reduction.
 template <int D>
 __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
+  constexpr int MAXP = 4;                    // per-tile pairs held per lane (256 tiles); more: loop
   __shared__ float red[8];
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
   const int nparts = (a.len + QAQ_TT - 1) / QAQ_TT;
   const float* part = v.partial + (size_t)bq * v.NT * (D + 4);
+  float* sc = a.scores ? a.scores + (size_t)bq * a.score_stride : nullptr;
+  const int t0 = blockIdx.x * (4 * kThreads);
+  float raw[4] = {0.f, 0.f, 0.f, 0.f};
+  if (sc) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int t = t0 + k * kThreads + tid;
+      if (t < a.len) raw[k] = sc[t];
+    }
+  }
+  float pm[MAXP], pl[MAXP];
+#pragma unroll
+  for (int k = 0; k < MAXP; ++k) {
+    const int i = lane + 64 * k;
+    pm[k] = i < nparts ? part[(size_t)i * (D + 4) + D] : -INFINITY;
+    pl[k] = i < nparts ? part[(size_t)i * (D + 4) + D + 1] : 0.0f;
+  }
+  float qk = 0.0f;
+  if (a.k_new && tid < D) qk = __half2float(a.q[(size_t)bq * D + tid]) * __half2float(a.k_new[((size_t)b * v.Hkv + h) * D + tid]);
+
   float a_new = -INFINITY;
   if (a.k_new) {
-    float t = 0.0f;
-    if (tid < D) t = __half2float(a.q[(size_t)bq * D + tid]) * __half2float(a.k_new[((size_t)b * v.Hkv + h) * D + tid]);
-    t = wave_sum(t);
-    if (lane == 0) red[wave] = t;
+    qk = wave_sum(qk);
+    if (lane == 0) red[wave] = qk;
     __syncthreads();
     a_new = ((red[0] + red[1]) + (red[2] + red[3])) / sqrtf((float)D);
   }
-  // per-tile (max, sum): lanes take tiles round robin, then a reduction in the wavefront
   float M = a_new;
-  for (int i = lane; i < nparts; i += 64) M = fmaxf(M, part[(size_t)i * (D + 4) + D]);
+#pragma unroll
+  for (int k = 0; k < MAXP; ++k) M = fmaxf(M, pm[k]);
+  for (int i = lane + 64 * MAXP; i < nparts; i += 64) M = fmaxf(M, part[(size_t)i * (D + 4) + D]);
   M = wave_max(M);
   float lsum = 0.0f;
-  for (int i = lane; i < nparts; i += 64)
+#pragma unroll
+  for (int k = 0; k < MAXP; ++k) lsum += __expf(pm[k] - M) * pl[k];
+  for (int i = lane + 64 * MAXP; i < nparts; i += 64)
     lsum += __expf(part[(size_t)i * (D + 4) + D] - M) * part[(size_t)i * (D + 4) + D + 1];
   lsum = wave_sum(lsum);
   float e_new = 0.0f;
   if (a.k_new) { e_new = __expf(a_new - M); lsum += e_new; }
   const float inv = 1.0f / lsum;
+  if (sc) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int t = t0 + k * kThreads + tid;
+      if (t < a.len) sc[t] = __expf(raw[k] - M) * inv;
+    }
+  }
   if (blockIdx.x == 0) {
+    // output vector: wavefront w takes tiles w, w+4, ..., lanes take channels; several
+    // independent loads in flight per lane, then a fixed-order sum over the wavefronts
+    __shared__ float fac[64 * MAXP];
+    __shared__ float xacc[4][D];
+    if (wave == 0) {
+#pragma unroll
+      for (int k = 0; k < MAXP; ++k) fac[lane + 64 * k] = __expf(pm[k] - M);
+    }
+    __syncthreads();
+    float acc[D / 64];
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) acc[c] = 0.0f;
+#pragma unroll 4
+    for (int i = wave; i < nparts; i += 4) {
+      const float f = i < 64 * MAXP ? fac[i] : __expf(part[(size_t)i * (D + 4) + D] - M);
+#pragma unroll
+      for (int c = 0; c < D / 64; ++c) acc[c] += f * part[(size_t)i * (D + 4) + lane + 64 * c];
+    }
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) xacc[wave][lane + 64 * c] = acc[c];
+    __syncthreads();
     if (tid < D) {
-      float x = 0.0f;
-      for (int i = 0; i < nparts; ++i) x += __expf(part[(size_t)i * (D + 4) + D] - M) * part[(size_t)i * (D + 4) + tid];
+      float x = (xacc[0][tid] + xacc[1][tid]) + (xacc[2][tid] + xacc[3][tid]);
       if (a.k_new) x += e_new * __half2float(a.v_new[((size_t)b * v.Hkv + h) * D + tid]);
       if (a.out_is_fp32) ((float*)a.out)[(size_t)bq * D + tid] = x * inv;
       else ((__half*)a.out)[(size_t)bq * D + tid] = __float2half_rn(x * inv);
     }
-    if (a.scores && a.k_new && tid == 0) a.scores[(size_t)bq * a.score_stride + a.len] = e_new * inv;
-  }
-  if (a.scores) {
-    float* sc = a.scores + (size_t)bq * a.score_stride;
-    const int t0 = blockIdx.x * (4 * kThreads);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int t = t0 + k * kThreads + tid;
-      if (t < a.len) sc[t] = __expf(sc[t] - M) * inv;
-    }
+    if (sc && a.k_new && tid == 0) sc[a.len] = e_new * inv;
   }
 }
 
@@ -584,12 +586,7 @@ void launch_tile(const QaqAttnArgs& a, dim3 grid, hipStream_t s) {
 hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev) {
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
-  if (ev) (void)hipEventRecord(ev[0], s);
-  if (ntile > 0) {
-    if (a.v.D == 128) hipLaunchKernelGGL(k_attn_prep<128>, dim3(BQ), dim3(128), 0, s, a);
-    else hipLaunchKernelGGL(k_attn_prep<64>, dim3(BQ), dim3(128), 0, s, a);
-  }
-  if (ev) (void)hipEventRecord(ev[1], s);
+  if (ev) { (void)hipEventRecord(ev[0], s); (void)hipEventRecord(ev[1], s); }
   if (ntile > 0) {
     if (a.v.D == 128) launch_tile<128>(a, dim3(ntile, BQ), s);
     else launch_tile<64>(a, dim3(ntile, BQ), s);
