@@ -27,6 +27,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int QAQ_MAX_NTC = 64;   // tiles per workgroup at most
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float h2f(uint16_t b) { return __half2float(__ushort_as_half(b)); }
@@ -53,6 +54,12 @@ __device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t (&w)[N]) 
     }
   }
 }
+
+// Workgroup barrier that orders LDS traffic only.  All communication between the threads
+// of these kernels goes through LDS, and __syncthreads() would also wait for every global
+// load in flight -- including the loads of the next tile that are meant to stay in flight
+// across the barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----
 template <int CTRL, int ROW_MASK = 0xf>
@@ -132,6 +139,7 @@ struct TileLds {
   float qf[D];
   alignas(16) int8_t ql[3][4][D];       // query digits [format][digit][position in record order]
   alignas(16) int8_t zrow[256];         // zeros: A operand of lanes whose row carries nothing
+  alignas(16) uint16_t cnt[QAQ_MAX_NTC][8]; // class counts of the workgroup's tiles: keys, values
   float logit[QAQ_TT];                  // raw logits by position
   alignas(16) int8_t wl2[4][QAQ_TT];    // weight digits per slot of the 2-bit field region
   alignas(16) int8_t wl1[4][QAQ_TT];    // ... of the 1-bit field region
@@ -162,29 +170,95 @@ __device__ __forceinline__ v4i k_contract(const uint32_t (&w)[KRec<D, BF>::RDW],
 }
 
 // Outlier side store of one slot: NO2 entries known at compile time (0 or 2), or up to 8
-// with a run-time count.
+// with a run-time count.  Loads only move raw words; unpacking happens where the values
+// are used, so that a load issued ahead of time is not waited for at its issue point.
 template <int NO2>
 struct Outl {
   static constexpr int CAP = NO2 ? NO2 : 1;
-  uint8_t idx[CAP];
-  uint16_t val[CAP];
+  uint32_t i2, v2, half;      // NO2 == 2: word holding the two channel bytes, two fp16 values
+  uint8_t idx8[CAP];          // NO2 > 2
+  uint16_t val8[CAP];
   __device__ __forceinline__ void load(const QaqView& v, int side, size_t gi, int no2) {
     if constexpr (NO2 == 2) {
-      const uint16_t i2 = *(const uint16_t*)(v.oidx[side] + gi * 2);
-      const uint32_t v2 = *(const uint32_t*)(v.oval[side] + gi * 2);
-      idx[0] = (uint8_t)i2; idx[1] = (uint8_t)(i2 >> 8);
-      val[0] = (uint16_t)v2; val[1] = (uint16_t)(v2 >> 16);
+      // whole aligned words only (the channel pair is one half of its word): nothing has
+      // to be done to the loaded register until it is used
+      i2 = *(const uint32_t*)(v.oidx[side] + ((gi * 2) & ~(size_t)3));
+      v2 = *(const uint32_t*)(v.oval[side] + gi * 2);
+      half = (uint32_t)(gi & 1);
     } else if constexpr (NO2 > 2) {
 #pragma unroll
       for (int j = 0; j < NO2; ++j)
-        if (j < no2) { idx[j] = v.oidx[side][gi * no2 + j]; val[j] = v.oval[side][gi * no2 + j]; }
+        if (j < no2) { idx8[j] = v.oidx[side][gi * no2 + j]; val8[j] = v.oval[side][gi * no2 + j]; }
     }
+  }
+  __device__ __forceinline__ int idx(int j) const {
+    if constexpr (NO2 == 2) return (int)((i2 >> (16 * half + 8 * j)) & 0xffu);
+    else return idx8[j];
+  }
+  __device__ __forceinline__ float val(int j) const {
+    if constexpr (NO2 == 2) return h2f((uint16_t)(v2 >> (16 * j)));
+    else return h2f(val8[j]);
+  }
+};
+
+// Everything of one tile that is loaded ahead of its arithmetic.
+template <int D, int NO2>
+struct TileRegs {
+  static constexpr int NCG = D / 16;
+  static constexpr int CGW = NCG / 4;
+  QaqCounts cK, cV;
+  int n_tok;
+  uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
+  uint32_t mmK, mmV;
+  uint32_t posK, posV, pbyte;
+  Outl<NO2> oK, oV;
+  uint32_t vw2[4][CGW], vw1[4];
+
+  // Part 1: everything whose address does not depend on the class counts.
+  __device__ __forceinline__ void load_fixed(const QaqView& v, int len, int b, int h, int tile, int tid, int wave, int nn, int g) {
+    n_tok = min(len - tile * QAQ_TT, QAQ_TT);
+    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
+    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    const size_t gis = qaq_slot_index(v, b, h, tile, min(tid, n_tok - 1));
+    mmK = v.mm[0][gis]; mmV = v.mm[1][gis];
+    posK = *(const uint32_t*)(v.perm[0] + (gis & ~(size_t)3));    // aligned word; byte gis%4 is the position
+    posV = *(const uint32_t*)(v.perm[1] + (gis & ~(size_t)3));
+    pbyte = 8u * (uint32_t)(gis & 3);
+    oK.load(v, 0, gis, v.no2);
+    oV.load(v, 1, gis, v.no2);
+    // The 2-bit field regions start at offset 0 of the tile side; slots past the region
+    // read other bytes of the same tile (always inside its reserved capacity) and their
+    // results are not used.
+    KRec<D, 2>::load(baseK, tid, kw2);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+      load_dwords<CGW>(baseV + (uint32_t)(blk * 4 + g) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, vw2[blk]);
+  }
+  // Part 2: the 1-bit field regions, behind the 2-bit ones, placed by the counts.
+  __device__ __forceinline__ void load_placed(const QaqView& v, int b, int h, int tile, const QaqCounts& ck,
+                                              const QaqCounts& cv, int tid, int wave, int nn, int g) {
+    cK = ck;
+    cV = cv;
+    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
+    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    const QaqKRegions rK = qaq_k_regions(cK, D);
+    const QaqVRegions rV = qaq_v_regions(cV, D);
+    if (wave * 64 < cK.n3) KRec<D, 1>::load(baseK + rK.r1, min(tid, cK.n3 - 1), kw1);
+    const int nu1 = (cV.n3 + 15) >> 4;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+      if (blk * 4 < nu1)
+        vw1[blk] = *(const uint32_t*)(baseV + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
   }
 };
 
 // ---------------------------------------------------------------------------------------
+// One workgroup: one (sequence, query head), tiles [chunk*ntc, chunk*ntc + ntc).  The loads
+// of tile t+1 are in flight while tile t is computed; the output, the softmax sum and the
+// constant terms are carried in registers across the tiles with the usual rescaling by
+// exp(old max - new max), and one partial is written per workgroup.
 template <int D, int NO2>
-__global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   // three wavefronts per SIMD
   constexpr int KS = D / 64;
   constexpr int NCG = D / 16;
   constexpr int CGW = NCG / 4;              // channel groups per wavefront on the value side
@@ -192,46 +266,21 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 15, g = lane >> 4;
-  const int tile = blockIdx.x;
+  const int chunk = blockIdx.x;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
-  const int n_tok = min(a.len - tile * QAQ_TT, QAQ_TT);
+  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  const int tile_begin = chunk * a.ntc, tile_end = min(tile_begin + a.ntc, ntile);
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
 
-  // ---- everything that can be loaded before any arithmetic -----------------------------------
-  const QaqCounts cK = qaq_load_counts(v, 0, b, h, tile);
-  const QaqCounts cV = qaq_load_counts(v, 1, b, h, tile);
-  const QaqKRegions rK = qaq_k_regions(cK, D);
-  const QaqVRegions rV = qaq_v_regions(cV, D);
-  const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
-  const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
-  const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
-  const int n32K = cK.n32(), n32V = cV.n32();
-  const int first8V = n32V + cV.n4;
-
+  TileRegs<D, NO2> nxt;
+  nxt.load_fixed(v, a.len, b, h, tile_begin, tid, wave, nn, g);
   const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
-  const size_t gis = gi0 + min(tid, n_tok - 1);
-  const uint32_t mmK = v.mm[0][gis], mmV = v.mm[1][gis];
-  const int posK = v.perm[0][gis], posV = v.perm[1][gis];
-  Outl<NO2> oK, oV;
-  oK.load(v, 0, gis, no2);
-  oV.load(v, 1, gis, no2);
-
-  // key records of the two narrow regions: slot tid is record tid (past the end: the last one)
-  uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
-  if (wave * 64 < n32K) KRec<D, 2>::load(baseK + rK.r2, min(tid, n32K - 1), kw2);
-  if (wave * 64 < cK.n3) KRec<D, 1>::load(baseK + rK.r1, min(tid, cK.n3 - 1), kw1);
-  // value side: this wavefront owns channel groups CGW*wave .. CGW*wave+CGW-1 of every unit
-  uint32_t vw2[4][CGW], vw1[4];
-  const int nu2 = (n32V + 15) >> 4, nu1 = (cV.n3 + 15) >> 4;
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) {
-    if (blk * 4 < nu2)
-      load_dwords<CGW>(baseV + rV.r2 + (uint32_t)min(blk * 4 + g, nu2 - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, vw2[blk]);
-    if (blk * 4 < nu1)
-      vw1[blk] = *(const uint32_t*)(baseV + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
-  }
+  // class counts of all tiles of the chunk -> LDS (one 16-byte load per tile), so that the
+  // tile loop needs no dependent global load to place its 1-bit regions
+  if (tid < tile_end - tile_begin)
+    *(uint4*)&S.cnt[tid][0] = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + tile_begin + tid) * 2) * 4);
 
   // ---- query: fixed point, signed base-256 digits, one table per spreading format ------------
   if (wave < KS) {          // the wavefronts that hold the D query channels
@@ -241,15 +290,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
     S.qf[tid] = qv; S.xcorr[tid] = 0.0f;
   }
   S.zrow[tid] = 0;
-  // bound on w/p over the tile: the largest effective value scale (known before the logits)
-  float smax_l = 0.0f;
-  if (tid < n_tok) {
-    const int bits = cV.bits_of_slot(tid);
-    const float range = h2f((uint16_t)(mmV >> 16)) - h2f((uint16_t)(mmV & 0xffffu));
-    smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
-  }
-  smax_l = wave_max(smax_l);
-  __syncthreads();
+  lds_barrier();
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
   int qexp = 0;
@@ -267,14 +308,16 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
       S.ql[f][0][pos] = (int8_t)dg; S.ql[f][1][pos] = (int8_t)(dg >> 8); S.ql[f][2][pos] = (int8_t)(dg >> 16);
     }
   }
-  __syncthreads();
+  lds_barrier();
   // A rows: row r = 4*tg + L is switched on in lane group tg only
   const bool arow = (g == (nn >> 2)) && ((nn & 3) < 3);
   const int8_t* abase0 = arow ? &S.ql[0][nn & 3][0] : &S.zrow[0];
   const int8_t* abase1 = arow ? &S.ql[1][nn & 3][0] : &S.zrow[0];
   const int8_t* abase2 = arow ? &S.ql[2][nn & 3][0] : &S.zrow[0];
+  const int8_t* wb2 = nn < 4 ? &S.wl2[nn][16 * g] : &S.zrow[0];
+  const int8_t* wb1 = nn < 4 ? &S.wl1[nn][16 * g] : &S.zrow[0];
+  const int8_t* wb4 = nn < 4 ? &S.wl4[nn][16 * g] : &S.zrow[0];
 
-  // ---- keys: logits ------------------------------------------------------------------------------
   auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale; };
   auto key_logit = [&](uint32_t m, const Outl<NO2>& o, int bits, float dotq) {
     const float mn = h2f((uint16_t)(m & 0xffffu)), mx = h2f((uint16_t)(m >> 16));
@@ -285,200 +328,254 @@ __global__ __launch_bounds__(kThreads) void k_attn_tile(QaqAttnArgs a) {
 #pragma unroll
     for (int j = 0; j < Outl<NO2>::CAP; ++j) {
       if (j < NO2 && j < no2) {
-        const float ov = h2f(o.val[j]);
+        const float ov = o.val(j);
         const float deq = mn + ((ov >= mx && range > 0.0f) ? ctop : 0.5f) * scale;
-        val += S.qf[o.idx[j]] * (ov - deq);
+        val += S.qf[o.idx(j)] * (ov - deq);
       }
     }
     return val * inv_sqrt_d;
   };
-  float vmax = -INFINITY;
-  if (wave * 64 < n32K) {
-    float dotq = real_of(k_contract<D, 2>(kw2, abase0));
-    const bool three = tid < cK.n3;
-    if (wave * 64 < cK.n3) {
-      const float low = real_of(k_contract<D, 1>(kw1, abase1));
-      dotq = three ? 2.0f * dotq + low : dotq;
-    }
-    if (tid < n32K) {
-      const float lg = key_logit(mmK, oK, three ? 3 : 2, dotq);
-      S.logit[posK] = lg;
-      vmax = lg;
-    }
-  }
-  // wider classes: loaded when needed (few tokens at the operating points of interest)
-  for (int grp = wave; grp * 64 < cK.n4; grp += 4) {
-    uint32_t w[KRec<D, 4>::RDW];
-    const int idx = grp * 64 + lane;
-    KRec<D, 4>::load(baseK + rK.r4, min(idx, cK.n4 - 1), w);
-    const v4i cc = k_contract<D, 4>(w, abase2);
-    if (idx < cK.n4) {
-      const size_t gi = gi0 + n32K + idx;
-      Outl<NO2> o; o.load(v, 0, gi, no2);
-      const float lg = key_logit(v.mm[0][gi], o, 4, real_of(cc));
-      S.logit[v.perm[0][gi]] = lg;
-      vmax = fmaxf(vmax, lg);
-    }
-  }
-  // 8-bit key bytes are stored as code - 128: the dot product needs 128 * sum of the
-  // (unscaled) query integers back, rebuilt here from their digits (this class is rare)
-  float sumqi = 0.0f;
-  if (cK.n8 > 0) {
-    int sq = 0;
-    for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
-    sumqi = (float)sq;
-  }
-  for (int grp = wave; grp * 64 < cK.n8; grp += 4) {
-    uint32_t w[KRec<D, 8>::RDW];
-    const int idx = grp * 64 + lane;
-    KRec<D, 8>::load(baseK + rK.r8, min(idx, cK.n8 - 1), w);
-    const v4i cc = k_contract<D, 8>(w, abase2);
-    if (idx < cK.n8) {
-      const size_t gi = gi0 + n32K + cK.n4 + idx;
-      Outl<NO2> o; o.load(v, 0, gi, no2);
-      const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
-      const float lg = key_logit(v.mm[0][gi], o, 8, dotq);
-      S.logit[v.perm[0][gi]] = lg;
-      vmax = fmaxf(vmax, lg);
-    }
-  }
-  vmax = wave_max(vmax);
-  if (lane == 0) { S.red[8 + wave] = vmax; S.red[12 + wave] = smax_l; }
-  __syncthreads();
-  const float M = fmaxf(fmaxf(S.red[8], S.red[9]), fmaxf(S.red[10], S.red[11]));
-  const float smax = fmaxf(fmaxf(S.red[12], S.red[13]), fmaxf(S.red[14], S.red[15]));
-  int wexp = 0;
-  if (smax > 0.0f) (void)frexpf(smax, &wexp);
-  const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 30) : 0.0f;
 
-  // ---- values: weight of slot `tid`, as digits ---------------------------------------------------
-  if (a.scores && tid < n_tok) a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
-  float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
-  {
-    const int s = tid;
-    const bool live = s < n_tok;
-    if (live) {
-      pt = __expf(S.logit[posV] - M);
-      const float mn = h2f((uint16_t)(mmV & 0xffffu)), mx = h2f((uint16_t)(mmV >> 16));
-      const float range = mx - mn;
-      const int bits = cV.bits_of_slot(s);
-      const float scale = ldexpf(range, -bits);
-      w = pt * scale;
-      bias_l = pt * mn + 0.5f * w;
-      const float ctop = (float)((1 << bits) - 1) + 0.5f;
+  auto counts_of = [&](int t, int side) {
+    const uint2 c = *(const uint2*)&S.cnt[t - tile_begin][4 * side];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
+    QaqCounts r;
+    r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
+    return r;
+  };
+  nxt.load_placed(v, b, h, tile_begin, counts_of(tile_begin, 0), counts_of(tile_begin, 1), tid, wave, nn, g);
+
+  // carried across the tiles
+  float m_run = -INFINITY;          // reference of everything below
+  float l_run = 0.0f, bias_run = 0.0f;    // per thread: softmax sum and constant terms of its slots
+  float xrun[CGW];                  // lanes of group 0: output of channel 16*(CGW*wave+j)+n
 #pragma unroll
-      for (int j = 0; j < Outl<NO2>::CAP; ++j) {
-        if (j < NO2 && j < no2) {
-          const float ov = h2f(oV.val[j]);
-          const float deq = mn + ((ov >= mx && range > 0.0f) ? ctop : 0.5f) * scale;
-          atomicAdd(&S.xcorr[oV.idx[j]], pt * (ov - deq));
-        }
+  for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const TileRegs<D, NO2> cur = nxt;
+    if (tile + 1 < tile_end) {
+      nxt.load_fixed(v, a.len, b, h, tile + 1, tid, wave, nn, g);
+      nxt.load_placed(v, b, h, tile + 1, counts_of(tile + 1, 0), counts_of(tile + 1, 1), tid, wave, nn, g);
+    }
+    const QaqCounts cK = cur.cK, cV = cur.cV;
+    const int n_tok = cur.n_tok;
+    const QaqKRegions rK = qaq_k_regions(cK, D);
+    const QaqVRegions rV = qaq_v_regions(cV, D);
+    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
+    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const int n32K = cK.n32(), n32V = cV.n32();
+    const int first8V = n32V + cV.n4;
+
+    // bound on w/p over the tile: the largest effective value scale
+    float smax_l = 0.0f;
+    if (tid < n_tok) {
+      const int bits = cV.bits_of_slot(tid);
+      const float range = h2f((uint16_t)(cur.mmV >> 16)) - h2f((uint16_t)(cur.mmV & 0xffffu));
+      smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
+    }
+    smax_l = wave_max(smax_l);
+
+    // ---- keys: logits ----------------------------------------------------------------------------
+    float vmax = -INFINITY;
+    if (wave * 64 < n32K) {
+      float dotq = real_of(k_contract<D, 2>(cur.kw2, abase0));
+      const bool three = tid < cK.n3;
+      if (wave * 64 < cK.n3) {
+        const float low = real_of(k_contract<D, 1>(cur.kw1, abase1));
+        dotq = three ? 2.0f * dotq + low : dotq;
       }
-      if (s >= first8V) S.w8[s - first8V] = w;
+      if (tid < n32K) {
+        const float lg = key_logit(cur.mmK, cur.oK, three ? 3 : 2, dotq);
+        S.logit[(cur.posK >> cur.pbyte) & 0xffu] = lg;
+        vmax = lg;
+      }
     }
-    // Fixed point in units of 2^(e-30), e = exponent of the bound: W = round(w * 2^(30-e-sh)),
-    // sh = what the spreading mask of the slot's place in its unit leaves on the code.  A
-    // 3-bit code is 2*top + low, so its top plane weighs 2w (at most the bound) and its
-    // low plane w.  Every entry of a digit table in use is written exactly once (zero
-    // where the slot is not in that region), so partial units multiply padding by zero.
-    const bool fx = live && smax > 0.0f;
-    const int vg = (s & 15) >> 2;
-    const int W2 = (fx && s < n32V) ? (int)rintf(ldexpf(w, 30 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0;
-    const uint32_t d2 = digits_packed(W2);
-    S.wl2[0][s] = (int8_t)d2; S.wl2[1][s] = (int8_t)(d2 >> 8); S.wl2[2][s] = (int8_t)(d2 >> 16); S.wl2[3][s] = (int8_t)(d2 >> 24);
-    if (cV.n3 > 0) {
-      const int W1 = (fx && s < cV.n3) ? (int)rintf(ldexpf(w, 30 - wexp - shift1(vg))) : 0;
-      const uint32_t d1 = digits_packed(W1);
-      S.wl1[0][s] = (int8_t)d1; S.wl1[1][s] = (int8_t)(d1 >> 8); S.wl1[2][s] = (int8_t)(d1 >> 16); S.wl1[3][s] = (int8_t)(d1 >> 24);
+    // wider classes: loaded when needed (few tokens at the operating points of interest)
+    for (int grp = wave; grp * 64 < cK.n4; grp += 4) {
+      uint32_t w[KRec<D, 4>::RDW];
+      const int idx = grp * 64 + lane;
+      KRec<D, 4>::load(baseK + rK.r4, min(idx, cK.n4 - 1), w);
+      const v4i cc = k_contract<D, 4>(w, abase2);
+      if (idx < cK.n4) {
+        const size_t gi = gi0 + n32K + idx;
+        Outl<NO2> o; o.load(v, 0, gi, no2);
+        const float lg = key_logit(v.mm[0][gi], o, 4, real_of(cc));
+        S.logit[v.perm[0][gi]] = lg;
+        vmax = fmaxf(vmax, lg);
+      }
     }
-    if (cV.n4 > 0) {
-      const int i4 = (s - n32V) & (QAQ_TT - 1);
-      const int W4 = (fx && s >= n32V && s < first8V) ? (int)rintf(ldexpf(w, 30 - wexp)) : 0;
-      const uint32_t d4 = digits_packed(W4);
-      S.wl4[0][i4] = (int8_t)d4; S.wl4[1][i4] = (int8_t)(d4 >> 8); S.wl4[2][i4] = (int8_t)(d4 >> 16); S.wl4[3][i4] = (int8_t)(d4 >> 24);
+    // 8-bit key bytes are stored as code - 128: the dot product needs 128 * sum of the
+    // (unscaled) query integers back, rebuilt here from their digits (this class is rare)
+    float sumqi = 0.0f;
+    if (cK.n8 > 0) {
+      int sq = 0;
+      for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
+      sumqi = (float)sq;
+    }
+    for (int grp = wave; grp * 64 < cK.n8; grp += 4) {
+      uint32_t w[KRec<D, 8>::RDW];
+      const int idx = grp * 64 + lane;
+      KRec<D, 8>::load(baseK + rK.r8, min(idx, cK.n8 - 1), w);
+      const v4i cc = k_contract<D, 8>(w, abase2);
+      if (idx < cK.n8) {
+        const size_t gi = gi0 + n32K + cK.n4 + idx;
+        Outl<NO2> o; o.load(v, 0, gi, no2);
+        const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
+        const float lg = key_logit(v.mm[0][gi], o, 8, dotq);
+        S.logit[v.perm[0][gi]] = lg;
+        vmax = fmaxf(vmax, lg);
+      }
+    }
+    vmax = wave_max(vmax);
+    if (lane == 0) { S.red[8 + wave] = vmax; S.red[12 + wave] = smax_l; }
+    lds_barrier();
+    const float m_tile = fmaxf(fmaxf(S.red[8], S.red[9]), fmaxf(S.red[10], S.red[11]));
+    const float smax = fmaxf(fmaxf(S.red[12], S.red[13]), fmaxf(S.red[14], S.red[15]));
+    const float M = fmaxf(m_run, m_tile);
+    const float keep = __expf(m_run - M);          // 0 on the first tile
+    m_run = M;
+    int wexp = 0;
+    if (smax > 0.0f) (void)frexpf(smax, &wexp);
+    const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 30) : 0.0f;
+
+    // ---- values: weight of slot `tid`, as digits -------------------------------------------------
+    if (a.scores && tid < n_tok) a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
+    {
+      const int s = tid;
+      const bool live = s < n_tok;
+      float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
+      if (live) {
+        pt = __expf(S.logit[(cur.posV >> cur.pbyte) & 0xffu] - M);
+        const float mn = h2f((uint16_t)(cur.mmV & 0xffffu)), mx = h2f((uint16_t)(cur.mmV >> 16));
+        const float range = mx - mn;
+        const int bits = cV.bits_of_slot(s);
+        const float scale = ldexpf(range, -bits);
+        w = pt * scale;
+        bias_l = pt * mn + 0.5f * w;
+        const float ctop = (float)((1 << bits) - 1) + 0.5f;
+#pragma unroll
+        for (int j = 0; j < Outl<NO2>::CAP; ++j) {
+          if (j < NO2 && j < no2) {
+            const float ov = cur.oV.val(j);
+            const float deq = mn + ((ov >= mx && range > 0.0f) ? ctop : 0.5f) * scale;
+            atomicAdd(&S.xcorr[cur.oV.idx(j)], pt * (ov - deq));
+          }
+        }
+        if (s >= first8V) S.w8[s - first8V] = w;
+      }
+      l_run = l_run * keep + pt;
+      bias_run = bias_run * keep + bias_l;
+      // Fixed point in units of 2^(e-30), e = exponent of the bound: W = round(w * 2^(30-e-sh)),
+      // sh = what the spreading mask of the slot's place in its unit leaves on the code.  A
+      // 3-bit code is 2*top + low, so its top plane weighs 2w (at most the bound) and its
+      // low plane w.  Every entry of a digit table in use is written exactly once (zero
+      // where the slot is not in that region), so partial units multiply padding by zero.
+      const bool fx = live && smax > 0.0f;
+      const int vg = (s & 15) >> 2;
+      const int W2 = (fx && s < n32V) ? (int)rintf(ldexpf(w, 30 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0;
+      const uint32_t d2 = digits_packed(W2);
+      S.wl2[0][s] = (int8_t)d2; S.wl2[1][s] = (int8_t)(d2 >> 8); S.wl2[2][s] = (int8_t)(d2 >> 16); S.wl2[3][s] = (int8_t)(d2 >> 24);
+      if (cV.n3 > 0) {
+        const int W1 = (fx && s < cV.n3) ? (int)rintf(ldexpf(w, 30 - wexp - shift1(vg))) : 0;
+        const uint32_t d1 = digits_packed(W1);
+        S.wl1[0][s] = (int8_t)d1; S.wl1[1][s] = (int8_t)(d1 >> 8); S.wl1[2][s] = (int8_t)(d1 >> 16); S.wl1[3][s] = (int8_t)(d1 >> 24);
+      }
+      if (cV.n4 > 0) {
+        const int i4 = (s - n32V) & (QAQ_TT - 1);
+        const int W4 = (fx && s >= n32V && s < first8V) ? (int)rintf(ldexpf(w, 30 - wexp)) : 0;
+        const uint32_t d4 = digits_packed(W4);
+        S.wl4[0][i4] = (int8_t)d4; S.wl4[1][i4] = (int8_t)(d4 >> 8); S.wl4[2][i4] = (int8_t)(d4 >> 16); S.wl4[3][i4] = (int8_t)(d4 >> 24);
+      }
+    }
+    lds_barrier();
+
+    // ---- values: integer contractions, rows 0..3 of the tile = the four digits of w -----------
+    v4i cv[CGW];
+#pragma unroll
+    for (int j = 0; j < CGW; ++j) cv[j] = zero4;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      if (blk * 64 < n32V) {
+        const v4i wa = *(const v4i*)(wb2 + 64 * blk);
+#pragma unroll
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&cur.vw2[blk][j], 0), cv[j]);
+      }
+      if (blk * 64 < cV.n3) {
+        const v4i wa = *(const v4i*)(wb1 + 64 * blk);
+#pragma unroll
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&cur.vw1[blk], (CGW * wave + j) & 1), cv[j]);
+      }
+    }
+    for (int blk = 0; blk * 64 < cV.n4; ++blk) {
+      const int u = blk * 4 + g;                 // 16 slots = half-units 2u, 2u+1
+      const int nhu = (cV.n4 + 7) >> 3;
+      uint32_t w0[CGW], w1d[CGW];
+      // a half-unit past the end repeats the last one; its slots carry zero digits
+      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
+      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
+      const v4i wa = *(const v4i*)(wb4 + 64 * blk);
+#pragma unroll
+      for (int j = 0; j < CGW; ++j) {
+        const uint32_t pr[2] = {w0[j], w1d[j]};
+        cv[j] = mma(wa, spread<4>(pr, 0), cv[j]);
+      }
+    }
+    // 8-bit codes: token-major bytes, plain fp32 multiply-add; this wavefront's D/4 channels,
+    // lane = (token sub-index, 4 channels)
+    if (cV.n8 > 0) {
+      constexpr int LPT8 = D / 16;         // lanes per token (4 channels each)
+      constexpr int TPW = 64 / LPT8;       // tokens per pass
+      float a8[4] = {0.f, 0.f, 0.f, 0.f};
+      const int sub = lane / LPT8, ch4 = lane % LPT8;
+      for (int i8 = sub; i8 < cV.n8; i8 += TPW) {
+        const float w8 = S.w8[i8];
+        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)i8 * D + (D / 4) * wave + 4 * ch4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw >> (8 * j)) & 255u);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float t = a8[j];
+#pragma unroll
+        for (int o = LPT8; o < 64; o <<= 1) t += __shfl_xor(t, o);
+        if (sub == 0) S.xw[wave][4 * ch4 + j] = t;
+      }
+    }
+    // lanes of group 0 hold rows 0..3 = digit sums of channel 16*(CGW*wave + j) + n
+    if (g == 0) {
+#pragma unroll
+      for (int j = 0; j < CGW; ++j) {
+        const float hi = (float)cv[j][3] * 16777216.0f + (float)cv[j][2] * 65536.0f;
+        const float lo = (float)cv[j][1] * 256.0f + (float)cv[j][0];
+        const int chl = 16 * j + nn;                   // channel inside this wavefront's share
+        const int ch = (D / 4) * wave + chl;
+        float xt = (hi + lo) * wscale + S.xcorr[ch];
+        S.xcorr[ch] = 0.0f;                            // ready for the next tile's corrections
+        if (cV.n8 > 0) xt += S.xw[wave][chl];
+        xrun[j] = xrun[j] * keep + xt;
+      }
     }
   }
+
+  // ---- one partial per workgroup -----------------------------------------------------------------
   {
-    const float ls = wave_sum(pt);
-    const float bs = wave_sum(bias_l);
+    const float ls = wave_sum(l_run);
+    const float bs = wave_sum(bias_run);
     if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
   }
-  __syncthreads();
+  lds_barrier();
   const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
   const float bias = (S.red[4] + S.red[5]) + (S.red[6] + S.red[7]);
-
-  // ---- values: integer contractions, rows 0..3 of the tile = the four digits of w -------------
-  const int8_t* wb2 = nn < 4 ? &S.wl2[nn][16 * g] : &S.zrow[0];
-  const int8_t* wb1 = nn < 4 ? &S.wl1[nn][16 * g] : &S.zrow[0];
-  const int8_t* wb4 = nn < 4 ? &S.wl4[nn][16 * g] : &S.zrow[0];
-  v4i cv[CGW];
-#pragma unroll
-  for (int j = 0; j < CGW; ++j) cv[j] = zero4;
-#pragma unroll
-  for (int blk = 0; blk < 4; ++blk) {
-    if (blk * 64 < n32V) {
-      const v4i wa = *(const v4i*)(wb2 + 64 * blk);
-#pragma unroll
-      for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&vw2[blk][j], 0), cv[j]);
-    }
-    if (blk * 64 < cV.n3) {
-      const v4i wa = *(const v4i*)(wb1 + 64 * blk);
-#pragma unroll
-      for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&vw1[blk], (CGW * wave + j) & 1), cv[j]);
-    }
-  }
-  for (int blk = 0; blk * 64 < cV.n4; ++blk) {
-    const int u = blk * 4 + g;                 // 16 slots = half-units 2u, 2u+1
-    const int nhu = (cV.n4 + 7) >> 3;
-    uint32_t w0[CGW], w1d[CGW];
-    // a half-unit past the end repeats the last one; its slots carry zero digits
-    load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
-    load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
-    const v4i wa = *(const v4i*)(wb4 + 64 * blk);
-#pragma unroll
-    for (int j = 0; j < CGW; ++j) {
-      const uint32_t pr[2] = {w0[j], w1d[j]};
-      cv[j] = mma(wa, spread<4>(pr, 0), cv[j]);
-    }
-  }
-  // 8-bit codes: token-major bytes, plain fp32 multiply-add; this wavefront's D/4 channels,
-  // lane = (token sub-index, 4 channels)
-  float x8 = 0.0f;
-  if (cV.n8 > 0) {
-    constexpr int LPT8 = D / 16;         // lanes per token (4 channels each)
-    constexpr int TPW = 64 / LPT8;       // tokens per pass
-    float a8[4] = {0.f, 0.f, 0.f, 0.f};
-    const int sub = lane / LPT8, ch4 = lane % LPT8;
-    for (int i8 = sub; i8 < cV.n8; i8 += TPW) {
-      const float w8 = S.w8[i8];
-      const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)i8 * D + (D / 4) * wave + 4 * ch4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw >> (8 * j)) & 255u);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float t = a8[j];
-#pragma unroll
-      for (int o = LPT8; o < 64; o <<= 1) t += __shfl_xor(t, o);
-      if (sub == 0) S.xw[wave][4 * ch4 + j] = t;
-    }
-  }
-  // lanes of group 0 hold rows 0..3 = digit sums of channel 16*(CGW*wave + j) + n
-  float* part = v.partial + ((size_t)bq * v.NT + tile) * (D + 4);
+  float* part = v.partial + ((size_t)bq * v.NT + chunk) * (D + 4);
   if (g == 0) {
 #pragma unroll
-    for (int j = 0; j < CGW; ++j) {
-      const float hi = (float)cv[j][3] * 16777216.0f + (float)cv[j][2] * 65536.0f;
-      const float lo = (float)cv[j][1] * 256.0f + (float)cv[j][0];
-      const int chl = 16 * j + nn;                   // channel inside this wavefront's share
-      const int ch = (D / 4) * wave + chl;
-      if (cV.n8 > 0) x8 = S.xw[wave][chl];
-      part[ch] = (hi + lo) * wscale + x8 + S.xcorr[ch] + bias;
-    }
+    for (int j = 0; j < CGW; ++j) part[(D / 4) * wave + 16 * j + nn] = xrun[j] + bias;
   }
-  if (tid == 0) { part[D] = M; part[D + 1] = lsum; }
+  if (tid == 0) { part[D] = m_run; part[D + 1] = lsum; }
 }
 
 // Merge the tiles of one (sequence, query head), add the unquantized new token and
@@ -492,7 +589,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
-  const int nparts = (a.len + QAQ_TT - 1) / QAQ_TT;
+  const int nparts = a.nparts;
   const float* part = v.partial + (size_t)bq * v.NT * (D + 4);
   float* sc = a.scores ? a.scores + (size_t)bq * a.score_stride : nullptr;
   const int t0 = blockIdx.x * (4 * kThreads);
@@ -583,13 +680,28 @@ void launch_tile(const QaqAttnArgs& a, dim3 grid, hipStream_t s) {
 
 }  // namespace
 
-hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev) {
+hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent_t* ev) {
+  QaqAttnArgs a = a_in;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
+  // tiles per workgroup: as few as keeps the whole grid resident at once (three workgroups
+  // per compute unit), so that no second, partly filled round of workgroups trails the first
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+    if (n_cu <= 0) n_cu = 256;
+  }
+  const int slots = 3 * n_cu;
+  const int per_head = slots / BQ > 0 ? slots / BQ : 1;
+  a.ntc = ntile > 0 ? (ntile + per_head - 1) / per_head : 1;
+  if (a.ntc > QAQ_MAX_NTC) a.ntc = QAQ_MAX_NTC;
+  a.nparts = ntile > 0 ? (ntile + a.ntc - 1) / a.ntc : 0;
   if (ev) { (void)hipEventRecord(ev[0], s); (void)hipEventRecord(ev[1], s); }
   if (ntile > 0) {
-    if (a.v.D == 128) launch_tile<128>(a, dim3(ntile, BQ), s);
-    else launch_tile<64>(a, dim3(ntile, BQ), s);
+    if (a.v.D == 128) launch_tile<128>(a, dim3(a.nparts, BQ), s);
+    else launch_tile<64>(a, dim3(a.nparts, BQ), s);
   }
   if (ev) (void)hipEventRecord(ev[2], s);
   const int nblk = a.scores ? (a.len + 4 * kThreads - 1) / (4 * kThreads) : 1;

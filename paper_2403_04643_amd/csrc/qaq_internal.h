@@ -76,6 +76,8 @@ struct QaqAttnArgs {
   int out_is_fp32;
   float* scores;          // [B,Hq,len(+1)] or null
   int score_stride;       // len (+1)
+  int ntc;                // tiles per workgroup of the tile kernel (set by the launcher)
+  int nparts;             // partials per (sequence, query head)
 };
 
 struct QaqExportArgs {
