@@ -55,6 +55,15 @@ __device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t (&w)[N]) 
   }
 }
 
+// Tells the compiler that a pointer is the same in every lane (it then lives in scalar
+// registers and loads take the scalar-base + 32-bit-lane-offset form).
+template <class T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+  const uint64_t x = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+  return (T*)(((uint64_t)hi << 32) | lo);
+}
+
 // Workgroup barrier that orders LDS traffic only.  All communication between the threads
 // of these kernels goes through LDS, and __syncthreads() would also wait for every global
 // load in flight -- including the loads of the next tile that are meant to stay in flight
@@ -146,7 +155,11 @@ struct TileLds {
   alignas(16) int8_t wl4[4][QAQ_TT];    // ... of the 4-bit region
   float w8[QAQ_TT];                     // fp32 weights of the 8-bit slots
   float xw[4][D / 4];                   // per-wavefront 8-bit-class outputs (its own channels)
-  float xcorr[D];                       // outlier corrections of the output
+  float xcorr[D];                       // outlier corrections of the output (end of the chunk)
+  alignas(16) int xc[D][16];            // ... of one tile, fixed point, 16 copies per channel (by lane % 16):
+                                        // integer LDS atomics are several times faster than float ones, the
+                                        // copies keep tokens that share a hot channel off one address, and
+                                        // the sums do not depend on the order of arrival
   float red[16];
   int redi[4];
 };
@@ -175,24 +188,26 @@ __device__ __forceinline__ v4i k_contract(const uint32_t (&w)[KRec<D, BF>::RDW],
 template <int NO2>
 struct Outl {
   static constexpr int CAP = NO2 ? NO2 : 1;
-  uint32_t i2, v2, half;      // NO2 == 2: word holding the two channel bytes, two fp16 values
+  uint32_t i2, v2;            // NO2 == 2: word holding the two channel bytes, two fp16 values
   uint8_t idx8[CAP];          // NO2 > 2
   uint16_t val8[CAP];
-  __device__ __forceinline__ void load(const QaqView& v, int side, size_t gi, int no2) {
+  // gi0: first slot of the tile (uniform), slot: the lane's slot inside the tile
+  __device__ __forceinline__ void load(const QaqView& v, int side, size_t gi0, uint32_t slot, int no2) {
     if constexpr (NO2 == 2) {
       // whole aligned words only (the channel pair is one half of its word): nothing has
       // to be done to the loaded register until it is used
-      i2 = *(const uint32_t*)(v.oidx[side] + ((gi * 2) & ~(size_t)3));
-      v2 = *(const uint32_t*)(v.oval[side] + gi * 2);
-      half = (uint32_t)(gi & 1);
+      i2 = *(const uint32_t*)(uniform_ptr(v.oidx[side] + gi0 * 2) + ((2u * slot) & ~3u));
+      v2 = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.oval[side] + gi0 * 2)) + 4u * slot);
     } else if constexpr (NO2 > 2) {
+      const size_t gi = gi0 + slot;
 #pragma unroll
       for (int j = 0; j < NO2; ++j)
         if (j < no2) { idx8[j] = v.oidx[side][gi * no2 + j]; val8[j] = v.oval[side][gi * no2 + j]; }
     }
   }
-  __device__ __forceinline__ int idx(int j) const {
-    if constexpr (NO2 == 2) return (int)((i2 >> (16 * half + 8 * j)) & 0xffu);
+  // slot: the slot the store was loaded for (selects the half of the channel word)
+  __device__ __forceinline__ int idx(int j, uint32_t slot) const {
+    if constexpr (NO2 == 2) return (int)((i2 >> (16 * (slot & 1u) + 8 * j)) & 0xffu);
     else return idx8[j];
   }
   __device__ __forceinline__ float val(int j) const {
@@ -210,29 +225,31 @@ struct TileRegs {
   int n_tok;
   uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
   uint32_t mmK, mmV;
-  uint32_t posK, posV, pbyte;
+  uint32_t posK, posV;
   Outl<NO2> oK, oV;
   uint32_t vw2[4][CGW], vw1[4];
 
-  // Part 1: everything whose address does not depend on the class counts.
+  // Part 1: everything whose address does not depend on the class counts.  Addresses are
+  // a per-tile uniform base (scalar registers) plus a 32-bit lane offset.
   __device__ __forceinline__ void load_fixed(const QaqView& v, int len, int b, int h, int tile, int tid, int wave, int nn, int g) {
     n_tok = min(len - tile * QAQ_TT, QAQ_TT);
-    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
-    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
-    const size_t gis = qaq_slot_index(v, b, h, tile, min(tid, n_tok - 1));
-    mmK = v.mm[0][gis]; mmV = v.mm[1][gis];
-    posK = *(const uint32_t*)(v.perm[0] + (gis & ~(size_t)3));    // aligned word; byte gis%4 is the position
-    posV = *(const uint32_t*)(v.perm[1] + (gis & ~(size_t)3));
-    pbyte = 8u * (uint32_t)(gis & 3);
-    oK.load(v, 0, gis, v.no2);
-    oV.load(v, 1, gis, v.no2);
+    const uint8_t* baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    const uint8_t* baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
+    mmK = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.mm[0] + gi0)) + 4u * slot);
+    mmV = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.mm[1] + gi0)) + 4u * slot);
+    posK = *(const uint32_t*)(uniform_ptr(v.perm[0] + gi0) + (slot & ~3u));   // aligned word; byte slot%4 is the position
+    posV = *(const uint32_t*)(uniform_ptr(v.perm[1] + gi0) + (slot & ~3u));
+    oK.load(v, 0, gi0, slot, v.no2);
+    oV.load(v, 1, gi0, slot, v.no2);
     // The 2-bit field regions start at offset 0 of the tile side; slots past the region
     // read other bytes of the same tile (always inside its reserved capacity) and their
     // results are not used.
-    KRec<D, 2>::load(baseK, tid, kw2);
+    load_dwords<KRec<D, 2>::RDW>(baseK + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
+    const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
-      load_dwords<CGW>(baseV + (uint32_t)(blk * 4 + g) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, vw2[blk]);
+    for (int blk = 0; blk < 4; ++blk) load_dwords<CGW>(baseV + voff + (uint32_t)blk * (16u * D), vw2[blk]);
   }
   // Part 2: the 1-bit field regions, behind the 2-bit ones, placed by the counts.
   __device__ __forceinline__ void load_placed(const QaqView& v, int b, int h, int tile, const QaqCounts& ck,
@@ -287,9 +304,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     const float am = wave_max(fabsf(qv));
     const float sm = wave_sum(qv);
     if (lane == 0) { S.red[wave] = am; S.red[4 + wave] = sm; }
-    S.qf[tid] = qv; S.xcorr[tid] = 0.0f;
+    S.qf[tid] = qv;
   }
   S.zrow[tid] = 0;
+  for (int e = tid; e < D * 16; e += kThreads) (&S.xc[0][0])[e] = 0;
   lds_barrier();
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
@@ -319,18 +337,20 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   const int8_t* wb4 = nn < 4 ? &S.wl4[nn][16 * g] : &S.zrow[0];
 
   auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale; };
-  auto key_logit = [&](uint32_t m, const Outl<NO2>& o, int bits, float dotq) {
+  auto key_logit = [&](uint32_t m, const Outl<NO2>& o, uint32_t slot, int bits, float dotq) {
     const float mn = h2f((uint16_t)(m & 0xffffu)), mx = h2f((uint16_t)(m >> 16));
     const float range = mx - mn;
     const float scale = ldexpf(range, -bits);
     float val = mn * sumq + scale * (dotq + 0.5f * sumq);
-    const float ctop = (float)((1 << bits) - 1) + 0.5f;
+    // an outlier above the range was coded 2^B-1 (reconstruction max - scale/2), one below
+    // it 0 (min + scale/2): replace that reconstruction by the stored value
+    const float hs = 0.5f * scale;
 #pragma unroll
     for (int j = 0; j < Outl<NO2>::CAP; ++j) {
       if (j < NO2 && j < no2) {
         const float ov = o.val(j);
-        const float deq = mn + ((ov >= mx && range > 0.0f) ? ctop : 0.5f) * scale;
-        val += S.qf[o.idx(j)] * (ov - deq);
+        const bool top = ov >= mx;
+        val += S.qf[o.idx(j, slot)] * ((ov - (top ? mx : mn)) + (top ? hs : -hs));
       }
     }
     return val * inv_sqrt_d;
@@ -348,18 +368,22 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   // carried across the tiles
   float m_run = -INFINITY;          // reference of everything below
   float l_run = 0.0f, bias_run = 0.0f;    // per thread: softmax sum and constant terms of its slots
+  float c_run = 0.0f;               // threads 0..D-1: outlier correction of channel tid
   float xrun[CGW];                  // lanes of group 0: output of channel 16*(CGW*wave+j)+n
 #pragma unroll
   for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const TileRegs<D, NO2> cur = nxt;
+  // Two register sets take turns (the tile being computed, the tile being loaded), so no
+  // register copies are needed between iterations.
+  TileRegs<D, NO2> alt;
+  auto do_tile = [&](const TileRegs<D, NO2>& cur, TileRegs<D, NO2>& nxt, int tile) {
     if (tile + 1 < tile_end) {
       nxt.load_fixed(v, a.len, b, h, tile + 1, tid, wave, nn, g);
       nxt.load_placed(v, b, h, tile + 1, counts_of(tile + 1, 0), counts_of(tile + 1, 1), tid, wave, nn, g);
     }
     const QaqCounts cK = cur.cK, cV = cur.cV;
     const int n_tok = cur.n_tok;
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);   // the slot this lane's metadata was loaded for
     const QaqKRegions rK = qaq_k_regions(cK, D);
     const QaqVRegions rV = qaq_v_regions(cV, D);
     const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
@@ -372,8 +396,16 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     float smax_l = 0.0f;
     if (tid < n_tok) {
       const int bits = cV.bits_of_slot(tid);
-      const float range = h2f((uint16_t)(cur.mmV >> 16)) - h2f((uint16_t)(cur.mmV & 0xffffu));
+      const float mn = h2f((uint16_t)(cur.mmV & 0xffffu)), mx = h2f((uint16_t)(cur.mmV >> 16));
+      const float range = mx - mn;
       smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
+      // ... and of what an outlier correction can be (same fixed-point exponent serves both)
+#pragma unroll
+      for (int j = 0; j < Outl<NO2>::CAP; ++j)
+        if (j < NO2 && j < no2) {
+          const float ov = cur.oV.val(j);
+          smax_l = fmaxf(smax_l, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
+        }
     }
     smax_l = wave_max(smax_l);
 
@@ -387,8 +419,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
         dotq = three ? 2.0f * dotq + low : dotq;
       }
       if (tid < n32K) {
-        const float lg = key_logit(cur.mmK, cur.oK, three ? 3 : 2, dotq);
-        S.logit[(cur.posK >> cur.pbyte) & 0xffu] = lg;
+        const float lg = key_logit(cur.mmK, cur.oK, slot, three ? 3 : 2, dotq);
+        S.logit[(cur.posK >> (8u * (slot & 3u))) & 0xffu] = lg;
         vmax = lg;
       }
     }
@@ -400,8 +432,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
       const v4i cc = k_contract<D, 4>(w, abase2);
       if (idx < cK.n4) {
         const size_t gi = gi0 + n32K + idx;
-        Outl<NO2> o; o.load(v, 0, gi, no2);
-        const float lg = key_logit(v.mm[0][gi], o, 4, real_of(cc));
+        Outl<NO2> o; o.load(v, 0, gi0, (uint32_t)(n32K + idx), no2);
+        const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + idx), 4, real_of(cc));
         S.logit[v.perm[0][gi]] = lg;
         vmax = fmaxf(vmax, lg);
       }
@@ -423,9 +455,9 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
       const v4i cc = k_contract<D, 8>(w, abase2);
       if (idx < cK.n8) {
         const size_t gi = gi0 + n32K + cK.n4 + idx;
-        Outl<NO2> o; o.load(v, 0, gi, no2);
+        Outl<NO2> o; o.load(v, 0, gi0, (uint32_t)(n32K + cK.n4 + idx), no2);
         const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
-        const float lg = key_logit(v.mm[0][gi], o, 8, dotq);
+        const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + cK.n4 + idx), 8, dotq);
         S.logit[v.perm[0][gi]] = lg;
         vmax = fmaxf(vmax, lg);
       }
@@ -440,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     m_run = M;
     int wexp = 0;
     if (smax > 0.0f) (void)frexpf(smax, &wexp);
-    const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 30) : 0.0f;
+    const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 28) : 0.0f;
 
     // ---- values: weight of slot `tid`, as digits -------------------------------------------------
     if (a.scores && tid < n_tok) a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
@@ -449,49 +481,65 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
       const bool live = s < n_tok;
       float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
       if (live) {
-        pt = __expf(S.logit[(cur.posV >> cur.pbyte) & 0xffu] - M);
+        pt = __expf(S.logit[(cur.posV >> (8u * (slot & 3u))) & 0xffu] - M);
         const float mn = h2f((uint16_t)(cur.mmV & 0xffffu)), mx = h2f((uint16_t)(cur.mmV >> 16));
         const float range = mx - mn;
         const int bits = cV.bits_of_slot(s);
         const float scale = ldexpf(range, -bits);
         w = pt * scale;
         bias_l = pt * mn + 0.5f * w;
-        const float ctop = (float)((1 << bits) - 1) + 0.5f;
+        const float hs = 0.5f * scale;
 #pragma unroll
         for (int j = 0; j < Outl<NO2>::CAP; ++j) {
           if (j < NO2 && j < no2) {
             const float ov = cur.oV.val(j);
-            const float deq = mn + ((ov >= mx && range > 0.0f) ? ctop : 0.5f) * scale;
-            atomicAdd(&S.xcorr[cur.oV.idx(j)], pt * (ov - deq));
+            const bool top = ov >= mx;
+            // |correction| < 2^wexp, at most 32 arrive per copy: units of 2^(wexp-25) cannot overflow
+            const float cval = pt * ((ov - (top ? mx : mn)) + (top ? hs : -hs));
+            atomicAdd(&S.xc[cur.oV.idx(j, slot)][lane & 15], (int)rintf(ldexpf(cval, 25 - wexp)));
           }
         }
         if (s >= first8V) S.w8[s - first8V] = w;
       }
       l_run = l_run * keep + pt;
       bias_run = bias_run * keep + bias_l;
-      // Fixed point in units of 2^(e-30), e = exponent of the bound: W = round(w * 2^(30-e-sh)),
-      // sh = what the spreading mask of the slot's place in its unit leaves on the code.  A
-      // 3-bit code is 2*top + low, so its top plane weighs 2w (at most the bound) and its
-      // low plane w.  Every entry of a digit table in use is written exactly once (zero
-      // where the slot is not in that region), so partial units multiply padding by zero.
+      // Fixed point in units of 2^(e-28), e = exponent of the bound: W = round(w * 2^(28-e-sh)),
+      // sh = what the spreading mask of the slot's place in its unit leaves on the code.
+      // Weights are not negative, so W is split into four base-128 digits (0..127, valid
+      // signed bytes).  A 3-bit code is 2*top + low, so its top plane weighs 2w (at most the
+      // bound) and its low plane w.  Every entry of a digit table in use is written exactly
+      // once (zero where the slot is not in that region), so partial units multiply padding
+      // by zero.
       const bool fx = live && smax > 0.0f;
       const int vg = (s & 15) >> 2;
-      const int W2 = (fx && s < n32V) ? (int)rintf(ldexpf(w, 30 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0;
-      const uint32_t d2 = digits_packed(W2);
-      S.wl2[0][s] = (int8_t)d2; S.wl2[1][s] = (int8_t)(d2 >> 8); S.wl2[2][s] = (int8_t)(d2 >> 16); S.wl2[3][s] = (int8_t)(d2 >> 24);
+      const uint32_t W2 = (fx && s < n32V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0u;
+      S.wl2[0][s] = (int8_t)(W2 & 127u); S.wl2[1][s] = (int8_t)((W2 >> 7) & 127u);
+      S.wl2[2][s] = (int8_t)((W2 >> 14) & 127u); S.wl2[3][s] = (int8_t)(W2 >> 21);
       if (cV.n3 > 0) {
-        const int W1 = (fx && s < cV.n3) ? (int)rintf(ldexpf(w, 30 - wexp - shift1(vg))) : 0;
-        const uint32_t d1 = digits_packed(W1);
-        S.wl1[0][s] = (int8_t)d1; S.wl1[1][s] = (int8_t)(d1 >> 8); S.wl1[2][s] = (int8_t)(d1 >> 16); S.wl1[3][s] = (int8_t)(d1 >> 24);
+        const uint32_t W1 = (fx && s < cV.n3) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift1(vg))) : 0u;
+        S.wl1[0][s] = (int8_t)(W1 & 127u); S.wl1[1][s] = (int8_t)((W1 >> 7) & 127u);
+        S.wl1[2][s] = (int8_t)((W1 >> 14) & 127u); S.wl1[3][s] = (int8_t)(W1 >> 21);
       }
       if (cV.n4 > 0) {
         const int i4 = (s - n32V) & (QAQ_TT - 1);
-        const int W4 = (fx && s >= n32V && s < first8V) ? (int)rintf(ldexpf(w, 30 - wexp)) : 0;
-        const uint32_t d4 = digits_packed(W4);
-        S.wl4[0][i4] = (int8_t)d4; S.wl4[1][i4] = (int8_t)(d4 >> 8); S.wl4[2][i4] = (int8_t)(d4 >> 16); S.wl4[3][i4] = (int8_t)(d4 >> 24);
+        const uint32_t W4 = (fx && s >= n32V && s < first8V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp)) : 0u;
+        S.wl4[0][i4] = (int8_t)(W4 & 127u); S.wl4[1][i4] = (int8_t)((W4 >> 7) & 127u);
+        S.wl4[2][i4] = (int8_t)((W4 >> 14) & 127u); S.wl4[3][i4] = (int8_t)(W4 >> 21);
       }
     }
     lds_barrier();
+    // outlier corrections of this tile: channel tid sums its 16 copies in a fixed order,
+    // carries the result like the output, and clears the copies for the next tile
+    if (wave < KS) {
+      int4* c4 = (int4*)&S.xc[tid][0];
+      const int4 x0 = c4[0], x1 = c4[1], x2 = c4[2], x3 = c4[3];
+      const int4 z = {0, 0, 0, 0};
+      c4[0] = z; c4[1] = z; c4[2] = z; c4[3] = z;
+      // each copy is below 2^30 in magnitude: pairs are summed exactly as integers, then in fp32
+      const float sum = (((float)(x0.x + x0.y) + (float)(x0.z + x0.w)) + ((float)(x1.x + x1.y) + (float)(x1.z + x1.w))) +
+                        (((float)(x2.x + x2.y) + (float)(x2.z + x2.w)) + ((float)(x3.x + x3.y) + (float)(x3.z + x3.w)));
+      c_run = c_run * keep + sum * ldexpf(wscale, 3);     // wscale = 2^(wexp-28)
+    }
 
     // ---- values: integer contractions, rows 0..3 of the tile = the four digits of w -----------
     v4i cv[CGW];
@@ -549,16 +597,18 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     if (g == 0) {
 #pragma unroll
       for (int j = 0; j < CGW; ++j) {
-        const float hi = (float)cv[j][3] * 16777216.0f + (float)cv[j][2] * 65536.0f;
-        const float lo = (float)cv[j][1] * 256.0f + (float)cv[j][0];
+        const float hi = (float)cv[j][3] * 2097152.0f + (float)cv[j][2] * 16384.0f;   // base-128 digits
+        const float lo = (float)cv[j][1] * 128.0f + (float)cv[j][0];
         const int chl = 16 * j + nn;                   // channel inside this wavefront's share
-        const int ch = (D / 4) * wave + chl;
-        float xt = (hi + lo) * wscale + S.xcorr[ch];
-        S.xcorr[ch] = 0.0f;                            // ready for the next tile's corrections
+        float xt = (hi + lo) * wscale;
         if (cV.n8 > 0) xt += S.xw[wave][chl];
         xrun[j] = xrun[j] * keep + xt;
       }
     }
+  };
+  for (int tile = tile_begin; tile < tile_end; tile += 2) {
+    do_tile(nxt, alt, tile);
+    if (tile + 1 < tile_end) do_tile(alt, nxt, tile + 1);
   }
 
   // ---- one partial per workgroup -----------------------------------------------------------------
@@ -566,6 +616,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     const float ls = wave_sum(l_run);
     const float bs = wave_sum(bias_run);
     if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
+    if (wave < KS) S.xcorr[tid] = c_run;
   }
   lds_barrier();
   const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
@@ -573,7 +624,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   float* part = v.partial + ((size_t)bq * v.NT + chunk) * (D + 4);
   if (g == 0) {
 #pragma unroll
-    for (int j = 0; j < CGW; ++j) part[(D / 4) * wave + 16 * j + nn] = xrun[j] + bias;
+    for (int j = 0; j < CGW; ++j) part[(D / 4) * wave + 16 * j + nn] = xrun[j] + bias + S.xcorr[(D / 4) * wave + 16 * j + nn];
   }
   if (tid == 0) { part[D] = m_run; part[D + 1] = lsum; }
 }
