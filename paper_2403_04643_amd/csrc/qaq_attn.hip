@@ -55,13 +55,36 @@ __device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t (&w)[N]) 
   }
 }
 
-// Tells the compiler that a pointer is the same in every lane (it then lives in scalar
-// registers and loads take the scalar-base + 32-bit-lane-offset form).
-template <class T>
-__device__ __forceinline__ T* uniform_ptr(T* p) {
+// Global-memory pointer whose value is the same in every lane: goes through scalar
+// registers, keeps the global address space (a pointer rebuilt from integers would
+// otherwise become a generic one, whose loads also count as LDS traffic), and lets loads
+// take the scalar-base + 32-bit-lane-offset form.
+typedef const __attribute__((address_space(1))) uint8_t* gbytes_t;
+__device__ __forceinline__ gbytes_t uniform_ptr(const void* p) {
   const uint64_t x = (uint64_t)p;
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-  return (T*)(((uint64_t)hi << 32) | lo);
+  return (gbytes_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t gload32(gbytes_t base, uint32_t off) {
+  return *(const __attribute__((address_space(1))) uint32_t*)(base + off);
+}
+template <int N>
+__device__ __forceinline__ void gload_dwords(gbytes_t p, uint32_t (&w)[N]) {
+  typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  if constexpr (N == 1) {
+    w[0] = *(const __attribute__((address_space(1))) uint32_t*)p;
+  } else if constexpr (N == 2) {
+    const u2 t = *(const __attribute__((address_space(1))) u2*)p;
+    w[0] = t.x; w[1] = t.y;
+  } else {
+    static_assert(N % 4 == 0, "dword count");
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+      const u4 t = ((const __attribute__((address_space(1))) u4*)p)[i];
+      w[4 * i] = t.x; w[4 * i + 1] = t.y; w[4 * i + 2] = t.z; w[4 * i + 3] = t.w;
+    }
+  }
 }
 
 // Workgroup barrier that orders LDS traffic only.  All communication between the threads
@@ -196,8 +219,8 @@ struct Outl {
     if constexpr (NO2 == 2) {
       // whole aligned words only (the channel pair is one half of its word): nothing has
       // to be done to the loaded register until it is used
-      i2 = *(const uint32_t*)(uniform_ptr(v.oidx[side] + gi0 * 2) + ((2u * slot) & ~3u));
-      v2 = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.oval[side] + gi0 * 2)) + 4u * slot);
+      i2 = gload32(uniform_ptr(v.oidx[side] + gi0 * 2), (2u * slot) & ~3u);
+      v2 = gload32(uniform_ptr(v.oval[side] + gi0 * 2), 4u * slot);
     } else if constexpr (NO2 > 2) {
       const size_t gi = gi0 + slot;
 #pragma unroll
@@ -233,23 +256,23 @@ struct TileRegs {
   // a per-tile uniform base (scalar registers) plus a 32-bit lane offset.
   __device__ __forceinline__ void load_fixed(const QaqView& v, int len, int b, int h, int tile, int tid, int wave, int nn, int g) {
     n_tok = min(len - tile * QAQ_TT, QAQ_TT);
-    const uint8_t* baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
-    const uint8_t* baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
+    const gbytes_t baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    const gbytes_t baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
     const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
-    mmK = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.mm[0] + gi0)) + 4u * slot);
-    mmV = *(const uint32_t*)(uniform_ptr((const uint8_t*)(v.mm[1] + gi0)) + 4u * slot);
-    posK = *(const uint32_t*)(uniform_ptr(v.perm[0] + gi0) + (slot & ~3u));   // aligned word; byte slot%4 is the position
-    posV = *(const uint32_t*)(uniform_ptr(v.perm[1] + gi0) + (slot & ~3u));
+    mmK = gload32(uniform_ptr(v.mm[0] + gi0), 4u * slot);
+    mmV = gload32(uniform_ptr(v.mm[1] + gi0), 4u * slot);
+    posK = gload32(uniform_ptr(v.perm[0] + gi0), slot & ~3u);   // aligned word; byte slot%4 is the position
+    posV = gload32(uniform_ptr(v.perm[1] + gi0), slot & ~3u);
     oK.load(v, 0, gi0, slot, v.no2);
     oV.load(v, 1, gi0, slot, v.no2);
     // The 2-bit field regions start at offset 0 of the tile side; slots past the region
     // read other bytes of the same tile (always inside its reserved capacity) and their
     // results are not used.
-    load_dwords<KRec<D, 2>::RDW>(baseK + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
+    gload_dwords<KRec<D, 2>::RDW>(baseK + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
     const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) load_dwords<CGW>(baseV + voff + (uint32_t)blk * (16u * D), vw2[blk]);
+    for (int blk = 0; blk < 4; ++blk) gload_dwords<CGW>(baseV + voff + (uint32_t)blk * (16u * D), vw2[blk]);
   }
   // Part 2: the 1-bit field regions, behind the 2-bit ones, placed by the counts.
   __device__ __forceinline__ void load_placed(const QaqView& v, int b, int h, int tile, const QaqCounts& ck,
