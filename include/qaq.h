@@ -172,12 +172,19 @@ int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* de
 int qaq_stats(qaq_cache* c, qaq_stats_t* host_out, void* stream);
 
 /* Measurement aid: after qaq_profile_begin(c, n), the next n qaq_decode_attention calls
- * record HIP events on their stream before, between and after their three kernels (query
- * preparation, the per-tile kernel and the merge).  qaq_profile_read waits for them and returns the
- * elapsed milliseconds of each; host arrays of at least n floats.  n = 0 switches it off. */
+ * record HIP events on their stream before, between and after their two kernels (the
+ * per-tile kernel that scans the cache, and the merge).  qaq_profile_read waits for them
+ * and returns the elapsed milliseconds of each; host arrays of at least n floats.
+ * n = 0 switches it off. */
 int qaq_profile_begin(qaq_cache* c, int32_t max_calls);
-int qaq_profile_read(qaq_cache* c, float* host_ms_prep, float* host_ms_main, float* host_ms_merge,
-                     int32_t* n_calls);
+int qaq_profile_read(qaq_cache* c, float* host_ms_tile, float* host_ms_merge, int32_t* n_calls);
+
+/* Measurement aids: plain streaming kernels over caller-owned device memory, the yardstick
+ * for what this GPU sustains on a pure read (16-byte loads, every byte once, a checksum
+ * per workgroup written to dev_sink[0..1023] so that the loads are kept) and on a copy.
+ * bytes must be a multiple of 16, pointers 16-byte aligned.  Asynchronous on `stream`. */
+int qaq_stream_read(const void* dev_src, size_t bytes, uint32_t* dev_sink, void* stream);
+int qaq_stream_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stream);
 
 /* Number of outliers kept per end of a token vector for this configuration. */
 int qaq_outliers_per_side(const qaq_config* cfg);

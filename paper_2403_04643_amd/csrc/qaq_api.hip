@@ -84,6 +84,35 @@ void thresholds(const qaq_cache* c, int T, float* tau_k, float* c_v) {
 
 }  // namespace
 
+// ---- streaming yardsticks ------------------------------------------------------------
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Grid-stride 16-byte loads; every workgroup folds what it read into one word so that the
+// compiler keeps the loads.
+__global__ void __launch_bounds__(256) k_stream_read(const u32x4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+  u32x4 acc = {0, 0, 0, 0};
+  size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+    u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+    acc ^= a ^ b ^ c ^ d;
+  }
+  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+  for (int o = 32; o; o >>= 1) x ^= __shfl_xor(x, o);
+  __shared__ uint32_t part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+__global__ void __launch_bounds__(256) k_stream_copy(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
+  size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 extern "C" {
 
 const char* qaq_last_error(void) { return g_err; }
@@ -135,7 +164,6 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.counts = (uint16_t*)(base + a.counts);
   v.ring = (float*)(base + a.ring);
   v.partial = (float*)(base + a.partial);
-  v.qprep = base + a.qprep;
   v.statbuf = (long long*)(base + a.statbuf);
   v.refused = (unsigned int*)(base + a.refused);
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
@@ -274,7 +302,7 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
   a.scores = dev_scores_out;
   a.score_stride = c->len + (dev_k_new ? 1 : 0);
   hipEvent_t* ev = nullptr;
-  if (!c->prof_ev.empty() && (size_t)(4 * c->prof_n + 4) <= c->prof_ev.size()) ev = &c->prof_ev[4 * c->prof_n++];
+  if (!c->prof_ev.empty() && (size_t)(3 * c->prof_n + 3) <= c->prof_ev.size()) ev = &c->prof_ev[3 * c->prof_n++];
   hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev);
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
   return QAQ_OK;
@@ -285,7 +313,7 @@ int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.clear();
   c->prof_n = 0;
-  for (int i = 0; i < 4 * max_calls; ++i) {
+  for (int i = 0; i < 3 * max_calls; ++i) {
     hipEvent_t e;
     hipError_t r = hipEventCreate(&e);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_begin");
@@ -294,14 +322,13 @@ int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   return QAQ_OK;
 }
 
-int qaq_profile_read(qaq_cache* c, float* host_ms_prep, float* host_ms_main, float* host_ms_merge, int32_t* n_calls) {
-  if (!c || !host_ms_prep || !host_ms_main || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+int qaq_profile_read(qaq_cache* c, float* host_ms_tile, float* host_ms_merge, int32_t* n_calls) {
+  if (!c || !host_ms_tile || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   *n_calls = c->prof_n;
   for (int i = 0; i < c->prof_n; ++i) {
-    hipError_t r = hipEventSynchronize(c->prof_ev[4 * i + 3]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_prep[i], c->prof_ev[4 * i], c->prof_ev[4 * i + 1]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_main[i], c->prof_ev[4 * i + 1], c->prof_ev[4 * i + 2]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[4 * i + 2], c->prof_ev[4 * i + 3]);
+    hipError_t r = hipEventSynchronize(c->prof_ev[3 * i + 2]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_tile[i], c->prof_ev[3 * i], c->prof_ev[3 * i + 1]);
+    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[3 * i + 1], c->prof_ev[3 * i + 2]);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_read");
   }
   c->prof_n = 0;
@@ -360,6 +387,23 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
   out->refused_upgrades = refused;
   return QAQ_OK;
+}
+
+int qaq_stream_read(const void* dev_src, size_t bytes, uint32_t* dev_sink, void* stream) {
+  if (!dev_src || !dev_sink || (bytes & 15) || ((uintptr_t)dev_src & 15)) return fail(QAQ_ERR_INVALID_ARG, "qaq_stream_read: NULL or unaligned argument");
+  if (bytes == 0) return QAQ_OK;
+  hipLaunchKernelGGL(k_stream_read, dim3(1024), dim3(256), 0, (hipStream_t)stream, (const u32x4*)dev_src, bytes / 16, dev_sink);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? QAQ_OK : hip_fail(e, "qaq_stream_read");
+}
+
+int qaq_stream_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stream) {
+  if (!dev_src || !dev_dst || (bytes & 15) || ((uintptr_t)dev_src & 15) || ((uintptr_t)dev_dst & 15))
+    return fail(QAQ_ERR_INVALID_ARG, "qaq_stream_copy: NULL or unaligned argument");
+  if (bytes == 0) return QAQ_OK;
+  hipLaunchKernelGGL(k_stream_copy, dim3(2048), dim3(256), 0, (hipStream_t)stream, (u32x4*)dev_dst, (const u32x4*)dev_src, bytes / 16);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? QAQ_OK : hip_fail(e, "qaq_stream_copy");
 }
 
 // Host-only view of the code layout, for layout tests: where the field of width

@@ -772,16 +772,16 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   a.ntc = ntile > 0 ? (ntile + per_head - 1) / per_head : 1;
   if (a.ntc > QAQ_MAX_NTC) a.ntc = QAQ_MAX_NTC;
   a.nparts = ntile > 0 ? (ntile + a.ntc - 1) / a.ntc : 0;
-  if (ev) { (void)hipEventRecord(ev[0], s); (void)hipEventRecord(ev[1], s); }
+  if (ev) (void)hipEventRecord(ev[0], s);
   if (ntile > 0) {
     if (a.v.D == 128) launch_tile<128>(a, dim3(a.nparts, BQ), s);
     else launch_tile<64>(a, dim3(a.nparts, BQ), s);
   }
-  if (ev) (void)hipEventRecord(ev[2], s);
+  if (ev) (void)hipEventRecord(ev[1], s);
   const int nblk = a.scores ? (a.len + 4 * kThreads - 1) / (4 * kThreads) : 1;
   dim3 grid(nblk < 1 ? 1 : nblk, BQ);
   if (a.v.D == 128) hipLaunchKernelGGL(k_attn_combine<128>, grid, dim3(kThreads), 0, s, a);
   else hipLaunchKernelGGL(k_attn_combine<64>, grid, dim3(kThreads), 0, s, a);
-  if (ev) (void)hipEventRecord(ev[3], s);
+  if (ev) (void)hipEventRecord(ev[2], s);
   return hipGetLastError();
 }

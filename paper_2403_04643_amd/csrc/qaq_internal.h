@@ -21,7 +21,6 @@ struct QaqView {
   uint16_t* counts;
   float* ring;
   float* partial;
-  uint8_t* qprep;
   long long* statbuf;
   unsigned int* refused;
   int B, Hq, Hkv, D, Tmax, NT, no2, window;

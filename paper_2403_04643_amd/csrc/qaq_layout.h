@@ -160,7 +160,6 @@ struct QaqArena {
   size_t counts;      // u16  [B][Hkv][NT][2][4]
   size_t ring;        // f32  [window][B][Hkv][Tmax]
   size_t partial;     // f32  [B][Hq][NT][D+4]
-  size_t qprep;       // per (B,Hq): query digits for the key contractions, 12*D + 16 bytes
   size_t statbuf;     // i64  [32]
   size_t refused;     // u32  [4]
   size_t total;
@@ -182,7 +181,6 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   a.counts = off; off = qaq_up256(off + bh * d.NT * 2 * 4 * 2);
   a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * 4);
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
-  a.qprep = off; off = qaq_up256(off + (size_t)d.B * d.Hq * (12 * d.D + 16));
   a.statbuf = off; off = qaq_up256(off + 32 * 8);
   a.refused = off; off = qaq_up256(off + 16);
   a.total = off;

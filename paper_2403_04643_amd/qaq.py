@@ -52,7 +52,9 @@ SIGNATURES = {
     "qaq_select_bits": (C.c_int, [_vp, _f32p, _u8p, _u8p, _vp]),
     "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _i32, _vp]),
     "qaq_profile_begin": (C.c_int, [_vp, _i32]),
-    "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
+    "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
+    "qaq_stream_read": (C.c_int, [_vp, C.c_size_t, _vp, _vp]),
+    "qaq_stream_copy": (C.c_int, [_vp, _vp, C.c_size_t, _vp]),
     "qaq_decode_attention": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _f32p, _vp]),
     "qaq_dequantize": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp]),
     "qaq_export_canonical": (C.c_int, [_vp, _i32, _u8p, _vp, _u8p, _vp, _u8p, _vp]),
@@ -207,14 +209,13 @@ class Cache:
         self._prof_cap = max_calls
 
     def profile_read(self):
-        """Returns (ms of the query preparation, of the per-tile kernel, of the merge kernel), one
-        list entry per profiled call."""
+        """Returns (ms of the per-tile kernel, ms of the merge kernel), one list entry per
+        profiled call."""
         n = C.c_int32()
         a = (C.c_float * max(self._prof_cap, 1))()
         b = (C.c_float * max(self._prof_cap, 1))()
-        p = (C.c_float * max(self._prof_cap, 1))()
-        _check(self.lib.qaq_profile_read(self.h, p, a, b, C.byref(n)))
-        return list(p[: n.value]), list(a[: n.value]), list(b[: n.value])
+        _check(self.lib.qaq_profile_read(self.h, a, b, C.byref(n)))
+        return list(a[: n.value]), list(b[: n.value])
 
     def decode_attention(self, q, k_new=None, v_new=None, out=None, scores_out=None, want_scores=False, out_fp32=True):
         """q: fp16 [B, Hq, D]; k_new, v_new: fp16 [B, Hkv, D] or None.
