@@ -1,0 +1,152 @@
+"""GPU parity at the full sizes of the stated configurations (2^20 token-heads per layer),
+in the launch configuration the benchmark times: the whole batch goes through libqaq in
+one call per operation, and the CPU oracle recomputes a seeded sample of (sequence, KV head)
+units one by one -- every unit is independent of the others, so a unit's oracle result is the
+full-size result for that unit.  Widths, codes, [min,max] and outlier lists of the sampled
+units are compared bit for bit, attention within 2e-3; properties that hold at any size
+(scores sum to one, outputs inside the value range) are checked on every head."""
+import numpy as np
+import pytest
+
+from oracle import qaq_oracle as O
+from paper_2403_04643_amd import qaq, workloads as W
+from tests.parity_util import F16, F32, attention_errors, dev
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def _unit_oracle(sh, qn, b, h, **kw):
+    """Oracle cache holding the single unit (sequence b, KV head h) with its G query heads."""
+    G = sh.n_q_heads // sh.n_kv_heads
+    cfg = O.Config(1, G, 1, sh.head_dim, qnorm2=np.asarray([qn[h]], F32), **kw)
+    return O.OracleCache(cfg), G
+
+
+def _compare_unit(ex, side_heads, b, h, D, n_o, tag):
+    hc = side_heads
+    np.testing.assert_array_equal(ex["bits"][b, h], hc.bits, err_msg=tag + " bits")
+    np.testing.assert_array_equal(ex["minmax"][b, h, :, 0].astype(F32), hc.mn.astype(F32), err_msg=tag + " min")
+    np.testing.assert_array_equal(ex["minmax"][b, h, :, 1].astype(F32), hc.mx.astype(F32), err_msg=tag + " max")
+    if n_o:
+        idx, val = hc.outlier_lists()
+        np.testing.assert_array_equal(ex["oidx"][b, h], idx, err_msg=tag + " outlier idx")
+        np.testing.assert_array_equal(ex["oval"][b, h].view(np.uint16), val.view(np.uint16), err_msg=tag + " outlier val")
+    want = np.zeros((hc.T, D), np.uint8)
+    for t in range(hc.T):
+        p = hc.packed(t)
+        want[t, : len(p)] = p
+    np.testing.assert_array_equal(ex["codes"][b, h], want, err_msg=tag + " packed codes")
+
+
+def _global_properties(X, S, V, Vnew):
+    S = S.cpu().numpy()
+    np.testing.assert_allclose(S.sum(-1, dtype=np.float64), 1.0, rtol=2e-5)
+    assert np.isfinite(S).all() and (S >= 0).all()
+    X = X.cpu().numpy()
+    assert np.isfinite(X).all()
+    # a convex combination of reconstructed values: inside the per-channel value range,
+    # widened by half a 2-bit quantization step of the widest token range
+    G = X.shape[1] // V.shape[1]
+    lo = np.minimum(V.min(2), Vnew).astype(F32).repeat(G, 1)
+    hi = np.maximum(V.max(2), Vnew).astype(F32).repeat(G, 1)
+    slack = (hi.max(-1, keepdims=True) - lo.min(-1, keepdims=True)) / 8 + 1e-3
+    assert (X >= lo - slack).all() and (X <= hi + slack).all()
+
+
+def _sample_units(sh, n, seed):
+    rng = np.random.default_rng(seed)
+    picks = {(0, 0), (sh.batch - 1, sh.n_kv_heads - 1)}
+    while len(picks) < n:
+        picks.add((int(rng.integers(sh.batch)), int(rng.integers(sh.n_kv_heads))))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("cfgno,p_k,p_v", [
+    (2, (0.49, 0.50, 0.007, 0.003), (0.89, 0.10, 0.007, 0.003)),   # the benchmark's operating point, plus a few wide tokens
+    (5, (0.3, 0.3, 0.3, 0.1), (0.5, 0.3, 0.15, 0.05)),              # 8 query heads per KV head
+])
+def test_full_size_given_widths(cfgno, p_k, p_v):
+    sh = W.shape(cfgno)
+    _log(f"full size cfg={cfgno} shape={sh}")
+    K, V = W.make_kv(cfgno, sh)
+    rng = np.random.default_rng(97 + cfgno)
+    widths = np.array([2, 3, 4, 8], np.uint8)
+    bk = rng.choice(widths, size=K.shape[:3], p=p_k)
+    bv = rng.choice(widths, size=K.shape[:3], p=p_v)
+    qn = np.full(sh.n_kv_heads, 0.01, F32)
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context + 1, qn.tolist()))
+    gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(cfgno, sh)[0]
+    kn, vn = W.make_new_token(cfgno, sh)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    _global_properties(X, S, V, vn)
+    Xg, Sg = X.cpu().numpy(), S.cpu().numpy()
+    exK = {k: v.cpu().numpy() for k, v in gc.export_canonical(0).items()}
+    exV = {k: v.cpu().numpy() for k, v in gc.export_canonical(1).items()}
+    worst = 0.0
+    for b, h in _sample_units(sh, 5, 11 + cfgno):
+        oc, G = _unit_oracle(sh, qn, b, h)
+        oc.append(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], bk[b:b + 1, h:h + 1], bv[b:b + 1, h:h + 1])
+        _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"K b={b} h={h}")
+        _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"V b={b} h={h}")
+        Xo, So = oc.decode_attention(q[b:b + 1, h * G:(h + 1) * G], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
+        _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+        worst = max(worst, ex.max(), es.max())
+        assert ex.max() < TOL and es.max() < TOL
+    _log(f"  worst sampled error {worst:.2e}")
+
+
+def test_long_context_selected_widths():
+    """Config 4: context 32768, widths chosen by the value rule from a Zipf(1.1) importance
+    profile and by the key rule, narrowed in place from the 8-bit prefill, then attention."""
+    sh = W.shape(4)
+    _log(f"full size cfg=4 shape={sh}")
+    K, V = W.make_kv(4, sh)
+    T = sh.context
+    rows = W.zipf_score_rows(sh, T)
+    qcal = W.make_queries(4, sh, n=32, seed_offset=9)
+    qn = np.full(sh.n_kv_heads, O.query_norm_statistic(qcal, sh.head_dim), F32)
+    # hyper-parameters that spread the widths: centre the thresholds on the ranges of one unit
+    probe, _ = _unit_oracle(sh, qn, 0, 0)
+    probe.append(K[:1, :1], V[:1, :1])
+    rk, rv = probe.K[0][0].ranges().astype(np.float64), probe.V[0][0].ranges().astype(np.float64)
+    sigma_x = float(np.median(rv * rows[0, 0]) * np.sqrt(T) / (2 * np.sqrt(3)) / 2 ** 2.5)
+    var_k = (np.median(rk) / 2 ** 3.0 / (2 * np.sqrt(3))) ** 2
+    sigma_s = float(np.sqrt(np.expm1(var_k * float(qn[0])) * (T - 1) / T ** 3))
+    kw = dict(sigma_s_max=sigma_s, sigma_x_max=sigma_x, window=5)
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, T + 1, qn.tolist(), **kw))
+    gc.quantize_append(dev(K), dev(V))
+    bk, bv = gc.select_bits(dev(rows))
+    gc.requantize(bk, bv)
+    bk, bv = bk.cpu().numpy(), bv.cpu().numpy()
+    hist_v = [int((bv == w).sum()) for w in (2, 3, 4, 8)]
+    hist_k = [int((bk == w).sum()) for w in (2, 3, 4, 8)]
+    _log(f"  width histograms K {hist_k} V {hist_v}")
+    assert min(hist_v) > 0, "value widths must spread over all of {2,3,4,8}"
+    q = W.make_queries(4, sh)[0]
+    kn, vn = W.make_new_token(4, sh)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    _global_properties(X, S, V, vn)
+    Xg, Sg = X.cpu().numpy(), S.cpu().numpy()
+    exK = {k: v.cpu().numpy() for k, v in gc.export_canonical(0).items()}
+    exV = {k: v.cpu().numpy() for k, v in gc.export_canonical(1).items()}
+    for b, h in _sample_units(sh, 3, 15):
+        oc, G = _unit_oracle(sh, qn, b, h, **kw)
+        oc.append(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1])
+        oc.observe(rows[b:b + 1, h * G:(h + 1) * G])
+        bko, bvo = oc.select_bits()
+        np.testing.assert_array_equal(bk[b, h], bko[0, 0])
+        np.testing.assert_array_equal(bv[b, h], bvo[0, 0])
+        oc.requantize(bko, bvo)
+        _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"K b={b} h={h}")
+        _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"V b={b} h={h}")
+        Xo, So = oc.decode_attention(q[b:b + 1, h * G:(h + 1) * G], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
+        _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+        assert ex.max() < TOL and es.max() < TOL
