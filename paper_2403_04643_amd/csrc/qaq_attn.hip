@@ -2,9 +2,12 @@
 // the midpoint reconstruction of Section 4.1 with the outlier side store of Section 4.2).
 //
 // Two kernels per call:
-//   k_attn_tile     one workgroup per (sequence, query head, tile of 256 positions):
-//                   logits, tile-local softmax, unnormalised output -> partial (max, sum, X)
-//   k_attn_combine  merges the tiles, adds the unquantized new token, normalises scores
+//   k_attn_tile     one workgroup per chunk of consecutive 256-position tiles of one
+//                   (sequence, query head), three workgroups resident per compute unit:
+//                   logits, softmax with a running max and sum over the chunk, unnormalised
+//                   output -> partial (max, sum, X); the next tile's loads stay in flight
+//                   while the current tile is computed
+//   k_attn_combine  merges the chunks, adds the unquantized new token, normalises scores
 //
 // Arithmetic.  With per-token scale_t = range_t / 2^B and codes c_td,
 //   q.K^_t  = min_t * sum(q) + scale_t * (sum_d q_d c_td + sum(q)/2) + outlier terms
