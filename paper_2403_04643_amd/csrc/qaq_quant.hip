@@ -84,13 +84,69 @@ __device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, in
 }
 
 // ---------------------------------------------------------------------------------
-// Encoder for one token vector, run by a group of D/8 consecutive lanes (8 channels
-// per lane).  Outliers: the n_o largest, then the n_o smallest of the rest, ties to
-// the lower channel; [min,max] over what remains; code = clamp(floor((x-min)*inv)).
+// Tile build (append / requantize).  Codes travel through LDS as one byte per
+// (position, channel); both directions between that staging form and the stored code
+// planes work on whole 32-bit words: one AND and one shift move four codes, and the
+// token-transposed value planes go through 4x4 byte transposes in registers.
 // ---------------------------------------------------------------------------------
 template <int D>
-__device__ void encode_token(const __half* src, int gl, bool fresh, int bits, int n_o, uint32_t* mm_pos,
-                             uint8_t* oidx_row, uint16_t* oval_row, uint8_t* stage_row) {
+struct BuildLds {
+  static constexpr int SROW = D / 4 + 1;   // dwords per staged row; the odd stride spreads rows over the banks
+  uint32_t stage[QAQ_TT * SROW];           // byte d of row pos = code of channel d
+  uint32_t mm[QAQ_TT];                     // fp16 min | fp16 max << 16, by position
+  uint8_t oidx[QAQ_TT][QAQ_MAX_NO2];       // outlier channels, by position
+  uint16_t oval[QAQ_TT][QAQ_MAX_NO2];      // outlier fp16 values
+  uint8_t bits_old[QAQ_TT];
+  uint8_t bits_new[QAQ_TT];
+  uint8_t shf[QAQ_TT];                     // low bits a staged code still has to drop (narrowing)
+  uint16_t pos_of_slot[QAQ_TT];
+  uint16_t slot_of_pos[QAQ_TT];
+  int wave_cnt[4][4];
+};
+
+// rows of four bytes <-> columns of four bytes: t[k] byte j = w[j] byte k
+__device__ __forceinline__ void transpose4(const uint32_t (&w)[4], uint32_t (&t)[4]) {
+  const uint32_t a = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);   // w0.b0 w1.b0 w0.b1 w1.b1
+  const uint32_t b = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);   // w0.b2 w1.b2 w0.b3 w1.b3
+  const uint32_t c = __builtin_amdgcn_perm(w[3], w[2], 0x05010400u);
+  const uint32_t d = __builtin_amdgcn_perm(w[3], w[2], 0x07030602u);
+  t[0] = __builtin_amdgcn_perm(c, a, 0x05040100u);
+  t[1] = __builtin_amdgcn_perm(c, a, 0x07060302u);
+  t[2] = __builtin_amdgcn_perm(d, b, 0x05040100u);
+  t[3] = __builtin_amdgcn_perm(d, b, 0x07060302u);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xf, 0xf, false);
+}
+// Reduction over the LPT (8 or 16) consecutive lanes that share a token; every lane of the
+// group ends up with the result.  Groups are aligned, so the exchanges stay inside them.
+template <int LPT, class Op>
+__device__ __forceinline__ uint32_t group_reduce(uint32_t x, Op op) {
+  x = op(x, dpp_u<0xB1>(x));                       // quad_perm [1,0,3,2]
+  x = op(x, dpp_u<0x4E>(x));                       // quad_perm [2,3,0,1]
+  x = op(x, dpp_u<0x141>(x));                      // row_half_mirror
+  if constexpr (LPT == 16) x = op(x, dpp_u<0x140>(x));   // row_mirror
+  return x;
+}
+struct OpUMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
+struct OpUMin { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; } };
+struct OpFMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b))); } };
+struct OpFMin { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return __float_as_uint(fminf(__uint_as_float(a), __uint_as_float(b))); } };
+
+// ---------------------------------------------------------------------------------
+// Encoder for one token vector, run by a group of D/8 consecutive lanes (8 channels
+// per lane).  Outliers (Section 4.2): the n_o largest, then the n_o smallest of the
+// rest, ties to the lower channel; [min,max] over what remains; then the midpoint
+// quantizer of Section 4.1: code = clamp(floor((x-min)*2^B/range)).
+// Values are ordered through integer keys: the fp32 image of an fp16 value has its low
+// 13 bits clear, so the channel number rides in the low 7 bits of the order-preserving
+// integer form, and "largest value, lowest channel" is a single unsigned maximum.
+// ---------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void encode_token(const __half* src, int gl, bool fresh, int bits, int n_o, uint32_t* mm_pos,
+                                             uint8_t* oidx_row, uint16_t* oval_row, uint32_t* stage_row) {
   constexpr int LPT = D / 8;
   const uint4 raw = ((const uint4*)src)[gl];
   const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -99,39 +155,41 @@ __device__ void encode_token(const __half* src, int gl, bool fresh, int bits, in
   for (int j = 0; j < 8; ++j) x[j] = h2f((uint16_t)(rw[j >> 1] >> (16 * (j & 1))));
   float mn, mx;
   if (fresh) {
+    uint32_t ord[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t b = __float_as_uint(x[j] + 0.0f);   // -0 compares equal to +0
+      ord[j] = (b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u)) & ~0x7fu;
+    }
     uint32_t marked = 0;
     for (int k = 0; k < 2 * n_o; ++k) {
       const bool top = k < n_o;
-      float best = top ? -INFINITY : INFINITY;
-      int bidx = 1 << 20;
+      uint32_t best = top ? 0u : 0xffffffffu;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        // the first free element of the lane always enters, later ones only if
-        // strictly better: equal values keep the lower channel
-        const bool free_ = !((marked >> j) & 1u);
-        const bool better = top ? (x[j] > best) : (x[j] < best);
-        if (free_ && (bidx == (1 << 20) || better)) { best = x[j]; bidx = gl * 8 + j; }
+        const uint32_t ch = (uint32_t)(gl * 8 + j);
+        const uint32_t key = ord[j] | (top ? 127u - ch : ch);
+        if (!((marked >> j) & 1u)) best = top ? (key > best ? key : best) : (key < best ? key : best);
       }
+      best = top ? group_reduce<LPT>(best, OpUMax()) : group_reduce<LPT>(best, OpUMin());
+      const uint32_t ch = top ? 127u - (best & 127u) : (best & 127u);
+      if ((int)(ch >> 3) == gl) {
+        const uint32_t jj = ch & 7u;
+        marked |= 1u << jj;
+        uint32_t hv = 0;
 #pragma unroll
-      for (int off = LPT / 2; off >= 1; off >>= 1) {
-        const float ob = __shfl_xor(best, off);
-        const int oi = __shfl_xor(bidx, off);
-        const bool take = (oi < (1 << 20)) &&
-                          (bidx == (1 << 20) || (top ? (ob > best) : (ob < best)) || (ob == best && oi < bidx));
-        if (take) { best = ob; bidx = oi; }
+        for (int j = 0; j < 8; ++j)
+          if (jj == (uint32_t)j) hv = (rw[j >> 1] >> (16 * (j & 1))) & 0xffffu;
+        oidx_row[k] = (uint8_t)ch;
+        oval_row[k] = (uint16_t)hv;
       }
-      if ((bidx >> 3) == gl) marked |= 1u << (bidx & 7);
-      if (gl == 0) { oidx_row[k] = (uint8_t)bidx; oval_row[k] = f2h(best); }
     }
     mn = INFINITY; mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       if (!((marked >> j) & 1u)) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-#pragma unroll
-    for (int off = LPT / 2; off >= 1; off >>= 1) {
-      mn = fminf(mn, __shfl_xor(mn, off));
-      mx = fmaxf(mx, __shfl_xor(mx, off));
-    }
+    mn = __uint_as_float(group_reduce<LPT>(__float_as_uint(mn), OpFMin()));
+    mx = __uint_as_float(group_reduce<LPT>(__float_as_uint(mx), OpFMax()));
     if (gl == 0) *mm_pos = (uint32_t)f2h(mn) | ((uint32_t)f2h(mx) << 16);
   } else {
     const uint32_t m = *mm_pos;
@@ -140,7 +198,7 @@ __device__ void encode_token(const __half* src, int gl, bool fresh, int bits, in
   }
   const float range = mx - mn;
   const float levels = (float)(1 << bits);
-  const float inv = levels / range;
+  const float inv = range > 0.0f ? levels / range : 0.0f;   // an empty range gives code 0 everywhere
   const float top_code = levels - 1.0f;
   uint32_t lo = 0, hi = 0;
 #pragma unroll
@@ -149,12 +207,246 @@ __device__ void encode_token(const __half* src, int gl, bool fresh, int bits, in
     const float prod = diff * inv;
     float c = floorf(prod);
     c = fminf(fmaxf(c, 0.0f), top_code);
-    if (!(range > 0.0f)) c = 0.0f;
     const uint32_t ci = (uint32_t)c;
     if (j < 4) lo |= ci << (8 * j); else hi |= ci << (8 * (j - 4));
   }
-  uint2* dst = (uint2*)(stage_row + gl * 8);
-  *dst = make_uint2(lo, hi);
+  stage_row[2 * gl] = lo;
+  stage_row[2 * gl + 1] = hi;
+}
+
+// Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet).
+template <int D>
+__device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, BuildLds<D>& L) {
+  constexpr int SROW = BuildLds<D>::SROW, NQ = D / 16, KS = D / 64;
+  const int tid = threadIdx.x;
+  const int n32 = c.n32();
+  if (side == 0) {
+    const QaqKRegions r = qaq_k_regions(c, D);
+    for (int it = tid; it < n32 * NQ; it += kThreads) {
+      const int s = it / NQ, q = it % NQ;
+      const bool three = s < c.n3;
+      const uint32_t w2 = *(const uint32_t*)(base + r.r2 + 4u * (uint32_t)it);
+      uint32_t w1 = 0;
+      if (three) w1 = *(const uint32_t*)(base + r.r1 + (uint32_t)s * (D / 8) + 4u * (uint32_t)(q >> 1)) >> (4 * (q & 1));
+      uint32_t* row = &L.stage[L.pos_of_slot[s] * SROW + 16 * (q % KS) + 4 * (q / KS)];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        uint32_t code = (w2 >> (2 * v)) & 0x03030303u;
+        if (three) code = (code << 1) | ((w1 >> v) & 0x01010101u);
+        row[v] = code;
+      }
+    }
+    for (int it = tid; it < c.n4 * (D / 8); it += kThreads) {
+      const int i4 = it / (D / 8), jj = it % (D / 8), q = jj >> 1, dw = jj & 1;
+      const uint32_t w = *(const uint32_t*)(base + r.r4 + 4u * (uint32_t)it);
+      uint32_t* row = &L.stage[L.pos_of_slot[n32 + i4] * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
+      row[0] = w & 0x0f0f0f0fu;
+      row[1] = (w >> 4) & 0x0f0f0f0fu;
+    }
+    for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
+      const int i8 = it / (D / 4), jj = it % (D / 4), q = jj >> 2, v = jj & 3;
+      const uint32_t w = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
+      L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + 16 * (q % KS) + 4 * (q / KS) + v] = w ^ 0x80808080u;
+    }
+    return;
+  }
+  const QaqVRegions r = qaq_v_regions(c, D);
+  // two-bit fields: a work item is (unit of 16 tokens, four channels)
+  for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
+    const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      o[k] = *(const uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg));
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      uint32_t f[4], w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (2 * v)) & 0x03030303u;
+      transpose4(f, w);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int s = 16 * u + 4 * v + j;
+        if (s < n32) L.stage[L.pos_of_slot[s] * SROW + c4] = s < c.n3 ? w[j] << 1 : w[j];
+      }
+    }
+  }
+  // four-bit codes: (half-unit of 8 tokens, four channels)
+  for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
+    const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      o[k] = *(const uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg));
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+      uint32_t f[4], w[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (4 * g2)) & 0x0f0f0f0fu;
+      transpose4(f, w);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i4 = 8 * hu + 4 * g2 + j;
+        if (i4 < c.n4) L.stage[L.pos_of_slot[n32 + i4] * SROW + c4] = w[j];
+      }
+    }
+  }
+  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
+    const int i8 = it / (D / 4), dq = it % (D / 4);
+    L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + dq] = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
+  }
+  __syncthreads();
+  // low bits of the three-bit tokens: (unit, pair of channel groups, four channels of each)
+  for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      o[k] = *(const uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp));
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int c4 = 4 * (2 * cgp + hh) + n4;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        uint32_t f[4], w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (4 * hh + v)) & 0x01010101u;
+        transpose4(f, w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int s = 16 * u + 4 * v + j;
+          if (s < c.n3) L.stage[L.pos_of_slot[s] * SROW + c4] |= w[j];
+        }
+      }
+    }
+  }
+}
+
+// Staged bytes -> stored code planes of one tile side, in the new slot order; codes that
+// narrow drop their low bits here (the coarser grid's segments contain the finer one's).
+template <int D>
+__device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const BuildLds<D>& L) {
+  constexpr int SROW = BuildLds<D>::SROW, NQ = D / 16, KS = D / 64;
+  const int tid = threadIdx.x;
+  const int n32 = c.n32();
+  if (side == 0) {
+    const QaqKRegions r = qaq_k_regions(c, D);
+    for (int it = tid; it < n32 * NQ; it += kThreads) {
+      const int s = it / NQ, q = it % NQ;
+      const int pos = L.pos_of_slot[s];
+      const int sh = L.shf[pos] + (s < c.n3 ? 1 : 0);
+      const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
+      uint32_t w = 0;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) w |= ((row[v] >> sh) & 0x03030303u) << (2 * v);
+      *(uint32_t*)(base + r.r2 + 4u * (uint32_t)it) = w;
+    }
+    for (int it = tid; it < c.n3 * (D / 32); it += kThreads) {
+      const int s = it / (D / 32), jj = it % (D / 32);
+      const int pos = L.pos_of_slot[s];
+      const int sh = L.shf[pos];
+      uint32_t w = 0;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int q = 2 * jj + hh;
+        const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) w |= ((row[v] >> sh) & 0x01010101u) << (4 * hh + v);
+      }
+      *(uint32_t*)(base + r.r1 + 4u * (uint32_t)it) = w;
+    }
+    for (int it = tid; it < c.n4 * (D / 8); it += kThreads) {
+      const int i4 = it / (D / 8), jj = it % (D / 8), q = jj >> 1, dw = jj & 1;
+      const int pos = L.pos_of_slot[n32 + i4];
+      const int sh = L.shf[pos];
+      const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
+      *(uint32_t*)(base + r.r4 + 4u * (uint32_t)it) = ((row[0] >> sh) & 0x0f0f0f0fu) | (((row[1] >> sh) & 0x0f0f0f0fu) << 4);
+    }
+    for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
+      const int i8 = it / (D / 4), jj = it % (D / 4), q = jj >> 2, v = jj & 3;
+      const int pos = L.pos_of_slot[n32 + c.n4 + i8];
+      *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] ^ 0x80808080u;
+    }
+    return;
+  }
+  const QaqVRegions r = qaq_v_regions(c, D);
+  for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
+    const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      uint32_t w[4], t[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int s = 16 * u + 4 * v + j;
+        w[j] = 0;
+        if (s < n32) {
+          const int pos = L.pos_of_slot[s];
+          w[j] = (L.stage[pos * SROW + c4] >> (L.shf[pos] + (s < c.n3 ? 1 : 0))) & 0x03030303u;
+        }
+      }
+      transpose4(w, t);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] |= t[k] << (2 * v);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *(uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
+  }
+  for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int c4 = 4 * (2 * cgp + hh) + n4;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        uint32_t w[4], t[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int s = 16 * u + 4 * v + j;
+          w[j] = 0;
+          if (s < c.n3) {
+            const int pos = L.pos_of_slot[s];
+            w[j] = (L.stage[pos * SROW + c4] >> L.shf[pos]) & 0x01010101u;
+          }
+        }
+        transpose4(w, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * hh + v);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *(uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) = o[k];
+  }
+  for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
+    const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) {
+      uint32_t w[4], t[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i4 = 8 * hu + 4 * g2 + j;
+        w[j] = 0;
+        if (i4 < c.n4) {
+          const int pos = L.pos_of_slot[n32 + i4];
+          w[j] = (L.stage[pos * SROW + c4] >> L.shf[pos]) & 0x0f0f0f0fu;
+        }
+      }
+      transpose4(w, t);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * g2);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *(uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
+  }
+  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
+    const int i8 = it / (D / 4), dq = it % (D / 4);
+    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + dq];
+  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -163,10 +455,8 @@ __device__ void encode_token(const __half* src, int gl, bool fresh, int bits, in
 // ---------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  TileLds<D>& L = *reinterpret_cast<TileLds<D>*>(smem_raw);
-  uint32_t* outb = reinterpret_cast<uint32_t*>(smem_raw + ((sizeof(TileLds<D>) + 15) & ~(size_t)15));
-  constexpr int OUTB = QAQ_TT * D / 2 + 12 * D;   // bytes: every region but the 8-bit one
+  __shared__ BuildLds<D> L;
+  constexpr int SROW = BuildLds<D>::SROW;
 
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -195,17 +485,36 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (!__syncthreads_or(changed ? 1 : 0)) return;
   }
 
-  if (n_before > 0) tile_load<D>(v, side, b, h, tile, n_before, L);
+  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
+
+  // cached tokens: metadata by position, codes into the stage
+  if (n_before > 0) {
+    const QaqCounts c = qaq_load_counts(v, side, b, h, tile);
+    if (tid < n_before) {
+      const size_t gi = qaq_slot_index(v, b, h, tile, tid);
+      const int pos = v.perm[side][gi];
+      L.mm[pos] = v.mm[side][gi];
+      L.pos_of_slot[tid] = (uint16_t)pos;
+      L.bits_old[pos] = (uint8_t)c.bits_of_slot(tid);
+      for (int k = 0; k < v.no2; ++k) {
+        L.oidx[pos][k] = v.oidx[side][gi * v.no2 + k];
+        L.oval[pos][k] = v.oval[side][gi * v.no2 + k];
+      }
+    }
+    __syncthreads();
+    unpack_tile<D>(side, base, c, L);
+  }
 
   // final width of every position
   if (tid < n_after) {
-    int nb;
+    int nb, drop = 0;
     if (tid < n_before) {
       const int oldb = L.bits_old[tid];
       nb = oldb;
       if (a.mode == 1) {
         const int req = a.newbits[side][(size_t)bh * a.len_before + t0 + tid];
-        if (req < oldb || (req > oldb && a.orig[side])) nb = req;
+        if (req < oldb) { nb = req; drop = oldb - req; }
+        else if (req > oldb && a.orig[side]) nb = req;
       }
     } else {
       const int r = t0 + tid - a.len_before;
@@ -213,6 +522,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       L.bits_old[tid] = (uint8_t)nb;
     }
     L.bits_new[tid] = (uint8_t)nb;
+    L.shf[tid] = (uint8_t)drop;
   }
   __syncthreads();
 
@@ -229,18 +539,12 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (!fresh && !widen) continue;
       const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
-      encode_token<D>(src, gl, fresh, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], L.stage[p]);
+      encode_token<D>(src, gl, fresh, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW]);
     }
   }
   __syncthreads();
 
-  // narrowing: drop low code bits (the coarser grid's segments contain the finer one's);
   // side store of fresh tokens: order by channel
-  for (int e = tid; e < n_before * D; e += kThreads) {
-    const int pos = e / D, d = e % D;
-    const int sh = (int)L.bits_old[pos] - (int)L.bits_new[pos];
-    if (sh > 0) L.stage[pos][d] = L.stage[pos][d] >> sh;
-  }
   if (tid >= n_before && tid < n_after && v.no2 > 1) {
     for (int i = 1; i < v.no2; ++i) {
       const uint8_t ki = L.oidx[tid][i];
@@ -279,10 +583,6 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     L.slot_of_pos[tid] = (uint16_t)s;
     L.pos_of_slot[s] = (uint16_t)tid;
   }
-  uint32_t r2, r1, r4, r8, rend;
-  if (side == 0) { QaqKRegions r = qaq_k_regions(cn, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; rend = r.end; }
-  else { QaqVRegions r = qaq_v_regions(cn, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; rend = r.end; }
-  for (int i = tid; i < OUTB / 4; i += kThreads) outb[i] = 0u;
   __syncthreads();
 
   // metadata in slot order, widths by position, class counts
@@ -301,52 +601,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     uint16_t* cp = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
     cp[QC3] = (uint16_t)cn.n3; cp[QC2] = (uint16_t)cn.n2; cp[QC4] = (uint16_t)cn.n4; cp[QC8] = (uint16_t)cn.n8;
   }
-
-  // scatter the sub-byte fields into the output image
-  const int n32 = cn.n32();
-  for (int e = tid; e < n_after * D; e += kThreads) {
-    const int pos = e / D, d = e % D;
-    const int s = L.slot_of_pos[pos];
-    const uint32_t c = L.stage[pos][d];
-    if (s < n32) {
-      const bool three = s < cn.n3;
-      const uint32_t f2 = three ? (c >> 1) : c;
-      const QaqFieldPos p = side == 0 ? qaq_k_field(r2, 2, s, d, D) : qaq_v_field(r2, 2, s, d, D);
-      if (f2) atomicOr(&outb[p.byte_off >> 2], f2 << p.shift);
-      if (three && (c & 1u)) {
-        const QaqFieldPos p1 = side == 0 ? qaq_k_field(r1, 1, s, d, D) : qaq_v_field(r1, 1, s, d, D);
-        atomicOr(&outb[p1.byte_off >> 2], 1u << p1.shift);
-      }
-    } else if (s < n32 + cn.n4) {
-      const QaqFieldPos p = side == 0 ? qaq_k_field(r4, 4, s - n32, d, D) : qaq_v_field(r4, 4, s - n32, d, D);
-      if (c) atomicOr(&outb[p.byte_off >> 2], c << p.shift);
-    }
-  }
-  __syncthreads();
-
-  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
-  for (uint32_t i = tid; i < r8 / 16; i += kThreads) ((uint4*)base)[i] = ((const uint4*)outb)[i];
-  // 8-bit class: one byte per channel, straight from the stage
-  const int first8 = n32 + cn.n4;
-  for (int e = tid; e < cn.n8 * (D / 4); e += kThreads) {
-    const int i8 = e / (D / 4), dq = e % (D / 4);
-    const int pos = L.pos_of_slot[first8 + i8];
-    uint32_t w;
-    if (side == 0) {
-      constexpr int KS = D / 64;
-      const int q = dq >> 2, vv = dq & 3, g = q / KS, ks = q % KS;
-      w = *(const uint32_t*)&L.stage[pos][64 * ks + 16 * g + 4 * vv] ^ 0x80808080u;
-    } else {
-      w = *(const uint32_t*)&L.stage[pos][4 * dq];
-    }
-    *(uint32_t*)(base + r8 + (uint32_t)i8 * D + 4u * dq) = w;
-  }
-  (void)rend;
-}
-
-template <int D>
-constexpr size_t build_smem() {
-  return ((sizeof(TileLds<D>) + 15) & ~(size_t)15) + (QAQ_TT * D / 2 + 12 * D);
+  pack_tile<D>(side, base, cn, L);
 }
 
 // ---------------------------------------------------------------------------------
@@ -520,8 +775,8 @@ hipError_t qaq_launch_init(const QaqView& v, hipStream_t s) {
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles, a.v.B * a.v.Hkv, 2);
-  if (a.v.D == 128) hipLaunchKernelGGL(k_build<128>, grid, dim3(kThreads), build_smem<128>(), s, a);
-  else hipLaunchKernelGGL(k_build<64>, grid, dim3(kThreads), build_smem<64>(), s, a);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_build<128>, grid, dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(k_build<64>, grid, dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 
