@@ -120,99 +120,152 @@ template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, 0xf, 0xf, false);
 }
-// Reduction over the LPT (8 or 16) consecutive lanes that share a token; every lane of the
-// group ends up with the result.  Groups are aligned, so the exchanges stay inside them.
-template <int LPT, class Op>
-__device__ __forceinline__ uint32_t group_reduce(uint32_t x, Op op) {
-  x = op(x, dpp_u<0xB1>(x));                       // quad_perm [1,0,3,2]
-  x = op(x, dpp_u<0x4E>(x));                       // quad_perm [2,3,0,1]
-  x = op(x, dpp_u<0x141>(x));                      // row_half_mirror
-  if constexpr (LPT == 16) x = op(x, dpp_u<0x140>(x));   // row_mirror
-  return x;
+// Reductions over the four consecutive lanes (one quad) that share a token; every lane
+// of the quad ends up with the result.
+__device__ __forceinline__ uint32_t quad_umax(uint32_t x) {
+  uint32_t y = dpp_u<0xB1>(x); x = x > y ? x : y;      // quad_perm [1,0,3,2]
+  y = dpp_u<0x4E>(x); return x > y ? x : y;            // quad_perm [2,3,0,1]
 }
-struct OpUMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; } };
-struct OpUMin { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; } };
-struct OpFMax { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b))); } };
-struct OpFMin { __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return __float_as_uint(fminf(__uint_as_float(a), __uint_as_float(b))); } };
+__device__ __forceinline__ uint32_t quad_umin(uint32_t x) {
+  uint32_t y = dpp_u<0xB1>(x); x = x < y ? x : y;
+  y = dpp_u<0x4E>(x); return x < y ? x : y;
+}
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// Integer image of a float that orders like the float (unsigned compare), maps +0 and -0
+// to the same number, and has its low 13 bits clear when the float is an fp16 value: the
+// channel number can ride in the low 7 bits, so that "largest value, lowest channel" is a
+// single unsigned maximum of key + (127 - channel), and "smallest value, lowest channel"
+// a single unsigned minimum of key + channel.
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t b = __float_as_uint(x);
+  const uint32_t mag = b & 0x7fffffffu;
+  return (int32_t)b < 0 ? 0x80000000u - mag : 0x80000000u + mag;
+}
+__device__ __forceinline__ float key_value(uint32_t key) {
+  key &= ~0x7fu;
+  return key >= 0x80000000u ? __uint_as_float(key - 0x80000000u) : __uint_as_float((0x80000000u - key) | 0x80000000u);
+}
 
 // ---------------------------------------------------------------------------------
-// Encoder for one token vector, run by a group of D/8 consecutive lanes (8 channels
-// per lane).  Outliers (Section 4.2): the n_o largest, then the n_o smallest of the
-// rest, ties to the lower channel; [min,max] over what remains; then the midpoint
-// quantizer of Section 4.1: code = clamp(floor((x-min)*2^B/range)).
-// Values are ordered through integer keys: the fp32 image of an fp16 value has its low
-// 13 bits clear, so the channel number rides in the low 7 bits of the order-preserving
-// integer form, and "largest value, lowest channel" is a single unsigned maximum.
+// Encoder for one token vector, run by the four lanes of a quad; lane c holds the 8-channel
+// chunks c, c+4, c+8, ... (a quad reads 64 contiguous bytes per load).  Outliers
+// (Section 4.2): the n_o largest, then the n_o smallest of the rest, ties to the lower
+// channel; [min,max] over what remains; then the midpoint quantizer of Section 4.1:
+// code = clamp(floor((x-min)*2^B/range)).
 // ---------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void encode_token(const __half* src, int gl, bool fresh, int bits, int n_o, uint32_t* mm_pos,
+template <int D, bool ONE>   // ONE: exactly one outlier per end (the common case) has its own, shorter search
+struct TokenEncoder {
+  static constexpr int NCH = D / 32;          // 16-byte chunks per lane
+  static constexpr int EPL = 8 * NCH;         // elements per lane
+
+  __device__ static __forceinline__ uint32_t half_bits(const uint4 (&raw)[NCH], int i, int e) {
+    const uint32_t w = e < 2 ? raw[i].x : e < 4 ? raw[i].y : e < 6 ? raw[i].z : raw[i].w;
+    return (w >> (16 * (e & 1))) & 0xffffu;
+  }
+  __device__ static __forceinline__ int channel(int c, int i, int e) { return 32 * i + 8 * c + e; }
+
+  // fp16 bits of the outlier on channel ch (held by this lane), whose value is `val`
+  __device__ static __forceinline__ uint16_t outlier_bits(const uint4 (&raw)[NCH], int c, int ch, float val) {
+    uint32_t hv = f2h(val);
+    if (val == 0.0f) {   // the key does not keep the sign of a zero: take the stored bits
+#pragma unroll
+      for (int i = 0; i < NCH; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (channel(c, i, e) == ch) hv = half_bits(raw, i, e);
+    }
+    return (uint16_t)hv;
+  }
+
+  __device__ static __forceinline__ void run(const uint4 (&raw)[NCH], int c, bool fresh, int bits, int n_o, uint32_t* mm_pos,
                                              uint8_t* oidx_row, uint16_t* oval_row, uint32_t* stage_row) {
-  constexpr int LPT = D / 8;
-  const uint4 raw = ((const uint4*)src)[gl];
-  const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
-  float x[8];
+    float mn, mx;
+    if (fresh) {
+      uint32_t key_mx, key_mn;
+      if constexpr (ONE) {
+        // largest and second largest key, smallest and second smallest key, in one sweep
+        uint32_t a1 = 0u, a2 = 0u, b1 = 0xffffffffu, b2 = 0xffffffffu;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) x[j] = h2f((uint16_t)(rw[j >> 1] >> (16 * (j & 1))));
-  float mn, mx;
-  if (fresh) {
-    uint32_t ord[8];
+        for (int i = 0; i < NCH; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t b = __float_as_uint(x[j] + 0.0f);   // -0 compares equal to +0
-      ord[j] = (b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u)) & ~0x7fu;
-    }
-    uint32_t marked = 0;
-    for (int k = 0; k < 2 * n_o; ++k) {
-      const bool top = k < n_o;
-      uint32_t best = top ? 0u : 0xffffffffu;
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t k = order_key(h2f((uint16_t)half_bits(raw, i, e)));
+            const uint32_t kx = k + (uint32_t)(127 - channel(c, i, e)), kn = k + (uint32_t)channel(c, i, e);
+            a2 = umed3(a1, a2, kx); a1 = a1 > kx ? a1 : kx;
+            b2 = umed3(b1, b2, kn); b1 = b1 < kn ? b1 : kn;
+          }
+        const uint32_t A1 = quad_umax(a1), A2 = quad_umax(a1 == A1 ? a2 : a1);
+        const uint32_t B1 = quad_umin(b1), B2 = quad_umin(b1 == B1 ? b2 : b1);
+        const int ch_top = 127 - (int)(A1 & 127u);
+        // the smallest of the rest is the overall smallest unless that is the top element
+        // itself (all values equal): then it is the runner-up
+        const uint32_t Bb = (int)(B1 & 127u) == ch_top ? B2 : B1;
+        const int ch_bot = (int)(Bb & 127u);
+        if (((ch_top >> 3) & 3) == c) { oidx_row[0] = (uint8_t)ch_top; oval_row[0] = outlier_bits(raw, c, ch_top, key_value(A1)); }
+        if (((ch_bot >> 3) & 3) == c) { oidx_row[1] = (uint8_t)ch_bot; oval_row[1] = outlier_bits(raw, c, ch_bot, key_value(Bb)); }
+        // what remains: its largest value is the runner-up of the maximum search, its smallest
+        // the runner-up of the minimum search (equal values make the choice of element moot)
+        key_mx = A2; key_mn = B2;
+      } else {
+        uint32_t kx[EPL], kn[EPL];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint32_t ch = (uint32_t)(gl * 8 + j);
-        const uint32_t key = ord[j] | (top ? 127u - ch : ch);
-        if (!((marked >> j) & 1u)) best = top ? (key > best ? key : best) : (key < best ? key : best);
+        for (int i = 0; i < NCH; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t k = order_key(h2f((uint16_t)half_bits(raw, i, e)));
+            kx[8 * i + e] = k + (uint32_t)(127 - channel(c, i, e));
+            kn[8 * i + e] = k + (uint32_t)channel(c, i, e);
+          }
+        for (int k = 0; k < 2 * n_o; ++k) {
+          const bool top = k < n_o;
+          uint32_t m = top ? 0u : 0xffffffffu;
+#pragma unroll
+          for (int j = 0; j < EPL; ++j) m = top ? (m > kx[j] ? m : kx[j]) : (m < kn[j] ? m : kn[j]);
+          const uint32_t M = top ? quad_umax(m) : quad_umin(m);
+          const int ch = top ? 127 - (int)(M & 127u) : (int)(M & 127u);
+#pragma unroll
+          for (int j = 0; j < EPL; ++j) {
+            const bool dead = top ? kx[j] == M : kn[j] == M;
+            if (dead) { kx[j] = 0u; kn[j] = 0xffffffffu; }
+          }
+          if (((ch >> 3) & 3) == c) { oidx_row[k] = (uint8_t)ch; oval_row[k] = outlier_bits(raw, c, ch, key_value(M)); }
+        }
+        uint32_t m1 = 0u, m0 = 0xffffffffu;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) { m1 = m1 > kx[j] ? m1 : kx[j]; m0 = m0 < kn[j] ? m0 : kn[j]; }
+        key_mx = quad_umax(m1); key_mn = quad_umin(m0);
       }
-      best = top ? group_reduce<LPT>(best, OpUMax()) : group_reduce<LPT>(best, OpUMin());
-      const uint32_t ch = top ? 127u - (best & 127u) : (best & 127u);
-      if ((int)(ch >> 3) == gl) {
-        const uint32_t jj = ch & 7u;
-        marked |= 1u << jj;
-        uint32_t hv = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (jj == (uint32_t)j) hv = (rw[j >> 1] >> (16 * (j & 1))) & 0xffffu;
-        oidx_row[k] = (uint8_t)ch;
-        oval_row[k] = (uint16_t)hv;
-      }
+      mx = key_value(key_mx); mn = key_value(key_mn);
+      if (c == 0) *mm_pos = (uint32_t)f2h(mn) | ((uint32_t)f2h(mx) << 16);
+    } else {
+      const uint32_t m = *mm_pos;
+      mn = h2f((uint16_t)(m & 0xffffu));
+      mx = h2f((uint16_t)(m >> 16));
     }
-    mn = INFINITY; mx = -INFINITY;
+    const float range = mx - mn;
+    const float levels = (float)(1 << bits);
+    const float inv = range > 0.0f ? levels / range : 0.0f;   // an empty range gives code 0 everywhere
+    const float top_code = levels - 1.0f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (!((marked >> j) & 1u)) { mn = fminf(mn, x[j]); mx = fmaxf(mx, x[j]); }
-    mn = __uint_as_float(group_reduce<LPT>(__float_as_uint(mn), OpFMin()));
-    mx = __uint_as_float(group_reduce<LPT>(__float_as_uint(mx), OpFMax()));
-    if (gl == 0) *mm_pos = (uint32_t)f2h(mn) | ((uint32_t)f2h(mx) << 16);
-  } else {
-    const uint32_t m = *mm_pos;
-    mn = h2f((uint16_t)(m & 0xffffu));
-    mx = h2f((uint16_t)(m >> 16));
-  }
-  const float range = mx - mn;
-  const float levels = (float)(1 << bits);
-  const float inv = range > 0.0f ? levels / range : 0.0f;   // an empty range gives code 0 everywhere
-  const float top_code = levels - 1.0f;
-  uint32_t lo = 0, hi = 0;
+    for (int i = 0; i < NCH; ++i) {
+      uint32_t w[2] = {0u, 0u};
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float diff = x[j] - mn;
-    const float prod = diff * inv;
-    float c = floorf(prod);
-    c = fminf(fmaxf(c, 0.0f), top_code);
-    const uint32_t ci = (uint32_t)c;
-    if (j < 4) lo |= ci << (8 * j); else hi |= ci << (8 * (j - 4));
+      for (int e = 0; e < 8; ++e) {
+        const float diff = h2f((uint16_t)half_bits(raw, i, e)) - mn;
+        const float prod = diff * inv;
+        // the byte conversion saturates: a negative product (an outlier below min) gives 0
+        w[e >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(floorf(prod), top_code), e & 3, w[e >> 2]);
+      }
+      stage_row[2 * (4 * i + c)] = w[0];
+      stage_row[2 * (4 * i + c) + 1] = w[1];
+    }
   }
-  stage_row[2 * gl] = lo;
-  stage_row[2 * gl + 1] = hi;
-}
+};
 
 // Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet).
 template <int D>
@@ -453,7 +506,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
 // Tile build: append new tokens and / or move cached tokens to other widths, then
 // write the tile side back in class order.
 // ---------------------------------------------------------------------------------
-template <int D>
+template <int D, bool ONE>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   __shared__ BuildLds<D> L;
   constexpr int SROW = BuildLds<D>::SROW;
@@ -526,20 +579,37 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   __syncthreads();
 
-  // encode: new tokens, and cached tokens that widen (from the unquantized copy)
+  // encode: new tokens, and cached tokens that widen (from the unquantized copy).  A quad of
+  // lanes per token, 64 tokens per pass; the rows of the next pass are requested before the
+  // current pass is computed.
   {
-    constexpr int LPT = D / 8;
-    constexpr int TPP = kThreads / LPT;   // tokens per pass
-    const int gl = tid % LPT, gt = tid / LPT;
-    for (int p0 = 0; p0 < n_after; p0 += TPP) {
-      const int p = p0 + gt;
-      if (p >= n_after) continue;          // whole lane groups drop out together
+    typedef TokenEncoder<D, ONE> Enc;
+    constexpr int TPP = kThreads / 4;     // tokens per pass
+    constexpr int NP = QAQ_TT / TPP;
+    const int c = tid & 3, gt = tid >> 2;
+    auto fetch = [&](int pass, uint4 (&raw)[Enc::NCH]) -> int {   // 0 = nothing to do, 1 = fresh, 2 = widen
+      const int p = pass * TPP + gt;
+      if (pass >= NP || p >= n_after) return 0;
       const bool fresh = p >= n_before;
-      const bool widen = !fresh && L.bits_new[p] > L.bits_old[p];
-      if (!fresh && !widen) continue;
+      if (!fresh && !(L.bits_new[p] > L.bits_old[p])) return 0;
       const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
-      encode_token<D>(src, gl, fresh, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW]);
+#pragma unroll
+      for (int i = 0; i < Enc::NCH; ++i) raw[i] = ((const uint4*)src)[4 * i + c];
+      return fresh ? 1 : 2;
+    };
+    uint4 cur[Enc::NCH], nxt[Enc::NCH];
+    int kind = fetch(0, cur);
+#pragma unroll 1
+    for (int pass = 0; pass < NP; ++pass) {
+      const int kind_next = fetch(pass + 1, nxt);
+      if (kind) {                          // whole quads drop out together
+        const int p = pass * TPP + gt;
+        Enc::run(cur, c, kind == 1, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW]);
+      }
+#pragma unroll
+      for (int i = 0; i < Enc::NCH; ++i) cur[i] = nxt[i];
+      kind = kind_next;
     }
   }
   __syncthreads();
@@ -775,8 +845,14 @@ hipError_t qaq_launch_init(const QaqView& v, hipStream_t s) {
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(ntiles, a.v.B * a.v.Hkv, 2);
-  if (a.v.D == 128) hipLaunchKernelGGL(k_build<128>, grid, dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL(k_build<64>, grid, dim3(kThreads), 0, s, a);
+  const bool one = a.v.no2 == 2;
+  if (a.v.D == 128) {
+    if (one) hipLaunchKernelGGL((k_build<128, true>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_build<128, false>), grid, dim3(kThreads), 0, s, a);
+  } else {
+    if (one) hipLaunchKernelGGL((k_build<64, true>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_build<64, false>), grid, dim3(kThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 
