@@ -172,20 +172,25 @@ struct KRec {
 template <int D>
 struct TileLds {
   float qf[D];
-  alignas(16) int8_t ql[3][4][D];       // query digits [format][digit][position in record order]
+  // Rows that different lanes of one 16-byte LDS read address together (digit rows of the
+  // query, digit rows of the weights) are 16 bytes longer than their payload, so that equal
+  // offsets in different rows fall into different banks.
+  alignas(16) int8_t ql[3][4][D + 16];  // query digits [format][digit][position in record order]
   alignas(16) int8_t zrow[256];         // zeros: A operand of lanes whose row carries nothing
   alignas(16) uint16_t cnt[QAQ_MAX_NTC][8]; // class counts of the workgroup's tiles: keys, values
   float logit[QAQ_TT];                  // raw logits by position
-  alignas(16) int8_t wl2[4][QAQ_TT];    // weight digits per slot of the 2-bit field region
-  alignas(16) int8_t wl1[4][QAQ_TT];    // ... of the 1-bit field region
-  alignas(16) int8_t wl4[4][QAQ_TT];    // ... of the 4-bit region
+  alignas(16) int8_t wl2[4][QAQ_TT + 16];   // weight digits per slot of the 2-bit field region
+  alignas(16) int8_t wl1[4][QAQ_TT + 16];   // ... of the 1-bit field region
+  alignas(16) int8_t wl4[4][QAQ_TT + 16];   // ... of the 4-bit region
   float w8[QAQ_TT];                     // fp32 weights of the 8-bit slots
   float xw[4][D / 4];                   // per-wavefront 8-bit-class outputs (its own channels)
   float xcorr[D];                       // outlier corrections of the output (end of the chunk)
   alignas(16) int xc[D][16];            // ... of one tile, fixed point, 16 copies per channel (by lane % 16):
                                         // integer LDS atomics are several times faster than float ones, the
                                         // copies keep tokens that share a hot channel off one address, and
-                                        // the sums do not depend on the order of arrival
+                                        // the sums do not depend on the order of arrival.  Copy c of channel
+                                        // ch sits at column (c + 4*(ch/2)) % 16, so that neighbouring channels'
+                                        // 16-byte reads of their copies start in different banks.
   float red[16];
   int redi[4];
 };
@@ -242,56 +247,64 @@ struct Outl {
   }
 };
 
-// Everything of one tile that is loaded ahead of its arithmetic.
+// Everything of one tile that is loaded ahead of its arithmetic, in two halves: what the
+// key phase reads and what the softmax / value phases read.  Each half is reloaded for the
+// next tile as soon as its phase is over, so one register set serves the whole chunk and the
+// loads still have more than half a tile of arithmetic to arrive.  Addresses are a per-tile
+// uniform base (scalar registers) plus a 32-bit lane offset.
 template <int D, int NO2>
-struct TileRegs {
-  static constexpr int NCG = D / 16;
-  static constexpr int CGW = NCG / 4;
-  QaqCounts cK, cV;
+struct KeyRegs {
+  QaqCounts c;
   int n_tok;
   uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
-  uint32_t mmK, mmV;
-  uint32_t posK, posV;
-  Outl<NO2> oK, oV;
-  uint32_t vw2[4][CGW], vw1[4];
-
-  // Part 1: everything whose address does not depend on the class counts.  Addresses are
-  // a per-tile uniform base (scalar registers) plus a 32-bit lane offset.
-  __device__ __forceinline__ void load_fixed(const QaqView& v, int len, int b, int h, int tile, int tid, int wave, int nn, int g) {
+  uint32_t mm, pos;
+  Outl<NO2> o;
+  __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& ck, int tid, int wave) {
+    c = ck;
     n_tok = min(len - tile * QAQ_TT, QAQ_TT);
-    const gbytes_t baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
-    const gbytes_t baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
+    const uint8_t* base = qaq_tile_codes(v, 0, b, h, tile);
+    const gbytes_t ubase = uniform_ptr(base);
     const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
-    mmK = gload32(uniform_ptr(v.mm[0] + gi0), 4u * slot);
-    mmV = gload32(uniform_ptr(v.mm[1] + gi0), 4u * slot);
-    posK = gload32(uniform_ptr(v.perm[0] + gi0), slot & ~3u);   // aligned word; byte slot%4 is the position
-    posV = gload32(uniform_ptr(v.perm[1] + gi0), slot & ~3u);
-    oK.load(v, 0, gi0, slot, v.no2);
-    oV.load(v, 1, gi0, slot, v.no2);
-    // The 2-bit field regions start at offset 0 of the tile side; slots past the region
+    mm = gload32(uniform_ptr(v.mm[0] + gi0), 4u * slot);
+    pos = gload32(uniform_ptr(v.perm[0] + gi0), slot & ~3u);   // aligned word; byte slot%4 is the position
+    o.load(v, 0, gi0, slot, v.no2);
+    // The 2-bit field region starts at offset 0 of the tile side; slots past the region
     // read other bytes of the same tile (always inside its reserved capacity) and their
     // results are not used.
-    gload_dwords<KRec<D, 2>::RDW>(baseK + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
+    gload_dwords<KRec<D, 2>::RDW>(ubase + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
+    const QaqKRegions rK = qaq_k_regions(c, D);
+    if (wave * 64 < c.n3) KRec<D, 1>::load(base + rK.r1, min(tid, c.n3 - 1), kw1);
+  }
+};
+
+template <int D, int NO2>
+struct ValRegs {
+  static constexpr int NCG = D / 16;
+  static constexpr int CGW = NCG / 4;
+  QaqCounts c;
+  uint32_t mm, pos;
+  Outl<NO2> o;
+  uint32_t vw2[4][CGW], vw1[4];
+  __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& cv, int tid, int wave, int nn, int g) {
+    c = cv;
+    const int n_tok = min(len - tile * QAQ_TT, QAQ_TT);
+    const uint8_t* base = qaq_tile_codes(v, 1, b, h, tile);
+    const gbytes_t ubase = uniform_ptr(base);
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
+    mm = gload32(uniform_ptr(v.mm[1] + gi0), 4u * slot);
+    pos = gload32(uniform_ptr(v.perm[1] + gi0), slot & ~3u);
+    o.load(v, 1, gi0, slot, v.no2);
     const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) gload_dwords<CGW>(baseV + voff + (uint32_t)blk * (16u * D), vw2[blk]);
-  }
-  // Part 2: the 1-bit field regions, behind the 2-bit ones, placed by the counts.
-  __device__ __forceinline__ void load_placed(const QaqView& v, int b, int h, int tile, const QaqCounts& ck,
-                                              const QaqCounts& cv, int tid, int wave, int nn, int g) {
-    cK = ck;
-    cV = cv;
-    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
-    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
-    const QaqKRegions rK = qaq_k_regions(cK, D);
-    const QaqVRegions rV = qaq_v_regions(cV, D);
-    if (wave * 64 < cK.n3) KRec<D, 1>::load(baseK + rK.r1, min(tid, cK.n3 - 1), kw1);
-    const int nu1 = (cV.n3 + 15) >> 4;
+    for (int blk = 0; blk < 4; ++blk) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);
+    const QaqVRegions rV = qaq_v_regions(c, D);
+    const int nu1 = (c.n3 + 15) >> 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
       if (blk * 4 < nu1)
-        vw1[blk] = *(const uint32_t*)(baseV + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+        vw1[blk] = *(const uint32_t*)(base + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
   }
 };
 
@@ -317,8 +330,6 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
 
-  TileRegs<D, NO2> nxt;
-  nxt.load_fixed(v, a.len, b, h, tile_begin, tid, wave, nn, g);
   const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
   // class counts of all tiles of the chunk -> LDS (one 16-byte load per tile), so that the
   // tile loop needs no dependent global load to place its 1-bit regions
@@ -389,7 +400,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
     return r;
   };
-  nxt.load_placed(v, b, h, tile_begin, counts_of(tile_begin, 0), counts_of(tile_begin, 1), tid, wave, nn, g);
+  KeyRegs<D, NO2> kr;
+  ValRegs<D, NO2> vr;
+  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid, wave);
+  vr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
 
   // carried across the tiles
   float m_run = -INFINITY;          // reference of everything below
@@ -399,16 +413,9 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
 #pragma unroll
   for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
 
-  // Two register sets take turns (the tile being computed, the tile being loaded), so no
-  // register copies are needed between iterations.
-  TileRegs<D, NO2> alt;
-  auto do_tile = [&](const TileRegs<D, NO2>& cur, TileRegs<D, NO2>& nxt, int tile) {
-    if (tile + 1 < tile_end) {
-      nxt.load_fixed(v, a.len, b, h, tile + 1, tid, wave, nn, g);
-      nxt.load_placed(v, b, h, tile + 1, counts_of(tile + 1, 0), counts_of(tile + 1, 1), tid, wave, nn, g);
-    }
-    const QaqCounts cK = cur.cK, cV = cur.cV;
-    const int n_tok = cur.n_tok;
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const QaqCounts cK = kr.c, cV = vr.c;
+    const int n_tok = kr.n_tok;
     const uint32_t slot = (uint32_t)min(tid, n_tok - 1);   // the slot this lane's metadata was loaded for
     const QaqKRegions rK = qaq_k_regions(cK, D);
     const QaqVRegions rV = qaq_v_regions(cV, D);
@@ -418,35 +425,18 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     const int n32K = cK.n32(), n32V = cV.n32();
     const int first8V = n32V + cV.n4;
 
-    // bound on w/p over the tile: the largest effective value scale
-    float smax_l = 0.0f;
-    if (tid < n_tok) {
-      const int bits = cV.bits_of_slot(tid);
-      const float mn = h2f((uint16_t)(cur.mmV & 0xffffu)), mx = h2f((uint16_t)(cur.mmV >> 16));
-      const float range = mx - mn;
-      smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
-      // ... and of what an outlier correction can be (same fixed-point exponent serves both)
-#pragma unroll
-      for (int j = 0; j < Outl<NO2>::CAP; ++j)
-        if (j < NO2 && j < no2) {
-          const float ov = cur.oV.val(j);
-          smax_l = fmaxf(smax_l, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
-        }
-    }
-    smax_l = wave_max(smax_l);
-
     // ---- keys: logits ----------------------------------------------------------------------------
     float vmax = -INFINITY;
     if (wave * 64 < n32K) {
-      float dotq = real_of(k_contract<D, 2>(cur.kw2, abase0));
+      float dotq = real_of(k_contract<D, 2>(kr.kw2, abase0));
       const bool three = tid < cK.n3;
       if (wave * 64 < cK.n3) {
-        const float low = real_of(k_contract<D, 1>(cur.kw1, abase1));
+        const float low = real_of(k_contract<D, 1>(kr.kw1, abase1));
         dotq = three ? 2.0f * dotq + low : dotq;
       }
       if (tid < n32K) {
-        const float lg = key_logit(cur.mmK, cur.oK, slot, three ? 3 : 2, dotq);
-        S.logit[(cur.posK >> (8u * (slot & 3u))) & 0xffu] = lg;
+        const float lg = key_logit(kr.mm, kr.o, slot, three ? 3 : 2, dotq);
+        S.logit[(kr.pos >> (8u * (slot & 3u))) & 0xffu] = lg;
         vmax = lg;
       }
     }
@@ -488,6 +478,25 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
         vmax = fmaxf(vmax, lg);
       }
     }
+    // the key registers are free: request the next tile's keys
+    if (tile + 1 < tile_end) kr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid, wave);
+
+    // bound on w/p over the tile: the largest effective value scale
+    float smax_l = 0.0f;
+    if (tid < n_tok) {
+      const int bits = cV.bits_of_slot(tid);
+      const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
+      const float range = mx - mn;
+      smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
+      // ... and of what an outlier correction can be (same fixed-point exponent serves both)
+#pragma unroll
+      for (int j = 0; j < Outl<NO2>::CAP; ++j)
+        if (j < NO2 && j < no2) {
+          const float ov = vr.o.val(j);
+          smax_l = fmaxf(smax_l, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
+        }
+    }
+    smax_l = wave_max(smax_l);
     vmax = wave_max(vmax);
     if (lane == 0) { S.red[8 + wave] = vmax; S.red[12 + wave] = smax_l; }
     lds_barrier();
@@ -507,8 +516,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
       const bool live = s < n_tok;
       float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
       if (live) {
-        pt = __expf(S.logit[(cur.posV >> (8u * (slot & 3u))) & 0xffu] - M);
-        const float mn = h2f((uint16_t)(cur.mmV & 0xffffu)), mx = h2f((uint16_t)(cur.mmV >> 16));
+        pt = __expf(S.logit[(vr.pos >> (8u * (slot & 3u))) & 0xffu] - M);
+        const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
         const float range = mx - mn;
         const int bits = cV.bits_of_slot(s);
         const float scale = ldexpf(range, -bits);
@@ -518,11 +527,12 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
 #pragma unroll
         for (int j = 0; j < Outl<NO2>::CAP; ++j) {
           if (j < NO2 && j < no2) {
-            const float ov = cur.oV.val(j);
+            const float ov = vr.o.val(j);
             const bool top = ov >= mx;
             // |correction| < 2^wexp, at most 32 arrive per copy: units of 2^(wexp-25) cannot overflow
             const float cval = pt * ((ov - (top ? mx : mn)) + (top ? hs : -hs));
-            atomicAdd(&S.xc[cur.oV.idx(j, slot)][lane & 15], (int)rintf(ldexpf(cval, 25 - wexp)));
+            const int och = vr.o.idx(j, slot);
+            atomicAdd(&S.xc[och][(lane + 4 * (och >> 1)) & 15], (int)rintf(ldexpf(cval, 25 - wexp)));
           }
         }
         if (s >= first8V) S.w8[s - first8V] = w;
@@ -558,9 +568,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     // carries the result like the output, and clears the copies for the next tile
     if (wave < KS) {
       int4* c4 = (int4*)&S.xc[tid][0];
-      const int4 x0 = c4[0], x1 = c4[1], x2 = c4[2], x3 = c4[3];
+      const int r0 = (tid >> 1) & 3, r1 = (r0 + 1) & 3, r2 = (r0 + 2) & 3, r3 = (r0 + 3) & 3;   // bank-staggered order
+      const int4 x0 = c4[r0], x1 = c4[r1], x2 = c4[r2], x3 = c4[r3];
       const int4 z = {0, 0, 0, 0};
-      c4[0] = z; c4[1] = z; c4[2] = z; c4[3] = z;
+      c4[r0] = z; c4[r1] = z; c4[r2] = z; c4[r3] = z;
       // each copy is below 2^30 in magnitude: pairs are summed exactly as integers, then in fp32
       const float sum = (((float)(x0.x + x0.y) + (float)(x0.z + x0.w)) + ((float)(x1.x + x1.y) + (float)(x1.z + x1.w))) +
                         (((float)(x2.x + x2.y) + (float)(x2.z + x2.w)) + ((float)(x3.x + x3.y) + (float)(x3.z + x3.w)));
@@ -576,12 +587,12 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
       if (blk * 64 < n32V) {
         const v4i wa = *(const v4i*)(wb2 + 64 * blk);
 #pragma unroll
-        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&cur.vw2[blk][j], 0), cv[j]);
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&vr.vw2[blk][j], 0), cv[j]);
       }
       if (blk * 64 < cV.n3) {
         const v4i wa = *(const v4i*)(wb1 + 64 * blk);
 #pragma unroll
-        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&cur.vw1[blk], (CGW * wave + j) & 1), cv[j]);
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&vr.vw1[blk], (CGW * wave + j) & 1), cv[j]);
       }
     }
     for (int blk = 0; blk * 64 < cV.n4; ++blk) {
@@ -631,10 +642,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
         xrun[j] = xrun[j] * keep + xt;
       }
     }
-  };
-  for (int tile = tile_begin; tile < tile_end; tile += 2) {
-    do_tile(nxt, alt, tile);
-    if (tile + 1 < tile_end) do_tile(alt, nxt, tile + 1);
+    // the value registers are free: request the next tile's values
+    if (tile + 1 < tile_end) vr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
   }
 
   // ---- one partial per workgroup -----------------------------------------------------------------
