@@ -162,6 +162,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
     v.tags[s] = base + a.tags[s];
   }
   v.counts = (uint16_t*)(base + a.counts);
+  v.vbound = (float*)(base + a.vbound);
   v.ring = (float*)(base + a.ring);
   v.partial = (float*)(base + a.partial);
   v.statbuf = (long long*)(base + a.statbuf);

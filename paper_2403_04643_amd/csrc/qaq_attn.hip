@@ -178,6 +178,7 @@ struct TileLds {
   alignas(16) int8_t ql[3][4][D + 16];  // query digits [format][digit][position in record order]
   alignas(16) int8_t zrow[256];         // zeros: A operand of lanes whose row carries nothing
   alignas(16) uint16_t cnt[QAQ_MAX_NTC][8]; // class counts of the workgroup's tiles: keys, values
+  float vb[QAQ_MAX_NTC];                // per tile: bound on the value-side weights and outlier corrections
   float logit[QAQ_TT];                  // raw logits by position
   alignas(16) int8_t wl2[4][QAQ_TT + 16];   // weight digits per slot of the 2-bit field region
   alignas(16) int8_t wl1[4][QAQ_TT + 16];   // ... of the 1-bit field region
@@ -333,8 +334,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
   // class counts of all tiles of the chunk -> LDS (one 16-byte load per tile), so that the
   // tile loop needs no dependent global load to place its 1-bit regions
-  if (tid < tile_end - tile_begin)
+  if (tid < tile_end - tile_begin) {
     *(uint4*)&S.cnt[tid][0] = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + tile_begin + tid) * 2) * 4);
+    S.vb[tid] = v.vbound[qaq_bh(v, b, h) * v.NT + tile_begin + tid];
+  }
 
   // ---- query: fixed point, signed base-256 digits, one table per spreading format ------------
   if (wave < KS) {          // the wavefronts that hold the D query channels
@@ -481,27 +484,11 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     // the key registers are free: request the next tile's keys
     if (tile + 1 < tile_end) kr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid, wave);
 
-    // bound on w/p over the tile: the largest effective value scale
-    float smax_l = 0.0f;
-    if (tid < n_tok) {
-      const int bits = cV.bits_of_slot(tid);
-      const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
-      const float range = mx - mn;
-      smax_l = ldexpf(range, bits == 3 ? -2 : -bits);
-      // ... and of what an outlier correction can be (same fixed-point exponent serves both)
-#pragma unroll
-      for (int j = 0; j < Outl<NO2>::CAP; ++j)
-        if (j < NO2 && j < no2) {
-          const float ov = vr.o.val(j);
-          smax_l = fmaxf(smax_l, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
-        }
-    }
-    smax_l = wave_max(smax_l);
     vmax = wave_max(vmax);
-    if (lane == 0) { S.red[8 + wave] = vmax; S.red[12 + wave] = smax_l; }
+    if (lane == 0) S.red[8 + wave] = vmax;
     lds_barrier();
     const float m_tile = fmaxf(fmaxf(S.red[8], S.red[9]), fmaxf(S.red[10], S.red[11]));
-    const float smax = fmaxf(fmaxf(S.red[12], S.red[13]), fmaxf(S.red[14], S.red[15]));
+    const float smax = S.vb[tile - tile_begin];     // bound on w/p and on the outlier corrections over the tile
     const float M = fmaxf(m_run, m_tile);
     const float keep = __expf(m_run - M);          // 0 on the first tile
     m_run = M;

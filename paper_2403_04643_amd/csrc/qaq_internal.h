@@ -19,6 +19,7 @@ struct QaqView {
   uint16_t* oval[2];
   uint8_t* tags[2];
   uint16_t* counts;
+  float* vbound;
   float* ring;
   float* partial;
   long long* statbuf;

@@ -102,6 +102,7 @@ struct BuildLds {
   uint16_t pos_of_slot[QAQ_TT];
   uint16_t slot_of_pos[QAQ_TT];
   int wave_cnt[4][4];
+  float wave_bound[4];
 };
 
 // rows of four bytes <-> columns of four bytes: t[k] byte j = w[j] byte k
@@ -630,6 +631,26 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     }
   }
 
+  // values: what the attention kernel needs as the fixed-point range of a tile -- the largest
+  // per-token step range/2^B (a 3-bit code is split into planes, the upper one weighs twice the
+  // step) and the largest magnitude an outlier correction (stored value minus reconstruction) can have
+  if (side == 1) {
+    float bnd = 0.0f;
+    if (tid < n_after) {
+      const int bits = L.bits_new[tid];
+      const float mn = h2f((uint16_t)(L.mm[tid] & 0xffffu)), mx = h2f((uint16_t)(L.mm[tid] >> 16));
+      const float range = mx - mn;
+      bnd = ldexpf(range, bits == 3 ? -2 : -bits);
+      for (int k = 0; k < v.no2; ++k) {
+        const float ov = h2f(L.oval[tid][k]);
+        bnd = fmaxf(bnd, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) bnd = fmaxf(bnd, __shfl_xor(bnd, o));
+    if (lane == 0) L.wave_bound[wave] = bnd;
+  }
+
   // stable counting sort of the positions by class (3, 2, 4, 8)
   const int cls = tid < n_after ? qaq_class_of_bits(L.bits_new[tid]) : -1;
   int my_rank = 0;
@@ -670,6 +691,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   if (tid == 0) {
     uint16_t* cp = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
     cp[QC3] = (uint16_t)cn.n3; cp[QC2] = (uint16_t)cn.n2; cp[QC4] = (uint16_t)cn.n4; cp[QC8] = (uint16_t)cn.n8;
+    if (side == 1)
+      v.vbound[qaq_bh(v, b, h) * v.NT + tile] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
   }
   pack_tile<D>(side, base, cn, L);
 }
