@@ -523,9 +523,31 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   if (n_after == 0) return;
   const int n_o = v.no2 / 2;
 
+  if (a.mode == 1 && a.newbits[side] == nullptr) return;   // requantize: nothing to do for this side
+
+  // cached tokens: everything whose address is known up front is requested in one go (the
+  // slot-order metadata, and for a requantize the widths that decide whether the tile is
+  // touched at all), so that a rebuild costs two dependent round trips to memory, not three
+  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
+  QaqCounts c_old;
+  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = 0;
+  int pos_old = 0;
+  uint32_t mm_old = 0;
+  uint8_t oi_old[QAQ_MAX_NO2];
+  uint16_t ov_old[QAQ_MAX_NO2];
+  if (n_before > 0) {
+    c_old = qaq_load_counts(v, side, b, h, tile);
+    if (tid < n_before) {
+      const size_t gi = qaq_slot_index(v, b, h, tile, tid);
+      pos_old = v.perm[side][gi];
+      mm_old = v.mm[side][gi];
+#pragma unroll
+      for (int k = 0; k < QAQ_MAX_NO2; ++k)
+        if (k < v.no2) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
+    }
+  }
   if (a.mode == 1) {
-    // requantize: nothing to do for this side, or no token of the tile changes
-    if (a.newbits[side] == nullptr) return;
+    // no token of the tile changes: leave it alone
     bool changed = false;
     if (tid < n_before) {
       const int oldb = v.tags[side][qaq_slot_index(v, b, h, tile, tid)];
@@ -539,24 +561,18 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (!__syncthreads_or(changed ? 1 : 0)) return;
   }
 
-  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
-
-  // cached tokens: metadata by position, codes into the stage
+  // metadata by position, codes into the stage
   if (n_before > 0) {
-    const QaqCounts c = qaq_load_counts(v, side, b, h, tile);
     if (tid < n_before) {
-      const size_t gi = qaq_slot_index(v, b, h, tile, tid);
-      const int pos = v.perm[side][gi];
-      L.mm[pos] = v.mm[side][gi];
-      L.pos_of_slot[tid] = (uint16_t)pos;
-      L.bits_old[pos] = (uint8_t)c.bits_of_slot(tid);
-      for (int k = 0; k < v.no2; ++k) {
-        L.oidx[pos][k] = v.oidx[side][gi * v.no2 + k];
-        L.oval[pos][k] = v.oval[side][gi * v.no2 + k];
-      }
+      L.mm[pos_old] = mm_old;
+      L.pos_of_slot[tid] = (uint16_t)pos_old;
+      L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
+#pragma unroll
+      for (int k = 0; k < QAQ_MAX_NO2; ++k)
+        if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
     }
     __syncthreads();
-    unpack_tile<D>(side, base, c, L);
+    unpack_tile<D>(side, base, c_old, L);
   }
 
   // final width of every position
