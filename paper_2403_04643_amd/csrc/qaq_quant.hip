@@ -724,33 +724,31 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
   const int t0 = tile * QAQ_TT;
   const int n_tok = min(a.len - t0, QAQ_TT);
   if (n_tok <= 0) return;
-  if (tid < n_tok) {
-    const size_t gi = qaq_slot_index(v, b, h, tile, tid);
-    {
-      const uint32_t m = v.mm[0][gi];
-      rk[v.perm[0][gi]] = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
-    }
-    {
-      const uint32_t m = v.mm[1][gi];
-      rv[v.perm[1][gi]] = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
-    }
-  }
-  __syncthreads();
-  if (tid >= n_tok) return;
+  // all loads first (slot-order ranges, this step's scores, the window rows), one barrier,
+  // then the comparisons
   const int t = t0 + tid;
   const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
   const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
   float pred = 0.0f;
-  if (a.scores) {
+  if (tid < n_tok) {
+    const size_t gi = qaq_slot_index(v, b, h, tile, tid);
+    const uint32_t mk = v.mm[0][gi], mv = v.mm[1][gi];
+    const int pk = v.perm[0][gi], pv = v.perm[1][gi];
     float s = 0.0f;
-    for (int g = 0; g < a.G; ++g) s = fmaxf(s, a.scores[((size_t)b * v.Hq + (h * a.G + g)) * a.len + t]);
-    v.ring[(size_t)a.new_row * ring_row + ri] = s;
-    pred = s;
+    if (a.scores) {
+      for (int g = 0; g < a.G; ++g) s = fmaxf(s, a.scores[((size_t)b * v.Hq + (h * a.G + g)) * a.len + t]);
+      pred = s;
+    }
+    for (int r = 0; r < v.window; ++r) {
+      if (a.scores && r == a.new_row) continue;
+      if (t < a.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
+    }
+    if (a.scores) v.ring[(size_t)a.new_row * ring_row + ri] = s;
+    rk[pk] = h2f((uint16_t)(mk >> 16)) - h2f((uint16_t)(mk & 0xffffu));
+    rv[pv] = h2f((uint16_t)(mv >> 16)) - h2f((uint16_t)(mv & 0xffffu));
   }
-  for (int r = 0; r < v.window; ++r) {
-    if (a.scores && r == a.new_row) continue;
-    if (t < a.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
-  }
+  __syncthreads();
+  if (tid >= n_tok) return;
   const float tau = a.tau_k[h];
   const float lhs_v = rv[tid] * pred;
   int bk = a.bit_set[a.nbits - 1], bv = a.bit_set[a.nbits - 1];
