@@ -101,23 +101,37 @@ template <int CTRL, int ROW_MASK = 0xf>
 __device__ __forceinline__ float dpp_f(float old, float x) {
   return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
 }
+// One instruction per step: the DPP form of the arithmetic instruction itself (the compiler
+// would emit a move with the lane pattern, a NaN-quieting max of each input and the max).
+// A VGPR written by a vector instruction needs two wait states before a DPP read.
+#define QAQ_DPP_STEP(op, pat) "s_nop 1\n\t" op " %0, %0, %0 " pat "\n\t"
 __device__ __forceinline__ float wave_max(float x) {
-  x = fmaxf(x, dpp_f<0xB1>(x, x));          // quad_perm [1,0,3,2]
-  x = fmaxf(x, dpp_f<0x4E>(x, x));          // quad_perm [2,3,0,1]
-  x = fmaxf(x, dpp_f<0x141>(x, x));         // row_half_mirror
-  x = fmaxf(x, dpp_f<0x140>(x, x));         // row_mirror
-  x = fmaxf(x, dpp_f<0x142, 0xa>(x, x));    // row_bcast:15 into rows 1 and 3
-  x = fmaxf(x, dpp_f<0x143, 0xc>(x, x));    // row_bcast:31 into rows 2 and 3
+  asm volatile(QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_bcast:15 row_mask:0xa bank_mask:0xf")      // into rows 1 and 3
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_bcast:31 row_mask:0xc bank_mask:0xf")      // into rows 2 and 3
+               "s_nop 1"
+               : "+v"(x));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 __device__ __forceinline__ float wave_sum(float x) {
-  x += dpp_f<0xB1>(0.0f, x);
-  x += dpp_f<0x4E>(0.0f, x);
-  x += dpp_f<0x141>(0.0f, x);
-  x += dpp_f<0x140>(0.0f, x);
-  x += dpp_f<0x142, 0xa>(0.0f, x);
-  x += dpp_f<0x143, 0xc>(0.0f, x);
+  asm volatile(QAQ_DPP_STEP("v_add_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_bcast:15 row_mask:0xa bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_bcast:31 row_mask:0xc bank_mask:0xf")
+               "s_nop 1"
+               : "+v"(x));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+// max of two numbers that are known not to be NaN: one instruction
+__device__ __forceinline__ float vmaxf(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 
 // Signed base-256 digits of an integer (each in [-128, 127]), packed little endian.
@@ -454,7 +468,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
         Outl<NO2> o; o.load(v, 0, gi0, (uint32_t)(n32K + idx), no2);
         const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + idx), 4, real_of(cc));
         S.logit[v.perm[0][gi]] = lg;
-        vmax = fmaxf(vmax, lg);
+        vmax = vmaxf(vmax, lg);
       }
     }
     // 8-bit key bytes are stored as code - 128: the dot product needs 128 * sum of the
@@ -478,7 +492,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
         const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
         const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + cK.n4 + idx), 8, dotq);
         S.logit[v.perm[0][gi]] = lg;
-        vmax = fmaxf(vmax, lg);
+        vmax = vmaxf(vmax, lg);
       }
     }
     // the key registers are free: request the next tile's keys
@@ -487,9 +501,9 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     vmax = wave_max(vmax);
     if (lane == 0) S.red[8 + wave] = vmax;
     lds_barrier();
-    const float m_tile = fmaxf(fmaxf(S.red[8], S.red[9]), fmaxf(S.red[10], S.red[11]));
+    const float m_tile = vmaxf(vmaxf(S.red[8], S.red[9]), vmaxf(S.red[10], S.red[11]));
     const float smax = S.vb[tile - tile_begin];     // bound on w/p and on the outlier corrections over the tile
-    const float M = fmaxf(m_run, m_tile);
+    const float M = vmaxf(m_run, m_tile);
     const float keep = __expf(m_run - M);          // 0 on the first tile
     m_run = M;
     int wexp = 0;
