@@ -98,12 +98,18 @@ struct BuildLds {
   uint16_t oval[QAQ_TT][QAQ_MAX_NO2];      // outlier fp16 values
   uint8_t bits_old[QAQ_TT];
   uint8_t bits_new[QAQ_TT];
-  uint8_t shf[QAQ_TT];                     // low bits a staged code still has to drop (narrowing)
+  uint8_t shf[QAQ_TT];                     // by position: low bits a staged code still has to drop (narrowing);
+                                           // bit 7: the token keeps its slot and its width (what is stored for it stays valid)
+  uint8_t kept[QAQ_TT];                    // by slot: a token stays here
   uint16_t pos_of_slot[QAQ_TT];
   uint16_t slot_of_pos[QAQ_TT];
+  uint16_t freeslot[QAQ_TT];               // per class, in slot order: the slots nobody keeps
   int wave_cnt[4][4];
+  int wave_need[4][4];
+  int wave_free[4][4];
   float wave_bound[4];
 };
+constexpr int kKeptFlag = 0x80;
 
 // rows of four bytes <-> columns of four bytes: t[k] byte j = w[j] byte k
 __device__ __forceinline__ void transpose4(const uint32_t (&w)[4], uint32_t (&t)[4]) {
@@ -378,17 +384,26 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 
 // Staged bytes -> stored code planes of one tile side, in the new slot order; codes that
 // narrow drop their low bits here (the coarser grid's segments contain the finer one's).
+// c0 = the class counts the tile had before (all zero for a tile that did not exist): a
+// word whose tokens all keep slot and width, in a region that has not moved, is left alone.
 template <int D>
-__device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const BuildLds<D>& L) {
+__device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D>& L) {
   constexpr int SROW = BuildLds<D>::SROW, NQ = D / 16, KS = D / 64;
   const int tid = threadIdx.x;
   const int n32 = c.n32();
+  const bool had = c0.total() > 0;
+  const bool same32 = had && c0.n32() == n32;
   if (side == 0) {
-    const QaqKRegions r = qaq_k_regions(c, D);
+    const QaqKRegions r = qaq_k_regions(c, D), r0 = qaq_k_regions(c0, D);
+    const bool same1 = had && r.r1 == r0.r1;
+    const bool same4 = same32 && r.r4 == r0.r4;
+    const bool same8 = same4 && c0.n4 == c.n4 && r.r8 == r0.r8;
     for (int it = tid; it < n32 * NQ; it += kThreads) {
       const int s = it / NQ, q = it % NQ;
       const int pos = L.pos_of_slot[s];
-      const int sh = L.shf[pos] + (s < c.n3 ? 1 : 0);
+      const int f = L.shf[pos];
+      if (had && (f & kKeptFlag)) continue;
+      const int sh = (f & 7) + (s < c.n3 ? 1 : 0);
       const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
       uint32_t w = 0;
 #pragma unroll
@@ -398,7 +413,9 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
     for (int it = tid; it < c.n3 * (D / 32); it += kThreads) {
       const int s = it / (D / 32), jj = it % (D / 32);
       const int pos = L.pos_of_slot[s];
-      const int sh = L.shf[pos];
+      const int f = L.shf[pos];
+      if (same1 && (f & kKeptFlag)) continue;
+      const int sh = f & 7;
       uint32_t w = 0;
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
@@ -412,21 +429,31 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
     for (int it = tid; it < c.n4 * (D / 8); it += kThreads) {
       const int i4 = it / (D / 8), jj = it % (D / 8), q = jj >> 1, dw = jj & 1;
       const int pos = L.pos_of_slot[n32 + i4];
-      const int sh = L.shf[pos];
+      const int f = L.shf[pos];
+      if (same4 && (f & kKeptFlag)) continue;
+      const int sh = f & 7;
       const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
       *(uint32_t*)(base + r.r4 + 4u * (uint32_t)it) = ((row[0] >> sh) & 0x0f0f0f0fu) | (((row[1] >> sh) & 0x0f0f0f0fu) << 4);
     }
     for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
       const int i8 = it / (D / 4), jj = it % (D / 4), q = jj >> 2, v = jj & 3;
       const int pos = L.pos_of_slot[n32 + c.n4 + i8];
+      if (same8 && (L.shf[pos] & kKeptFlag)) continue;
       *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] ^ 0x80808080u;
     }
     return;
   }
-  const QaqVRegions r = qaq_v_regions(c, D);
+  const QaqVRegions r = qaq_v_regions(c, D), r0 = qaq_v_regions(c0, D);
+  const bool same1 = had && r.r1 == r0.r1;
+  const bool same4 = same32 && r.r4 == r0.r4;
+  const bool same8 = same4 && c0.n4 == c.n4 && r.r8 == r0.r8;
+  // A unit holds up to 16 tokens; the part of the last unit past the region is zero padding.
+  // It is left alone when every token it held keeps slot and width and its padding is where
+  // it was: the unit lies below both the old and the new end, or the end has not moved.
   for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
     const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
+    bool stays = had && (same32 || 16 * u + 16 <= min(n32, c0.n32()));
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       uint32_t w[4], t[4];
@@ -436,13 +463,16 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
         w[j] = 0;
         if (s < n32) {
           const int pos = L.pos_of_slot[s];
-          w[j] = (L.stage[pos * SROW + c4] >> (L.shf[pos] + (s < c.n3 ? 1 : 0))) & 0x03030303u;
+          const int f = L.shf[pos];
+          stays = stays && (f & kKeptFlag);
+          w[j] = (L.stage[pos * SROW + c4] >> ((f & 7) + (s < c.n3 ? 1 : 0))) & 0x03030303u;
         }
       }
       transpose4(w, t);
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] |= t[k] << (2 * v);
     }
+    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
@@ -450,6 +480,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
   for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
+    bool stays = same1 && (c0.n3 == c.n3 || 16 * u + 16 <= min(c.n3, c0.n3));
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       const int c4 = 4 * (2 * cgp + hh) + n4;
@@ -462,7 +493,9 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
           w[j] = 0;
           if (s < c.n3) {
             const int pos = L.pos_of_slot[s];
-            w[j] = (L.stage[pos * SROW + c4] >> L.shf[pos]) & 0x01010101u;
+            const int f = L.shf[pos];
+            stays = stays && (f & kKeptFlag);
+            w[j] = (L.stage[pos * SROW + c4] >> (f & 7)) & 0x01010101u;
           }
         }
         transpose4(w, t);
@@ -470,6 +503,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
         for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * hh + v);
       }
     }
+    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) = o[k];
@@ -477,6 +511,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
   for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
     const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
+    bool stays = same4 && (c0.n4 == c.n4 || 8 * hu + 8 <= min(c.n4, c0.n4));
 #pragma unroll
     for (int g2 = 0; g2 < 2; ++g2) {
       uint32_t w[4], t[4];
@@ -486,20 +521,25 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Bui
         w[j] = 0;
         if (i4 < c.n4) {
           const int pos = L.pos_of_slot[n32 + i4];
-          w[j] = (L.stage[pos * SROW + c4] >> L.shf[pos]) & 0x0f0f0f0fu;
+          const int f = L.shf[pos];
+          stays = stays && (f & kKeptFlag);
+          w[j] = (L.stage[pos * SROW + c4] >> (f & 7)) & 0x0f0f0f0fu;
         }
       }
       transpose4(w, t);
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * g2);
     }
+    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
   }
   for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
     const int i8 = it / (D / 4), dq = it % (D / 4);
-    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + dq];
+    const int pos = L.pos_of_slot[n32 + c.n4 + i8];
+    if (same8 && (L.shf[pos] & kKeptFlag)) continue;
+    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
   }
 }
 
@@ -566,6 +606,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (tid < n_before) {
       L.mm[pos_old] = mm_old;
       L.pos_of_slot[tid] = (uint16_t)pos_old;
+      L.slot_of_pos[pos_old] = (uint16_t)tid;
       L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
 #pragma unroll
       for (int k = 0; k < QAQ_MAX_NO2; ++k)
@@ -667,15 +708,19 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (lane == 0) L.wave_bound[wave] = bnd;
   }
 
-  // stable counting sort of the positions by class (3, 2, 4, 8)
+  // Slots: class by class (3, 2, 4, 8).  A cached token whose class is unchanged and whose
+  // old slot still lies in its class's range stays where it is; the others (new tokens, tokens
+  // that change class, tokens squeezed out by a moved class boundary) take the remaining
+  // slots of their class, in position order.  A freshly built tile thus comes out sorted by
+  // position inside each class, and a rebuild moves only as many tokens as it has to -- what
+  // is stored for the tokens that stay is not written again.
   const int cls = tid < n_after ? qaq_class_of_bits(L.bits_new[tid]) : -1;
-  int my_rank = 0;
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const unsigned long long bal = __ballot(cls == c);
     if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
-    if (cls == c) my_rank = __popcll(bal & ((1ull << lane) - 1ull));
   }
+  L.kept[tid] = 0;
   __syncthreads();
   QaqCounts cn;
   {
@@ -684,16 +729,51 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     for (int c = 0; c < 4; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
     cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8];
   }
+  const bool was_cached = tid < n_before;
+  const int old_slot = was_cached ? (int)L.slot_of_pos[tid] : -1;
+  bool keep = false;
+  if (was_cached && cls == qaq_class_of_bits(L.bits_old[tid])) {
+    const int lo = cn.start(cls);
+    const int cnt = cls == QC3 ? cn.n3 : cls == QC2 ? cn.n2 : cls == QC4 ? cn.n4 : cn.n8;
+    keep = old_slot >= lo && old_slot < lo + cnt;
+  }
+  if (keep) L.kept[old_slot] = 1;
+  __syncthreads();
+  // ranks: of the tokens that need a slot (by position), of the free slots (by slot)
+  const bool need = cls >= 0 && !keep;
+  const int slot_cls = tid < n_after ? qaq_class_of_bits(cn.bits_of_slot(tid)) : -1;   // class owning slot `tid`
+  const bool is_free = slot_cls >= 0 && !L.kept[tid];
+  int need_rank = 0, free_rank = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const unsigned long long bn = __ballot(need && cls == c);
+    const unsigned long long bf = __ballot(is_free && slot_cls == c);
+    if (lane == 0) { L.wave_need[c][wave] = __popcll(bn); L.wave_free[c][wave] = __popcll(bf); }
+    if (need && cls == c) need_rank = __popcll(bn & ((1ull << lane) - 1ull));
+    if (is_free && slot_cls == c) free_rank = __popcll(bf & ((1ull << lane) - 1ull));
+  }
+  __syncthreads();
+  if (is_free) {
+    int r = cn.start(slot_cls) + free_rank;
+    for (int w = 0; w < wave; ++w) r += L.wave_free[slot_cls][w];
+    L.freeslot[r] = (uint16_t)tid;
+  }
+  __syncthreads();
   if (cls >= 0) {
-    int s = cn.start(cls) + my_rank;
-    for (int w = 0; w < wave; ++w) s += L.wave_cnt[cls][w];
-    L.slot_of_pos[tid] = (uint16_t)s;
-    L.pos_of_slot[s] = (uint16_t)tid;
+    int sl = old_slot;
+    if (!keep) {
+      int r = cn.start(cls) + need_rank;
+      for (int w = 0; w < wave; ++w) r += L.wave_need[cls][w];
+      sl = L.freeslot[r];
+    }
+    L.slot_of_pos[tid] = (uint16_t)sl;
+    L.pos_of_slot[sl] = (uint16_t)tid;
+    if (keep && L.bits_new[tid] == L.bits_old[tid] && was_cached) L.shf[tid] |= kKeptFlag;
   }
   __syncthreads();
 
   // metadata in slot order, widths by position, class counts
-  if (tid < n_after) {
+  if (tid < n_after && !(L.shf[tid] & kKeptFlag)) {
     const int s = L.slot_of_pos[tid];
     const size_t gi = qaq_slot_index(v, b, h, tile, s);
     v.mm[side][gi] = L.mm[tid];
@@ -710,7 +790,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (side == 1)
       v.vbound[qaq_bh(v, b, h) * v.NT + tile] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
   }
-  pack_tile<D>(side, base, cn, L);
+  pack_tile<D>(side, base, cn, c_old, L);
 }
 
 // ---------------------------------------------------------------------------------
