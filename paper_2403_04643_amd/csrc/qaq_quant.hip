@@ -729,48 +729,65 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     for (int c = 0; c < 4; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
     cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8];
   }
-  const bool was_cached = tid < n_before;
-  const int old_slot = was_cached ? (int)L.slot_of_pos[tid] : -1;
-  bool keep = false;
-  if (was_cached && cls == qaq_class_of_bits(L.bits_old[tid])) {
-    const int lo = cn.start(cls);
-    const int cnt = cls == QC3 ? cn.n3 : cls == QC2 ? cn.n2 : cls == QC4 ? cn.n4 : cn.n8;
-    keep = old_slot >= lo && old_slot < lo + cnt;
-  }
-  if (keep) L.kept[old_slot] = 1;
-  __syncthreads();
-  // ranks: of the tokens that need a slot (by position), of the free slots (by slot)
-  const bool need = cls >= 0 && !keep;
-  const int slot_cls = tid < n_after ? qaq_class_of_bits(cn.bits_of_slot(tid)) : -1;   // class owning slot `tid`
-  const bool is_free = slot_cls >= 0 && !L.kept[tid];
-  int need_rank = 0, free_rank = 0;
+  if (n_before == 0) {
+    // nothing cached: a plain stable counting sort (rank inside the wavefront + wavefront offsets)
+    int my_rank = 0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const unsigned long long bn = __ballot(need && cls == c);
-    const unsigned long long bf = __ballot(is_free && slot_cls == c);
-    if (lane == 0) { L.wave_need[c][wave] = __popcll(bn); L.wave_free[c][wave] = __popcll(bf); }
-    if (need && cls == c) need_rank = __popcll(bn & ((1ull << lane) - 1ull));
-    if (is_free && slot_cls == c) free_rank = __popcll(bf & ((1ull << lane) - 1ull));
-  }
-  __syncthreads();
-  if (is_free) {
-    int r = cn.start(slot_cls) + free_rank;
-    for (int w = 0; w < wave; ++w) r += L.wave_free[slot_cls][w];
-    L.freeslot[r] = (uint16_t)tid;
-  }
-  __syncthreads();
-  if (cls >= 0) {
-    int sl = old_slot;
-    if (!keep) {
-      int r = cn.start(cls) + need_rank;
-      for (int w = 0; w < wave; ++w) r += L.wave_need[cls][w];
-      sl = L.freeslot[r];
+    for (int c = 0; c < 4; ++c) {
+      const unsigned long long bal = __ballot(cls == c);
+      if (cls == c) my_rank = __popcll(bal & ((1ull << lane) - 1ull));
     }
-    L.slot_of_pos[tid] = (uint16_t)sl;
-    L.pos_of_slot[sl] = (uint16_t)tid;
-    if (keep && L.bits_new[tid] == L.bits_old[tid] && was_cached) L.shf[tid] |= kKeptFlag;
+    if (cls >= 0) {
+      int sl = cn.start(cls) + my_rank;
+      for (int w = 0; w < wave; ++w) sl += L.wave_cnt[cls][w];
+      L.slot_of_pos[tid] = (uint16_t)sl;
+      L.pos_of_slot[sl] = (uint16_t)tid;
+    }
+    __syncthreads();
+  } else {
+    const bool was_cached = tid < n_before;
+    const int old_slot = was_cached ? (int)L.slot_of_pos[tid] : -1;
+    bool keep = false;
+    if (was_cached && cls == qaq_class_of_bits(L.bits_old[tid])) {
+      const int lo = cn.start(cls);
+      const int cnt = cls == QC3 ? cn.n3 : cls == QC2 ? cn.n2 : cls == QC4 ? cn.n4 : cn.n8;
+      keep = old_slot >= lo && old_slot < lo + cnt;
+    }
+    if (keep) L.kept[old_slot] = 1;
+    __syncthreads();
+    // ranks: of the tokens that need a slot (by position), of the free slots (by slot)
+    const bool need = cls >= 0 && !keep;
+    const int slot_cls = tid < n_after ? qaq_class_of_bits(cn.bits_of_slot(tid)) : -1;   // class owning slot `tid`
+    const bool is_free = slot_cls >= 0 && !L.kept[tid];
+    int need_rank = 0, free_rank = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const unsigned long long bn = __ballot(need && cls == c);
+      const unsigned long long bf = __ballot(is_free && slot_cls == c);
+      if (lane == 0) { L.wave_need[c][wave] = __popcll(bn); L.wave_free[c][wave] = __popcll(bf); }
+      if (need && cls == c) need_rank = __popcll(bn & ((1ull << lane) - 1ull));
+      if (is_free && slot_cls == c) free_rank = __popcll(bf & ((1ull << lane) - 1ull));
+    }
+    __syncthreads();
+    if (is_free) {
+      int r = cn.start(slot_cls) + free_rank;
+      for (int w = 0; w < wave; ++w) r += L.wave_free[slot_cls][w];
+      L.freeslot[r] = (uint16_t)tid;
+    }
+    __syncthreads();
+    if (cls >= 0) {
+      int sl = old_slot;
+      if (!keep) {
+        int r = cn.start(cls) + need_rank;
+        for (int w = 0; w < wave; ++w) r += L.wave_need[cls][w];
+        sl = L.freeslot[r];
+      }
+      L.slot_of_pos[tid] = (uint16_t)sl;
+      L.pos_of_slot[sl] = (uint16_t)tid;
+      if (keep && L.bits_new[tid] == L.bits_old[tid] && was_cached) L.shf[tid] |= kKeptFlag;
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   // metadata in slot order, widths by position, class counts
   if (tid < n_after && !(L.shf[tid] & kKeptFlag)) {
