@@ -271,25 +271,38 @@ template <int D, int NO2>
 struct KeyRegs {
   QaqCounts c;
   int n_tok;
-  uint32_t kw2[KRec<D, 2>::RDW], kw1[KRec<D, 1>::RDW];
+  // code words of the lane's own slot: a 2-bit field record in ka, the 1-bit record of a 3-bit
+  // token in kb, or a 4-bit record in ka followed by kb (8-bit records, rare, are fetched when
+  // needed)
+  static constexpr int HALF = KRec<D, 2>::RDW;
+  uint32_t ka[HALF], kb[HALF];
   uint32_t mm, pos;
   Outl<NO2> o;
-  __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& ck, int tid, int wave) {
+  __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& ck, int tid) {
     c = ck;
     n_tok = min(len - tile * QAQ_TT, QAQ_TT);
     const uint8_t* base = qaq_tile_codes(v, 0, b, h, tile);
-    const gbytes_t ubase = uniform_ptr(base);
     const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
     mm = gload32(uniform_ptr(v.mm[0] + gi0), 4u * slot);
     pos = gload32(uniform_ptr(v.perm[0] + gi0), slot & ~3u);   // aligned word; byte slot%4 is the position
     o.load(v, 0, gi0, slot, v.no2);
-    // The 2-bit field region starts at offset 0 of the tile side; slots past the region
-    // read other bytes of the same tile (always inside its reserved capacity) and their
-    // results are not used.
-    gload_dwords<KRec<D, 2>::RDW>(ubase + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, kw2);
+    // one straight-line sequence of loads for every lane, whatever its class: only the offsets
+    // differ (lanes with nothing to fetch read the first bytes of the tile side)
     const QaqKRegions rK = qaq_k_regions(c, D);
-    if (wave * 64 < c.n3) KRec<D, 1>::load(base + rK.r1, min(tid, c.n3 - 1), kw1);
+    const int n32 = c.n32();
+    const bool is3 = tid < c.n3, is23 = tid < n32, is4 = !is23 && tid < n32 + c.n4;
+    const uint32_t rec4 = rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
+    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : is4 ? rec4 : 0u;
+    const uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    const uint32_t off_b1 = is4 ? rec4 + 4u * HALF + 2u * HALF : 0u;
+    const gbytes_t ubase = uniform_ptr(base);
+    gload_dwords<HALF>(ubase + off_a, ka);
+    uint32_t b0[HALF / 2], b1[HALF / 2];
+    gload_dwords<HALF / 2>(ubase + off_b0, b0);
+    gload_dwords<HALF / 2>(ubase + off_b1, b1);
+#pragma unroll
+    for (int i = 0; i < HALF / 2; ++i) { kb[i] = b0[i]; kb[HALF / 2 + i] = b1[i]; }
   }
 };
 
@@ -419,7 +432,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
   };
   KeyRegs<D, NO2> kr;
   ValRegs<D, NO2> vr;
-  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid, wave);
+  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
   vr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
 
   // carried across the tiles
@@ -443,60 +456,51 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   //
     const int first8V = n32V + cV.n4;
 
     // ---- keys: logits ----------------------------------------------------------------------------
+    // Every lane owns slot `tid`; the wavefront runs one contraction chain per width class that
+    // occurs among its 64 slots (one, except where a class boundary falls inside them) and
+    // every lane keeps the result of its own class.
     float vmax = -INFINITY;
-    if (wave * 64 < n32K) {
-      float dotq = real_of(k_contract<D, 2>(kr.kw2, abase0));
-      const bool three = tid < cK.n3;
-      if (wave * 64 < cK.n3) {
-        const float low = real_of(k_contract<D, 1>(kr.kw1, abase1));
-        dotq = three ? 2.0f * dotq + low : dotq;
+    {
+      const int w0 = wave * 64, w1 = w0 + 64;
+      const int first8K = n32K + cK.n4;
+      float dotq = 0.0f;
+      if (w0 < n32K) {
+        dotq = real_of(k_contract<D, 2>(kr.ka, abase0));
+        if (w0 < cK.n3) {
+          uint32_t k1[KRec<D, 1>::RDW];
+#pragma unroll
+          for (int i = 0; i < KRec<D, 1>::RDW; ++i) k1[i] = kr.kb[i];
+          const float low = real_of(k_contract<D, 1>(k1, abase1));
+          dotq = tid < cK.n3 ? 2.0f * dotq + low : dotq;
+        }
       }
-      if (tid < n32K) {
-        const float lg = key_logit(kr.mm, kr.o, slot, three ? 3 : 2, dotq);
+      if (w1 > n32K && w0 < first8K) {
+        uint32_t k4[KRec<D, 4>::RDW];
+#pragma unroll
+        for (int i = 0; i < KeyRegs<D, NO2>::HALF; ++i) { k4[i] = kr.ka[i]; k4[KeyRegs<D, NO2>::HALF + i] = kr.kb[i]; }
+        const float d4 = real_of(k_contract<D, 4>(k4, abase2));
+        if (tid >= n32K) dotq = d4;
+      }
+      if (__builtin_expect(w1 > first8K && cK.n8 > 0, 0)) {
+        // 8-bit key bytes are stored as code - 128: the dot product gets 128 * (sum of the
+        // unscaled query integers) back, rebuilt here from their digits (this class is rare)
+        int sq = 0;
+        for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
+        uint32_t w[KRec<D, 8>::RDW];
+        KRec<D, 8>::load(baseK + rK.r8, min(max(tid - first8K, 0), cK.n8 - 1), w);
+        const v4i cc = k_contract<D, 8>(w, abase2);
+        if (tid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
+      }
+      if (tid < n_tok) {
+        const float lg = key_logit(kr.mm, kr.o, slot, cK.bits_of_slot(tid), dotq);
         S.logit[(kr.pos >> (8u * (slot & 3u))) & 0xffu] = lg;
         vmax = lg;
       }
     }
-    // wider classes: loaded when needed (few tokens at the operating points of interest)
-    for (int grp = wave; grp * 64 < cK.n4; grp += 4) {
-      uint32_t w[KRec<D, 4>::RDW];
-      const int idx = grp * 64 + lane;
-      KRec<D, 4>::load(baseK + rK.r4, min(idx, cK.n4 - 1), w);
-      const v4i cc = k_contract<D, 4>(w, abase2);
-      if (idx < cK.n4) {
-        const size_t gi = gi0 + n32K + idx;
-        Outl<NO2> o; o.load(v, 0, gi0, (uint32_t)(n32K + idx), no2);
-        const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + idx), 4, real_of(cc));
-        S.logit[v.perm[0][gi]] = lg;
-        vmax = vmaxf(vmax, lg);
-      }
-    }
-    // 8-bit key bytes are stored as code - 128: the dot product needs 128 * sum of the
-    // (unscaled) query integers back, rebuilt here from their digits (this class is rare)
-    float sumqi = 0.0f;
-    if (cK.n8 > 0) {
-      int sq = 0;
-      for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
-      sumqi = (float)sq;
-    }
-    for (int grp = wave; grp * 64 < cK.n8; grp += 4) {
-      uint32_t w[KRec<D, 8>::RDW];
-      const int idx = grp * 64 + lane;
-      KRec<D, 8>::load(baseK + rK.r8, min(idx, cK.n8 - 1), w);
-      const v4i cc = k_contract<D, 8>(w, abase2);
-      if (idx < cK.n8) {
-        const size_t gi = gi0 + n32K + cK.n4 + idx;
-        Outl<NO2> o; o.load(v, 0, gi0, (uint32_t)(n32K + cK.n4 + idx), no2);
-        const float dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * sumqi) * qscale;
-        const float lg = key_logit(v.mm[0][gi], o, (uint32_t)(n32K + cK.n4 + idx), 8, dotq);
-        S.logit[v.perm[0][gi]] = lg;
-        vmax = vmaxf(vmax, lg);
-      }
-    }
     // the key registers are free: request the next tile's keys
-    if (tile + 1 < tile_end) kr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid, wave);
+    if (tile + 1 < tile_end) kr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid);
 
     vmax = wave_max(vmax);
     if (lane == 0) S.red[8 + wave] = vmax;
