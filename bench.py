@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--context", type=int, default=None, help="override the context length (debugging)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-op", action="store_true", help="skip the attention-only probe of the other operating point")
     ap.add_argument("--cpu-sequences", type=int, default=8, help="sequences of the oracle's timed sample")
     return ap.parse_args()
 
@@ -89,7 +90,7 @@ def stream_read_gbs(lib, nbytes, reps=16, n_buf=8):
     import torch
     nbytes = int(nbytes) // 16 * 16
     buf = torch.randint(0, 255, (n_buf, nbytes), dtype=torch.uint8, device="cuda")
-    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     for i in range(4):
@@ -305,6 +306,41 @@ def main():
                      "stream_read_GBps": read_gbs, "frac_of_stream_read": gbs_main / read_gbs,
                      "stream_copy_GBps": copy_gbs, "yardstick_bytes": yard_bytes},
     }
+    # the other operating point, attention only: recalibrate, requantize (widening from the fp16
+    # originals), time the tile kernel the same way
+    others = {}
+    for op2 in sorted(OPERATING_POINTS):
+        if op2 == args.op or args.single_op:
+            continue
+        ss2, sx2 = calibrate(caches[0], *OPERATING_POINTS[op2], torch)
+        for l, c in enumerate(caches):
+            c.set_sigmas(ss2, sx2)
+            kb, vb = c.select_bits(None)
+            c.requantize(kb, vb, origK[l], origV[l])
+        torch.cuda.synchronize()
+        n_calls = 4 * L
+        for c in caches:
+            c.profile_begin(n_calls // L + 1)
+        for i in range(n_calls + L):
+            c = caches[i % L]
+            c.decode_attention(qs[i % total_steps], newk[i % L][0], newv[i % L][0], want_scores=True)
+        torch.cuda.synchronize()
+        t_main = []
+        for c in caches:
+            a_ms, _ = c.profile_read()
+            t_main += a_ms[1:]
+            c.profile_begin(0)
+        st2 = caches[0].stats()
+        cb2, _ = algorithmic_bytes(st2, sh, n_o, st2.tokens + 1)
+        b2 = cb2 + B * Hq * D * 2 + B * Hq * st2.tokens * 4
+        us2 = 1e3 * float(np.mean(t_main))
+        th2 = B * Hkv * st2.tokens
+        others[op2] = {"us_tile_kernel": us2, "algorithmic_bytes": b2, "GBps": b2 / (us2 * 1e-6) / 1e9,
+                       "frac_of_hbm_peak": b2 / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                       "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_k)) / th2,
+                       "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_v)) / th2}
+    if others:
+        rec["other_operating_points"] = others
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(sh, s.hist_k, s.hist_v, qn, n_o, args.cpu_sequences)
     print(json.dumps(rec))

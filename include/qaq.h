@@ -181,7 +181,7 @@ int qaq_profile_read(qaq_cache* c, float* host_ms_tile, float* host_ms_merge, in
 
 /* Measurement aids: plain streaming kernels over caller-owned device memory, the yardstick
  * for what this GPU sustains on a pure read (16-byte loads, every byte once, a checksum
- * per workgroup written to dev_sink[0..1023] so that the loads are kept) and on a copy.
+ * per workgroup written to dev_sink[0..4095] so that the loads are kept) and on a copy.
  * bytes must be a multiple of 16, pointers 16-byte aligned.  Asynchronous on `stream`. */
 int qaq_stream_read(const void* dev_src, size_t bytes, uint32_t* dev_sink, void* stream);
 int qaq_stream_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stream);

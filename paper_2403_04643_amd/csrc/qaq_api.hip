@@ -87,18 +87,19 @@ void thresholds(const qaq_cache* c, int T, float* tau_k, float* c_v) {
 // ---- streaming yardsticks ------------------------------------------------------------
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Grid-stride 16-byte loads; every workgroup folds what it read into one word so that the
-// compiler keeps the loads.
+// Every workgroup walks over contiguous 16 KB blocks (four 16-byte loads per thread in
+// flight) and folds what it read into one word so that the compiler keeps the loads.
 __global__ void __launch_bounds__(256) k_stream_read(const u32x4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
   u32x4 acc = {0, 0, 0, 0};
-  size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
-    u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+  const size_t nblk = n16 / 1024;                       // whole blocks of 1024 x 16 bytes
+  for (size_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+    const u32x4* p = src + blk * 1024 + threadIdx.x;
+    const u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 256);
+    const u32x4 c = __builtin_nontemporal_load(p + 512), d = __builtin_nontemporal_load(p + 768);
     acc ^= a ^ b ^ c ^ d;
   }
-  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  for (size_t i = nblk * 1024 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+    acc ^= __builtin_nontemporal_load(src + i);
   uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
   for (int o = 32; o; o >>= 1) x ^= __shfl_xor(x, o);
   __shared__ uint32_t part[4];
@@ -393,7 +394,7 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
 int qaq_stream_read(const void* dev_src, size_t bytes, uint32_t* dev_sink, void* stream) {
   if (!dev_src || !dev_sink || (bytes & 15) || ((uintptr_t)dev_src & 15)) return fail(QAQ_ERR_INVALID_ARG, "qaq_stream_read: NULL or unaligned argument");
   if (bytes == 0) return QAQ_OK;
-  hipLaunchKernelGGL(k_stream_read, dim3(1024), dim3(256), 0, (hipStream_t)stream, (const u32x4*)dev_src, bytes / 16, dev_sink);
+  hipLaunchKernelGGL(k_stream_read, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const u32x4*)dev_src, bytes / 16, dev_sink);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? QAQ_OK : hip_fail(e, "qaq_stream_read");
 }
