@@ -3,7 +3,7 @@
 //
 // Two kernels per call:
 //   k_attn_tile     one workgroup per chunk of consecutive 256-position tiles of one
-//                   (sequence, query head), three workgroups resident per compute unit:
+//                   (sequence, query head), four workgroups resident per compute unit:
 //                   logits, softmax with a running max and sum over the chunk, unnormalised
 //                   output -> partial (max, sum, X); the next tile's loads stay in flight
 //                   while the current tile is computed
@@ -342,7 +342,7 @@ struct ValRegs {
 // constant terms are carried in registers across the tiles with the usual rescaling by
 // exp(old max - new max), and one partial is written per workgroup.
 template <int D, int NO2>
-__global__ __launch_bounds__(kThreads, 3) void k_attn_tile(QaqAttnArgs a) {   // three wavefronts per SIMD
+__global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
   constexpr int KS = D / 64;
   constexpr int NCG = D / 16;
   constexpr int CGW = NCG / 4;              // channel groups per wavefront on the value side
@@ -775,7 +775,7 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   QaqAttnArgs a = a_in;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
-  // tiles per workgroup: as few as keeps the whole grid resident at once (three workgroups
+  // tiles per workgroup: as few as keeps the whole grid resident at once (four workgroups
   // per compute unit), so that no second, partly filled round of workgroups trails the first
   static int n_cu = 0;
   if (n_cu == 0) {
@@ -784,7 +784,7 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
     if (n_cu <= 0) n_cu = 256;
   }
-  const int slots = 3 * n_cu;
+  const int slots = 4 * n_cu;
   const int per_head = slots / BQ > 0 ? slots / BQ : 1;
   a.ntc = ntile > 0 ? (ntile + per_head - 1) / per_head : 1;
   if (a.ntc > QAQ_MAX_NTC) a.ntc = QAQ_MAX_NTC;
