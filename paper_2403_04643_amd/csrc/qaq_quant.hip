@@ -89,13 +89,13 @@ __device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, in
 // planes work on whole 32-bit words: one AND and one shift move four codes, and the
 // token-transposed value planes go through 4x4 byte transposes in registers.
 // ---------------------------------------------------------------------------------
-template <int D>
+template <int D, int MAXO = QAQ_MAX_NO2>   // MAXO: outlier entries held per token (2 in the common one-per-end build)
 struct BuildLds {
   static constexpr int SROW = D / 4 + 1;   // dwords per staged row; the odd stride spreads rows over the banks
   uint32_t stage[QAQ_TT * SROW];           // byte d of row pos = code of channel d
   uint32_t mm[QAQ_TT];                     // fp16 min | fp16 max << 16, by position
-  uint8_t oidx[QAQ_TT][QAQ_MAX_NO2];       // outlier channels, by position
-  uint16_t oval[QAQ_TT][QAQ_MAX_NO2];      // outlier fp16 values
+  uint8_t oidx[QAQ_TT][MAXO];              // outlier channels, by position
+  uint16_t oval[QAQ_TT][MAXO];             // outlier fp16 values
   uint8_t bits_old[QAQ_TT];
   uint8_t bits_new[QAQ_TT];
   uint8_t shf[QAQ_TT];                     // by position: low bits a staged code still has to drop (narrowing);
@@ -275,9 +275,9 @@ struct TokenEncoder {
 };
 
 // Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet).
-template <int D>
-__device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, BuildLds<D>& L) {
-  constexpr int SROW = BuildLds<D>::SROW, NQ = D / 16, KS = D / 64;
+template <int D, int MAXO>
+__device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, BuildLds<D, MAXO>& L) {
+  constexpr int SROW = BuildLds<D, MAXO>::SROW, NQ = D / 16, KS = D / 64;
   const int tid = threadIdx.x;
   const int n32 = c.n32();
   if (side == 0) {
@@ -386,9 +386,9 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 // narrow drop their low bits here (the coarser grid's segments contain the finer one's).
 // c0 = the class counts the tile had before (all zero for a tile that did not exist): a
 // word whose tokens all keep slot and width, in a region that has not moved, is left alone.
-template <int D>
-__device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D>& L) {
-  constexpr int SROW = BuildLds<D>::SROW, NQ = D / 16, KS = D / 64;
+template <int D, int MAXO>
+__device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D, MAXO>& L) {
+  constexpr int SROW = BuildLds<D, MAXO>::SROW, NQ = D / 16, KS = D / 64;
   const int tid = threadIdx.x;
   const int n32 = c.n32();
   const bool had = c0.total() > 0;
@@ -549,8 +549,9 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
 // ---------------------------------------------------------------------------------
 template <int D, bool ONE>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
-  __shared__ BuildLds<D> L;
-  constexpr int SROW = BuildLds<D>::SROW;
+  constexpr int MAXO = ONE ? 2 : QAQ_MAX_NO2;
+  __shared__ BuildLds<D, MAXO> L;
+  constexpr int SROW = BuildLds<D, MAXO>::SROW;
 
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -573,8 +574,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = 0;
   int pos_old = 0;
   uint32_t mm_old = 0;
-  uint8_t oi_old[QAQ_MAX_NO2];
-  uint16_t ov_old[QAQ_MAX_NO2];
+  uint8_t oi_old[MAXO];
+  uint16_t ov_old[MAXO];
   if (n_before > 0) {
     c_old = qaq_load_counts(v, side, b, h, tile);
     if (tid < n_before) {
@@ -582,7 +583,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       pos_old = v.perm[side][gi];
       mm_old = v.mm[side][gi];
 #pragma unroll
-      for (int k = 0; k < QAQ_MAX_NO2; ++k)
+      for (int k = 0; k < MAXO; ++k)
         if (k < v.no2) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
     }
   }
@@ -609,11 +610,11 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       L.slot_of_pos[pos_old] = (uint16_t)tid;
       L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
 #pragma unroll
-      for (int k = 0; k < QAQ_MAX_NO2; ++k)
+      for (int k = 0; k < MAXO; ++k)
         if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
     }
     __syncthreads();
-    unpack_tile<D>(side, base, c_old, L);
+    unpack_tile<D, MAXO>(side, base, c_old, L);
   }
 
   // final width of every position
@@ -807,7 +808,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (side == 1)
       v.vbound[qaq_bh(v, b, h) * v.NT + tile] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
   }
-  pack_tile<D>(side, base, cn, c_old, L);
+  pack_tile<D, MAXO>(side, base, cn, c_old, L);
 }
 
 // ---------------------------------------------------------------------------------
