@@ -97,10 +97,6 @@ __device__ __forceinline__ void gload_dwords(gbytes_t p, uint32_t (&w)[N]) {
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----
-template <int CTRL, int ROW_MASK = 0xf>
-__device__ __forceinline__ float dpp_f(float old, float x) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
-}
 // One instruction per step: the DPP form of the arithmetic instruction itself (the compiler
 // would emit a move with the lane pattern, a NaN-quieting max of each input and the max).
 // A VGPR written by a vector instruction needs two wait states before a DPP read.
@@ -207,7 +203,6 @@ struct TileLds {
                                         // ch sits at column (c + 4*(ch/2)) % 16, so that neighbouring channels'
                                         // 16-byte reads of their copies start in different banks.
   float red[16];
-  int redi[4];
 };
 
 // 64 key records through the matrix unit, one per lane.  Lane (n, g) of the wavefront
@@ -451,7 +446,6 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
     const QaqVRegions rV = qaq_v_regions(cV, D);
     const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
     const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
-    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const int n32K = cK.n32(), n32V = cV.n32();
     const int first8V = n32V + cV.n4;
 
