@@ -293,3 +293,53 @@ def test_decode_steps_chain():
     compare_canonical(oc, gc, "after chain")
     assert len(widths) >= 3
     assert oc.ratio_codes() > 2.0
+
+
+# ------------------------------------------------------------------------------ edge cases
+def test_attention_on_empty_cache_with_new_token():
+    """Nothing cached: the output is the new token's value, its score is one."""
+    sh = W.shape(2, batch=2, n_q_heads=4, n_kv_heads=2, context=8)
+    _, gc = make_pair(sh, 0.01, max_tokens=8)
+    q = W.make_queries(2, sh)[0]
+    kn, vn = W.make_new_token(2, sh)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    G = sh.n_q_heads // sh.n_kv_heads
+    np.testing.assert_allclose(X.cpu().numpy(), np.repeat(vn.astype(F32), G, axis=1), rtol=1e-6, atol=1e-6)
+    np.testing.assert_array_equal(S.cpu().numpy(), np.ones((sh.batch, sh.n_q_heads, 1), F32))
+
+
+def test_attention_is_deterministic():
+    """Same inputs, same bits: nothing in the path depends on the order in which wavefronts
+    or atomics arrive."""
+    sh = W.shape(2, batch=2, n_q_heads=4, n_kv_heads=4, context=1500)
+    K, V = W.make_kv(2, sh)
+    rng = np.random.default_rng(17)
+    bk, bv = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3])
+    _, gc = make_pair(sh, 0.01)
+    gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(2, sh)[0]
+    kn, vn = W.make_new_token(2, sh)
+    X0, S0 = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    for _ in range(3):
+        X1, S1 = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+        np.testing.assert_array_equal(X0.cpu().numpy().view(np.uint32), X1.cpu().numpy().view(np.uint32))
+        np.testing.assert_array_equal(S0.cpu().numpy().view(np.uint32), S1.cpu().numpy().view(np.uint32))
+
+
+def test_single_head_long_context():
+    """One head, 70 000 positions: 274 tiles, one workgroup each, more partials to merge than
+    a wavefront holds in registers."""
+    sh = W.shape(4, batch=1, n_q_heads=1, n_kv_heads=1, context=70000)
+    K, V = W.make_kv(4, sh)
+    rng = np.random.default_rng(23)
+    bk, bv = _rand_bits(rng, K.shape[:3], (0.45, 0.45, 0.07, 0.03)), _rand_bits(rng, K.shape[:3], (0.8, 0.15, 0.03, 0.02))
+    oc, gc = make_pair(sh, 0.01)
+    oc.append(K, V, bk, bv); gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(4, sh)[0]
+    kn, vn = W.make_new_token(4, sh)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    Xo, So = oc.decode_attention(q, kn, vn)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    _log(f"  70000 positions: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+    assert ex.max() < TOL and es.max() < TOL
+    np.testing.assert_allclose(S.cpu().numpy().sum(-1, dtype=np.float64), 1.0, rtol=2e-5)
