@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--context", type=int, default=None, help="override the context length (debugging)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true", help="append, select and requantize as three library calls instead of qaq_decode_update")
     ap.add_argument("--single-op", action="store_true", help="skip the attention-only probe of the other operating point")
     ap.add_argument("--cpu-sequences", type=int, default=8, help="sequences of the oracle's timed sample")
     return ap.parse_args()
@@ -241,9 +242,13 @@ def main():
         l, j = i % L, i // L
         c = caches[l]
         rc = lib.qaq_decode_attention(c.h, P(qs[i]), P(newk[l][j]), P(newv[l][j]), P(out), 1, P(scores), stream)
-        rc |= lib.qaq_quantize_append(c.h, P(newk[l][j]), P(newv[l][j]), 1, None, None, stream)
-        rc |= lib.qaq_select_bits(c.h, P(scores), P(kbits), P(vbits), stream)
-        rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(origK[l]), P(origV[l]), Tcap, stream)
+        if args.separate_calls:
+            rc |= lib.qaq_quantize_append(c.h, P(newk[l][j]), P(newv[l][j]), 1, None, None, stream)
+            rc |= lib.qaq_select_bits(c.h, P(scores), P(kbits), P(vbits), stream)
+            rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(origK[l]), P(origV[l]), Tcap, stream)
+        else:   # the same three operations in one pass over the cache
+            rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(origK[l]), P(origV[l]), Tcap,
+                                        P(kbits), P(vbits), stream)
         assert rc == 0, lib.qaq_last_error()
 
     for i in range(warm):
@@ -291,7 +296,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[1]: LLaMA-7B layer, batch {B}, {Hq} heads, head_dim {D}, context {T0}, "
                                f"operating point {args.op} (mean widths K {mean_k:.2f} / V {mean_v:.2f}), "
-                               f"{L} cache instances rotated", "op": args.op, "layers": L},
+                               f"{L} cache instances rotated", "op": args.op, "layers": L,
+                   "step": "decode_attention + " + ("quantize_append + select_bits + requantize" if args.separate_calls else "decode_update")},
         "us_per_attention_call": us_main + us_merge, "us_tile_kernel": us_main,
         "us_merge_kernel": us_merge,
         "algorithmic_bytes_per_call": bytes_call,

@@ -135,6 +135,22 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
                    const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
                    void* stream);
 
+/* Section 4.2 "Integration in text generation process", the part of one decode step that
+ * follows the attention, in one pass over the cache: record this step's scores in the
+ * window, append the new token, compute the width of every token (the new one included) by
+ * the bit rules, and move every token to its width.  Same result as qaq_quantize_append of
+ * the new token (at the widest width) + qaq_select_bits(dev_scores) + qaq_requantize.
+ *   dev_scores  fp32 [B, Hq, T+1] normalised scores of this step, the new token last
+ *               (what qaq_decode_attention emits when it is given the new token)
+ *   dev_k_new, dev_v_new    fp16 [B, Hkv, D], 16-byte aligned
+ *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, orig_tokens, D] unquantized copies incl. the new
+ *                           token (orig_tokens >= T+1), or NULL as for qaq_requantize
+ *   dev_k_bits, dev_v_bits  out, uint8 [B, Hkv, T+1], or NULL
+ * Returns QAQ_ERR_CAPACITY and changes nothing if the token does not fit. */
+int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_new, const void* dev_v_new,
+                      const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
+                      uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream);
+
 /* Section 2.1 attention over the quantized cache for one new query per head:
  * S = softmax(q K^^T / sqrt(D)), X = S V^, with K^, V^ the midpoint reconstruction and
  * outlier channels at their stored fp16 value.  If dev_k_new/dev_v_new are given, that

@@ -286,6 +286,46 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
   return QAQ_OK;
 }
 
+int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_new, const void* dev_v_new,
+                      const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
+                      uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream) {
+  if (!c || !dev_scores || !dev_k_new || !dev_v_new) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if (((uintptr_t)dev_k_new & 15) || ((uintptr_t)dev_v_new & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
+  if (((uintptr_t)dev_k_orig & 15) || ((uintptr_t)dev_v_orig & 15)) return fail(QAQ_ERR_INVALID_ARG, "originals must be 16-byte aligned");
+  if (c->len + 1 > c->cfg.max_tokens)
+    return fail(QAQ_ERR_CAPACITY, "%d cached + 1 new token exceed max_tokens %d", c->len, c->cfg.max_tokens);
+  if ((dev_k_orig || dev_v_orig) && orig_tokens < c->len + 1)
+    return fail(QAQ_ERR_INVALID_ARG, "unquantized copies hold %d tokens, cache will have %d", orig_tokens, c->len + 1);
+  QaqBuildArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.mode = 2;
+  a.len_before = c->len;
+  a.len_after = c->len + 1;
+  a.tile0 = 0;
+  a.n_new = 1;
+  a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
+  a.newx[0] = (const __half*)dev_k_new; a.newx[1] = (const __half*)dev_v_new;
+  a.orig[0] = (const __half*)dev_k_orig; a.orig[1] = (const __half*)dev_v_orig;
+  a.orig_tokens = orig_tokens;
+  QaqRuleArgs& r = a.rule;
+  r.G = c->dims.Hq / c->dims.Hkv;
+  r.scores = dev_scores;
+  r.score_stride = a.len_after;
+  r.new_row = c->ring_next;
+  c->row_len[c->ring_next] = a.len_after;
+  c->ring_next = (c->ring_next + 1) % c->dims.window;
+  for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
+  r.nbits = c->cfg.n_bits;
+  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+  thresholds(c, a.len_after, r.tau_k, &r.c_v);
+  r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
+  hipError_t e = qaq_launch_build(a, (a.len_after + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_decode_update");
+  c->len = a.len_after;
+  return QAQ_OK;
+}
+
 int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
                          void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
   if (!c || !dev_q || !dev_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");

@@ -42,9 +42,24 @@ __device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side,
   return c;
 }
 
+// What the width rules need (Section 4.1 written as comparisons, Section 4.2 window).
+struct QaqRuleArgs {
+  int G;                   // query heads per KV head
+  const float* scores;     // [B,Hq,score_stride] or null
+  int score_stride;
+  int new_row;             // ring row that receives `scores` (ignored if null)
+  int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
+  int nbits;
+  int bit_set[4];
+  float tau_k[QAQ_MAX_KV_HEADS];
+  float c_v;
+  uint8_t* out_bits[2];    // [B,Hkv,len] or null
+};
+
 struct QaqBuildArgs {
   QaqView v;
-  int mode;          // 0 = append, 1 = requantize
+  int mode;          // 0 = append, 1 = requantize, 2 = decode-step update (append one token, select, requantize)
+  QaqRuleArgs rule;  // mode 2
   int len_before, len_after, tile0, n_new, widest;
   const __half* newx[2];       // append: [B,Hkv,n_new,D]
   const uint8_t* newbits[2];   // append: [B,Hkv,n_new] or null; requantize: [B,Hkv,len] or null

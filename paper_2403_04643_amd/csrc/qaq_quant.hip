@@ -587,6 +587,23 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
         if (k < v.no2) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
     }
   }
+  // decode-step update: the inputs of the width rules that are indexed by position (this
+  // step's scores, the window rows) are requested now as well; the value side keeps the window
+  float pred = 0.0f;
+  if (a.mode == 2 && side == 1 && tid < n_after) {
+    const QaqRuleArgs& ru = a.rule;
+    const int t = t0 + tid;
+    const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
+    const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
+    float s = 0.0f;
+    for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
+    pred = s;
+    for (int r = 0; r < v.window; ++r) {
+      if (r == ru.new_row) continue;
+      if (t < ru.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
+    }
+    v.ring[(size_t)ru.new_row * ring_row + ri] = s;
+  }
   if (a.mode == 1) {
     // no token of the tile changes: leave it alone
     bool changed = false;
@@ -602,20 +619,49 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (!__syncthreads_or(changed ? 1 : 0)) return;
   }
 
-  // metadata by position, codes into the stage
-  if (n_before > 0) {
-    if (tid < n_before) {
-      L.mm[pos_old] = mm_old;
-      L.pos_of_slot[tid] = (uint16_t)pos_old;
-      L.slot_of_pos[pos_old] = (uint16_t)tid;
-      L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
+  // metadata by position
+  if (n_before > 0 && tid < n_before) {
+    L.mm[pos_old] = mm_old;
+    L.pos_of_slot[tid] = (uint16_t)pos_old;
+    L.slot_of_pos[pos_old] = (uint16_t)tid;
+    L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
 #pragma unroll
-      for (int k = 0; k < MAXO; ++k)
-        if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
-    }
-    __syncthreads();
-    unpack_tile<D, MAXO>(side, base, c_old, L);
+    for (int k = 0; k < MAXO; ++k)
+      if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
   }
+  __syncthreads();
+
+  // decode-step update: widths of the cached positions by the rules; the tile is left alone
+  // if none of them moves and the new token is not in it
+  auto rule_width = [&](uint32_t m) {
+    const QaqRuleArgs& ru = a.rule;
+    const float range = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
+    const float lhs = side == 0 ? range : range * pred;
+    const float thr = side == 0 ? ru.tau_k[h] : ru.c_v;
+    int w = ru.bit_set[ru.nbits - 1];
+    for (int i = ru.nbits - 1; i >= 0; --i)
+      if (lhs <= ldexpf(thr, ru.bit_set[i])) w = ru.bit_set[i];
+    return w;
+  };
+  int req_rule = 0;
+  if (a.mode == 2) {
+    bool changed = false;
+    if (tid < n_before) {
+      const int oldb = L.bits_old[tid];
+      req_rule = rule_width(L.mm[tid]);
+      if (a.rule.out_bits[side]) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)req_rule;
+      if (req_rule < oldb) changed = true;
+      else if (req_rule > oldb) {
+        if (a.orig[side]) changed = true;
+        else atomicAdd(v.refused, 1u);
+      }
+    }
+    const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
+    if (!__syncthreads_or(changed ? 1 : 0) && !has_new) return;
+  }
+
+  // codes into the stage
+  if (n_before > 0) unpack_tile<D, MAXO>(side, base, c_old, L);
 
   // final width of every position
   if (tid < n_after) {
@@ -623,8 +669,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (tid < n_before) {
       const int oldb = L.bits_old[tid];
       nb = oldb;
-      if (a.mode == 1) {
-        const int req = a.newbits[side][(size_t)bh * a.len_before + t0 + tid];
+      if (a.mode != 0) {
+        const int req = a.mode == 1 ? (int)a.newbits[side][(size_t)bh * a.len_before + t0 + tid] : req_rule;
         if (req < oldb) { nb = req; drop = oldb - req; }
         else if (req > oldb && a.orig[side]) nb = req;
       }
@@ -672,6 +718,15 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     }
   }
   __syncthreads();
+
+  // decode-step update: the width of the new token by the rules, from the range the encoder
+  // has just found (it was encoded at the widest width; narrowing drops low bits)
+  if (a.mode == 2 && tid == a.len_before - t0) {
+    const int w = rule_width(L.mm[tid]);
+    if (a.rule.out_bits[side]) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)w;
+    L.shf[tid] = (uint8_t)(a.widest - w);
+    L.bits_new[tid] = (uint8_t)w;
+  }
 
   // side store of fresh tokens: order by channel
   if (tid >= n_before && tid < n_after && v.no2 > 1) {

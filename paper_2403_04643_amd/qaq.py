@@ -51,6 +51,7 @@ SIGNATURES = {
     "qaq_quantize_append": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
     "qaq_select_bits": (C.c_int, [_vp, _f32p, _u8p, _u8p, _vp]),
     "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _i32, _vp]),
+    "qaq_decode_update": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
     "qaq_profile_begin": (C.c_int, [_vp, _i32]),
     "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
     "qaq_stream_read": (C.c_int, [_vp, C.c_size_t, _vp, _vp]),
@@ -203,6 +204,23 @@ class Cache:
         if k_orig is not None and v_orig is not None:
             assert k_orig.shape[2] == v_orig.shape[2]
         _check(self.lib.qaq_requantize(self.h, _ptr(k_bits), _ptr(v_bits), _ptr(k_orig), _ptr(v_orig), n_orig, _stream()))
+
+    def decode_update(self, scores, k_new, v_new, k_orig=None, v_orig=None, want_bits=False):
+        """The part of a decode step after the attention, in one call: scores fp32
+        [B, Hq, T+1]; k_new, v_new fp16 [B, Hkv, D]; originals fp16 [B, Hkv, >=T+1, D] or
+        None.  Returns (k_bits, v_bits) uint8 [B, Hkv, T+1] if want_bits."""
+        import torch
+        cfg = self.cfg
+        src = k_orig if k_orig is not None else v_orig
+        n_orig = src.shape[2] if src is not None else 0
+        kb = vb = None
+        if want_bits:
+            T1 = self.length() + 1
+            kb = torch.empty((cfg.batch, cfg.n_kv_heads, T1), dtype=torch.uint8, device="cuda")
+            vb = torch.empty_like(kb)
+        _check(self.lib.qaq_decode_update(self.h, _ptr(scores), _ptr(k_new), _ptr(v_new), _ptr(k_orig), _ptr(v_orig),
+                                          n_orig, _ptr(kb), _ptr(vb), _stream()))
+        return kb, vb
 
     def profile_begin(self, max_calls: int):
         _check(self.lib.qaq_profile_begin(self.h, max_calls))

@@ -343,3 +343,48 @@ def test_single_head_long_context():
     _log(f"  70000 positions: max rel err X {ex.max():.2e}, S {es.max():.2e}")
     assert ex.max() < TOL and es.max() < TOL
     np.testing.assert_allclose(S.cpu().numpy().sum(-1, dtype=np.float64), 1.0, rtol=2e-5)
+
+
+def test_decode_update_in_one_call():
+    """The part of a decode step after the attention as one library call (window update,
+    append, width selection, requantization) against the oracle's four separate steps,
+    and against the library's own three-call sequence."""
+    sh = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=4, context=505)     # crosses a tile border at 512
+    steps = 12
+    K, V = W.make_kv(3, sh)
+    qcal = W.make_queries(3, sh, n=64, seed_offset=9)
+    qn = O.query_norm_statistic(qcal, sh.head_dim)
+    kw = dict(max_tokens=sh.context + steps, window=3, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc, gc = make_pair(sh, qn, **kw)
+    _, gc3 = make_pair(sh, qn, **kw)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V)); gc3.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Xo, So = oc.decode_attention(qs[s], kn, vn)
+        ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+        assert ex.max() < TOL and es.max() < TOL
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        with_orig = s % 3 != 2          # every third step: no unquantized copies, widening is refused
+        ko, vo = (dev(Korig), dev(Vorig)) if with_orig else (None, None)
+        # one call
+        bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), ko, vo, want_bits=True)
+        # three calls on a second cache fed with the same scores
+        gc3.quantize_append(dev(kn[:, :, None]), dev(vn[:, :, None]))
+        bk_3, bv_3 = gc3.select_bits(S)
+        gc3.requantize(bk_3, bv_3, ko, vo)
+        # the oracle
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig if with_orig else None, Vorig if with_orig else None)
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+        np.testing.assert_array_equal(bk_3.cpu().numpy(), bk_o)
+        assert gc.length() == oc.T == gc3.length()
+        if s in (0, 6, steps - 1):
+            compare_canonical(oc, gc, f"one call, step {s}")
+            compare_canonical(oc, gc3, f"three calls, step {s}")
+    assert gc.stats().refused_upgrades == gc3.stats().refused_upgrades == oc.refused
