@@ -104,6 +104,12 @@ struct BuildLds {
   uint16_t pos_of_slot[QAQ_TT];
   uint16_t slot_of_pos[QAQ_TT];
   uint16_t freeslot[QAQ_TT];               // per class, in slot order: the slots nobody keeps
+  uint16_t pos_old[QAQ_TT];                // position of the token that held a slot before
+  uint8_t need[QAQ_TT];                    // by position: 1 = the stored code of this cached token is read again
+                                           // (it moves, or shares a stored word with a token that does), 2 = it is
+                                           // re-encoded from the unquantized copy, 0 = neither
+  uint8_t rew2[16], rew1[16], rew4[32];    // value side: units of the new layout that are written
+  uint8_t old2[16], old1[16], old4[32];    // value side: units of the old layout that hold a needed token
   int wave_cnt[4][4];
   int wave_need[4][4];
   int wave_free[4][4];
@@ -274,7 +280,9 @@ struct TokenEncoder {
   }
 };
 
-// Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet).
+// Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet), for
+// the cached tokens whose codes are read again (L.need == 1); whole words / units that hold
+// none of them are not touched.
 template <int D, int MAXO>
 __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, BuildLds<D, MAXO>& L) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW, NQ = D / 16, KS = D / 64;
@@ -284,11 +292,13 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
     const QaqKRegions r = qaq_k_regions(c, D);
     for (int it = tid; it < n32 * NQ; it += kThreads) {
       const int s = it / NQ, q = it % NQ;
+      const int pos = L.pos_old[s];
+      if (L.need[pos] != 1) continue;
       const bool three = s < c.n3;
       const uint32_t w2 = *(const uint32_t*)(base + r.r2 + 4u * (uint32_t)it);
       uint32_t w1 = 0;
       if (three) w1 = *(const uint32_t*)(base + r.r1 + (uint32_t)s * (D / 8) + 4u * (uint32_t)(q >> 1)) >> (4 * (q & 1));
-      uint32_t* row = &L.stage[L.pos_of_slot[s] * SROW + 16 * (q % KS) + 4 * (q / KS)];
+      uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         uint32_t code = (w2 >> (2 * v)) & 0x03030303u;
@@ -298,15 +308,19 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
     }
     for (int it = tid; it < c.n4 * (D / 8); it += kThreads) {
       const int i4 = it / (D / 8), jj = it % (D / 8), q = jj >> 1, dw = jj & 1;
+      const int pos = L.pos_old[n32 + i4];
+      if (L.need[pos] != 1) continue;
       const uint32_t w = *(const uint32_t*)(base + r.r4 + 4u * (uint32_t)it);
-      uint32_t* row = &L.stage[L.pos_of_slot[n32 + i4] * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
+      uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
       row[0] = w & 0x0f0f0f0fu;
       row[1] = (w >> 4) & 0x0f0f0f0fu;
     }
     for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
       const int i8 = it / (D / 4), jj = it % (D / 4), q = jj >> 2, v = jj & 3;
+      const int pos = L.pos_old[n32 + c.n4 + i8];
+      if (L.need[pos] != 1) continue;
       const uint32_t w = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
-      L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + 16 * (q % KS) + 4 * (q / KS) + v] = w ^ 0x80808080u;
+      L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] = w ^ 0x80808080u;
     }
     return;
   }
@@ -314,6 +328,7 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
   // two-bit fields: a work item is (unit of 16 tokens, four channels)
   for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
     const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    if (!L.old2[u]) continue;
     uint32_t o[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
@@ -327,13 +342,17 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int s = 16 * u + 4 * v + j;
-        if (s < n32) L.stage[L.pos_of_slot[s] * SROW + c4] = s < c.n3 ? w[j] << 1 : w[j];
+        if (s < n32) {
+          const int pos = L.pos_old[s];
+          if (L.need[pos] == 1) L.stage[pos * SROW + c4] = s < c.n3 ? w[j] << 1 : w[j];
+        }
       }
     }
   }
   // four-bit codes: (half-unit of 8 tokens, four channels)
   for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
     const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    if (!L.old4[hu]) continue;
     uint32_t o[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
@@ -347,18 +366,23 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int i4 = 8 * hu + 4 * g2 + j;
-        if (i4 < c.n4) L.stage[L.pos_of_slot[n32 + i4] * SROW + c4] = w[j];
+        if (i4 < c.n4) {
+          const int pos = L.pos_old[n32 + i4];
+          if (L.need[pos] == 1) L.stage[pos * SROW + c4] = w[j];
+        }
       }
     }
   }
   for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
     const int i8 = it / (D / 4), dq = it % (D / 4);
-    L.stage[L.pos_of_slot[n32 + c.n4 + i8] * SROW + dq] = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
+    const int pos = L.pos_old[n32 + c.n4 + i8];
+    if (L.need[pos] == 1) L.stage[pos * SROW + dq] = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
   }
   __syncthreads();
   // low bits of the three-bit tokens: (unit, pair of channel groups, four channels of each)
   for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    if (!L.old1[u]) continue;
     uint32_t o[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
@@ -375,7 +399,10 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int s = 16 * u + 4 * v + j;
-          if (s < c.n3) L.stage[L.pos_of_slot[s] * SROW + c4] |= w[j];
+          if (s < c.n3) {
+            const int pos = L.pos_old[s];
+            if (L.need[pos] == 1) L.stage[pos * SROW + c4] |= w[j];
+          }
         }
       }
     }
@@ -444,16 +471,12 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
     return;
   }
   const QaqVRegions r = qaq_v_regions(c, D), r0 = qaq_v_regions(c0, D);
-  const bool same1 = had && r.r1 == r0.r1;
-  const bool same4 = same32 && r.r4 == r0.r4;
-  const bool same8 = same4 && c0.n4 == c.n4 && r.r8 == r0.r8;
-  // A unit holds up to 16 tokens; the part of the last unit past the region is zero padding.
-  // It is left alone when every token it held keeps slot and width and its padding is where
-  // it was: the unit lies below both the old and the new end, or the end has not moved.
+  const bool same8 = same32 && r.r4 == r0.r4 && c0.n4 == c.n4 && r.r8 == r0.r8;
+  // units: the caller has marked the ones that are written (L.rew2 / rew1 / rew4)
   for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
     const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    if (!L.rew2[u]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
-    bool stays = had && (same32 || 16 * u + 16 <= min(n32, c0.n32()));
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       uint32_t w[4], t[4];
@@ -463,24 +486,21 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
         w[j] = 0;
         if (s < n32) {
           const int pos = L.pos_of_slot[s];
-          const int f = L.shf[pos];
-          stays = stays && (f & kKeptFlag);
-          w[j] = (L.stage[pos * SROW + c4] >> ((f & 7) + (s < c.n3 ? 1 : 0))) & 0x03030303u;
+          w[j] = (L.stage[pos * SROW + c4] >> ((L.shf[pos] & 7) + (s < c.n3 ? 1 : 0))) & 0x03030303u;
         }
       }
       transpose4(w, t);
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] |= t[k] << (2 * v);
     }
-    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
   }
   for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    if (!L.rew1[u]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
-    bool stays = same1 && (c0.n3 == c.n3 || 16 * u + 16 <= min(c.n3, c0.n3));
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       const int c4 = 4 * (2 * cgp + hh) + n4;
@@ -493,9 +513,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
           w[j] = 0;
           if (s < c.n3) {
             const int pos = L.pos_of_slot[s];
-            const int f = L.shf[pos];
-            stays = stays && (f & kKeptFlag);
-            w[j] = (L.stage[pos * SROW + c4] >> (f & 7)) & 0x01010101u;
+            w[j] = (L.stage[pos * SROW + c4] >> (L.shf[pos] & 7)) & 0x01010101u;
           }
         }
         transpose4(w, t);
@@ -503,15 +521,14 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
         for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * hh + v);
       }
     }
-    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) = o[k];
   }
   for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
     const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    if (!L.rew4[hu]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
-    bool stays = same4 && (c0.n4 == c.n4 || 8 * hu + 8 <= min(c.n4, c0.n4));
 #pragma unroll
     for (int g2 = 0; g2 < 2; ++g2) {
       uint32_t w[4], t[4];
@@ -521,16 +538,13 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
         w[j] = 0;
         if (i4 < c.n4) {
           const int pos = L.pos_of_slot[n32 + i4];
-          const int f = L.shf[pos];
-          stays = stays && (f & kKeptFlag);
-          w[j] = (L.stage[pos * SROW + c4] >> (f & 7)) & 0x0f0f0f0fu;
+          w[j] = (L.stage[pos * SROW + c4] >> (L.shf[pos] & 7)) & 0x0f0f0f0fu;
         }
       }
       transpose4(w, t);
 #pragma unroll
       for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * g2);
     }
-    if (stays) continue;
 #pragma unroll
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
@@ -623,6 +637,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   if (n_before > 0 && tid < n_before) {
     L.mm[pos_old] = mm_old;
     L.pos_of_slot[tid] = (uint16_t)pos_old;
+    L.pos_old[tid] = (uint16_t)pos_old;
     L.slot_of_pos[pos_old] = (uint16_t)tid;
     L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
 #pragma unroll
@@ -659,9 +674,6 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
     if (!__syncthreads_or(changed ? 1 : 0) && !has_new) return;
   }
-
-  // codes into the stage
-  if (n_before > 0) unpack_tile<D, MAXO>(side, base, c_old, L);
 
   // final width of every position
   if (tid < n_after) {
@@ -777,6 +789,10 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
   }
   L.kept[tid] = 0;
+  if (tid < 32) {
+    L.rew4[tid] = 0; L.old4[tid] = 0;
+    if (tid < 16) { L.rew2[tid] = 0; L.rew1[tid] = 0; L.old2[tid] = 0; L.old1[tid] = 0; }
+  }
   __syncthreads();
   QaqCounts cn;
   {
@@ -843,6 +859,71 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (keep && L.bits_new[tid] == L.bits_old[tid] && was_cached) L.shf[tid] |= kKeptFlag;
     }
     __syncthreads();
+  }
+
+  // Which stored words are written, and which cached tokens therefore have their stored codes
+  // read back: a key-side word belongs to one token; a value-side unit holds up to 16 tokens
+  // (the part of the last unit past its region is zero padding) and is left alone when every
+  // token in it keeps slot and width, its region has not moved, and its padding is where it
+  // was (the unit lies below both the old and the new end of the region, or the end has not
+  // moved).
+  {
+    const bool had = n_before > 0;
+    const int n32 = cn.n32(), n32o = c_old.n32();
+    bool same1, same4, same8;
+    if (side == 0) {
+      const QaqKRegions r = qaq_k_regions(cn, D), r0 = qaq_k_regions(c_old, D);
+      same1 = had && r.r1 == r0.r1;
+      same4 = had && n32 == n32o && r.r4 == r0.r4;
+      same8 = same4 && c_old.n4 == cn.n4 && r.r8 == r0.r8;
+    } else {
+      const QaqVRegions r = qaq_v_regions(cn, D), r0 = qaq_v_regions(c_old, D);
+      same1 = had && r.r1 == r0.r1;
+      same4 = had && n32 == n32o && r.r4 == r0.r4;
+      same8 = same4 && c_old.n4 == cn.n4 && r.r8 == r0.r8;
+    }
+    // every slot of the new layout votes on its unit (threads of one unit all store the same 1)
+    if (side == 1 && tid < n_after) {
+      const bool kept_here = (L.shf[L.pos_of_slot[tid]] & kKeptFlag) != 0;
+      if (tid < n32) {
+        const int u = tid >> 4;
+        if (!(kept_here && had && (n32 == n32o || 16 * u + 16 <= min(n32, n32o)))) L.rew2[u] = 1;
+        if (tid < cn.n3 && !(kept_here && same1 && (cn.n3 == c_old.n3 || 16 * u + 16 <= min(cn.n3, c_old.n3)))) L.rew1[u] = 1;
+      } else if (tid < n32 + cn.n4) {
+        const int hu = (tid - n32) >> 3;
+        if (!(kept_here && same4 && (cn.n4 == c_old.n4 || 8 * hu + 8 <= min(cn.n4, c_old.n4)))) L.rew4[hu] = 1;
+      }
+    }
+    __syncthreads();
+    if (tid < n_after) {
+      int nd = 0;
+      if (tid < n_before) {
+        if (L.bits_new[tid] > L.bits_old[tid]) nd = 2;
+        else {
+          const bool kept = (L.shf[tid] & kKeptFlag) != 0;
+          const int sl = L.slot_of_pos[tid];
+          if (side == 0) nd = (!kept || (cls == QC3 && !same1) || (cls == QC4 && !same4) || (cls == QC8 && !same8)) ? 1 : 0;
+          else nd = cls == QC3 ? (L.rew2[sl >> 4] | L.rew1[sl >> 4]) : cls == QC2 ? L.rew2[sl >> 4]
+                  : cls == QC4 ? L.rew4[(sl - n32) >> 3] : ((!kept || !same8) ? 1 : 0);
+        }
+      }
+      L.need[tid] = (uint8_t)nd;
+    }
+    __syncthreads();
+    // and every slot of the old layout on the unit its codes are read from
+    if (side == 1 && tid < n_before && L.need[L.pos_old[tid]] == 1) {
+      if (tid < n32o) {
+        L.old2[tid >> 4] = 1;
+        if (tid < c_old.n3) L.old1[tid >> 4] = 1;
+      } else if (tid < n32o + c_old.n4) {
+        L.old4[(tid - n32o) >> 3] = 1;
+      }
+    }
+    __syncthreads();
+    if (had) {
+      unpack_tile<D, MAXO>(side, base, c_old, L);
+      __syncthreads();
+    }
   }
 
   // metadata in slot order, widths by position, class counts
