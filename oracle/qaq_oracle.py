@@ -13,8 +13,8 @@ binary32, round to nearest even, one rounding per operation, never fused);
 attention is evaluated in float64.
 
 Parity status of the parts (what pins each one is listed in tests/test_oracle_*):
-  * attention, quantizer, requantization, outlier split, thresholds, bit rule,
-    window, accounting: pinned.
+  * attention, prompt score rows, quantizer, requantization, outlier split,
+    thresholds, bit rule, window, accounting: pinned.
   * the variance approximation behind the key rule (second-order expansion of
     a ratio, Section 4.1 "Key cache quantization") is a heuristic of the paper:
     only its algebra is pinned -- "parity unpinned" beyond that.
@@ -51,6 +51,32 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray) -> Tuple[np.ndarray, 
     S = e / e.sum()
     X = S @ V
     return X, S
+
+
+# ----------------------------------------------------------------------------
+# Section 2.1, prompt encoding: every prompt token attends to itself and to the
+# tokens before it.  Section 4.2 "attention window" needs, when generation
+# starts, the scores each token received in the last n steps: those are the last
+# n rows of the prompt's causal score matrix.  The paper does not say which keys
+# the prompt's scores are taken over; reading: the unquantized ones (the prompt
+# is encoded before anything is quantized).
+# ----------------------------------------------------------------------------
+def prefill_score_rows(q_last: np.ndarray, K: np.ndarray) -> List[np.ndarray]:
+    """Last n causal score rows of one head.  q_last: [n, D], the queries of prompt
+    positions T-n .. T-1; K: [T, D].  Row i is softmax(q_i K[:T-n+i+1]^T / sqrt(D)),
+    of length T-n+i+1 (a token does not attend to later ones).  float64."""
+    q_last = np.asarray(q_last, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    n, D = q_last.shape
+    T = K.shape[0]
+    assert 1 <= n <= T
+    rows = []
+    for i in range(n):
+        length = T - n + i + 1
+        a = (K[:length] @ q_last[i]) / math.sqrt(D)
+        e = np.exp(a - a.max())
+        rows.append(e / e.sum())
+    return rows
 
 
 # ----------------------------------------------------------------------------
@@ -388,6 +414,30 @@ class OracleCache:
         row = np.stack([gqa_reduce(scores[b], cfg.n_kv_heads) for b in range(cfg.batch)])
         self.history.append(row.astype(F32))
         self.history = self.history[-cfg.window:]
+
+    def prefill(self, q_last: np.ndarray, k: np.ndarray, v: np.ndarray, score_rows=None):
+        """Prompt encoding (Section 2.1) followed by the first quantization (Section 4.2):
+        the last n causal score rows of the prompt (from the unquantized keys) become the
+        window, every prompt token gets the width the rules give for T = prompt length,
+        and is quantized at it.  q_last: fp16 [B, Hq, n, D]; k, v: fp16 [B, Hkv, T, D].
+        score_rows: n arrays fp32 [B, Hq, T-n+i+1] to use instead of computing them (a
+        caller that has to take the width decisions from given fp32 numbers).
+        Returns (k_bits, v_bits, rows)."""
+        cfg = self.cfg
+        assert self.T == 0
+        G = cfg.n_q_heads // cfg.n_kv_heads
+        n = q_last.shape[2]
+        if score_rows is None:
+            per_head = [[prefill_score_rows(q_last[b, hq], k[b, hq // G]) for hq in range(cfg.n_q_heads)]
+                        for b in range(cfg.batch)]
+            score_rows = [np.stack([np.stack([per_head[b][hq][i] for hq in range(cfg.n_q_heads)])
+                                    for b in range(cfg.batch)]).astype(F32) for i in range(n)]
+        self.append(k, v)             # widest width: fixes [min, max] and the outliers
+        for row in score_rows:
+            self.observe(row)
+        bk, bv = self.select_bits()
+        self.requantize(bk, bv)       # narrowing only; equals direct quantization at that width
+        return bk, bv, score_rows
 
     def select_bits(self) -> Tuple[np.ndarray, np.ndarray]:
         """Bits for all T cached tokens from the current window (Section 4.2:

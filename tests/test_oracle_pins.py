@@ -71,6 +71,72 @@ def test_attention_special_cases():
     np.testing.assert_allclose(S[1] / S[0], math.exp(3.0), rtol=1e-13)
 
 
+def test_prefill_rows_brute_force_and_special_cases():
+    """Last n causal score rows of a prompt (Section 2.1 prompt encoding): against explicit
+    loops, and against what the definition fixes -- a token never attends to a later one
+    (row i has T-n+i+1 entries), rows sum to one, equal keys give uniform rows, a common
+    shift of all keys changes nothing, and a key far along the query takes all the weight."""
+    rng = np.random.default_rng(21)
+    T, D, n = 7, 4, 3
+    K = rng.normal(size=(T, D))
+    Q = rng.normal(size=(n, D))
+    rows = O.prefill_score_rows(Q, K)
+    assert [len(r) for r in rows] == [T - n + i + 1 for i in range(n)]
+    for i in range(n):
+        pos = T - n + i                       # position of the query in the prompt
+        logit = [sum(Q[i][d] * K[t][d] for d in range(D)) / math.sqrt(D) for t in range(pos + 1)]
+        z = sum(math.exp(a) for a in logit)
+        for t in range(pos + 1):
+            assert abs(rows[i][t] - math.exp(logit[t]) / z) < 1e-14
+        assert abs(sum(rows[i]) - 1.0) < 1e-14
+    same = O.prefill_score_rows(Q, np.tile(K[:1], (T, 1)))
+    for i, r in enumerate(same):
+        np.testing.assert_allclose(r, 1.0 / (T - n + i + 1), rtol=1e-13)
+    shifted = O.prefill_score_rows(Q, K + rng.normal(size=(1, D)))
+    for r, r2 in zip(rows, shifted):
+        np.testing.assert_allclose(r, r2, rtol=1e-11)
+    K2 = K.copy()
+    K2[2] = 200.0 * Q[0] / np.linalg.norm(Q[0])
+    assert O.prefill_score_rows(Q, K2)[0][2] > 1.0 - 1e-9
+    # one row over the whole prompt is single-query attention over all tokens
+    e = np.exp(K @ Q[-1] / math.sqrt(D))
+    np.testing.assert_allclose(rows[-1], e / e.sum(), rtol=1e-13)
+
+
+def test_prefill_quantizes_at_the_selected_widths():
+    """Prompt encoding followed by the first quantization: every token ends at the width the
+    two rules give for its range and its window maximum, and its codes are those of a direct
+    quantization at that width (checked here with the quantizer formula written out)."""
+    rng = np.random.default_rng(22)
+    B, Hq, Hkv, D, T, n = 1, 4, 2, 16, 40, 3
+    k = rng.normal(size=(B, Hkv, T, D)).astype(F16)
+    v = (rng.normal(size=(B, Hkv, T, D)) * np.exp(rng.normal(size=(1, 1, T, 1)))).astype(F16)
+    q = rng.normal(size=(B, Hq, n, D)).astype(F16)
+    cfg = O.Config(B, Hq, Hkv, D, n_outlier_per_side=0, window=5, sigma_s_max=2e-3, sigma_x_max=0.2,
+                   qnorm2=np.full(Hkv, 1.0, F32))
+    oc = O.OracleCache(cfg)
+    bk, bv, rows = oc.prefill(q, k, v)
+    assert len(set(bv.ravel().tolist())) > 1, "the case must exercise several widths"
+    c_v = 2.0 * math.sqrt(3.0) * cfg.sigma_x_max / math.sqrt(T)
+    for h in range(Hkv):
+        pred = np.zeros(T)
+        for i, row in enumerate(rows):
+            length = T - n + i + 1
+            assert row.shape == (B, Hq, length)
+            pred[:length] = np.maximum(pred[:length], row[0, 2 * h:2 * h + 2].max(0))
+        x = v[0, h].astype(np.float64)
+        rng_t = x.max(1) - x.min(1)
+        for t in range(T):
+            want = next((b for b in (2, 3, 4, 8) if rng_t[t] * pred[t] <= 2.0 ** b * c_v * (1 - 1e-6)), 8)
+            loose = next((b for b in (2, 3, 4, 8) if rng_t[t] * pred[t] <= 2.0 ** b * c_v * (1 + 1e-6)), 8)
+            assert bv[0, h, t] in (want, loose)
+            b_t = int(bv[0, h, t])
+            code = np.clip(np.floor((x[t] - x[t].min()) * 2.0 ** b_t / rng_t[t]), 0, 2 ** b_t - 1)
+            got = oc.V[0][h].codes[t]
+            assert np.abs(got.astype(np.int64) - code.astype(np.int64)).max() <= 1   # fp32 vs fp64 at a segment border
+            assert (got == code).mean() > 0.9
+
+
 def test_attention_sensitivities_finite_difference():
     """Section 3.1: dX_j/dV_ti = S_t [i == j];  dX_j/dK_ti = S_t Q_i (V_tj - X_j),
     times the 1/sqrt(D) the paper leaves out of the key derivative."""
