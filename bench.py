@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true", help="append, select and requantize as three library calls instead of qaq_decode_update")
+    ap.add_argument("--no-extras", action="store_true", help="skip the prompt-encoding timing and the uniform-width sweep")
     ap.add_argument("--single-op", action="store_true", help="skip the attention-only probe of the other operating point")
     ap.add_argument("--cpu-sequences", type=int, default=8, help="sequences of the oracle's timed sample")
     return ap.parse_args()
@@ -347,6 +348,59 @@ def main():
                        "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_v)) / th2}
     if others:
         rec["other_operating_points"] = others
+
+    def time_tile_kernel(n_calls):
+        for c in caches:
+            c.profile_begin(n_calls // L + 1)
+        for i in range(n_calls + L):
+            caches[i % L].decode_attention(qs[i % total_steps], newk[i % L][0], newv[i % L][0], want_scores=True)
+        torch.cuda.synchronize()
+        t = []
+        for c in caches:
+            a_ms, _ = c.profile_read()
+            t += a_ms[1:]
+            c.profile_begin(0)
+        return 1e3 * float(np.mean(t))
+
+    if not args.no_extras:
+        # prompt encoding: window from the last five causal score rows + first quantization at
+        # the selected widths (operating point A's hyper-parameters), on one instance at a time
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        q_last = torch.from_numpy(np.ascontiguousarray(
+            W.make_queries(2, sh, n=5, seed_offset=3).transpose(1, 2, 0, 3))).cuda()
+        rows = torch.empty((5, B, Hq, T0), dtype=torch.float32, device="cuda")
+        t_win, t_app = [], []
+        for l, c in enumerate(caches):
+            Kd, Vd = origK[l][:, :, :T0].contiguous(), origV[l][:, :, :T0].contiguous()
+            c.reset(); c.set_sigmas(ss, sx)
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record(); c.prefill_window(q_last, Kd, rows); e1.record()
+            c.quantize_append_selected(Kd, Vd); e2.record(); torch.cuda.synchronize()
+            t_win.append(e0.elapsed_time(e1)); t_app.append(e1.elapsed_time(e2))
+            del Kd, Vd
+        stp = caches[0].stats()
+        ms_w, ms_a = float(np.mean(t_win[1:] or t_win)), float(np.mean(t_app[1:] or t_app))
+        rec["prompt_encoding"] = {
+            "us_prefill_window": 1e3 * ms_w, "us_quantize_append_selected": 1e3 * ms_a,
+            "tokens_per_s": B * T0 / ((ms_w + ms_a) * 1e-3),
+            "fp16_key_bytes_read": B * Hkv * T0 * D * 2, "window_GBps": B * Hkv * T0 * D * 2 / (ms_w * 1e-3) / 1e9,
+            "hist_k": list(stp.hist_k), "hist_v": list(stp.hist_v)}
+        # every token at one width (the uniform baseline of the paper's comparison): where the
+        # tile kernel sits between instruction issue and HBM as the bytes per token grow
+        sweep = {}
+        for w in (2, 3, 4, 8):
+            for l, c in enumerate(caches):
+                Kd, Vd = origK[l][:, :, :T0].contiguous(), origV[l][:, :, :T0].contiguous()
+                bits = torch.full((B, Hkv, T0), w, dtype=torch.uint8, device="cuda")
+                c.reset(); c.quantize_append(Kd, Vd, bits, bits)
+                del Kd, Vd, bits
+            us_w = time_tile_kernel(2 * L)
+            stw = caches[0].stats()
+            cbw, _ = algorithmic_bytes(stw, sh, n_o, stw.tokens + 1)
+            bw = cbw + B * Hq * D * 2 + B * Hq * stw.tokens * 4
+            sweep[str(w)] = {"us_tile_kernel": us_w, "algorithmic_bytes": bw, "GBps": bw / (us_w * 1e-6) / 1e9,
+                             "frac_of_hbm_peak": bw / (us_w * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        rec["uniform_width_sweep"] = sweep
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(sh, s.hist_k, s.hist_v, qn, n_o, args.cpu_sequences)
     print(json.dumps(rec))

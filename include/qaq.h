@@ -135,6 +135,32 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
                    const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
                    void* stream);
 
+/* Section 2.1 (prompt encoding) with Section 4.2 "Attention score prediction": when generation
+ * starts, the scores each prompt token received in the last n steps are the last n rows of
+ * the prompt's causal score matrix.  Computes those rows from the unquantized keys (a token
+ * attends to itself and to the tokens before it; row i belongs to prompt position
+ * T - n_rows + i and covers T - n_rows + i + 1 tokens) and makes them the window.  The cache
+ * must be empty; follow with qaq_quantize_append_selected (or qaq_quantize_append and
+ * qaq_select_bits(NULL)).
+ *   dev_q_last      fp16 [B, Hq, n_rows, D], queries of the last n_rows prompt positions,
+ *                   1 <= n_rows <= min(window, T), 16-byte aligned
+ *   dev_k           fp16 [B, Hkv, T, D], 16-byte aligned
+ *   dev_scores_out  fp32 [n_rows][B, Hq, T], required (it is also the kernels' working
+ *                   buffer); entries of a row past its length are 0 */
+int qaq_prefill_window(qaq_cache* c, const void* dev_q_last, int32_t n_rows, const void* dev_k, int32_t T,
+                       float* dev_scores_out, void* stream);
+
+/* Section 4.2 (outliers, then the quantizer of Section 4.1) at the widths of Section 4.1's
+ * rules: appends n_new tokens, each at the width the key rule resp. the value rule gives for
+ * its range, the window as it stands (a token no row covers has predicted score 0) and
+ * T = tokens after the append.  Same result as qaq_quantize_append at the widest width +
+ * qaq_select_bits(NULL) + qaq_requantize restricted to the new tokens; cached tokens are not
+ * touched.
+ *   dev_k, dev_v            fp16 [B, Hkv, n_new, D], 16-byte aligned
+ *   dev_k_bits, dev_v_bits  out, uint8 [B, Hkv, n_new], or NULL */
+int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
+                                 uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream);
+
 /* Section 4.2 "Integration in text generation process", the part of one decode step that
  * follows the attention, in one pass over the cache: record this step's scores in the
  * window, append the new token, compute the width of every token (the new one included) by

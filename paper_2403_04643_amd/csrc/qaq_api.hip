@@ -326,6 +326,65 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   return QAQ_OK;
 }
 
+int qaq_prefill_window(qaq_cache* c, const void* dev_q_last, int32_t n_rows, const void* dev_k, int32_t T,
+                       float* dev_scores_out, void* stream) {
+  if (!c || !dev_q_last || !dev_k || !dev_scores_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if (c->len != 0) return fail(QAQ_ERR_INVALID_ARG, "the cache already holds %d tokens", c->len);
+  if (n_rows < 1 || n_rows > c->dims.window) return fail(QAQ_ERR_INVALID_ARG, "n_rows %d outside [1, window %d]", n_rows, c->dims.window);
+  if (T < n_rows) return fail(QAQ_ERR_INVALID_ARG, "prompt of %d tokens is shorter than %d rows", T, n_rows);
+  if (T > c->cfg.max_tokens) return fail(QAQ_ERR_CAPACITY, "prompt of %d tokens exceeds max_tokens %d", T, c->cfg.max_tokens);
+  if (((uintptr_t)dev_q_last & 15) || ((uintptr_t)dev_k & 15)) return fail(QAQ_ERR_INVALID_ARG, "Q/K input must be 16-byte aligned");
+  QaqPrefillArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.T = T;
+  a.n_rows = n_rows;
+  a.G = c->dims.Hq / c->dims.Hkv;
+  a.q = (const __half*)dev_q_last;
+  a.k = (const __half*)dev_k;
+  a.scores = dev_scores_out;
+  hipError_t e = qaq_launch_prefill_window(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_prefill_window");
+  std::memset(c->row_len, 0, sizeof(c->row_len));
+  for (int r = 0; r < n_rows; ++r) c->row_len[r] = T - n_rows + r + 1;
+  c->ring_next = n_rows % c->dims.window;
+  return QAQ_OK;
+}
+
+int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
+                                 uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream) {
+  if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
+  if (n_new < 0) return fail(QAQ_ERR_INVALID_ARG, "n_new is negative");
+  if (n_new == 0) return QAQ_OK;
+  if (!dev_k || !dev_v) return fail(QAQ_ERR_INVALID_ARG, "K/V input is NULL");
+  if (((uintptr_t)dev_k & 15) || ((uintptr_t)dev_v & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
+  if ((long long)c->len + n_new > c->cfg.max_tokens)
+    return fail(QAQ_ERR_CAPACITY, "%d cached + %d new tokens exceed max_tokens %d", c->len, n_new, c->cfg.max_tokens);
+  QaqBuildArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.v = c->view;
+  a.mode = 3;
+  a.len_before = c->len;
+  a.len_after = c->len + n_new;
+  a.tile0 = c->len / QAQ_TT;
+  a.n_new = n_new;
+  a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
+  a.newx[0] = (const __half*)dev_k; a.newx[1] = (const __half*)dev_v;
+  QaqRuleArgs& r = a.rule;
+  r.G = c->dims.Hq / c->dims.Hkv;
+  r.new_row = -1;
+  for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
+  r.nbits = c->cfg.n_bits;
+  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+  thresholds(c, a.len_after, r.tau_k, &r.c_v);
+  r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
+  const int tile_last = (a.len_after - 1) / QAQ_TT;
+  hipError_t e = qaq_launch_build(a, tile_last - a.tile0 + 1, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "qaq_quantize_append_selected");
+  c->len = a.len_after;
+  return QAQ_OK;
+}
+
 int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
                          void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
   if (!c || !dev_q || !dev_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");

@@ -58,8 +58,9 @@ struct QaqRuleArgs {
 
 struct QaqBuildArgs {
   QaqView v;
-  int mode;          // 0 = append, 1 = requantize, 2 = decode-step update (append one token, select, requantize)
-  QaqRuleArgs rule;  // mode 2
+  int mode;          // 0 = append, 1 = requantize, 2 = decode-step update (append one token, select, requantize),
+                     // 3 = append at the widths the rules give from the window as it stands
+  QaqRuleArgs rule;  // modes 2 and 3
   int len_before, len_after, tile0, n_new, widest;
   const __half* newx[2];       // append: [B,Hkv,n_new,D]
   const uint8_t* newbits[2];   // append: [B,Hkv,n_new] or null; requantize: [B,Hkv,len] or null
@@ -95,6 +96,14 @@ struct QaqAttnArgs {
   int nparts;             // partials per (sequence, query head)
 };
 
+struct QaqPrefillArgs {
+  QaqView v;
+  int T, n_rows, G;
+  const __half* q;        // [B,Hq,n_rows,D]: queries of prompt positions T-n_rows .. T-1
+  const __half* k;        // [B,Hkv,T,D]
+  float* scores;          // [n_rows][B,Hq,T]
+};
+
 struct QaqExportArgs {
   QaqView v;
   int len, side;
@@ -117,6 +126,7 @@ hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
 hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
 // ev: NULL, or four events recorded before, between and after the three kernels
 hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev);
+hipError_t qaq_launch_prefill_window(const QaqPrefillArgs& a, hipStream_t s);
 hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
 hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);
 hipError_t qaq_launch_stats(const QaqView& v, int len, hipStream_t s);

@@ -603,20 +603,22 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   // decode-step update: the inputs of the width rules that are indexed by position (this
   // step's scores, the window rows) are requested now as well; the value side keeps the window
+  // (an append by the rules, mode 3, takes the window as it stands and writes no row)
   float pred = 0.0f;
-  if (a.mode == 2 && side == 1 && tid < n_after) {
+  if ((a.mode == 2 || (a.mode == 3 && tid >= n_before)) && side == 1 && tid < n_after) {
     const QaqRuleArgs& ru = a.rule;
     const int t = t0 + tid;
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
     float s = 0.0f;
-    for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
+    if (a.mode == 2)
+      for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
     pred = s;
     for (int r = 0; r < v.window; ++r) {
       if (r == ru.new_row) continue;
       if (t < ru.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
     }
-    v.ring[(size_t)ru.new_row * ring_row + ri] = s;
+    if (a.mode == 2) v.ring[(size_t)ru.new_row * ring_row + ri] = s;
   }
   if (a.mode == 1) {
     // no token of the tile changes: leave it alone
@@ -731,11 +733,14 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   __syncthreads();
 
-  // decode-step update: the width of the new token by the rules, from the range the encoder
-  // has just found (it was encoded at the widest width; narrowing drops low bits)
-  if (a.mode == 2 && tid == a.len_before - t0) {
+  // decode-step update, append by the rules: the width of a new token from the range the
+  // encoder has just found (it was encoded at the widest width; narrowing drops low bits)
+  if ((a.mode == 2 || a.mode == 3) && tid >= n_before && tid < n_after) {
     const int w = rule_width(L.mm[tid]);
-    if (a.rule.out_bits[side]) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)w;
+    if (a.rule.out_bits[side]) {
+      if (a.mode == 2) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)w;
+      else a.rule.out_bits[side][(size_t)bh * a.n_new + (t0 + tid - a.len_before)] = (uint8_t)w;
+    }
     L.shf[tid] = (uint8_t)(a.widest - w);
     L.bits_new[tid] = (uint8_t)w;
   }

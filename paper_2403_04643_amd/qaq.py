@@ -52,6 +52,8 @@ SIGNATURES = {
     "qaq_select_bits": (C.c_int, [_vp, _f32p, _u8p, _u8p, _vp]),
     "qaq_requantize": (C.c_int, [_vp, _u8p, _u8p, _vp, _vp, _i32, _vp]),
     "qaq_decode_update": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
+    "qaq_prefill_window": (C.c_int, [_vp, _vp, _i32, _vp, _i32, _f32p, _vp]),
+    "qaq_quantize_append_selected": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
     "qaq_profile_begin": (C.c_int, [_vp, _i32]),
     "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
     "qaq_stream_read": (C.c_int, [_vp, C.c_size_t, _vp, _vp]),
@@ -220,6 +222,31 @@ class Cache:
             vb = torch.empty_like(kb)
         _check(self.lib.qaq_decode_update(self.h, _ptr(scores), _ptr(k_new), _ptr(v_new), _ptr(k_orig), _ptr(v_orig),
                                           n_orig, _ptr(kb), _ptr(vb), _stream()))
+        return kb, vb
+
+    def prefill_window(self, q_last, k, scores_out=None):
+        """Prompt encoding: q_last fp16 [B, Hq, n, D] (queries of the last n prompt positions),
+        k fp16 [B, Hkv, T, D].  The last n causal score rows become the window.
+        Returns them: fp32 [n, B, Hq, T] (entries of a row past its length are 0)."""
+        import torch
+        cfg = self.cfg
+        n, T = q_last.shape[2], k.shape[2]
+        if scores_out is None:
+            scores_out = torch.empty((n, cfg.batch, cfg.n_q_heads, T), dtype=torch.float32, device=self.device)
+        _check(self.lib.qaq_prefill_window(self.h, _ptr(q_last), n, _ptr(k), T, _ptr(scores_out), _stream()))
+        return scores_out
+
+    def quantize_append_selected(self, k, v, want_bits=False):
+        """k, v: fp16 [B, Hkv, n_new, D], appended at the widths the rules give from the window
+        as it stands.  Returns (k_bits, v_bits) uint8 [B, Hkv, n_new] if want_bits."""
+        import torch
+        cfg = self.cfg
+        n_new = k.shape[2]
+        kb = vb = None
+        if want_bits:
+            kb = torch.empty((cfg.batch, cfg.n_kv_heads, n_new), dtype=torch.uint8, device=self.device)
+            vb = torch.empty_like(kb)
+        _check(self.lib.qaq_quantize_append_selected(self.h, _ptr(k), _ptr(v), n_new, _ptr(kb), _ptr(vb), _stream()))
         return kb, vb
 
     def profile_begin(self, max_calls: int):

@@ -150,3 +150,48 @@ def test_long_context_selected_widths():
         ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
         _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
         assert ex.max() < TOL and es.max() < TOL
+
+
+def test_full_size_prompt_encoding():
+    """Config 2 at full size: the window from the last five causal score rows of the prompt
+    and the first quantization at the selected widths, in the two library calls the
+    benchmark times; sampled units against the oracle."""
+    sh = W.shape(2)
+    _log(f"full size prompt encoding cfg=2 shape={sh}")
+    T, n = sh.context, 5
+    G = sh.n_q_heads // sh.n_kv_heads
+    K, V = W.make_kv(2, sh)
+    q_last = np.ascontiguousarray(W.make_queries(2, sh, n=n, seed_offset=3).transpose(1, 2, 0, 3))
+    qcal = W.make_queries(2, sh, n=4, seed_offset=7).astype(np.float64)
+    qn = np.full(sh.n_kv_heads, float(np.quantile((qcal ** 2).sum(-1).reshape(-1), 0.9)) / sh.head_dim, F32)
+    kw = dict(sigma_s_max=1.8e-5, sigma_x_max=1.85e-2, window=5)     # near the benchmark's operating point A
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, T + 1, qn.tolist(), **kw))
+    rows = gc.prefill_window(dev(q_last), dev(K)).cpu().numpy()
+    np.testing.assert_allclose(rows.sum(-1, dtype=np.float64), 1.0, rtol=2e-5)
+    for i in range(n):
+        assert (rows[i][..., T - n + i + 1:] == 0).all()
+    bk, bv = gc.quantize_append_selected(dev(K), dev(V), want_bits=True)
+    bk, bv = bk.cpu().numpy(), bv.cpu().numpy()
+    hist_k = [int((bk == w).sum()) for w in (2, 3, 4, 8)]
+    hist_v = [int((bv == w).sum()) for w in (2, 3, 4, 8)]
+    _log(f"  width histograms K {hist_k} V {hist_v}")
+    assert sum(c > 0 for c in hist_k) > 1 and sum(c > 0 for c in hist_v) > 1
+    exK = {k: v.cpu().numpy() for k, v in gc.export_canonical(0).items()}
+    exV = {k: v.cpu().numpy() for k, v in gc.export_canonical(1).items()}
+    for b, h in _sample_units(sh, 4, 23):
+        worst = 0.0
+        for g in range(G):
+            hq = h * G + g
+            ref = O.prefill_score_rows(q_last[b, hq], K[b, h])
+            for i in range(n):
+                got = rows[i, b, hq, : T - n + i + 1]
+                worst = max(worst, np.abs(got.astype(np.float64) - ref[i]).max() / ref[i].max())
+        _log(f"  unit b={b} h={h}: worst score error {worst:.2e}")
+        assert worst < TOL
+        oc, _ = _unit_oracle(sh, qn, b, h, **kw)
+        unit_rows = [rows[i][b:b + 1, h * G:(h + 1) * G, : T - n + i + 1] for i in range(n)]
+        bko, bvo, _ = oc.prefill(q_last[b:b + 1, h * G:(h + 1) * G], K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], score_rows=unit_rows)
+        np.testing.assert_array_equal(bk[b, h], bko[0, 0])
+        np.testing.assert_array_equal(bv[b, h], bvo[0, 0])
+        _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"K b={b} h={h}")
+        _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"V b={b} h={h}")
