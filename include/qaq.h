@@ -73,6 +73,8 @@ typedef struct {
   int64_t meta_bytes;        /* min/max, order bytes, outlier side store              */
   int64_t fp16_bytes;        /* the same tokens as an fp16 cache                      */
   int64_t refused_upgrades;  /* widenings asked for without an unquantized copy       */
+  int64_t served_upgrades;   /* widenings done from the unquantized copy (each one reads
+                                one fp16 token vector of it), since qaq_create           */
 } qaq_stats_t;
 
 /* Bytes of device memory the cache needs for this configuration (worst case: every
@@ -169,13 +171,26 @@ int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* de
  *   dev_scores  fp32 [B, Hq, T+1] normalised scores of this step, the new token last
  *               (what qaq_decode_attention emits when it is given the new token)
  *   dev_k_new, dev_v_new    fp16 [B, Hkv, D], 16-byte aligned
- *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, orig_tokens, D] unquantized copies incl. the new
- *                           token (orig_tokens >= T+1), or NULL as for qaq_requantize
+ *   dev_k_orig, dev_v_orig  fp16 [B, Hkv, orig_tokens, D] unquantized copies of the T cached
+ *                           tokens (orig_tokens >= T+1), or NULL as for qaq_requantize.  The
+ *                           call writes the new token into row T of each ("copy the
+ *                           unquantized new KV" of the same passage) and reads the rows of
+ *                           the tokens that widen.  Any memory the device can address
+ *                           serves: HBM, or host memory from qaq_host_alloc (then these two
+ *                           accesses are the transfers between CPU and GPU the passage
+ *                           speaks of, made by the kernel itself, row by row).
  *   dev_k_bits, dev_v_bits  out, uint8 [B, Hkv, T+1], or NULL
  * Returns QAQ_ERR_CAPACITY and changes nothing if the token does not fit. */
 int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_new, const void* dev_v_new,
-                      const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
+                      void* dev_k_orig, void* dev_v_orig, int32_t orig_tokens,
                       uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream);
+
+/* Section 4.2 "Integration": the unquantized copies may live in CPU memory.  Allocates
+ * `bytes` of page-locked host memory that the device can address and returns both views of
+ * it: *host_ptr for the CPU (owned by the caller until qaq_host_free), *dev_ptr for the
+ * dev_*_orig arguments of qaq_requantize and qaq_decode_update.  The contents are undefined. */
+int qaq_host_alloc(size_t bytes, void** host_ptr, void** dev_ptr);
+int qaq_host_free(void* host_ptr);
 
 /* Section 2.1 attention over the quantized cache for one new query per head:
  * S = softmax(q K^^T / sqrt(D)), X = S V^, with K^, V^ the midpoint reconstruction and

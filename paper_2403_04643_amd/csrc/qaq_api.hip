@@ -287,7 +287,7 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
 }
 
 int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_new, const void* dev_v_new,
-                      const void* dev_k_orig, const void* dev_v_orig, int32_t orig_tokens,
+                      void* dev_k_orig, void* dev_v_orig, int32_t orig_tokens,
                       uint8_t* dev_k_bits, uint8_t* dev_v_bits, void* stream) {
   if (!c || !dev_scores || !dev_k_new || !dev_v_new) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   if (((uintptr_t)dev_k_new & 15) || ((uintptr_t)dev_v_new & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
@@ -307,6 +307,7 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
   a.newx[0] = (const __half*)dev_k_new; a.newx[1] = (const __half*)dev_v_new;
   a.orig[0] = (const __half*)dev_k_orig; a.orig[1] = (const __half*)dev_v_orig;
+  a.orig_put[0] = (__half*)dev_k_orig; a.orig_put[1] = (__half*)dev_v_orig;
   a.orig_tokens = orig_tokens;
   QaqRuleArgs& r = a.rule;
   r.G = c->dims.Hq / c->dims.Hkv;
@@ -470,10 +471,10 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   std::memset(out, 0, sizeof(*out));
   out->tokens = c->len;
   long long buf[16] = {0};
-  unsigned int refused = 0;
+  unsigned int refused[2] = {0, 0};
   hipError_t e = qaq_launch_stats(c->view, c->len, (hipStream_t)stream);
   if (e == hipSuccess) e = hipMemcpyAsync(buf, c->view.statbuf, sizeof(buf), hipMemcpyDeviceToHost, (hipStream_t)stream);
-  if (e == hipSuccess) e = hipMemcpyAsync(&refused, c->view.refused, sizeof(refused), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(refused, c->view.refused, sizeof(refused), hipMemcpyDeviceToHost, (hipStream_t)stream);
   if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_stats");
   static const int widths[4] = {2, 3, 4, 8};
@@ -486,7 +487,29 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   out->layout_code_bytes = buf[8];
   out->meta_bytes = buf[9];
   out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
-  out->refused_upgrades = refused;
+  out->refused_upgrades = refused[0];
+  out->served_upgrades = refused[1];
+  return QAQ_OK;
+}
+
+int qaq_host_alloc(size_t bytes, void** host_ptr, void** dev_ptr) {
+  if (!host_ptr || !dev_ptr || bytes == 0) return fail(QAQ_ERR_INVALID_ARG, "qaq_host_alloc: NULL argument or zero size");
+  *host_ptr = *dev_ptr = nullptr;
+  void* h = nullptr;
+  hipError_t e = hipHostMalloc(&h, bytes, hipHostMallocMapped | hipHostMallocPortable);
+  if (e != hipSuccess) return hip_fail(e, "qaq_host_alloc");
+  void* d = nullptr;
+  e = hipHostGetDevicePointer(&d, h, 0);
+  if (e != hipSuccess) { (void)hipHostFree(h); return hip_fail(e, "qaq_host_alloc: device address"); }
+  *host_ptr = h;
+  *dev_ptr = d;
+  return QAQ_OK;
+}
+
+int qaq_host_free(void* host_ptr) {
+  if (!host_ptr) return QAQ_OK;
+  hipError_t e = hipHostFree(host_ptr);
+  if (e != hipSuccess) return hip_fail(e, "qaq_host_free");
   return QAQ_OK;
 }
 

@@ -23,7 +23,7 @@ struct QaqView {
   float* ring;
   float* partial;
   long long* statbuf;
-  unsigned int* refused;
+  unsigned int* refused;   // [0] widenings refused for want of the unquantized copy, [1] widenings served
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
   uint32_t cap[2];
 };
@@ -65,6 +65,7 @@ struct QaqBuildArgs {
   const __half* newx[2];       // append: [B,Hkv,n_new,D]
   const uint8_t* newbits[2];   // append: [B,Hkv,n_new] or null; requantize: [B,Hkv,len] or null
   const __half* orig[2];       // requantize: [B,Hkv,orig_tokens,D] or null
+  __half* orig_put[2];         // same buffers when the appended tokens are to be written into them, else null
   int orig_tokens;             // token extent of the unquantized copies (>= len)
 };
 

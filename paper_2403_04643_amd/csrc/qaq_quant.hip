@@ -629,7 +629,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (req < oldb) changed = true;
       else if (req > oldb) {
         if (a.orig[side]) changed = true;
-        else atomicAdd(v.refused, 1u);
+        atomicAdd(v.refused + (a.orig[side] ? 1 : 0), 1u);     // [0] refused, [1] served
       }
     }
     if (!__syncthreads_or(changed ? 1 : 0)) return;
@@ -670,7 +670,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (req_rule < oldb) changed = true;
       else if (req_rule > oldb) {
         if (a.orig[side]) changed = true;
-        else atomicAdd(v.refused, 1u);
+        atomicAdd(v.refused + (a.orig[side] ? 1 : 0), 1u);
       }
     }
     const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
@@ -715,6 +715,11 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
 #pragma unroll
       for (int i = 0; i < Enc::NCH; ++i) raw[i] = ((const uint4*)src)[4 * i + c];
+      if (fresh && a.orig_put[side]) {     // keep the unquantized token for later widening
+        uint4* dst = (uint4*)(a.orig_put[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D);
+#pragma unroll
+        for (int i = 0; i < Enc::NCH; ++i) dst[4 * i + c] = raw[i];
+      }
       return fresh ? 1 : 2;
     };
     uint4 cur[Enc::NCH], nxt[Enc::NCH];

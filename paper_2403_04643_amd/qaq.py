@@ -34,7 +34,7 @@ class Stats(C.Structure):
     _fields_ = [
         ("tokens", C.c_int64), ("hist_k", C.c_int64 * 4), ("hist_v", C.c_int64 * 4),
         ("code_bytes", C.c_int64), ("layout_code_bytes", C.c_int64), ("meta_bytes", C.c_int64),
-        ("fp16_bytes", C.c_int64), ("refused_upgrades", C.c_int64),
+        ("fp16_bytes", C.c_int64), ("refused_upgrades", C.c_int64), ("served_upgrades", C.c_int64),
     ]
 
 
@@ -54,6 +54,8 @@ SIGNATURES = {
     "qaq_decode_update": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
     "qaq_prefill_window": (C.c_int, [_vp, _vp, _i32, _vp, _i32, _f32p, _vp]),
     "qaq_quantize_append_selected": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
+    "qaq_host_alloc": (C.c_int, [C.c_size_t, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
+    "qaq_host_free": (C.c_int, [_vp]),
     "qaq_profile_begin": (C.c_int, [_vp, _i32]),
     "qaq_profile_read": (C.c_int, [_vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_int32)]),
     "qaq_stream_read": (C.c_int, [_vp, C.c_size_t, _vp, _vp]),
@@ -119,6 +121,8 @@ def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequ
 def _ptr(t) -> Optional[int]:
     if t is None:
         return None
+    if isinstance(t, HostBuffer):
+        return t.dev_ptr
     assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
     return t.data_ptr()
 
@@ -126,6 +130,36 @@ def _ptr(t) -> Optional[int]:
 def _stream() -> int:
     import torch
     return torch.cuda.current_stream().cuda_stream
+
+
+class HostBuffer:
+    """Page-locked host memory the device can address (qaq_host_alloc): `array` is the CPU's
+    view (numpy, the given dtype and shape), `dev_ptr` the address to hand to the library as
+    an unquantized copy."""
+
+    def __init__(self, shape, dtype):
+        import numpy as np
+        self.lib = load()
+        nbytes = int(np.prod(shape)) * np.dtype(dtype).itemsize
+        h, d = C.c_void_p(), C.c_void_p()
+        _check(self.lib.qaq_host_alloc(nbytes, C.byref(h), C.byref(d)))
+        self.host_ptr, self.dev_ptr, self.shape = h.value, d.value, tuple(shape)
+        self.array = np.frombuffer((C.c_char * nbytes).from_address(h.value), dtype=dtype).reshape(shape)
+
+    def data_ptr(self):
+        return self.dev_ptr
+
+    def close(self):
+        if getattr(self, "host_ptr", None):
+            self.array = None
+            self.lib.qaq_host_free(self.host_ptr)
+            self.host_ptr = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Cache:
