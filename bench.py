@@ -178,7 +178,8 @@ def main():
     L, steps, warm = args.layers, args.steps, args.warmup
     total_steps = steps + warm
     per_layer = (total_steps + L - 1) // L
-    Tcap = sh.context + per_layer + 1
+    XS = 0 if args.no_extras else 2          # further steps per instance with the unquantized copies in host memory
+    Tcap = sh.context + per_layer + XS + 1
     B, Hq, Hkv, D, T0 = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
 
     qcal = W.make_queries(2, sh, n=max(1, 1024 // (B * Hq)), seed_offset=7).astype(np.float64)
@@ -222,15 +223,16 @@ def main():
     st0 = [c.stats() for c in caches]
 
     # inputs of the timed steps, resident in HBM before timing starts
-    qs = torch.from_numpy(W.make_queries(2, sh, n=total_steps, seed_offset=1)).cuda()
+    qs = torch.from_numpy(W.make_queries(2, sh, n=(per_layer + XS) * L, seed_offset=1)).cuda()
     newk, newv = [], []
     for l in range(L):
         ks, vs = [], []
-        for j in range(per_layer):
+        for j in range(per_layer + XS):
             kn, vn = W.make_new_token(2, sh, step=1000 * l + j)
             ks.append(kn); vs.append(vn)
         nk = torch.from_numpy(np.stack(ks)).cuda(); nv = torch.from_numpy(np.stack(vs)).cuda()
-        origK[l][:, :, T0:T0 + per_layer] = nk.permute(1, 2, 0, 3); origV[l][:, :, T0:T0 + per_layer] = nv.permute(1, 2, 0, 3)
+        # (qaq_decode_update writes each new token into the copies itself; the separate calls rely on this)
+        origK[l][:, :, T0:T0 + per_layer + XS] = nk.permute(1, 2, 0, 3); origV[l][:, :, T0:T0 + per_layer + XS] = nv.permute(1, 2, 0, 3)
         newk.append(nk); newv.append(nv)
     out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
     scores = torch.empty(B * Hq * (Tcap + 1), dtype=torch.float32, device="cuda")
@@ -239,16 +241,17 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     P = lambda t: C.c_void_p(t.data_ptr())
 
-    def step(i):
+    def step(i, copies=None):
         l, j = i % L, i // L
         c = caches[l]
+        oK, oV = copies if copies else (origK[l], origV[l])
         rc = lib.qaq_decode_attention(c.h, P(qs[i]), P(newk[l][j]), P(newv[l][j]), P(out), 1, P(scores), stream)
         if args.separate_calls:
             rc |= lib.qaq_quantize_append(c.h, P(newk[l][j]), P(newv[l][j]), 1, None, None, stream)
             rc |= lib.qaq_select_bits(c.h, P(scores), P(kbits), P(vbits), stream)
-            rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(origK[l]), P(origV[l]), Tcap, stream)
+            rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(oK), P(oV), Tcap, stream)
         else:   # the same three operations in one pass over the cache
-            rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(origK[l]), P(origV[l]), Tcap,
+            rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(oK), P(oV), Tcap,
                                         P(kbits), P(vbits), stream)
         assert rc == 0, lib.qaq_last_error()
 
@@ -313,6 +316,56 @@ def main():
                      "stream_read_GBps": read_gbs, "frac_of_stream_read": gbs_main / read_gbs,
                      "stream_copy_GBps": copy_gbs, "yardstick_bytes": yard_bytes},
     }
+    served_main = sum(b_.served_upgrades - a_.served_upgrades for a_, b_ in zip(st0, st1)) / total_steps
+    rec["served_upgrades_per_step"] = served_main
+    if not args.no_extras:
+        # Unquantized copies in page-locked host memory instead of HBM: the update kernel writes
+        # the new token there and reads the rows of the tokens that widen, over the host link.
+        hostK = [qaq.HostBuffer((B, Hkv, Tcap, D), np.float16) for _ in range(L)]
+        hostV = [qaq.HostBuffer((B, Hkv, Tcap, D), np.float16) for _ in range(L)]
+        for l in range(L):
+            hostK[l].array[:] = origK[l].cpu().numpy(); hostV[l].array[:] = origV[l].cpu().numpy()
+        torch.cuda.synchronize()
+        i0 = per_layer * L
+        for l in range(L):                 # bring every instance to the same step count
+            for j in range(per_layer):
+                if j * L + l >= total_steps:
+                    step(j * L + l)
+        torch.cuda.synchronize()
+        sa = [c.stats() for c in caches]
+        th0 = time.perf_counter()
+        for i in range(i0, i0 + XS * L):
+            step(i, (hostK[i % L], hostV[i % L]))
+        torch.cuda.synchronize()
+        t_host = (time.perf_counter() - th0) / (XS * L)
+        sb = [c.stats() for c in caches]
+        served_h = sum(b_.served_upgrades - a_.served_upgrades for a_, b_ in zip(sa, sb)) / (XS * L)
+        rec["copies_in_host_memory"] = {
+            "ms_per_step": 1e3 * t_host, "steps": XS * L, "served_upgrades_per_step": served_h,
+            "host_link_bytes_per_step": served_h * D * 2 + 2 * B * Hkv * D * 2}
+        for hb in hostK + hostV:
+            hb.close()
+        # The same steps with a window of one score row: how many more tokens widen when the
+        # prediction is the current score alone (Section 4.2 "attention window").
+        c1 = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=1))
+        c1.set_sigmas(ss, sx)
+        Kd, Vd = origK[0][:, :, :T0].contiguous(), origV[0][:, :, :T0].contiguous()
+        q1 = torch.from_numpy(np.ascontiguousarray(W.make_queries(2, sh, n=1, seed_offset=3).transpose(1, 2, 0, 3))).cuda()
+        c1.prefill_window(q1, Kd)
+        c1.quantize_append_selected(Kd, Vd)
+        del Kd, Vd
+        n1 = min(8, per_layer)
+        for j in range(n1):
+            rc = lib.qaq_decode_attention(c1.h, P(qs[j * L]), P(newk[0][j]), P(newv[0][j]), P(out), 1, P(scores), stream)
+            rc |= lib.qaq_decode_update(c1.h, P(scores), P(newk[0][j]), P(newv[0][j]), P(origK[0]), P(origV[0]), Tcap,
+                                        P(kbits), P(vbits), stream)
+            assert rc == 0, lib.qaq_last_error()
+        torch.cuda.synchronize()
+        s1w = c1.stats()
+        rec["window_of_one"] = {"steps": n1, "served_upgrades_per_step": s1w.served_upgrades / n1,
+                                "hist_k": list(s1w.hist_k), "hist_v": list(s1w.hist_v)}
+        del c1
+
     # the other operating point, attention only: recalibrate, requantize (widening from the fp16
     # originals), time the tile kernel the same way
     others = {}
