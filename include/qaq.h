@@ -229,10 +229,11 @@ int qaq_export_canonical(qaq_cache* c, int32_t side, uint8_t* dev_bits, void* de
 int qaq_stats(qaq_cache* c, qaq_stats_t* host_out, void* stream);
 
 /* Measurement aid: after qaq_profile_begin(c, n), the next n qaq_decode_attention calls
- * record HIP events on their stream before, between and after their two kernels (the
- * per-tile kernel that scans the cache, and the merge).  qaq_profile_read waits for them
- * and returns the elapsed milliseconds of each; host arrays of at least n floats.
- * n = 0 switches it off. */
+ * attach HIP events to the start and the end of their kernel dispatches.  qaq_profile_read
+ * waits for them and returns, per call, the milliseconds of the kernel that scans the cache
+ * (host_ms_tile) and, where the call needed a second kernel to merge partial results, the
+ * time from the end of the first to the end of the second (host_ms_merge; 0 for a call that
+ * ran as one kernel).  Host arrays of at least n floats.  n = 0 switches it off. */
 int qaq_profile_begin(qaq_cache* c, int32_t max_calls);
 int qaq_profile_read(qaq_cache* c, float* host_ms_tile, float* host_ms_merge, int32_t* n_calls);
 

@@ -21,6 +21,7 @@ struct qaq_cache {
   double sigma_s, sigma_x;
   std::vector<hipEvent_t> prof_ev;  // 4 events per profiled attention call
   int prof_n;
+  std::vector<int> prof_kernels;    // dispatches each profiled call made
 };
 
 namespace {
@@ -404,8 +405,11 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
   a.scores = dev_scores_out;
   a.score_stride = c->len + (dev_k_new ? 1 : 0);
   hipEvent_t* ev = nullptr;
-  if (!c->prof_ev.empty() && (size_t)(3 * c->prof_n + 3) <= c->prof_ev.size()) ev = &c->prof_ev[3 * c->prof_n++];
-  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev);
+  int kernels = 0;
+  const bool timed = !c->prof_ev.empty() && (size_t)(4 * c->prof_n + 4) <= c->prof_ev.size();
+  if (timed) ev = &c->prof_ev[4 * c->prof_n];
+  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev, &kernels);
+  if (timed && e == hipSuccess) c->prof_kernels[c->prof_n++] = kernels;
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
   return QAQ_OK;
 }
@@ -415,7 +419,8 @@ int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.clear();
   c->prof_n = 0;
-  for (int i = 0; i < 3 * max_calls; ++i) {
+  c->prof_kernels.assign(max_calls, 0);
+  for (int i = 0; i < 4 * max_calls; ++i) {
     hipEvent_t e;
     hipError_t r = hipEventCreate(&e);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_begin");
@@ -428,9 +433,12 @@ int qaq_profile_read(qaq_cache* c, float* host_ms_tile, float* host_ms_merge, in
   if (!c || !host_ms_tile || !host_ms_merge || !n_calls) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   *n_calls = c->prof_n;
   for (int i = 0; i < c->prof_n; ++i) {
-    hipError_t r = hipEventSynchronize(c->prof_ev[3 * i + 2]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_tile[i], c->prof_ev[3 * i], c->prof_ev[3 * i + 1]);
-    if (r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[3 * i + 1], c->prof_ev[3 * i + 2]);
+    const int k = c->prof_kernels[i];
+    host_ms_tile[i] = host_ms_merge[i] = 0.0f;
+    hipError_t r = hipSuccess;
+    if (k >= 1) r = hipEventSynchronize(c->prof_ev[4 * i + (k == 2 ? 3 : 1)]);
+    if (k >= 1 && r == hipSuccess) r = hipEventElapsedTime(&host_ms_tile[i], c->prof_ev[4 * i], c->prof_ev[4 * i + 1]);
+    if (k == 2 && r == hipSuccess) r = hipEventElapsedTime(&host_ms_merge[i], c->prof_ev[4 * i + 1], c->prof_ev[4 * i + 3]);
     if (r != hipSuccess) return hip_fail(r, "qaq_profile_read");
   }
   c->prof_n = 0;
@@ -471,7 +479,7 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   std::memset(out, 0, sizeof(*out));
   out->tokens = c->len;
   long long buf[16] = {0};
-  unsigned int refused[2] = {0, 0};
+  unsigned int refused[2 * QAQ_NCOUNT] = {0};
   hipError_t e = qaq_launch_stats(c->view, c->len, (hipStream_t)stream);
   if (e == hipSuccess) e = hipMemcpyAsync(buf, c->view.statbuf, sizeof(buf), hipMemcpyDeviceToHost, (hipStream_t)stream);
   if (e == hipSuccess) e = hipMemcpyAsync(refused, c->view.refused, sizeof(refused), hipMemcpyDeviceToHost, (hipStream_t)stream);
@@ -487,8 +495,10 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   out->layout_code_bytes = buf[8];
   out->meta_bytes = buf[9];
   out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
-  out->refused_upgrades = refused[0];
-  out->served_upgrades = refused[1];
+  for (int i = 0; i < QAQ_NCOUNT; ++i) {
+    out->refused_upgrades += refused[i];
+    out->served_upgrades += refused[QAQ_NCOUNT + i];
+  }
   return QAQ_OK;
 }
 

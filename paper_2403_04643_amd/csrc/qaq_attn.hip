@@ -26,11 +26,13 @@
 // signed byte, so it is shifted down instead).  One-bit planes use masks 1,2,4,8 after at
 // most one shift of the dword.
 #include "qaq_internal.h"
+#include <hip/hip_ext.h>
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int QAQ_MAX_NTC = 64;   // tiles per workgroup at most
+constexpr int kFusedMaxTiles = 32;   // fused form: tiles of one head whose raw logits are kept in LDS (1 KB each)
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float h2f(uint16_t b) { return __half2float(__ushort_as_half(b)); }
@@ -203,6 +205,7 @@ struct TileLds {
                                         // ch sits at column (c + 4*(ch/2)) % 16, so that neighbouring channels'
                                         // 16-byte reads of their copies start in different banks.
   float red[16];
+  float part[D + 4];                    // fused form: this part's partial (output, then max, sum)
 };
 
 // 64 key records through the matrix unit, one per lane.  Lane (n, g) of the wavefront
@@ -332,23 +335,35 @@ struct ValRegs {
 };
 
 // ---------------------------------------------------------------------------------------
-// One workgroup: one (sequence, query head), tiles [chunk*ntc, chunk*ntc + ntc).  The loads
+// One workgroup: one (sequence, query head), part `chunk` of its tiles: the tiles are split
+// into nparts runs whose lengths differ by at most one, the longer runs last (the last tile
+// is the one that may be partly filled).  The loads
 // of tile t+1 are in flight while tile t is computed; the output, the softmax sum and the
 // constant terms are carried in registers across the tiles with the usual rescaling by
 // exp(old max - new max), and one partial is written per workgroup.
-template <int D, int NO2>
-__global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
+//
+// Two forms.  P = 0: one part per workgroup of 256 threads; the partial goes to HBM and
+// k_attn_combine merges the parts.  P = 1..4 (fused): the P parts of a head are the P groups
+// of 256 threads of one workgroup, each with its own LDS block, in lockstep (every group runs
+// the same number of iterations and skips the work of those past its last tile, so that all
+// barriers are met by all wavefronts); raw logits stay in LDS, the parts are merged in LDS,
+// and the workgroup writes the output and the normalised scores itself: no second kernel.
+template <int D, int NO2, int P>
+__global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
   constexpr int KS = D / 64;
   constexpr int NCG = D / 16;
   constexpr int CGW = NCG / 4;              // channel groups per wavefront on the value side
-  __shared__ TileLds<D> S;
+  __shared__ TileLds<D> S_all[P ? P : 1];
+  extern __shared__ float lg_all[];         // fused form: raw logits [part][iteration][position]
   const QaqView& v = a.v;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = P ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8)) : (int)blockIdx.x;
+  TileLds<D>& S = S_all[P ? chunk : 0];
+  const int tid = threadIdx.x & (kThreads - 1), lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 15, g = lane >> 4;
-  const int chunk = blockIdx.x;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
-  const int tile_begin = chunk * a.ntc, tile_end = min(tile_begin + a.ntc, ntile);
+  const int tile_begin = (int)((long long)chunk * ntile / a.nparts);
+  const int tile_end = (int)((long long)(chunk + 1) * ntile / a.nparts);
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
@@ -438,7 +453,10 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
 #pragma unroll
   for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
+  const int n_iter = P ? a.ntc : tile_end - tile_begin;
+  for (int it = 0; it < n_iter; ++it) {
+    const int tile = tile_begin + it;
+    const bool on = !P || tile < tile_end;       // uniform over the part's 256 threads
     const QaqCounts cK = kr.c, cV = vr.c;
     const int n_tok = kr.n_tok;
     const uint32_t slot = (uint32_t)min(tid, n_tok - 1);   // the slot this lane's metadata was loaded for
@@ -454,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
     // occurs among its 64 slots (one, except where a class boundary falls inside them) and
     // every lane keeps the result of its own class.
     float vmax = -INFINITY;
-    {
+    if (on) {
       const int w0 = wave * 64, w1 = w0 + 64;
       const int first8K = n32K + cK.n4;
       float dotq = 0.0f;
@@ -500,17 +518,20 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
     if (lane == 0) S.red[8 + wave] = vmax;
     lds_barrier();
     const float m_tile = vmaxf(vmaxf(S.red[8], S.red[9]), vmaxf(S.red[10], S.red[11]));
-    const float smax = S.vb[tile - tile_begin];     // bound on w/p and on the outlier corrections over the tile
+    const float smax = on ? S.vb[tile - tile_begin] : 0.0f;     // bound on w/p and on the outlier corrections over the tile
     const float M = vmaxf(m_run, m_tile);
-    const float keep = __expf(m_run - M);          // 0 on the first tile
+    const float keep = on ? __expf(m_run - M) : 1.0f;          // 0 on the first tile
     m_run = M;
     int wexp = 0;
     if (smax > 0.0f) (void)frexpf(smax, &wexp);
     const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 28) : 0.0f;
 
     // ---- values: weight of slot `tid`, as digits -------------------------------------------------
-    if (a.scores && tid < n_tok) a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
-    {
+    if (a.scores && on && tid < n_tok) {
+      if (P) lg_all[((chunk * a.ntc + it) << 8) + tid] = S.logit[tid];
+      else a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
+    }
+    if (on) {
       const int s = tid;
       const bool live = s < n_tok;
       float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
@@ -563,6 +584,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
       }
     }
     lds_barrier();
+    if (!on) continue;
     // outlier corrections of this tile: channel tid sums its 16 copies in a fixed order,
     // carries the result like the output, and clears the copies for the next tile
     if (wave < KS) {
@@ -652,15 +674,53 @@ __global__ __launch_bounds__(kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   //
     if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
     if (wave < KS) S.xcorr[tid] = c_run;
   }
+  if (P && chunk == 0 && a.k_new) {      // fused form: the logit of the unquantized new token, by the first part
+    float qk = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) * __half2float(a.k_new[((size_t)b * v.Hkv + h) * D + tid]) : 0.0f;
+    qk = wave_sum(qk);
+    if (lane == 0) S.red[8 + wave] = qk;
+  }
   lds_barrier();
   const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
   const float bias = (S.red[4] + S.red[5]) + (S.red[6] + S.red[7]);
-  float* part = v.partial + ((size_t)bq * v.NT + chunk) * (D + 4);
+  float* part = P ? &S.part[0] : v.partial + ((size_t)bq * v.NT + chunk) * (D + 4);
   if (g == 0) {
 #pragma unroll
     for (int j = 0; j < CGW; ++j) part[(D / 4) * wave + 16 * j + nn] = xrun[j] + bias + S.xcorr[(D / 4) * wave + 16 * j + nn];
   }
   if (tid == 0) { part[D] = m_run; part[D + 1] = lsum; }
+  if (!P) return;
+
+  // ---- fused form: merge the P parts, add the new token, normalise, write -----------------------
+  lds_barrier();
+  const TileLds<D>& S0 = S_all[0];
+  float a_new = -INFINITY;
+  if (a.k_new) a_new = ((S0.red[8] + S0.red[9]) + (S0.red[10] + S0.red[11])) / sqrtf((float)D);
+  float Mx = a_new;
+#pragma unroll
+  for (int p = 0; p < (P ? P : 1); ++p) Mx = fmaxf(Mx, S_all[p].part[D]);
+  float fac[P ? P : 1];
+  float ltot = 0.0f;
+#pragma unroll
+  for (int p = 0; p < (P ? P : 1); ++p) { fac[p] = __expf(S_all[p].part[D] - Mx); ltot += fac[p] * S_all[p].part[D + 1]; }
+  float e_new = 0.0f;
+  if (a.k_new) { e_new = __expf(a_new - Mx); ltot += e_new; }
+  const float inv = 1.0f / ltot;
+  if (chunk == 0 && tid < D) {
+    float x = 0.0f;
+#pragma unroll
+    for (int p = 0; p < (P ? P : 1); ++p) x += fac[p] * S_all[p].part[tid];
+    if (a.k_new) x += e_new * __half2float(a.v_new[((size_t)b * v.Hkv + h) * D + tid]);
+    if (a.out_is_fp32) ((float*)a.out)[(size_t)bq * D + tid] = x * inv;
+    else ((__half*)a.out)[(size_t)bq * D + tid] = __float2half_rn(x * inv);
+  }
+  if (a.scores) {
+    float* sc = a.scores + (size_t)bq * a.score_stride;
+    for (int it = 0; it < tile_end - tile_begin; ++it) {
+      const int t = (tile_begin + it) * QAQ_TT + tid;
+      if (t < a.len) sc[t] = __expf(lg_all[((chunk * a.ntc + it) << 8) + tid] - Mx) * inv;
+    }
+    if (a.k_new && chunk == 0 && tid == 0) sc[a.len] = e_new * inv;
+  }
 }
 
 // Merge the tiles of one (sequence, query head), add the unquantized new token and
@@ -756,21 +816,36 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   }
 }
 
+// P = 0: grid (nparts, B*Hq), k_attn_combine follows.  P = nparts in 1..4: grid (1, B*Hq),
+// workgroups of 256*P threads, lds = bytes of the raw-logit store.
+// e0, e1: NULL, or events that take the start and the end of this dispatch.
+template <int D, int P>
+void launch_tile_p(const QaqAttnArgs& a, dim3 grid, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  const dim3 block((P ? P : 1) * kThreads);
+  if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P>), grid, block, lds, s, e0, e1, 0, a);
+  else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P>), grid, block, lds, s, e0, e1, 0, a);
+  else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P>), grid, block, lds, s, e0, e1, 0, a);
+}
 template <int D>
-void launch_tile(const QaqAttnArgs& a, dim3 grid, hipStream_t s) {
-  if (a.v.no2 == 2) hipLaunchKernelGGL((k_attn_tile<D, 2>), grid, dim3(kThreads), 0, s, a);
-  else if (a.v.no2 == 0) hipLaunchKernelGGL((k_attn_tile<D, 0>), grid, dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL((k_attn_tile<D, 8>), grid, dim3(kThreads), 0, s, a);
+void launch_tile(const QaqAttnArgs& a, int fused_parts, int BQ, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  switch (fused_parts) {
+    case 1: launch_tile_p<D, 1>(a, dim3(1, BQ), lds, s, e0, e1); break;
+    case 2: launch_tile_p<D, 2>(a, dim3(1, BQ), lds, s, e0, e1); break;
+    case 3: launch_tile_p<D, 3>(a, dim3(1, BQ), lds, s, e0, e1); break;
+    case 4: launch_tile_p<D, 4>(a, dim3(1, BQ), lds, s, e0, e1); break;
+    default: launch_tile_p<D, 0>(a, dim3(a.nparts, BQ), 0, s, e0, e1); break;
+  }
 }
 
 }  // namespace
 
-hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent_t* ev) {
+hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent_t* ev, int* kernels) {
   QaqAttnArgs a = a_in;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
-  // tiles per workgroup: as few as keeps the whole grid resident at once (four workgroups
-  // per compute unit), so that no second, partly filled round of workgroups trails the first
+  // parts per (sequence, query head): as many as keep the whole grid resident at once (four
+  // workgroups per compute unit), so that no second, partly filled round of workgroups trails
+  // the first; every part gets floor or ceil of ntile/nparts tiles
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0;
@@ -780,19 +855,25 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   }
   const int slots = 4 * n_cu;
   const int per_head = slots / BQ > 0 ? slots / BQ : 1;
-  a.ntc = ntile > 0 ? (ntile + per_head - 1) / per_head : 1;
-  if (a.ntc > QAQ_MAX_NTC) a.ntc = QAQ_MAX_NTC;
-  a.nparts = ntile > 0 ? (ntile + a.ntc - 1) / a.ntc : 0;
-  if (ev) (void)hipEventRecord(ev[0], s);
+  a.nparts = ntile < per_head ? ntile : per_head;
+  const int least = (ntile + QAQ_MAX_NTC - 1) / QAQ_MAX_NTC;    // a part holds at most QAQ_MAX_NTC tiles
+  if (a.nparts < least) a.nparts = least;
+  a.ntc = a.nparts > 0 ? (ntile + a.nparts - 1) / a.nparts : 0;
+  // Fused form (no second kernel) when the parts of a head fit one workgroup and their raw
+  // logits fit its LDS next to the parts' working blocks.
+  const bool fused = ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;
+  if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
   if (ntile > 0) {
-    if (a.v.D == 128) launch_tile<128>(a, dim3(a.nparts, BQ), s);
-    else launch_tile<64>(a, dim3(a.nparts, BQ), s);
+    const int fp = fused ? a.nparts : 0;
+    const size_t lds = fused && a.scores ? (size_t)a.nparts * a.ntc * QAQ_TT * sizeof(float) : 0;
+    if (a.v.D == 128) launch_tile<128>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
+    else launch_tile<64>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
   }
-  if (ev) (void)hipEventRecord(ev[1], s);
+  if (fused) return hipGetLastError();
   const int nblk = a.scores ? (a.len + 4 * kThreads - 1) / (4 * kThreads) : 1;
   dim3 grid(nblk < 1 ? 1 : nblk, BQ);
-  if (a.v.D == 128) hipLaunchKernelGGL(k_attn_combine<128>, grid, dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL(k_attn_combine<64>, grid, dim3(kThreads), 0, s, a);
-  if (ev) (void)hipEventRecord(ev[2], s);
+  hipEvent_t c0 = ev && ntile > 0 ? ev[2] : nullptr, c1 = ev && ntile > 0 ? ev[3] : nullptr;
+  if (a.v.D == 128) hipExtLaunchKernelGGL(k_attn_combine<128>, grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+  else hipExtLaunchKernelGGL(k_attn_combine<64>, grid, dim3(kThreads), 0, s, c0, c1, 0, a);
   return hipGetLastError();
 }

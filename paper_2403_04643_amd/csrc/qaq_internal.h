@@ -93,7 +93,7 @@ struct QaqAttnArgs {
   int out_is_fp32;
   float* scores;          // [B,Hq,len(+1)] or null
   int score_stride;       // len (+1)
-  int ntc;                // tiles per workgroup of the tile kernel (set by the launcher)
+  int ntc;                // most tiles any workgroup of the tile kernel gets (set by the launcher)
   int nparts;             // partials per (sequence, query head)
 };
 
@@ -125,8 +125,10 @@ struct QaqDequantArgs {
 hipError_t qaq_launch_init(const QaqView& v, hipStream_t s);
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
 hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
-// ev: NULL, or four events recorded before, between and after the three kernels
-hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev);
+// ev: NULL, or four events that take the start and the end of the dispatch of the tile kernel
+// ([0], [1]) and of the merge kernel ([2], [3], two-kernel form only); *kernels = dispatches
+// made (0 for an empty cache without timing, 1 fused, 2 tile + merge)
+hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev, int* kernels);
 hipError_t qaq_launch_prefill_window(const QaqPrefillArgs& a, hipStream_t s);
 hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
 hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);

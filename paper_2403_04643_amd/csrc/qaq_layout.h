@@ -36,6 +36,7 @@
 
 #define QAQ_TT 256           // positions per tile
 #define QAQ_MAX_NO2 8        // 2 * max outliers per side
+#define QAQ_NCOUNT 64         // partial counters per kind of widening (spreads the atomics)
 
 #if defined(__HIPCC__)
 #define QAQ_HD __host__ __device__ __forceinline__
@@ -162,7 +163,7 @@ struct QaqArena {
   size_t ring;        // f32  [window][B][Hkv][Tmax]
   size_t partial;     // f32  [B][Hq][NT][D+4]
   size_t statbuf;     // i64  [32]
-  size_t refused;     // u32  [4]
+  size_t refused;     // u32  [2][QAQ_NCOUNT] widenings refused / served, partial counts
   size_t total;
 };
 
@@ -184,7 +185,7 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * 4);
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
   a.statbuf = off; off = qaq_up256(off + 32 * 8);
-  a.refused = off; off = qaq_up256(off + 16);
+  a.refused = off; off = qaq_up256(off + 2 * QAQ_NCOUNT * 4);
   a.total = off;
   return a;
 }

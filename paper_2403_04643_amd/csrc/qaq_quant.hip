@@ -561,6 +561,16 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
 // Tile build: append new tokens and / or move cached tokens to other widths, then
 // write the tile side back in class order.
 // ---------------------------------------------------------------------------------
+// Widenings asked for in this wavefront: one atomic per wavefront that has any, spread over
+// QAQ_NCOUNT counters per kind (v.refused[kind * QAQ_NCOUNT + i]; kind 0 = refused for want of
+// the unquantized copy, 1 = served); the host sums them.
+__device__ __forceinline__ void count_widenings(const QaqView& v, bool wider, bool served) {
+  const unsigned long long bal = __ballot(wider);
+  if (bal != 0ull && (threadIdx.x & 63) == 0)
+    atomicAdd(v.refused + (served ? QAQ_NCOUNT : 0) + ((blockIdx.x + 5 * blockIdx.y + (threadIdx.x >> 6)) & (QAQ_NCOUNT - 1)),
+              (unsigned int)__popcll(bal));
+}
+
 template <int D, bool ONE>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   constexpr int MAXO = ONE ? 2 : QAQ_MAX_NO2;
@@ -622,16 +632,14 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   if (a.mode == 1) {
     // no token of the tile changes: leave it alone
-    bool changed = false;
+    bool changed = false, wider = false;
     if (tid < n_before) {
       const int oldb = v.tags[side][qaq_slot_index(v, b, h, tile, tid)];
       const int req = a.newbits[side][(size_t)bh * a.len_before + t0 + tid];
       if (req < oldb) changed = true;
-      else if (req > oldb) {
-        if (a.orig[side]) changed = true;
-        atomicAdd(v.refused + (a.orig[side] ? 1 : 0), 1u);     // [0] refused, [1] served
-      }
+      else if (req > oldb) { wider = true; if (a.orig[side]) changed = true; }
     }
+    count_widenings(v, wider, a.orig[side] != nullptr);
     if (!__syncthreads_or(changed ? 1 : 0)) return;
   }
 
@@ -662,17 +670,15 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   };
   int req_rule = 0;
   if (a.mode == 2) {
-    bool changed = false;
+    bool changed = false, wider = false;
     if (tid < n_before) {
       const int oldb = L.bits_old[tid];
       req_rule = rule_width(L.mm[tid]);
       if (a.rule.out_bits[side]) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)req_rule;
       if (req_rule < oldb) changed = true;
-      else if (req_rule > oldb) {
-        if (a.orig[side]) changed = true;
-        atomicAdd(v.refused + (a.orig[side] ? 1 : 0), 1u);
-      }
+      else if (req_rule > oldb) { wider = true; if (a.orig[side]) changed = true; }
     }
+    count_widenings(v, wider, a.orig[side] != nullptr);
     const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
     if (!__syncthreads_or(changed ? 1 : 0) && !has_new) return;
   }
@@ -700,17 +706,31 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
 
   // encode: new tokens, and cached tokens that widen (from the unquantized copy).  A quad of
   // lanes per token, 64 tokens per pass; the rows of the next pass are requested before the
-  // current pass is computed.
+  // current pass is computed.  In a tile that has cached tokens the few positions to encode
+  // are first gathered into a list, so that they fill passes densely.
   {
     typedef TokenEncoder<D, ONE> Enc;
     constexpr int TPP = kThreads / 4;     // tokens per pass
-    constexpr int NP = QAQ_TT / TPP;
+    const bool listed = n_before > 0;
+    int n_enc = n_after;
+    if (listed) {
+      const bool enc = tid < n_after && (tid >= n_before || L.bits_new[tid] > L.bits_old[tid]);
+      const unsigned long long bal = __ballot(enc);
+      if (lane == 0) L.wave_cnt[0][wave] = __popcll(bal);
+      __syncthreads();
+      int off = 0;
+      for (int w = 0; w < wave; ++w) off += L.wave_cnt[0][w];
+      if (enc) L.freeslot[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)tid;
+      n_enc = L.wave_cnt[0][0] + L.wave_cnt[0][1] + L.wave_cnt[0][2] + L.wave_cnt[0][3];
+      __syncthreads();
+    }
+    const int NP = (n_enc + TPP - 1) / TPP;
     const int c = tid & 3, gt = tid >> 2;
+    auto position = [&](int pass) { const int e = pass * TPP + gt; return listed ? (int)L.freeslot[min(e, QAQ_TT - 1)] : e; };
     auto fetch = [&](int pass, uint4 (&raw)[Enc::NCH]) -> int {   // 0 = nothing to do, 1 = fresh, 2 = widen
-      const int p = pass * TPP + gt;
-      if (pass >= NP || p >= n_after) return 0;
+      if (pass >= NP || pass * TPP + gt >= n_enc) return 0;
+      const int p = position(pass);
       const bool fresh = p >= n_before;
-      if (!fresh && !(L.bits_new[p] > L.bits_old[p])) return 0;
       const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
 #pragma unroll
@@ -728,7 +748,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     for (int pass = 0; pass < NP; ++pass) {
       const int kind_next = fetch(pass + 1, nxt);
       if (kind) {                          // whole quads drop out together
-        const int p = pass * TPP + gt;
+        const int p = position(pass);
         Enc::run(cur, c, kind == 1, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW]);
       }
 #pragma unroll
@@ -1109,7 +1129,7 @@ __global__ void k_init(QaqView v) {
   const size_t n = (size_t)v.B * v.Hkv * v.NT * 2 * 4;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) v.counts[i] = 0;
   if (blockIdx.x == 0 && threadIdx.x < 32) v.statbuf[threadIdx.x] = 0;
-  if (blockIdx.x == 0 && threadIdx.x < 4) v.refused[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 2 * QAQ_NCOUNT) v.refused[threadIdx.x] = 0;
 }
 
 __global__ void k_clear_stats(QaqView v) {
