@@ -386,6 +386,18 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   S.zrow[tid] = 0;
   for (int e = tid; e < D * 16; e += kThreads) (&S.xc[0][0])[e] = 0;
   lds_barrier();
+  // the first tile's codes and metadata are requested before the query digits are made
+  auto counts_of = [&](int t, int side) {
+    const uint2 c = *(const uint2*)&S.cnt[t - tile_begin][4 * side];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
+    QaqCounts r;
+    r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
+    return r;
+  };
+  KeyRegs<D, NO2> kr;
+  ValRegs<D, NO2> vr;
+  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
+  vr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
   int qexp = 0;
@@ -433,17 +445,6 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     return val * inv_sqrt_d;
   };
 
-  auto counts_of = [&](int t, int side) {
-    const uint2 c = *(const uint2*)&S.cnt[t - tile_begin][4 * side];
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
-    QaqCounts r;
-    r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
-    return r;
-  };
-  KeyRegs<D, NO2> kr;
-  ValRegs<D, NO2> vr;
-  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
-  vr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
 
   // carried across the tiles
   float m_run = -INFINITY;          // reference of everything below

@@ -325,19 +325,41 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
     return;
   }
   const QaqVRegions r = qaq_v_regions(c, D);
+  // The two-bit fields and the low bits of the three-bit tokens are requested together, before
+  // either is used (a thread has at most two work items of the first kind and one of the
+  // second), so that the tile costs one round trip to memory, not one per region and item.
   // two-bit fields: a work item is (unit of 16 tokens, four channels)
-  for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
+  constexpr int I2 = 16 * (D / 4) / kThreads;      // items per thread at most (16 units)
+  static_assert(16 * (D / 4) % kThreads == 0 && 16 * (D / 8) <= kThreads, "work split of the value-side unpack");
+  uint32_t o2[I2][4], o1[4];
+  const int n_it2 = ((n32 + 15) / 16) * (D / 4), n_it1 = ((c.n3 + 15) / 16) * (D / 8);
+#pragma unroll
+  for (int i = 0; i < I2; ++i) {
+    const int it = tid + i * kThreads;
     const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
-    if (!L.old2[u]) continue;
-    uint32_t o[4];
+    const bool live = it < n_it2 && L.old2[u];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-      o[k] = *(const uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg));
+      o2[i][k] = live ? *(const uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) : 0u;
+  }
+  {
+    const int it = tid;
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    const bool live = it < n_it1 && L.old1[u];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      o1[k] = live ? *(const uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) : 0u;
+  }
+#pragma unroll
+  for (int i = 0; i < I2; ++i) {
+    const int it = tid + i * kThreads;
+    const int u = it / (D / 4), c4 = it % (D / 4);
+    if (!(it < n_it2 && L.old2[u])) continue;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       uint32_t f[4], w[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (2 * v)) & 0x03030303u;
+      for (int k = 0; k < 4; ++k) f[k] = (o2[i][k] >> (2 * v)) & 0x03030303u;
       transpose4(f, w);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -380,28 +402,26 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
   }
   __syncthreads();
   // low bits of the three-bit tokens: (unit, pair of channel groups, four channels of each)
-  for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
+  {
+    const int it = tid;
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
-    if (!L.old1[u]) continue;
-    uint32_t o[4];
+    if (it < n_it1 && L.old1[u]) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-      o[k] = *(const uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp));
+      for (int hh = 0; hh < 2; ++hh) {
+        const int c4 = 4 * (2 * cgp + hh) + n4;
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const int c4 = 4 * (2 * cgp + hh) + n4;
+        for (int v = 0; v < 4; ++v) {
+          uint32_t f[4], w[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        uint32_t f[4], w[4];
+          for (int k = 0; k < 4; ++k) f[k] = (o1[k] >> (4 * hh + v)) & 0x01010101u;
+          transpose4(f, w);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (4 * hh + v)) & 0x01010101u;
-        transpose4(f, w);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int s = 16 * u + 4 * v + j;
-          if (s < c.n3) {
-            const int pos = L.pos_old[s];
-            if (L.need[pos] == 1) L.stage[pos * SROW + c4] |= w[j];
+          for (int j = 0; j < 4; ++j) {
+            const int s = 16 * u + 4 * v + j;
+            if (s < c.n3) {
+              const int pos = L.pos_old[s];
+              if (L.need[pos] == 1) L.stage[pos * SROW + c4] |= w[j];
+            }
           }
         }
       }
