@@ -106,10 +106,10 @@ struct BuildLds {
   uint16_t freeslot[QAQ_TT];               // per class, in slot order: the slots nobody keeps
   uint16_t pos_old[QAQ_TT];                // position of the token that held a slot before
   uint8_t need[QAQ_TT];                    // by position: 1 = the stored code of this cached token is read again
-                                           // (it moves, or shares a stored word with a token that does), 2 = it is
-                                           // re-encoded from the unquantized copy, 0 = neither
-  uint8_t rew2[16], rew1[16], rew4[32];    // value side: units of the new layout that are written
-  uint8_t old2[16], old1[16], old4[32];    // value side: units of the old layout that hold a needed token
+                                           // (it moves), 2 = it is re-encoded from the unquantized copy, 0 = neither
+  uint32_t mask2[16];                      // value side, per unit of 16 slots of the 2-bit field region: slots whose
+                                           // fields are written (bit i = slot 16u+i)
+  uint32_t mask4[32];                      // ... per half-unit of 8 slots of the 4-bit region
   int wave_cnt[4][4];
   int wave_need[4][4];
   int wave_free[4][4];
@@ -322,110 +322,25 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
       const uint32_t w = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
       L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] = w ^ 0x80808080u;
     }
-    return;
   }
+  // (value side: unpack_moved_v)
+}
+
+// Value side: codes of the cached tokens that move, token by token.  The list holds their
+// positions (L.freeslot) and the slots they had (L.kept, reused); a work item is (token, four
+// channels), and every code is read with the per-element accessor of the layout -- a tile in
+// a decode step moves a handful of tokens, far fewer than its units hold.
+template <int D, int MAXO>
+__device__ void unpack_moved_v(const uint8_t* base, const QaqCounts& c, int n_moved, BuildLds<D, MAXO>& L) {
+  constexpr int SROW = BuildLds<D, MAXO>::SROW;
   const QaqVRegions r = qaq_v_regions(c, D);
-  // The two-bit fields and the low bits of the three-bit tokens are requested together, before
-  // either is used (a thread has at most two work items of the first kind and one of the
-  // second), so that the tile costs one round trip to memory, not one per region and item.
-  // two-bit fields: a work item is (unit of 16 tokens, four channels)
-  constexpr int I2 = 16 * (D / 4) / kThreads;      // items per thread at most (16 units)
-  static_assert(16 * (D / 4) % kThreads == 0 && 16 * (D / 8) <= kThreads, "work split of the value-side unpack");
-  uint32_t o2[I2][4], o1[4];
-  const int n_it2 = ((n32 + 15) / 16) * (D / 4), n_it1 = ((c.n3 + 15) / 16) * (D / 8);
+  for (int e = threadIdx.x; e < n_moved * (D / 4); e += kThreads) {
+    const int m = e / (D / 4), c4 = e % (D / 4);
+    const int pos = L.freeslot[m], slot = L.kept[m];
+    uint32_t w = 0;
 #pragma unroll
-  for (int i = 0; i < I2; ++i) {
-    const int it = tid + i * kThreads;
-    const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
-    const bool live = it < n_it2 && L.old2[u];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      o2[i][k] = live ? *(const uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) : 0u;
-  }
-  {
-    const int it = tid;
-    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
-    const bool live = it < n_it1 && L.old1[u];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      o1[k] = live ? *(const uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) : 0u;
-  }
-#pragma unroll
-  for (int i = 0; i < I2; ++i) {
-    const int it = tid + i * kThreads;
-    const int u = it / (D / 4), c4 = it % (D / 4);
-    if (!(it < n_it2 && L.old2[u])) continue;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      uint32_t f[4], w[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) f[k] = (o2[i][k] >> (2 * v)) & 0x03030303u;
-      transpose4(f, w);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int s = 16 * u + 4 * v + j;
-        if (s < n32) {
-          const int pos = L.pos_old[s];
-          if (L.need[pos] == 1) L.stage[pos * SROW + c4] = s < c.n3 ? w[j] << 1 : w[j];
-        }
-      }
-    }
-  }
-  // four-bit codes: (half-unit of 8 tokens, four channels)
-  for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
-    const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
-    if (!L.old4[hu]) continue;
-    uint32_t o[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      o[k] = *(const uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg));
-#pragma unroll
-    for (int g2 = 0; g2 < 2; ++g2) {
-      uint32_t f[4], w[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) f[k] = (o[k] >> (4 * g2)) & 0x0f0f0f0fu;
-      transpose4(f, w);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int i4 = 8 * hu + 4 * g2 + j;
-        if (i4 < c.n4) {
-          const int pos = L.pos_old[n32 + i4];
-          if (L.need[pos] == 1) L.stage[pos * SROW + c4] = w[j];
-        }
-      }
-    }
-  }
-  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
-    const int i8 = it / (D / 4), dq = it % (D / 4);
-    const int pos = L.pos_old[n32 + c.n4 + i8];
-    if (L.need[pos] == 1) L.stage[pos * SROW + dq] = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
-  }
-  __syncthreads();
-  // low bits of the three-bit tokens: (unit, pair of channel groups, four channels of each)
-  {
-    const int it = tid;
-    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
-    if (it < n_it1 && L.old1[u]) {
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        const int c4 = 4 * (2 * cgp + hh) + n4;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          uint32_t f[4], w[4];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) f[k] = (o1[k] >> (4 * hh + v)) & 0x01010101u;
-          transpose4(f, w);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int s = 16 * u + 4 * v + j;
-            if (s < c.n3) {
-              const int pos = L.pos_old[s];
-              if (L.need[pos] == 1) L.stage[pos * SROW + c4] |= w[j];
-            }
-          }
-        }
-      }
-    }
+    for (int k = 0; k < 4; ++k) w |= load_code<D>(1, base, c, r.r2, r.r1, r.r4, r.r8, slot, 4 * c4 + k) << (8 * k);
+    L.stage[pos * SROW + c4] = w;
   }
 }
 
@@ -492,10 +407,9 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
   }
   const QaqVRegions r = qaq_v_regions(c, D), r0 = qaq_v_regions(c0, D);
   const bool same8 = same32 && r.r4 == r0.r4 && c0.n4 == c.n4 && r.r8 == r0.r8;
-  // units: the caller has marked the ones that are written (L.rew2 / rew1 / rew4)
+  // every unit is written (a tile that held nothing; see pack_masked_v for a rebuild)
   for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
     const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
-    if (!L.rew2[u]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -519,7 +433,6 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
   }
   for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
-    if (!L.rew1[u]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
@@ -547,7 +460,6 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
   }
   for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
     const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
-    if (!L.rew4[hu]) continue;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int g2 = 0; g2 < 2; ++g2) {
@@ -580,6 +492,96 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
 // ---------------------------------------------------------------------------------
 // Tile build: append new tokens and / or move cached tokens to other widths, then
 // write the tile side back in class order.
+// Value side of a rebuild: only the fields of the slots in L.mask2 / L.mask4 are written,
+// into the words as they are stored (read-modify-write; a word of a unit that did not exist,
+// or whose region has moved, starts from zero -- then the masks hold all its slots).  Fields
+// of slots past the end of a region are left as they are: no reader looks at them.
+template <int D, int MAXO>
+__device__ void pack_masked_v(uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D, MAXO>& L) {
+  constexpr int SROW = BuildLds<D, MAXO>::SROW;
+  const int tid = threadIdx.x;
+  const int n32 = c.n32(), n32o = c0.n32();
+  const QaqVRegions r = qaq_v_regions(c, D), r0 = qaq_v_regions(c0, D);
+  const bool same1 = r.r1 == r0.r1;
+  const bool same4 = n32 == n32o && r.r4 == r0.r4;
+  const bool same8 = same4 && c0.n4 == c.n4 && r.r8 == r0.r8;
+  const int units2_old = (n32o + 15) / 16;
+  const int units1_old = same1 ? (c0.n3 + 15) / 16 : 0;
+  const int half4_old = same4 ? (c0.n4 + 7) / 8 : 0;
+  for (int it = tid; it < ((n32 + 15) / 16) * (D / 4); it += kThreads) {
+    const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t m = L.mask2[u];
+    if (!m) continue;
+    uint32_t* wp = (uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D)) + (4 * (c4 & 3)) * (D / 16) + cg;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = u < units2_old ? wp[k * (D / 16)] : 0u;
+    while (m) {
+      const int i = __ffs(m) - 1;
+      m &= m - 1;
+      const int sl = 16 * u + i;
+      const int pos = L.pos_of_slot[sl];
+      const uint32_t w = (L.stage[pos * SROW + c4] >> ((L.shf[pos] & 7) + (sl < c.n3 ? 1 : 0))) & 0x03030303u;
+      const int bp = 8 * (i & 3) + 2 * (i >> 2);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(3u << bp)) | (((w >> (8 * k)) & 3u) << bp);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wp[k * (D / 16)] = o[k];
+  }
+  for (int it = tid; it < ((c.n3 + 15) / 16) * (D / 8); it += kThreads) {
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    const int in3 = c.n3 - 16 * u;                       // slots of this unit inside the 3-bit class
+    uint32_t m = L.mask2[u] & (in3 >= 16 ? 0xffffu : (1u << in3) - 1u);
+    if (!m) continue;
+    uint32_t* wp = (uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D)) + (4 * n4) * (D / 32) + cgp;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = u < units1_old ? wp[k * (D / 32)] : 0u;
+    while (m) {
+      const int i = __ffs(m) - 1;
+      m &= m - 1;
+      const int pos = L.pos_of_slot[16 * u + i];
+      const int sh = L.shf[pos] & 7;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const uint32_t w = (L.stage[pos * SROW + 4 * (2 * cgp + hh) + n4] >> sh) & 0x01010101u;
+        const int bp = 8 * (i & 3) + 4 * hh + (i >> 2);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(1u << bp)) | (((w >> (8 * k)) & 1u) << bp);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wp[k * (D / 32)] = o[k];
+  }
+  for (int it = tid; it < ((c.n4 + 7) / 8) * (D / 4); it += kThreads) {
+    const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+    uint32_t m = L.mask4[hu];
+    if (!m) continue;
+    uint32_t* wp = (uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D)) + (4 * (c4 & 3)) * (D / 16) + cg;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = hu < half4_old ? wp[k * (D / 16)] : 0u;
+    while (m) {
+      const int i = __ffs(m) - 1;
+      m &= m - 1;
+      const int pos = L.pos_of_slot[n32 + 8 * hu + i];
+      const uint32_t w = (L.stage[pos * SROW + c4] >> (L.shf[pos] & 7)) & 0x0f0f0f0fu;
+      const int bp = 8 * (i & 3) + 4 * (i >> 2);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(15u << bp)) | (((w >> (8 * k)) & 15u) << bp);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wp[k * (D / 16)] = o[k];
+  }
+  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
+    const int i8 = it / (D / 4), dq = it % (D / 4);
+    const int pos = L.pos_of_slot[n32 + c.n4 + i8];
+    if (same8 && (L.shf[pos] & kKeptFlag)) continue;
+    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
+  }
+}
+
 // ---------------------------------------------------------------------------------
 // Widenings asked for in this wavefront: one atomic per wavefront that has any, spread over
 // QAQ_NCOUNT counters per kind (v.refused[kind * QAQ_NCOUNT + i]; kind 0 = refused for want of
@@ -839,10 +841,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
   }
   L.kept[tid] = 0;
-  if (tid < 32) {
-    L.rew4[tid] = 0; L.old4[tid] = 0;
-    if (tid < 16) { L.rew2[tid] = 0; L.rew1[tid] = 0; L.old2[tid] = 0; L.old1[tid] = 0; }
-  }
+  if (tid < 32) L.mask4[tid] = 0;
   __syncthreads();
   QaqCounts cn;
   {
@@ -851,6 +850,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     for (int c = 0; c < 4; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
     cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8];
   }
+  int old_slot = -1;              // cached tokens: the slot held so far
   if (n_before == 0) {
     // nothing cached: a plain stable counting sort (rank inside the wavefront + wavefront offsets)
     int my_rank = 0;
@@ -868,7 +868,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     __syncthreads();
   } else {
     const bool was_cached = tid < n_before;
-    const int old_slot = was_cached ? (int)L.slot_of_pos[tid] : -1;
+    old_slot = was_cached ? (int)L.slot_of_pos[tid] : -1;
     bool keep = false;
     if (was_cached && cls == qaq_class_of_bits(L.bits_old[tid])) {
       const int lo = cn.start(cls);
@@ -911,12 +911,12 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     __syncthreads();
   }
 
-  // Which stored words are written, and which cached tokens therefore have their stored codes
-  // read back: a key-side word belongs to one token; a value-side unit holds up to 16 tokens
-  // (the part of the last unit past its region is zero padding) and is left alone when every
-  // token in it keeps slot and width, its region has not moved, and its padding is where it
-  // was (the unit lies below both the old and the new end of the region, or the end has not
-  // moved).
+  // Which tokens are written again: those that do not keep slot and width, and those whose
+  // region starts elsewhere than before.  A cached token among them that does not widen has
+  // its stored code read back (the others are left alone); on the value side, where a stored
+  // word holds one channel of up to 16 tokens, the slots to write are gathered per unit and
+  // the tokens to read back into a list.
+  int n_moved = 0;
   {
     const bool had = n_before > 0;
     const int n32 = cn.n32(), n32o = c_old.n32();
@@ -932,46 +932,37 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       same4 = had && n32 == n32o && r.r4 == r0.r4;
       same8 = same4 && c_old.n4 == cn.n4 && r.r8 == r0.r8;
     }
-    // every slot of the new layout votes on its unit (threads of one unit all store the same 1)
-    if (side == 1 && tid < n_after) {
-      const bool kept_here = (L.shf[L.pos_of_slot[tid]] & kKeptFlag) != 0;
-      if (tid < n32) {
-        const int u = tid >> 4;
-        if (!(kept_here && had && (n32 == n32o || 16 * u + 16 <= min(n32, n32o)))) L.rew2[u] = 1;
-        if (tid < cn.n3 && !(kept_here && same1 && (cn.n3 == c_old.n3 || 16 * u + 16 <= min(cn.n3, c_old.n3)))) L.rew1[u] = 1;
-      } else if (tid < n32 + cn.n4) {
-        const int hu = (tid - n32) >> 3;
-        if (!(kept_here && same4 && (cn.n4 == c_old.n4 || 8 * hu + 8 <= min(cn.n4, c_old.n4)))) L.rew4[hu] = 1;
-      }
+    auto written = [&](int pos, int c) {
+      return !(L.shf[pos] & kKeptFlag) || (c == QC3 && !same1) || (c == QC4 && !same4) || (c == QC8 && !same8);
+    };
+    if (side == 1 && had) {
+      // by slot of the new layout
+      const bool wr = tid < n_after && written(L.pos_of_slot[tid], qaq_class_of_bits(cn.bits_of_slot(tid)));
+      const unsigned long long bal = __ballot(wr && tid < n32);
+      if (lane < 4) L.mask2[4 * wave + lane] = (uint32_t)(bal >> (16 * lane)) & 0xffffu;
+      if (wr && tid >= n32 && tid < n32 + cn.n4) atomicOr(&L.mask4[(tid - n32) >> 3], 1u << ((tid - n32) & 7));
     }
-    __syncthreads();
-    if (tid < n_after) {
-      int nd = 0;
-      if (tid < n_before) {
-        if (L.bits_new[tid] > L.bits_old[tid]) nd = 2;
-        else {
-          const bool kept = (L.shf[tid] & kKeptFlag) != 0;
-          const int sl = L.slot_of_pos[tid];
-          if (side == 0) nd = (!kept || (cls == QC3 && !same1) || (cls == QC4 && !same4) || (cls == QC8 && !same8)) ? 1 : 0;
-          else nd = cls == QC3 ? (L.rew2[sl >> 4] | L.rew1[sl >> 4]) : cls == QC2 ? L.rew2[sl >> 4]
-                  : cls == QC4 ? L.rew4[(sl - n32) >> 3] : ((!kept || !same8) ? 1 : 0);
-        }
+    // by position
+    int nd = 0;
+    if (tid < n_before) nd = L.bits_new[tid] > L.bits_old[tid] ? 2 : written(tid, cls) ? 1 : 0;
+    if (tid < n_after) L.need[tid] = (uint8_t)nd;
+    if (side == 1 && had) {
+      const unsigned long long bal = __ballot(nd == 1);
+      if (lane == 0) L.wave_cnt[0][wave] = __popcll(bal);
+      __syncthreads();
+      int off = 0;
+      for (int w = 0; w < wave; ++w) off += L.wave_cnt[0][w];
+      if (nd == 1) {
+        const int k = off + __popcll(bal & ((1ull << lane) - 1ull));
+        L.freeslot[k] = (uint16_t)tid;       // position
+        L.kept[k] = (uint8_t)old_slot;       // the slot it had (both arrays are free by now)
       }
-      L.need[tid] = (uint8_t)nd;
-    }
-    __syncthreads();
-    // and every slot of the old layout on the unit its codes are read from
-    if (side == 1 && tid < n_before && L.need[L.pos_old[tid]] == 1) {
-      if (tid < n32o) {
-        L.old2[tid >> 4] = 1;
-        if (tid < c_old.n3) L.old1[tid >> 4] = 1;
-      } else if (tid < n32o + c_old.n4) {
-        L.old4[(tid - n32o) >> 3] = 1;
-      }
+      n_moved = L.wave_cnt[0][0] + L.wave_cnt[0][1] + L.wave_cnt[0][2] + L.wave_cnt[0][3];
     }
     __syncthreads();
     if (had) {
-      unpack_tile<D, MAXO>(side, base, c_old, L);
+      if (side == 0) unpack_tile<D, MAXO>(side, base, c_old, L);
+      else unpack_moved_v<D, MAXO>(base, c_old, n_moved, L);
       __syncthreads();
     }
   }
@@ -994,7 +985,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (side == 1)
       v.vbound[qaq_bh(v, b, h) * v.NT + tile] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
   }
-  pack_tile<D, MAXO>(side, base, cn, c_old, L);
+  if (side == 1 && n_before > 0) pack_masked_v<D, MAXO>(base, cn, c_old, L);
+  else pack_tile<D, MAXO>(side, base, cn, c_old, L);
 }
 
 // ---------------------------------------------------------------------------------
