@@ -252,7 +252,7 @@ def main():
             rc |= lib.qaq_requantize(c.h, P(kbits), P(vbits), P(oK), P(oV), Tcap, stream)
         else:   # the same three operations in one pass over the cache
             rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(oK), P(oV), Tcap,
-                                        P(kbits), P(vbits), stream)
+                                        None, None, stream)      # the chosen widths are applied, not returned
         assert rc == 0, lib.qaq_last_error()
 
     for i in range(warm):

@@ -165,6 +165,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   }
   v.counts = (uint16_t*)(base + a.counts);
   v.vbound = (float*)(base + a.vbound);
+  v.kthr = (float*)(base + a.kthr);
   v.ring = (float*)(base + a.ring);
   v.partial = (float*)(base + a.partial);
   v.statbuf = (long long*)(base + a.statbuf);
@@ -214,6 +215,11 @@ int qaq_thresholds(const qaq_cache* c, int32_t T, float* host_tau_k, float* host
   return QAQ_OK;
 }
 
+static void fill_bit_set(const qaq_cache* c, QaqRuleArgs& r) {
+  r.nbits = c->cfg.n_bits;
+  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+}
+
 int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
                         const uint8_t* dev_k_bits, const uint8_t* dev_v_bits, void* stream) {
   if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
@@ -227,6 +233,7 @@ int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int3
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
   a.mode = 0;
+  fill_bit_set(c, a.rule);
   a.len_before = c->len;
   a.len_after = c->len + n_new;
   a.tile0 = c->len / QAQ_TT;
@@ -276,6 +283,7 @@ int qaq_requantize(qaq_cache* c, const uint8_t* dev_k_bits, const uint8_t* dev_v
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
   a.mode = 1;
+  fill_bit_set(c, a.rule);
   a.len_before = a.len_after = c->len;
   a.tile0 = 0;
   a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];

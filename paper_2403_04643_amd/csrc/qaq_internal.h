@@ -20,6 +20,7 @@ struct QaqView {
   uint8_t* tags[2];
   uint16_t* counts;
   float* vbound;
+  float* kthr;
   float* ring;
   float* partial;
   long long* statbuf;

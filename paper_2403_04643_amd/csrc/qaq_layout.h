@@ -160,6 +160,7 @@ struct QaqArena {
   size_t tags[2];     // u8   [B][Hkv][Tmax]   width by position
   size_t counts;      // u16  [B][Hkv][NT][2][4]
   size_t vbound;      // f32  [B][Hkv][NT]   per tile: bound on (value scale, outlier correction) over its tokens
+  size_t kthr;        // f32  [B][Hkv][NT][2] per tile: key-rule thresholds [lo, hi) for which no token changes width
   size_t ring;        // f32  [window][B][Hkv][Tmax]
   size_t partial;     // f32  [B][Hq][NT][D+4]
   size_t statbuf;     // i64  [32]
@@ -182,6 +183,7 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   for (int s = 0; s < 2; ++s) { a.tags[s] = off; off = qaq_up256(off + bh * d.Tmax); }
   a.counts = off; off = qaq_up256(off + bh * d.NT * 2 * 4 * 2);
   a.vbound = off; off = qaq_up256(off + bh * d.NT * 4);
+  a.kthr = off; off = qaq_up256(off + bh * d.NT * 8);
   a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * 4);
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
   a.statbuf = off; off = qaq_up256(off + 32 * 8);

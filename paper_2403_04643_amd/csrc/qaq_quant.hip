@@ -114,6 +114,7 @@ struct BuildLds {
   int wave_need[4][4];
   int wave_free[4][4];
   float wave_bound[4];
+  float wave_bound2[4];
 };
 constexpr int kKeptFlag = 0x80;
 
@@ -612,6 +613,15 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
 
   if (a.mode == 1 && a.newbits[side] == nullptr) return;   // requantize: nothing to do for this side
 
+  // decode-step update, key side: the rule compares a token's range with one threshold per
+  // (T, head); the tile keeps, from when it was built, the interval of thresholds for which
+  // none of its tokens changes width, so a tile with nothing to do costs one 8-byte load
+  if (a.mode == 2 && side == 0 && n_before == n_after && !a.rule.out_bits[0]) {
+    const float2 keep = ((const float2*)v.kthr)[qaq_bh(v, b, h) * v.NT + tile];
+    const float tau = a.rule.tau_k[h];
+    if (tau >= keep.x && tau < keep.y) return;
+  }
+
   // cached tokens: everything whose address is known up front is requested in one go (the
   // slot-order metadata, and for a requantize the widths that decide whether the tile is
   // touched at all), so that a rebuild costs two dependent round trips to memory, not three
@@ -826,6 +836,23 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) bnd = fmaxf(bnd, __shfl_xor(bnd, o));
     if (lane == 0) L.wave_bound[wave] = bnd;
+  } else {
+    // keys: thresholds for which every token keeps its width (Section 4.1 key rule as the
+    // comparison range <= threshold * 2^B): a token at width B widens below range / 2^B and
+    // narrows from range / 2^B' on, B' the next narrower width; the power-of-two scalings are exact
+    float lo = 0.0f, hi = INFINITY;
+    if (tid < n_after) {
+      const int bits = L.bits_new[tid];
+      const float range = h2f((uint16_t)(L.mm[tid] >> 16)) - h2f((uint16_t)(L.mm[tid] & 0xffffu));
+      int narrower = 0;
+      for (int i = 0; i < a.rule.nbits; ++i)
+        if (a.rule.bit_set[i] < bits) narrower = a.rule.bit_set[i];
+      if (bits < a.rule.bit_set[a.rule.nbits - 1]) lo = ldexpf(range, -bits);
+      if (narrower > 0) hi = ldexpf(range, -narrower);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { lo = fmaxf(lo, __shfl_xor(lo, o)); hi = fminf(hi, __shfl_xor(hi, o)); }
+    if (lane == 0) { L.wave_bound[wave] = lo; L.wave_bound2[wave] = hi; }
   }
 
   // Slots: class by class (3, 2, 4, 8).  A cached token whose class is unchanged and whose
@@ -984,6 +1011,10 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     cp[QC3] = (uint16_t)cn.n3; cp[QC2] = (uint16_t)cn.n2; cp[QC4] = (uint16_t)cn.n4; cp[QC8] = (uint16_t)cn.n8;
     if (side == 1)
       v.vbound[qaq_bh(v, b, h) * v.NT + tile] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
+    else
+      ((float2*)v.kthr)[qaq_bh(v, b, h) * v.NT + tile] =
+          make_float2(fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3])),
+                      fminf(fminf(L.wave_bound2[0], L.wave_bound2[1]), fminf(L.wave_bound2[2], L.wave_bound2[3])));
   }
   if (side == 1 && n_before > 0) pack_masked_v<D, MAXO>(base, cn, c_old, L);
   else pack_tile<D, MAXO>(side, base, cn, c_old, L);

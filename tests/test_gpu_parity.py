@@ -388,3 +388,40 @@ def test_decode_update_in_one_call():
             compare_canonical(oc, gc, f"one call, step {s}")
             compare_canonical(oc, gc3, f"three calls, step {s}")
     assert gc.stats().refused_upgrades == gc3.stats().refused_upgrades == oc.refused
+
+
+def test_decode_update_skips_unchanged_key_tiles():
+    """qaq_decode_update without the width outputs leaves key-side tiles alone when the
+    threshold of this step lies inside the interval the tile recorded when it was built.
+    The hyper-parameter is moved during the run, so that key tokens narrow, then ask for
+    more bits (served from the copies, refused without them): cache and counters must follow
+    the oracle at every step."""
+    sh = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=4, context=505)
+    steps = 12
+    K, V = W.make_kv(3, sh)
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    kw = dict(max_tokens=sh.context + steps, window=3, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc, gc = make_pair(sh, qn, **kw)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    sig = {4: 1.6e-3, 7: 1.0e-4, 9: 2.0e-5}           # step -> new sigma_S_max from that step on
+    for s in range(steps):
+        if s in sig:
+            oc.cfg.sigma_s_max = sig[s]
+            gc.set_sigmas(sig[s], kw["sigma_x_max"])
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        with_orig = s != 10
+        ko, vo = (dev(Korig), dev(Vorig)) if with_orig else (None, None)
+        gc.decode_update(S, dev(kn), dev(vn), ko, vo, want_bits=False)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig if with_orig else None, Vorig if with_orig else None)
+        compare_canonical(oc, gc, f"step {s}")
+        assert gc.stats().refused_upgrades == oc.refused, f"step {s}"
+    hist = [int((bk_o == w).sum()) for w in (2, 3, 4, 8)]
+    print("  final key width histogram", hist, "refused", oc.refused, flush=True)
+    assert oc.refused > 0, "the case must refuse some widenings"
