@@ -281,7 +281,7 @@ def main():
     bytes_call = float(np.mean(cache_b) + np.mean(io_b))
     us_main, us_merge = (1e3 * float(np.mean(x)) for x in (ms_main, ms_merge))
     gbs_call = bytes_call / ((us_main + us_merge) * 1e-6) / 1e9
-    bytes_main = float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * T0 * 4   # cache + queries + raw scores out
+    bytes_main = float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * T0 * 4   # cache + queries + scores out
     gbs_main = bytes_main / (us_main * 1e-6) / 1e9
     read_gbs, copy_gbs, yard_bytes = stream_read_gbs(lib, bytes_main)
     s = st1[0]

@@ -1,13 +1,14 @@
 // Decode-step attention over the quantized cache (Section 2.1 attention evaluated on
 // the midpoint reconstruction of Section 4.1 with the outlier side store of Section 4.2).
 //
-// Two kernels per call:
-//   k_attn_tile     one workgroup per chunk of consecutive 256-position tiles of one
-//                   (sequence, query head), four workgroups resident per compute unit:
-//                   logits, softmax with a running max and sum over the chunk, unnormalised
-//                   output -> partial (max, sum, X); the next tile's loads stay in flight
-//                   while the current tile is computed
-//   k_attn_combine  merges the chunks, adds the unquantized new token, normalises scores
+// k_attn_tile scans the cache: the 256-position tiles of a (sequence, query head) are cut
+// into parts of consecutive tiles; a part is 256 threads that compute logits, a softmax with
+// a running max and sum over their tiles and the unnormalised output, with the next tile's
+// loads in flight while the current tile is computed.  Where a head has at most four parts
+// they are the 256-thread groups of one workgroup, which merges them in LDS, adds the
+// unquantized new token and writes output and normalised scores itself (one kernel per
+// call).  Otherwise every part is a workgroup of its own, writes a partial (max, sum, X), and
+// k_attn_combine merges the parts, adds the new token and normalises the scores.
 //
 // Arithmetic.  With per-token scale_t = range_t / 2^B and codes c_td,
 //   q.K^_t  = min_t * sum(q) + scale_t * (sum_d q_d c_td + sum(q)/2) + outlier terms
