@@ -271,10 +271,12 @@ struct KeyRegs {
   QaqCounts c;
   int n_tok;
   // code words of the lane's own slot: a 2-bit field record in ka, the 1-bit record of a 3-bit
-  // token in kb, or a 4-bit record in ka followed by kb (8-bit records, rare, are fetched when
-  // needed)
+  // token in kb, or a 4-bit record in ka followed by kb.  8-bit records are four times that:
+  // the first four 8-bit slots of a wavefront are fetched by its four groups of 16 lanes, 8
+  // bytes per lane (k8); further ones, rare, are fetched when needed.
   static constexpr int HALF = KRec<D, 2>::RDW;
   uint32_t ka[HALF], kb[HALF];
+  uint32_t k8[2];
   uint32_t mm, pos;
   Outl<NO2> o;
   __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& ck, int tid) {
@@ -302,6 +304,11 @@ struct KeyRegs {
     gload_dwords<HALF / 2>(ubase + off_b1, b1);
 #pragma unroll
     for (int i = 0; i < HALF / 2; ++i) { kb[i] = b0[i]; kb[HALF / 2 + i] = b1[i]; }
+    // lane group g of the wavefront: bytes 8*(lane%16) .. +8 of the record of its g-th 8-bit slot
+    const int first8 = n32 + c.n4;
+    const int s8 = max(first8, tid & ~63) + ((tid & 63) >> 4);
+    const uint32_t off8 = s8 < n_tok && 8 * (tid & 15) < D ? rK.r8 + (uint32_t)(s8 - first8) * (uint32_t)KRec<D, 8>::REC + 8u * (uint32_t)(tid & 15) : 0u;
+    if (c.n8 > 0) gload_dwords<2>(ubase + off8, k8);      // uniform over the workgroup
   }
 };
 
@@ -495,7 +502,30 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         const float d4 = real_of(k_contract<D, 4>(k4, abase2));
         if (tid >= n32K) dotq = d4;
       }
-      if (__builtin_expect(w1 > first8K && cK.n8 > 0, 0)) {
+      const int s8_0 = max(first8K, w0);                 // first 8-bit slot among this wavefront's
+      const int n8w = min(n_tok, w1) - s8_0;             // and how many there are
+      if (n8w > 0 && n8w <= 4) {
+        // a few 8-bit keys: every group of 16 lanes takes one, a lane 8 of its bytes (fetched
+        // with the rest of the tile), fp32 products with the query in a fixed order
+        const int j = 8 * (lane & 15) < D ? lane & 15 : 0, sl = j >> 1;   // a record has D bytes: D/8 lanes of the group carry it
+        const int ch0 = 64 * (sl % KS) + 16 * (sl / KS) + 8 * (j & 1);   // channel of the lane's first byte
+        const float4 q0 = *(const float4*)&S.qf[ch0], q1 = *(const float4*)&S.qf[ch0 + 4];
+        const uint32_t c0 = kr.k8[0] ^ 0x80808080u, c1 = kr.k8[1] ^ 0x80808080u;   // stored as code - 128
+        float d = (float)(c0 & 255u) * q0.x;
+        d += (float)((c0 >> 8) & 255u) * q0.y;
+        d += (float)((c0 >> 16) & 255u) * q0.z;
+        d += (float)(c0 >> 24) * q0.w;
+        d += (float)(c1 & 255u) * q1.x;
+        d += (float)((c1 >> 8) & 255u) * q1.y;
+        d += (float)((c1 >> 16) & 255u) * q1.z;
+        d += (float)(c1 >> 24) * q1.w;
+        if (8 * (lane & 15) >= D) d = 0.0f;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) d += __shfl_xor(d, o);
+        const int own = tid - s8_0;                        // the lane that owns the slot
+        const float dd = __shfl(d, 16 * (own & 3));
+        if (own >= 0 && own < n8w) dotq = dd;
+      } else if (__builtin_expect(n8w > 4, 0)) {
         // 8-bit key bytes are stored as code - 128: the dot product gets 128 * (sum of the
         // unscaled query integers) back, rebuilt here from their digits (this class is rare)
         int sq = 0;
