@@ -16,6 +16,7 @@ namespace {
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
+constexpr int kKeep = 16;          // logits per thread the softmax kernel keeps in registers (a 4096-token row)
 
 // tokens a query row attends to: row i belongs to prompt position T - n + i
 __device__ __forceinline__ int row_length(int T, int n, int i) { return T - n + i + 1; }
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_logits(QaqPrefillArgs a) {
   for (int g = 0; g < 4; ++g) {
     const int t = min(t_wave + 16 * g + col, a.T - 1);    // clamped: the tail reads a valid row and is masked below
 #pragma unroll
-    for (int s = 0; s < NS; ++s) key[g][s] = *(const h8*)(kbase + (size_t)t * D + 32 * s + 8 * kb);
+    for (int s = 0; s < NS; ++s) key[g][s] = __builtin_nontemporal_load((const h8*)(kbase + (size_t)t * D + 32 * s + 8 * kb));
   }
 
   const int R = a.G * a.n_rows;    // query rows of this KV head: (query head g, prompt row i) -> g * n + i
@@ -100,16 +101,36 @@ __global__ __launch_bounds__(kThreads) void k_prefill_softmax(QaqPrefillArgs a) 
   float* ring = v.ring + (size_t)i * ring_row + qaq_bh(v, b, h) * v.Tmax;
   for (int g = 0; g < a.G; ++g) {
     float* row = a.scores + (((size_t)i * v.B + b) * v.Hq + (h * a.G + g)) * a.T;
+    // maximum and sum in one sweep: every thread keeps its logits (T / 256 of them, at most
+    // kKeep in registers, the rest is read again), its own maximum and the sum against it
+    float mine[kKeep];
     float m = -INFINITY;
-    for (int t = tid; t < len; t += kThreads) m = fmaxf(m, row[t]);
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+      const int t = tid + k * kThreads;
+      mine[k] = t < len ? row[t] : -INFINITY;
+      m = fmaxf(m, mine[k]);
+    }
+    for (int t = tid + kKeep * kThreads; t < len; t += kThreads) m = fmaxf(m, row[t]);
     m = block_reduce(m, true, red);
     float l = 0.0f;
-    for (int t = tid; t < len; t += kThreads) l += expf(row[t] - m);
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) l += expf(mine[k] - m);        // exp(-inf) = 0 past the row's end
+    for (int t = tid + kKeep * kThreads; t < len; t += kThreads) l += expf(row[t] - m);
     l = block_reduce(l, false, red);
-    for (int t = tid; t < a.T; t += kThreads) {
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+      const int t = tid + k * kThreads;
+      if (t < a.T) {
+        const float s = t < len ? expf(mine[k] - m) / l : 0.0f;
+        row[t] = s;
+        if (t < len) ring[t] = g == 0 ? s : fmaxf(ring[t], s);   // thread tid is the only one to touch position t
+      }
+    }
+    for (int t = tid + kKeep * kThreads; t < a.T; t += kThreads) {
       const float s = t < len ? expf(row[t] - m) / l : 0.0f;
       row[t] = s;
-      if (t < len) ring[t] = g == 0 ? s : fmaxf(ring[t], s);   // thread tid is the only one to touch position t
+      if (t < len) ring[t] = g == 0 ? s : fmaxf(ring[t], s);
     }
   }
 }
