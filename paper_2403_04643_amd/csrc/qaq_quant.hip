@@ -766,7 +766,11 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
 #pragma unroll
-      for (int i = 0; i < Enc::NCH; ++i) raw[i] = ((const uint4*)src)[4 * i + c];
+      for (int i = 0; i < Enc::NCH; ++i) {      // read once: streaming loads
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 t = __builtin_nontemporal_load((const u32x4*)src + (4 * i + c));
+        raw[i] = make_uint4(t.x, t.y, t.z, t.w);
+      }
       if (fresh && a.orig_put[side]) {     // keep the unquantized token for later widening
         uint4* dst = (uint4*)(a.orig_put[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D);
 #pragma unroll
