@@ -179,8 +179,13 @@ def main():
     total_steps = steps + warm
     per_layer = (total_steps + L - 1) // L
     XS = 0 if args.no_extras else 2          # further steps per instance with the unquantized copies in host memory
-    Tcap = sh.context + per_layer + XS + 1
-    B, Hq, Hkv, D, T0 = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+    XT = 0 if args.no_extras else 2          # ... and past the configured context (one tile more per head)
+    B, Hq, Hkv, D, Tctx = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+    # The decode steps END at the configured context: the instances start from a prompt of
+    # T0 tokens and every timed attention call sees at most Tctx cached tokens plus the new one.
+    T0 = Tctx - per_layer - XS
+    assert T0 > 0, "more steps per instance than the context is long"
+    Tcap = Tctx + XT + 1
 
     qcal = W.make_queries(2, sh, n=max(1, 1024 // (B * Hq)), seed_offset=7).astype(np.float64)
     qn = np.full(Hkv, float(np.quantile((qcal ** 2).sum(-1).reshape(-1), 0.9)) / D, np.float32)
@@ -194,13 +199,14 @@ def main():
         Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
         oK = torch.zeros((B, Hkv, Tcap, D), dtype=torch.float16, device="cuda")
         oV = torch.zeros((B, Hkv, Tcap, D), dtype=torch.float16, device="cuda")
-        oK[:, :, :T0] = Kd; oV[:, :, :T0] = Vd
+        oK[:, :, :T0] = Kd[:, :, :T0]; oV[:, :, :T0] = Vd[:, :, :T0]
         c = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=5))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         if l == 0:   # untimed first touch of the kernel
             c.quantize_append(Kd, Vd); c.reset()
         e0.record(); c.quantize_append(Kd, Vd); e1.record(); torch.cuda.synchronize()
-        prefill_ms.append(e0.elapsed_time(e1))
+        prefill_ms.append(e0.elapsed_time(e1))       # bulk quantization of the full Tctx-token prompt
+        c.reset(); c.quantize_append(Kd[:, :, :T0].contiguous(), Vd[:, :, :T0].contiguous())
         caches.append(c); origK.append(oK); origV.append(oV)
         del K, V, Kd, Vd
     # attention window: five score rows from five seeded queries over the fp16 originals.
@@ -223,16 +229,16 @@ def main():
     st0 = [c.stats() for c in caches]
 
     # inputs of the timed steps, resident in HBM before timing starts
-    qs = torch.from_numpy(W.make_queries(2, sh, n=(per_layer + XS) * L, seed_offset=1)).cuda()
+    qs = torch.from_numpy(W.make_queries(2, sh, n=(per_layer + XS + XT) * L, seed_offset=1)).cuda()
     newk, newv = [], []
     for l in range(L):
         ks, vs = [], []
-        for j in range(per_layer + XS):
+        for j in range(per_layer + XS + XT):
             kn, vn = W.make_new_token(2, sh, step=1000 * l + j)
             ks.append(kn); vs.append(vn)
         nk = torch.from_numpy(np.stack(ks)).cuda(); nv = torch.from_numpy(np.stack(vs)).cuda()
         # (qaq_decode_update writes each new token into the copies itself; the separate calls rely on this)
-        origK[l][:, :, T0:T0 + per_layer + XS] = nk.permute(1, 2, 0, 3); origV[l][:, :, T0:T0 + per_layer + XS] = nv.permute(1, 2, 0, 3)
+        origK[l][:, :, T0:T0 + per_layer + XS + XT] = nk.permute(1, 2, 0, 3); origV[l][:, :, T0:T0 + per_layer + XS + XT] = nv.permute(1, 2, 0, 3)
         newk.append(nk); newv.append(nv)
     out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
     scores = torch.empty(B * Hq * (Tcap + 1), dtype=torch.float32, device="cuda")
@@ -281,14 +287,15 @@ def main():
     bytes_call = float(np.mean(cache_b) + np.mean(io_b))
     us_main, us_merge = (1e3 * float(np.mean(x)) for x in (ms_main, ms_merge))
     gbs_call = bytes_call / ((us_main + us_merge) * 1e-6) / 1e9
-    bytes_main = float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * T0 * 4   # cache + queries + scores out
+    t_mean = float(np.mean([s_.tokens for s_ in st0 + st1])) + 1
+    bytes_main = float(np.mean(cache_b)) + B * Hq * D * 2 + B * Hq * t_mean * 4   # cache + queries + scores out
     gbs_main = bytes_main / (us_main * 1e-6) / 1e9
     read_gbs, copy_gbs, yard_bytes = stream_read_gbs(lib, bytes_main)
     s = st1[0]
     th = B * Hkv * s.tokens
     mean_k = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_k)) / th
     mean_v = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_v)) / th
-    tokens_per_s = B * T0 / (float(np.mean(prefill_ms[1:] or prefill_ms)) * 1e-3)
+    tokens_per_s = B * Tctx / (float(np.mean(prefill_ms[1:] or prefill_ms)) * 1e-3)
 
     rec = {
         "metric": "quantized-KV decode attention HBM GB/s (% of peak) + tokens quantized/s",
@@ -298,7 +305,8 @@ def main():
         "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8 codes x fixed-point q/w (int32 accumulate), fp32 softmax",
         "data": "synthetic",
-        "config": {"workload": f"configs[1]: LLaMA-7B layer, batch {B}, {Hq} heads, head_dim {D}, context {T0}, "
+        "config": {"workload": f"configs[1]: LLaMA-7B layer, batch {B}, {Hq} heads, head_dim {D}, context {Tctx}: decode steps "
+                               f"from {st0[0].tokens} to {st1[0].tokens} cached tokens + 1 new per step, "
                                f"operating point {args.op} (mean widths K {mean_k:.2f} / V {mean_v:.2f}), "
                                f"{L} cache instances rotated", "op": args.op, "layers": L,
                    "step": "decode_attention + " + ("quantize_append + select_bits + requantize" if args.separate_calls else "decode_update")},
@@ -345,27 +353,6 @@ def main():
             "host_link_bytes_per_step": served_h * D * 2 + 2 * B * Hkv * D * 2}
         for hb in hostK + hostV:
             hb.close()
-        # The same steps with a window of one score row: how many more tokens widen when the
-        # prediction is the current score alone (Section 4.2 "attention window").
-        c1 = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=1))
-        c1.set_sigmas(ss, sx)
-        Kd, Vd = origK[0][:, :, :T0].contiguous(), origV[0][:, :, :T0].contiguous()
-        q1 = torch.from_numpy(np.ascontiguousarray(W.make_queries(2, sh, n=1, seed_offset=3).transpose(1, 2, 0, 3))).cuda()
-        c1.prefill_window(q1, Kd)
-        c1.quantize_append_selected(Kd, Vd)
-        del Kd, Vd
-        n1 = min(8, per_layer)
-        for j in range(n1):
-            rc = lib.qaq_decode_attention(c1.h, P(qs[j * L]), P(newk[0][j]), P(newv[0][j]), P(out), 1, P(scores), stream)
-            rc |= lib.qaq_decode_update(c1.h, P(scores), P(newk[0][j]), P(newv[0][j]), P(origK[0]), P(origV[0]), Tcap,
-                                        P(kbits), P(vbits), stream)
-            assert rc == 0, lib.qaq_last_error()
-        torch.cuda.synchronize()
-        s1w = c1.stats()
-        rec["window_of_one"] = {"steps": n1, "served_upgrades_per_step": s1w.served_upgrades / n1,
-                                "hist_k": list(s1w.hist_k), "hist_v": list(s1w.hist_v)}
-        del c1
-
     # the other operating point, attention only: recalibrate, requantize (widening from the fp16
     # originals), time the tile kernel the same way
     others = {}
@@ -402,6 +389,50 @@ def main():
     if others:
         rec["other_operating_points"] = others
 
+    if others and not args.no_extras:
+        # back to the benchmark's operating point (the window is unchanged: the same widths)
+        for c in caches:
+            c.set_sigmas(ss, sx)
+            kb, vb = c.select_bits(None)
+            c.requantize(kb, vb)
+        torch.cuda.synchronize()
+    if not args.no_extras:
+        # Past the configured context: Tctx + 1 ... cached tokens are one 256-position tile more
+        # per head (17 instead of 16), nearly empty, and the kernel's loop over a head's tiles,
+        # split four ways, takes five rounds instead of four.
+        for c in caches:
+            c.profile_begin(XT + 1)
+        i2 = i0 + XS * L
+        for i in range(i2, i2 + XT * L):
+            step(i)
+        torch.cuda.synchronize()
+        t17 = []
+        for c in caches:
+            a_ms, _ = c.profile_read()
+            t17 += a_ms
+            c.profile_begin(0)
+        rec["past_the_configured_context"] = {"cached_tokens": caches[0].length(), "us_tile_kernel": 1e3 * float(np.mean(t17))}
+        # The same steps with a window of one score row: how many more tokens widen when the
+        # prediction is the current score alone (Section 4.2 "attention window").
+        c1 = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=1))
+        c1.set_sigmas(ss, sx)
+        Kd, Vd = origK[0][:, :, :T0].contiguous(), origV[0][:, :, :T0].contiguous()     # the same prompt and steps as instance 0
+        q1 = torch.from_numpy(np.ascontiguousarray(W.make_queries(2, sh, n=1, seed_offset=3).transpose(1, 2, 0, 3))).cuda()
+        c1.prefill_window(q1, Kd)
+        c1.quantize_append_selected(Kd, Vd)
+        del Kd, Vd
+        n1 = min(8, per_layer)
+        for j in range(n1):
+            rc = lib.qaq_decode_attention(c1.h, P(qs[j * L]), P(newk[0][j]), P(newv[0][j]), P(out), 1, P(scores), stream)
+            rc |= lib.qaq_decode_update(c1.h, P(scores), P(newk[0][j]), P(newv[0][j]), P(origK[0]), P(origV[0]), Tcap,
+                                        P(kbits), P(vbits), stream)
+            assert rc == 0, lib.qaq_last_error()
+        torch.cuda.synchronize()
+        s1w = c1.stats()
+        rec["window_of_one"] = {"steps": n1, "served_upgrades_per_step": s1w.served_upgrades / n1,
+                                "hist_k": list(s1w.hist_k), "hist_v": list(s1w.hist_v)}
+        del c1
+
     def time_tile_kernel(n_calls):
         for c in caches:
             c.profile_begin(n_calls // L + 1)
@@ -421,10 +452,10 @@ def main():
         ev = lambda: torch.cuda.Event(enable_timing=True)
         q_last = torch.from_numpy(np.ascontiguousarray(
             W.make_queries(2, sh, n=5, seed_offset=3).transpose(1, 2, 0, 3))).cuda()
-        rows = torch.empty((5, B, Hq, T0), dtype=torch.float32, device="cuda")
+        rows = torch.empty((5, B, Hq, Tctx), dtype=torch.float32, device="cuda")
         t_win, t_app = [], []
         for l, c in enumerate(caches):
-            Kd, Vd = origK[l][:, :, :T0].contiguous(), origV[l][:, :, :T0].contiguous()
+            Kd, Vd = origK[l][:, :, :Tctx].contiguous(), origV[l][:, :, :Tctx].contiguous()
             c.reset(); c.set_sigmas(ss, sx)
             e0, e1, e2 = ev(), ev(), ev()
             e0.record(); c.prefill_window(q_last, Kd, rows); e1.record()
@@ -435,16 +466,16 @@ def main():
         ms_w, ms_a = float(np.mean(t_win[1:] or t_win)), float(np.mean(t_app[1:] or t_app))
         rec["prompt_encoding"] = {
             "us_prefill_window": 1e3 * ms_w, "us_quantize_append_selected": 1e3 * ms_a,
-            "tokens_per_s": B * T0 / ((ms_w + ms_a) * 1e-3),
-            "fp16_key_bytes_read": B * Hkv * T0 * D * 2, "window_GBps": B * Hkv * T0 * D * 2 / (ms_w * 1e-3) / 1e9,
+            "tokens_per_s": B * Tctx / ((ms_w + ms_a) * 1e-3),
+            "fp16_key_bytes_read": B * Hkv * Tctx * D * 2, "window_GBps": B * Hkv * Tctx * D * 2 / (ms_w * 1e-3) / 1e9,
             "hist_k": list(stp.hist_k), "hist_v": list(stp.hist_v)}
         # every token at one width (the uniform baseline of the paper's comparison): where the
         # tile kernel sits between instruction issue and HBM as the bytes per token grow
         sweep = {}
         for w in (2, 3, 4, 8):
             for l, c in enumerate(caches):
-                Kd, Vd = origK[l][:, :, :T0].contiguous(), origV[l][:, :, :T0].contiguous()
-                bits = torch.full((B, Hkv, T0), w, dtype=torch.uint8, device="cuda")
+                Kd, Vd = origK[l][:, :, :Tctx].contiguous(), origV[l][:, :, :Tctx].contiguous()
+                bits = torch.full((B, Hkv, Tctx), w, dtype=torch.uint8, device="cuda")
                 c.reset(); c.quantize_append(Kd, Vd, bits, bits)
                 del Kd, Vd, bits
             us_w = time_tile_kernel(2 * L)

@@ -66,14 +66,17 @@ struct QaqKRegions {
 };
 QAQ_HD QaqKRegions qaq_k_regions(const QaqCounts& c, int D) {
   QaqKRegions r;
+  // every region is sized for a multiple of 16 records, so that appending a token or moving
+  // one between width classes leaves the regions behind it where they are 15 times out of 16
   r.r2 = 0;
-  r.r1 = qaq_align16((uint32_t)c.n32() * (D / 4));
-  r.r4 = qaq_align16(r.r1 + (uint32_t)c.n3 * (D / 8));
-  r.r8 = qaq_align16(r.r4 + (uint32_t)c.n4 * (D / 2));
+  r.r1 = (uint32_t)((c.n32() + 15) / 16) * 16u * (D / 4);
+  r.r4 = r.r1 + (uint32_t)((c.n3 + 15) / 16) * 16u * (D / 8);
+  r.r8 = r.r4 + (uint32_t)((c.n4 + 15) / 16) * 16u * (D / 2);
   r.end = r.r8 + (uint32_t)c.n8 * D;
   return r;
 }
-QAQ_HD uint32_t qaq_k_cap(int D) { return QAQ_TT * D + 64; }
+// worst case: 253 8-bit records and one partly filled group of 16 in each other region
+QAQ_HD uint32_t qaq_k_cap(int D) { return QAQ_TT * D + 16 * D; }
 
 // ---- V side region offsets ----------------------------------------------------
 struct QaqVRegions {
