@@ -27,8 +27,8 @@ __global__ __launch_bounds__(kThreads) void k_prefill_logits(QaqPrefillArgs a) {
   const QaqView& v = a.v;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, kb = lane >> 4;
-  const int bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
-  const int t_wave = blockIdx.x * QAQ_TT + 64 * wave;
+  const int bh = blockIdx.x, b = bh / v.Hkv, h = bh % v.Hkv;     // heads fastest (see k_build)
+  const int t_wave = blockIdx.y * QAQ_TT + 64 * wave;
   if (t_wave >= a.T) return;
 
   // 64 keys of this wavefront: lane (col, kb) holds channels 32s + 8kb .. +8 of key 16g + col
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_softmax(QaqPrefillArgs a) 
 
 hipError_t qaq_launch_prefill_window(const QaqPrefillArgs& a, hipStream_t s) {
   const QaqView& v = a.v;
-  const dim3 grid((a.T + QAQ_TT - 1) / QAQ_TT, v.B * v.Hkv);
+  const dim3 grid(v.B * v.Hkv, (a.T + QAQ_TT - 1) / QAQ_TT);
   if (v.D == 128) hipLaunchKernelGGL(k_prefill_logits<128>, grid, dim3(kThreads), 0, s, a);
   else if (v.D == 64) hipLaunchKernelGGL(k_prefill_logits<64>, grid, dim3(kThreads), 0, s, a);
   else return hipErrorInvalidValue;
