@@ -261,6 +261,23 @@ def main():
                                         None, None, stream)      # the chosen widths are applied, not returned
         assert rc == 0, lib.qaq_last_error()
 
+    def output_error(l=0):
+        """Relative L2 error of the attention output over instance l as it stands, against
+        fp32 attention over the unquantized copies of the same tokens (a quality figure for
+        the synthetic data, per (sequence, head), averaged); the new token is left out."""
+        c = caches[l]
+        n = c.length()
+        qv = qs[0]
+        X, _ = c.decode_attention(qv)
+        Kf = origK[l][:, :, :n].float().repeat_interleave(Hq // Hkv, dim=1)
+        logits = torch.einsum("bhd,bhtd->bht", qv.float(), Kf) / float(np.sqrt(D))
+        del Kf
+        Vf = origV[l][:, :, :n].float().repeat_interleave(Hq // Hkv, dim=1)
+        ref = torch.einsum("bht,bhtd->bhd", torch.softmax(logits, dim=-1), Vf)
+        del Vf
+        err = (X - ref).norm(dim=-1) / ref.norm(dim=-1)
+        return float(err.mean())
+
     for i in range(warm):
         step(i)
     torch.cuda.synchronize()
@@ -324,6 +341,7 @@ def main():
                      "stream_read_GBps": read_gbs, "frac_of_stream_read": gbs_main / read_gbs,
                      "stream_copy_GBps": copy_gbs, "yardstick_bytes": yard_bytes},
     }
+    quality = {args.op: {"output_rel_l2_error": output_error(0), "ratio_codes": st1[0].fp16_bytes / st1[0].code_bytes}}
     served_main = sum(b_.served_upgrades - a_.served_upgrades for a_, b_ in zip(st0, st1)) / total_steps
     rec["served_upgrades_per_step"] = served_main
     if not args.no_extras:
@@ -382,6 +400,7 @@ def main():
         b2 = cb2 + B * Hq * D * 2 + B * Hq * st2.tokens * 4
         us2 = 1e3 * float(np.mean(t_main))
         th2 = B * Hkv * st2.tokens
+        quality[op2] = {"output_rel_l2_error": output_error(0), "ratio_codes": st2.fp16_bytes / st2.code_bytes}
         others[op2] = {"us_tile_kernel": us2, "algorithmic_bytes": b2, "GBps": b2 / (us2 * 1e-6) / 1e9,
                        "frac_of_hbm_peak": b2 / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
                        "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_k)) / th2,
@@ -482,9 +501,13 @@ def main():
             stw = caches[0].stats()
             cbw, _ = algorithmic_bytes(stw, sh, n_o, stw.tokens + 1)
             bw = cbw + B * Hq * D * 2 + B * Hq * stw.tokens * 4
+            quality[f"uniform {w}-bit"] = {"output_rel_l2_error": output_error(0), "ratio_codes": stw.fp16_bytes / stw.code_bytes}
             sweep[str(w)] = {"us_tile_kernel": us_w, "algorithmic_bytes": bw, "GBps": bw / (us_w * 1e-6) / 1e9,
                              "frac_of_hbm_peak": bw / (us_w * 1e-6) / 1e9 / HBM_PEAK_GBS}
         rec["uniform_width_sweep"] = sweep
+    # attention-output error against fp32 attention over the unquantized tokens, by compression
+    # ratio: the adaptive widths of the two operating points next to uniform widths
+    rec["quality_on_synthetic_data"] = quality
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(sh, s.hist_k, s.hist_v, qn, n_o, args.cpu_sequences)
     print(json.dumps(rec))
