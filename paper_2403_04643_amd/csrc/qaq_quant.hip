@@ -723,7 +723,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (tid < n_before) {
       const int oldb = L.bits_old[tid];
       nb = oldb;
-      if (a.mode != 0) {
+      if (a.mode == 1 || a.mode == 2) {       // appends leave the cached tokens at their widths
         const int req = a.mode == 1 ? (int)a.newbits[side][(size_t)bh * a.len_before + t0 + tid] : req_rule;
         if (req < oldb) { nb = req; drop = oldb - req; }
         else if (req > oldb && a.orig[side]) nb = req;

@@ -130,3 +130,34 @@ def test_prefill_argument_errors():
     gc.quantize_append(dev(K[:, :, :8]), dev(V[:, :, :8]))
     with pytest.raises(qaq.QaqError):
         gc.prefill_window(dev(q[:, :, :2]), dev(K))            # cache not empty
+
+
+def test_append_selected_to_a_partly_filled_tile():
+    """qaq_quantize_append_selected on a cache that already holds tokens: the new tokens get
+    the widths of the rules for T = tokens after the append and the window as it stands (no
+    row covers them: predicted score 0), the cached tokens are not touched."""
+    sh = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=4, context=300)
+    T, n, extra = sh.context, 3, 7
+    K, V = W.make_kv(3, sh, n_tokens=T + extra)
+    q_last = np.ascontiguousarray(W.make_queries(3, sh, n=n, seed_offset=6).transpose(1, 2, 0, 3))
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    kw = dict(window=5, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc, gc = make_pair(sh, qn, max_tokens=T + extra, **kw)
+    Kp, Vp = np.ascontiguousarray(K[:, :, :T]), np.ascontiguousarray(V[:, :, :T])
+    rows = gc.prefill_window(dev(q_last), dev(Kp)).cpu().numpy()
+    gc.quantize_append_selected(dev(Kp), dev(Vp))
+    oc.prefill(q_last, Kp, Vp, score_rows=[rows[i][..., : T - n + i + 1] for i in range(n)])
+    compare_canonical(oc, gc, "prompt")
+    Kn, Vn = np.ascontiguousarray(K[:, :, T:]), np.ascontiguousarray(V[:, :, T:])
+    bk_g, bv_g = gc.quantize_append_selected(dev(Kn), dev(Vn), want_bits=True)
+    # the oracle: append at the widest width, select for everybody, keep the cached tokens' widths
+    old_k = np.stack([[oc.K[b][h].bits.copy() for h in range(sh.n_kv_heads)] for b in range(sh.batch)])
+    old_v = np.stack([[oc.V[b][h].bits.copy() for h in range(sh.n_kv_heads)] for b in range(sh.batch)])
+    oc.append(Kn, Vn)
+    bk_o, bv_o = oc.select_bits()
+    bk_o[:, :, :T] = old_k; bv_o[:, :, :T] = old_v
+    oc.requantize(bk_o, bv_o)
+    np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o[:, :, T:])
+    np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o[:, :, T:])
+    assert (bv_o[:, :, T:] == 2).all(), "no window row covers the new tokens: narrowest value width"
+    compare_canonical(oc, gc, "after the append")
