@@ -425,3 +425,36 @@ def test_decode_update_skips_unchanged_key_tiles():
     hist = [int((bk_o == w).sum()) for w in (2, 3, 4, 8)]
     print("  final key width histogram", hist, "refused", oc.refused, flush=True)
     assert oc.refused > 0, "the case must refuse some widenings"
+
+
+def test_generation_from_an_empty_cache():
+    """Decode steps that start with nothing cached: the first call attends to the new token
+    alone, the first update appends it with T = 1 (the key rule's bound is unbounded there),
+    and the cache grows token by token through the fused update."""
+    sh = W.shape(3, batch=2, n_q_heads=4, n_kv_heads=2, context=8)
+    steps = 6
+    qn = 0.01
+    kw = dict(max_tokens=steps, window=2, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc, gc = make_pair(sh, qn, **kw)
+    qs = W.make_queries(3, sh, n=steps)
+    Korig = np.zeros((sh.batch, sh.n_kv_heads, 0, sh.head_dim), F16); Vorig = Korig.copy()
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Xo, So = oc.decode_attention(qs[s], kn, vn)
+        ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+        assert ex.max() < TOL and es.max() < TOL
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), dev(Korig), dev(Vorig), want_bits=True)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig, Vorig)
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+        compare_canonical(oc, gc, f"step {s}")
+    assert gc.length() == steps
+    from paper_2403_04643_amd import qaq
+    with pytest.raises(qaq.QaqError):
+        kn, vn = W.make_new_token(3, sh, step=steps)
+        gc.decode_update(S, dev(kn), dev(vn))                 # the cache is full
