@@ -458,3 +458,35 @@ def test_generation_from_an_empty_cache():
     with pytest.raises(qaq.QaqError):
         kn, vn = W.make_new_token(3, sh, step=steps)
         gc.decode_update(S, dev(kn), dev(vn))                 # the cache is full
+
+
+@pytest.mark.parametrize("head_dim,n_o,G", [(64, 2, 4), (64, 0, 1), (128, 0, 2), (128, 3, 1)])
+def test_decode_update_variants(head_dim, n_o, G):
+    """The fused decode step with other head dimensions, outlier counts (none; several per end:
+    the kernels' general outlier paths) and query heads per KV head."""
+    sh = W.shape(3, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=head_dim, context=250)   # crosses a tile border at 256
+    steps = 9
+    K, V = W.make_kv(3, sh)
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    kw = dict(max_tokens=sh.context + steps, window=4, sigma_s_max=1.5e-4, sigma_x_max=4e-2, n_outlier_per_side=n_o)
+    oc, gc = make_pair(sh, qn, **kw)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Xo, So = oc.decode_attention(qs[s], kn, vn)
+        ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+        assert ex.max() < TOL and es.max() < TOL, f"step {s}"
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), dev(Korig), dev(Vorig), want_bits=True)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig, Vorig)
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+        if s in (0, 5, steps - 1):
+            compare_canonical(oc, gc, f"step {s}")
+    assert len(np.unique(bv_o)) > 1 and len(np.unique(bk_o)) > 1, "the case must exercise several widths"
