@@ -460,15 +460,16 @@ def test_generation_from_an_empty_cache():
         gc.decode_update(S, dev(kn), dev(vn))                 # the cache is full
 
 
-@pytest.mark.parametrize("head_dim,n_o,G", [(64, 2, 4), (64, 0, 1), (128, 0, 2), (128, 3, 1)])
-def test_decode_update_variants(head_dim, n_o, G):
+@pytest.mark.parametrize("head_dim,n_o,G,bit_set", [(64, 2, 4, (2, 3, 4, 8)), (64, 0, 1, (2, 4, 8)),
+                                                    (128, 0, 2, (3, 8)), (128, 3, 1, (2, 3, 4, 8))])
+def test_decode_update_variants(head_dim, n_o, G, bit_set):
     """The fused decode step with other head dimensions, outlier counts (none; several per end:
-    the kernels' general outlier paths) and query heads per KV head."""
+    the kernels' general outlier paths), query heads per KV head and subsets of the widths."""
     sh = W.shape(3, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=head_dim, context=250)   # crosses a tile border at 256
     steps = 9
     K, V = W.make_kv(3, sh)
     qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
-    kw = dict(max_tokens=sh.context + steps, window=4, sigma_s_max=1.5e-4, sigma_x_max=4e-2, n_outlier_per_side=n_o)
+    kw = dict(max_tokens=sh.context + steps, window=4, sigma_s_max=1.5e-4, sigma_x_max=4e-2, n_outlier_per_side=n_o, bit_set=bit_set)
     oc, gc = make_pair(sh, qn, **kw)
     oc.append(K, V); gc.quantize_append(dev(K), dev(V))
     Korig, Vorig = K.copy(), V.copy()
