@@ -195,3 +195,33 @@ def test_full_size_prompt_encoding():
         np.testing.assert_array_equal(bv[b, h], bvo[0, 0])
         _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"K b={b} h={h}")
         _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"V b={b} h={h}")
+
+
+@pytest.mark.parametrize("batch,parts", [(16, 2), (10, 3)])
+def test_attention_with_two_and_three_parts_per_head(batch, parts):
+    """Head counts at which a head's tiles are split into two resp. three parts that share a
+    workgroup (512 resp. 320 query heads, five tiles each): sampled units against the oracle."""
+    sh = W.shape(3, batch=batch, n_q_heads=32, n_kv_heads=32, head_dim=64, context=1100)
+    _log(f"parts per head {parts}: {sh}")
+    K, V = W.make_kv(3, sh)
+    rng = np.random.default_rng(300 + parts)
+    widths = np.array([2, 3, 4, 8], np.uint8)
+    bk = rng.choice(widths, size=K.shape[:3], p=(0.4, 0.4, 0.15, 0.05))
+    bv = rng.choice(widths, size=K.shape[:3], p=(0.6, 0.25, 0.1, 0.05))
+    qn = np.full(sh.n_kv_heads, 0.02, F32)
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context + 1, qn.tolist()))
+    gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(3, sh)[0]
+    kn, vn = W.make_new_token(3, sh)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    _global_properties(X, S, V, vn)
+    Xg, Sg = X.cpu().numpy(), S.cpu().numpy()
+    X2, _ = gc.decode_attention(dev(q), dev(kn), dev(vn))                 # without scores: no logit store in LDS
+    np.testing.assert_array_equal(X2.cpu().numpy(), Xg)
+    for b, h in _sample_units(sh, 4, 31 + parts):
+        oc, G = _unit_oracle(sh, qn, b, h)
+        oc.append(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], bk[b:b + 1, h:h + 1], bv[b:b + 1, h:h + 1])
+        Xo, So = oc.decode_attention(q[b:b + 1, h * G:(h + 1) * G], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
+        _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+        assert ex.max() < TOL and es.max() < TOL
