@@ -281,7 +281,10 @@ def main():
     for i in range(warm):
         step(i)
     torch.cuda.synchronize()
-    for c in caches:
+    # Kernel durations come from events attached to the attention dispatches; an attached pair
+    # costs the step about 5 us (0.128 instead of 0.1225 ms per step with every call timed), so
+    # only one instance in two is sampled.
+    for c in caches[::2]:
         c.profile_begin(per_layer + 1)
     t0 = time.perf_counter()
     for i in range(warm, total_steps):
@@ -290,7 +293,7 @@ def main():
     elapsed = time.perf_counter() - t0
 
     ms_main, ms_merge = [], []
-    for c in caches:
+    for c in caches[::2]:
         a, b = c.profile_read()
         ms_main += a; ms_merge += b
         c.profile_begin(0)
