@@ -373,6 +373,7 @@ class Config:
     sigma_s_max: float = 1e-3
     sigma_x_max: float = 1e-2
     qnorm2: Optional[np.ndarray] = None   # [n_kv_heads]
+    window_fp16: bool = False             # variant: the window keeps its score rows in fp16
 
     def n_o(self) -> int:
         if self.n_outlier_per_side >= 0:
@@ -412,6 +413,11 @@ class OracleCache:
         """scores: fp32 [B, Hq, T] normalised attention of one decode step."""
         cfg = self.cfg
         row = np.stack([gqa_reduce(scores[b], cfg.n_kv_heads) for b in range(cfg.batch)])
+        if cfg.window_fp16:
+            # Section 4.2 "attention window" keeps scores, not a precision: a variant stores them
+            # as fp16 (round to nearest even); the predicted score is the maximum of the
+            # stored values, this step's included.
+            row = row.astype(F16)
         self.history.append(row.astype(F32))
         self.history = self.history[-cfg.window:]
 

@@ -452,6 +452,24 @@ def test_window():
 
 
 # ----------------------------------------------------------------- accounting
+def test_window_in_fp16_rounds_what_it_keeps():
+    """The fp16 window variant: the predicted score is the maximum of the *rounded* rows, and a
+    score that fp16 represents exactly is unaffected (written-out rounding, no oracle call)."""
+    cfg = O.Config(1, 2, 1, 8, window=2, window_fp16=True, qnorm2=np.ones(1, F32))
+    oc = O.OracleCache(cfg)
+    x = np.zeros((1, 1, 3, 8), F16); x[..., 0] = 1
+    oc.append(x, x)
+    s1 = np.array([[[0.1, 0.2, 0.7], [0.3, 0.3, 0.4]]], F32)
+    s2 = np.array([[[0.25, 0.125, 0.625], [0.2, 0.30001, 0.49999]]], F32)
+    oc.observe(s1); oc.observe(s2)
+    pred = O.window_predict([r[0, 0] for r in oc.history], 2, 3)
+    want = [max(float(np.float16(max(a, b))), float(np.float16(max(c, d))))
+            for (a, b, c, d) in zip(s1[0, 0], s1[0, 1], s2[0, 0], s2[0, 1])]
+    np.testing.assert_array_equal(pred, np.array(want, F32))
+    assert pred[0] == np.float32(np.float16(0.3)) != np.float32(0.3)      # rounded
+    assert float(np.float16(0.625)) == 0.625 and pred[2] == np.float32(np.float16(0.7))
+
+
 def test_accounting_and_canonical_pack():
     g = _golden("opt175b_sizing.txt")
     assert round(float(g["kv_gb"][0] / g["weights_gb"][0]), 2) == float(g["ratio"][0])
