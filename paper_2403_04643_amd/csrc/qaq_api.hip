@@ -71,6 +71,7 @@ bool valid_config(const qaq_config* c, QaqDims* d) {
   d->Tmax = d->NT * QAQ_TT;
   d->no2 = 2 * no;
   d->window = c->window;
+  d->ring_half = c->window_fp16 ? 1 : 0;
   return true;
 }
 
@@ -166,7 +167,8 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.counts = (uint16_t*)(base + a.counts);
   v.vbound = (float*)(base + a.vbound);
   v.kthr = (float*)(base + a.kthr);
-  v.ring = (float*)(base + a.ring);
+  v.ring = base + a.ring;
+  v.ring_half = d.ring_half;
   v.partial = (float*)(base + a.partial);
   v.statbuf = (long long*)(base + a.statbuf);
   v.refused = (unsigned int*)(base + a.refused);

@@ -21,7 +21,8 @@ struct QaqView {
   uint16_t* counts;
   float* vbound;
   float* kthr;
-  float* ring;
+  void* ring;               // score rows of the window, fp32 or (ring_half) fp16
+  int ring_half;
   float* partial;
   long long* statbuf;
   unsigned int* refused;   // [0] widenings refused for want of the unquantized copy, [1] widenings served
@@ -30,6 +31,17 @@ struct QaqView {
 };
 
 __host__ __device__ __forceinline__ size_t qaq_bh(const QaqView& v, int b, int h) { return (size_t)b * v.Hkv + h; }
+// The window's rows: value as stored (what the predicted score is taken over), load, store.
+__device__ __forceinline__ float qaq_ring_value(const QaqView& v, float s) {
+  return v.ring_half ? __half2float(__float2half_rn(s)) : s;
+}
+__device__ __forceinline__ float qaq_ring_load(const QaqView& v, size_t i) {
+  return v.ring_half ? __half2float(((const __half*)v.ring)[i]) : ((const float*)v.ring)[i];
+}
+__device__ __forceinline__ void qaq_ring_store(const QaqView& v, size_t i, float s) {
+  if (v.ring_half) ((__half*)v.ring)[i] = __float2half_rn(s);
+  else ((float*)v.ring)[i] = s;
+}
 __device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, int b, int h, int tile) {
   return v.codes[side] + ((qaq_bh(v, b, h) * v.NT + tile) * (size_t)v.cap[side]);
 }

@@ -151,6 +151,7 @@ QAQ_HD QaqFieldPos qaq_v_field(uint32_t roff, int bf, int idx, int d, int D) {
 // ---- arena carving --------------------------------------------------------------
 struct QaqDims {
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
+  int ring_half;      // the window's rows are fp16
 };
 
 struct QaqArena {
@@ -164,7 +165,7 @@ struct QaqArena {
   size_t counts;      // u16  [B][Hkv][NT][2][4]
   size_t vbound;      // f32  [B][Hkv][NT]   per tile: bound on (value scale, outlier correction) over its tokens
   size_t kthr;        // f32  [B][Hkv][NT][2] per tile: key-rule thresholds [lo, hi) for which no token changes width
-  size_t ring;        // f32  [window][B][Hkv][Tmax]
+  size_t ring;        // f32 (or fp16) [window][B][Hkv][Tmax]
   size_t partial;     // f32  [B][Hq][NT][D+4]
   size_t statbuf;     // i64  [32]
   size_t refused;     // u32  [2][QAQ_NCOUNT] widenings refused / served, partial counts
@@ -187,7 +188,7 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   a.counts = off; off = qaq_up256(off + bh * d.NT * 2 * 4 * 2);
   a.vbound = off; off = qaq_up256(off + bh * d.NT * 4);
   a.kthr = off; off = qaq_up256(off + bh * d.NT * 8);
-  a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * 4);
+  a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * (d.ring_half ? 2 : 4));
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
   a.statbuf = off; off = qaq_up256(off + 32 * 8);
   a.refused = off; off = qaq_up256(off + 2 * QAQ_NCOUNT * 4);

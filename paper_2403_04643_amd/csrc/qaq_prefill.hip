@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_softmax(QaqPrefillArgs a) 
   const int i = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
   const int len = row_length(a.T, a.n_rows, i);
   const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
-  float* ring = v.ring + (size_t)i * ring_row + qaq_bh(v, b, h) * v.Tmax;
+  const size_t ring0 = (size_t)i * ring_row + qaq_bh(v, b, h) * v.Tmax;
   for (int g = 0; g < a.G; ++g) {
     float* row = a.scores + (((size_t)i * v.B + b) * v.Hq + (h * a.G + g)) * a.T;
     // maximum and sum in one sweep: every thread keeps its logits (T / 256 of them, at most
@@ -124,13 +124,13 @@ __global__ __launch_bounds__(kThreads) void k_prefill_softmax(QaqPrefillArgs a) 
       if (t < a.T) {
         const float s = t < len ? expf(mine[k] - m) / l : 0.0f;
         row[t] = s;
-        if (t < len) ring[t] = g == 0 ? s : fmaxf(ring[t], s);   // thread tid is the only one to touch position t
+        if (t < len) qaq_ring_store(v, ring0 + t, g == 0 ? s : fmaxf(qaq_ring_load(v, ring0 + t), s));   // thread tid is the only one to touch position t
       }
     }
     for (int t = tid + kKeep * kThreads; t < a.T; t += kThreads) {
       const float s = t < len ? expf(row[t] - m) / l : 0.0f;
       row[t] = s;
-      if (t < len) ring[t] = g == 0 ? s : fmaxf(ring[t], s);
+      if (t < len) qaq_ring_store(v, ring0 + t, g == 0 ? s : fmaxf(qaq_ring_load(v, ring0 + t), s));
     }
   }
 }

@@ -657,12 +657,13 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     float s = 0.0f;
     if (a.mode == 2)
       for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
+    s = qaq_ring_value(v, s);
     pred = s;
     for (int r = 0; r < v.window; ++r) {
       if (r == ru.new_row) continue;
-      if (t < ru.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
+      if (t < ru.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
     }
-    if (a.mode == 2) v.ring[(size_t)ru.new_row * ring_row + ri] = s;
+    if (a.mode == 2) qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
   }
   if (a.mode == 1) {
     // no token of the tile changes: leave it alone
@@ -1050,13 +1051,14 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
     float s = 0.0f;
     if (a.scores) {
       for (int g = 0; g < a.G; ++g) s = fmaxf(s, a.scores[((size_t)b * v.Hq + (h * a.G + g)) * a.len + t]);
+      s = qaq_ring_value(v, s);
       pred = s;
     }
     for (int r = 0; r < v.window; ++r) {
       if (a.scores && r == a.new_row) continue;
-      if (t < a.row_len[r]) pred = fmaxf(pred, v.ring[(size_t)r * ring_row + ri]);
+      if (t < a.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
     }
-    if (a.scores) v.ring[(size_t)a.new_row * ring_row + ri] = s;
+    if (a.scores) qaq_ring_store(v, (size_t)a.new_row * ring_row + ri, s);
     rk[pk] = h2f((uint16_t)(mk >> 16)) - h2f((uint16_t)(mk & 0xffffu));
     rv[pv] = h2f((uint16_t)(mv >> 16)) - h2f((uint16_t)(mv & 0xffffu));
   }

@@ -161,3 +161,44 @@ def test_append_selected_to_a_partly_filled_tile():
     np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o[:, :, T:])
     assert (bv_o[:, :, T:] == 2).all(), "no window row covers the new tokens: narrowest value width"
     compare_canonical(oc, gc, "after the append")
+
+
+def test_window_kept_in_fp16():
+    """The variant that keeps the window's score rows in fp16: prompt encoding, separate
+    selection and fused decode steps all take the predicted score over the rounded rows."""
+    sh = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=4, context=520)
+    T, n, steps = sh.context, 4, 6
+    K, V = W.make_kv(3, sh)
+    q_last = np.ascontiguousarray(W.make_queries(3, sh, n=n, seed_offset=8).transpose(1, 2, 0, 3))
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    kw = dict(window=5, sigma_s_max=4e-4, sigma_x_max=6e-3, window_fp16=True)
+    oc, gc = make_pair(sh, qn, max_tokens=T + steps, **kw)
+    oc32, _ = make_pair(sh, qn, max_tokens=T + steps, **dict(kw, window_fp16=False))
+    rows = gc.prefill_window(dev(q_last), dev(K)).cpu().numpy()
+    bk_g, bv_g = gc.quantize_append_selected(dev(K), dev(V), want_bits=True)
+    given = [rows[i][..., : T - n + i + 1] for i in range(n)]
+    bk_o, bv_o, _ = oc.prefill(q_last, K, V, score_rows=given)
+    _, bv_32, _ = oc32.prefill(q_last, K, V, score_rows=given)
+    np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+    np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+    _log(f"  value widths that differ from the fp32 window: {int((bv_o != bv_32).sum())} of {bv_o.size}")
+    compare_canonical(oc, gc, "prompt")
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig, Vorig)
+        if s % 2 == 0:       # the fused call
+            bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), dev(Korig), dev(Vorig), want_bits=True)
+        else:                # the separate calls
+            gc.quantize_append(dev(kn[:, :, None]), dev(vn[:, :, None]))
+            bk_g, bv_g = gc.select_bits(S)
+            gc.requantize(bk_g, bv_g, dev(Korig), dev(Vorig))
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o)
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o)
+    compare_canonical(oc, gc, "after the decode steps")
