@@ -718,7 +718,9 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     if (!__syncthreads_or(changed ? 1 : 0) && !has_new) return;
   }
 
-  // final width of every position
+  // final width of every position; whether it is encoded in this pass (new tokens, and
+  // cached tokens that widen from the unquantized copy)
+  bool enc = false;
   if (tid < n_after) {
     int nb, drop = 0;
     if (tid < n_before) {
@@ -729,36 +731,40 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
         if (req < oldb) { nb = req; drop = oldb - req; }
         else if (req > oldb && a.orig[side]) nb = req;
       }
+      enc = nb > oldb;
     } else {
       const int r = t0 + tid - a.len_before;
       nb = a.newbits[side] ? a.newbits[side][(size_t)bh * a.n_new + r] : a.widest;
       L.bits_old[tid] = (uint8_t)nb;
+      enc = true;
     }
     L.bits_new[tid] = (uint8_t)nb;
     L.shf[tid] = (uint8_t)drop;
   }
+  // In a tile that has cached tokens the few positions to encode are gathered into a list,
+  // so that they fill the encoder's passes densely; a tile with none (most value-side tiles
+  // of a decode step without the unquantized copies) goes on after one barrier.
+  const bool listed = n_before > 0;
+  unsigned long long enc_bal = 0ull;
+  if (listed) {
+    enc_bal = __ballot(enc);
+    if (lane == 0) L.wave_need[0][wave] = __popcll(enc_bal);    // (this array's other use comes two barriers later)
+  }
   __syncthreads();
 
-  // encode: new tokens, and cached tokens that widen (from the unquantized copy).  A quad of
-  // lanes per token, 64 tokens per pass; the rows of the next pass are requested before the
-  // current pass is computed.  In a tile that has cached tokens the few positions to encode
-  // are first gathered into a list, so that they fill passes densely.
-  {
+  // encode: a quad of lanes per token, 64 tokens per pass; the rows of the next pass are
+  // requested before the current pass is computed
+  int n_enc = n_after;
+  if (listed) {
+    int off = 0;
+    for (int w = 0; w < wave; ++w) off += L.wave_need[0][w];
+    if (enc) L.freeslot[off + __popcll(enc_bal & ((1ull << lane) - 1ull))] = (uint16_t)tid;
+    n_enc = L.wave_need[0][0] + L.wave_need[0][1] + L.wave_need[0][2] + L.wave_need[0][3];
+    if (n_enc > 0) __syncthreads();          // uniform: every thread has the same sum
+  }
+  if (n_enc > 0) {
     typedef TokenEncoder<D, ONE> Enc;
     constexpr int TPP = kThreads / 4;     // tokens per pass
-    const bool listed = n_before > 0;
-    int n_enc = n_after;
-    if (listed) {
-      const bool enc = tid < n_after && (tid >= n_before || L.bits_new[tid] > L.bits_old[tid]);
-      const unsigned long long bal = __ballot(enc);
-      if (lane == 0) L.wave_cnt[0][wave] = __popcll(bal);
-      __syncthreads();
-      int off = 0;
-      for (int w = 0; w < wave; ++w) off += L.wave_cnt[0][w];
-      if (enc) L.freeslot[off + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)tid;
-      n_enc = L.wave_cnt[0][0] + L.wave_cnt[0][1] + L.wave_cnt[0][2] + L.wave_cnt[0][3];
-      __syncthreads();
-    }
     const int NP = (n_enc + TPP - 1) / TPP;
     const int c = tid & 3, gt = tid >> 2;
     auto position = [&](int pass) { const int e = pass * TPP + gt; return listed ? (int)L.freeslot[min(e, QAQ_TT - 1)] : e; };
@@ -794,8 +800,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       for (int i = 0; i < Enc::NCH; ++i) cur[i] = nxt[i];
       kind = kind_next;
     }
+    __syncthreads();
   }
-  __syncthreads();
 
   // decode-step update, append by the rules: the width of a new token from the range the
   // encoder has just found (it was encoded at the widest width; narrowing drops low bits)
