@@ -136,7 +136,7 @@ def cpu_baseline(sh, hist_k, hist_v, qn, n_o, n_seq):
     s1 = W.shape(2, batch=n_seq, context=sh.context, n_q_heads=sh.n_q_heads, n_kv_heads=sh.n_kv_heads)
     K, V = W.make_kv(2, s1)
     rng = np.random.default_rng(99)
-    widths = np.array([2, 3, 4, 8], np.uint8)
+    widths = np.array([2, 3, 4, 8, 1], np.uint8)     # the order of qaq_stats_t.hist_k
     bk = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_k) / np.sum(hist_k))
     bv = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_v) / np.sum(hist_v))
     oc = O.OracleCache(O.Config(n_seq, s1.n_q_heads, s1.n_kv_heads, s1.head_dim, qnorm2=qn))
@@ -313,8 +313,8 @@ def main():
     read_gbs, copy_gbs, yard_bytes = stream_read_gbs(lib, bytes_main)
     s = st1[0]
     th = B * Hkv * s.tokens
-    mean_k = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_k)) / th
-    mean_v = sum(w * n for w, n in zip((2, 3, 4, 8), s.hist_v)) / th
+    mean_k = sum(w * n for w, n in zip((2, 3, 4, 8, 1), s.hist_k)) / th
+    mean_v = sum(w * n for w, n in zip((2, 3, 4, 8, 1), s.hist_v)) / th
     tokens_per_s = B * Tctx / (float(np.mean(prefill_ms[1:] or prefill_ms)) * 1e-3)
 
     rec = {
@@ -406,8 +406,8 @@ def main():
         quality[op2] = {"output_rel_l2_error": output_error(0), "ratio_codes": st2.fp16_bytes / st2.code_bytes}
         others[op2] = {"us_tile_kernel": us2, "algorithmic_bytes": b2, "GBps": b2 / (us2 * 1e-6) / 1e9,
                        "frac_of_hbm_peak": b2 / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                       "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_k)) / th2,
-                       "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8), st2.hist_v)) / th2}
+                       "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8, 1), st2.hist_k)) / th2,
+                       "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8, 1), st2.hist_v)) / th2}
     if others:
         rec["other_operating_points"] = others
 

@@ -49,8 +49,9 @@ typedef struct {
   int32_t n_kv_heads;     /* Hkv                                                      */
   int32_t head_dim;       /* D: 64 or 128                                             */
   int32_t max_tokens;     /* capacity per sequence (rounded up to a tile of 256)      */
-  int32_t bit_set[4];     /* allowed code widths, ascending, a subset of {2,3,4,8}    */
-  int32_t n_bits;         /* how many entries of bit_set are used (1..4)              */
+  int32_t bit_set[5];     /* allowed code widths, ascending, a subset of {1,2,3,4,8}
+                             (the paper's experiments: {2,3,4,8}; 1 is a variant)     */
+  int32_t n_bits;         /* how many entries of bit_set are used (1..5)              */
   float   outlier_frac;   /* alpha, total over both ends (Section 4.2 "Outliers");
                              the paper's experiments use 0.01                        */
   int32_t n_outlier_per_side; /* <0: ceil(outlier_frac/2 * D); 0: none; at most 4     */
@@ -69,8 +70,8 @@ typedef struct {
 
 typedef struct {
   int64_t tokens;            /* cached positions per sequence                         */
-  int64_t hist_k[4];         /* token-heads per width, in bit_set {2,3,4,8} order     */
-  int64_t hist_v[4];
+  int64_t hist_k[5];         /* token-heads per width, in the order {2,3,4,8,1}       */
+  int64_t hist_v[5];
   int64_t code_bytes;        /* sum over token-heads of D*(bK+bV)/8 (Section 2.1:
                                 memory "calculated by the quantized bit")             */
   int64_t layout_code_bytes; /* bytes the device layout actually reads for codes      */

@@ -53,11 +53,11 @@ bool valid_config(const qaq_config* c, QaqDims* d) {
   if (c->n_kv_heads > QAQ_MAX_KV_HEADS) { fail(QAQ_ERR_INVALID_ARG, "at most %d KV heads", QAQ_MAX_KV_HEADS); return false; }
   if (c->head_dim != 64 && c->head_dim != 128) { fail(QAQ_ERR_INVALID_ARG, "head_dim must be 64 or 128, got %d", c->head_dim); return false; }
   if (c->max_tokens < 1) { fail(QAQ_ERR_INVALID_ARG, "max_tokens must be positive"); return false; }
-  if (c->n_bits < 1 || c->n_bits > 4) { fail(QAQ_ERR_INVALID_ARG, "n_bits must be 1..4"); return false; }
+  if (c->n_bits < 1 || c->n_bits > 5) { fail(QAQ_ERR_INVALID_ARG, "n_bits must be 1..5"); return false; }
   for (int i = 0; i < c->n_bits; ++i) {
     const int b = c->bit_set[i];
-    if (!(b == 2 || b == 3 || b == 4 || b == 8) || (i && b <= c->bit_set[i - 1])) {
-      fail(QAQ_ERR_INVALID_ARG, "bit_set must be an ascending subset of {2,3,4,8}"); return false; }
+    if (!(b == 1 || b == 2 || b == 3 || b == 4 || b == 8) || (i && b <= c->bit_set[i - 1])) {
+      fail(QAQ_ERR_INVALID_ARG, "bit_set must be an ascending subset of {1,2,3,4,8}"); return false; }
   }
   if (c->window < 1 || c->window > QAQ_MAX_WINDOW) { fail(QAQ_ERR_INVALID_ARG, "window must be 1..%d", QAQ_MAX_WINDOW); return false; }
   const int no = outliers_per_side(c);
@@ -173,6 +173,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.statbuf = (long long*)(base + a.statbuf);
   v.refused = (unsigned int*)(base + a.refused);
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
+  v.has1 = cfg->bit_set[0] == 1;
   v.cap[0] = qaq_k_cap(d.D);
   v.cap[1] = qaq_v_cap(d.D);
   hipError_t e = qaq_launch_init(v, nullptr);
@@ -219,7 +220,7 @@ int qaq_thresholds(const qaq_cache* c, int32_t T, float* host_tau_k, float* host
 
 static void fill_bit_set(const qaq_cache* c, QaqRuleArgs& r) {
   r.nbits = c->cfg.n_bits;
-  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+  for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
 }
 
 int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int32_t n_new,
@@ -266,7 +267,7 @@ int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits, 
   }
   for (int r = 0; r < QAQ_MAX_WINDOW; ++r) a.row_len[r] = r < c->dims.window ? c->row_len[r] : 0;
   a.nbits = c->cfg.n_bits;
-  for (int i = 0; i < 4; ++i) a.bit_set[i] = c->cfg.bit_set[i < a.nbits ? i : a.nbits - 1];
+  for (int i = 0; i < 5; ++i) a.bit_set[i] = c->cfg.bit_set[i < a.nbits ? i : a.nbits - 1];
   thresholds(c, c->len, a.tau_k, &a.c_v);
   a.out_bits[0] = dev_k_bits; a.out_bits[1] = dev_v_bits;
   hipError_t e = qaq_launch_select(a, (hipStream_t)stream);
@@ -329,7 +330,7 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   c->ring_next = (c->ring_next + 1) % c->dims.window;
   for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
   r.nbits = c->cfg.n_bits;
-  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+  for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
   thresholds(c, a.len_after, r.tau_k, &r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
   hipError_t e = qaq_launch_build(a, (a.len_after + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
@@ -387,7 +388,7 @@ int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* de
   r.new_row = -1;
   for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
   r.nbits = c->cfg.n_bits;
-  for (int i = 0; i < 4; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
+  for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
   thresholds(c, a.len_after, r.tau_k, &r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
   const int tile_last = (a.len_after - 1) / QAQ_TT;
@@ -502,6 +503,9 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
     out->hist_v[i] = buf[4 + i];
     out->code_bytes += (buf[i] + buf[4 + i]) * D * widths[i] / 8;
   }
+  out->hist_k[4] = buf[10];
+  out->hist_v[4] = buf[11];
+  out->code_bytes += (buf[10] + buf[11]) * D / 8;
   out->layout_code_bytes = buf[8];
   out->meta_bytes = buf[9];
   out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;

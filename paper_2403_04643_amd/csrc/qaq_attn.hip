@@ -196,6 +196,7 @@ struct TileLds {
   alignas(16) int8_t wl2[4][QAQ_TT + 16];   // weight digits per slot of the 2-bit field region
   alignas(16) int8_t wl1[4][QAQ_TT + 16];   // ... of the 1-bit field region
   alignas(16) int8_t wl4[4][QAQ_TT + 16];   // ... of the 4-bit region
+  alignas(16) int8_t wl1b[4][QAQ_TT + 16];  // ... of the 1-bit tokens' region
   float w8[QAQ_TT];                     // fp32 weights of the 8-bit slots
   float xw[4][D / 4];                   // per-wavefront 8-bit-class outputs (its own channels)
   float xcorr[D];                       // outlier corrections of the output (end of the chunk)
@@ -307,7 +308,7 @@ struct KeyRegs {
     // lane group g of the wavefront: bytes 8*(lane%16) .. +8 of the record of its g-th 8-bit slot
     const int first8 = n32 + c.n4;
     const int s8 = max(first8, tid & ~63) + ((tid & 63) >> 4);
-    const uint32_t off8 = s8 < n_tok && 8 * (tid & 15) < D ? rK.r8 + (uint32_t)(s8 - first8) * (uint32_t)KRec<D, 8>::REC + 8u * (uint32_t)(tid & 15) : 0u;
+    const uint32_t off8 = s8 < n_tok - c.n1 && 8 * (tid & 15) < D ? rK.r8 + (uint32_t)(s8 - first8) * (uint32_t)KRec<D, 8>::REC + 8u * (uint32_t)(tid & 15) : 0u;
     if (c.n8 > 0) gload_dwords<2>(ubase + off8, k8);      // uniform over the workgroup
   }
 };
@@ -356,7 +357,9 @@ struct ValRegs {
 // the same number of iterations and skips the work of those past its last tile, so that all
 // barriers are met by all wavefronts); raw logits stay in LDS, the parts are merged in LDS,
 // and the workgroup writes the output and the normalised scores itself: no second kernel.
-template <int D, int NO2, int P>
+// H1: the width set contains 1 (a fifth class at the end of every tile); without it that
+// class costs nothing.
+template <int D, int NO2, int P, bool H1>
 __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
   constexpr int KS = D / 64;
   constexpr int NCG = D / 16;
@@ -400,6 +403,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
     QaqCounts r;
     r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
+    r.n1 = H1 ? min(a.len - t * QAQ_TT, QAQ_TT) - (r.n3 + r.n2 + r.n4 + r.n8) : 0;      // the 1-bit class is the rest of the tile
     return r;
   };
   KeyRegs<D, NO2> kr;
@@ -432,6 +436,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   const int8_t* wb2 = nn < 4 ? &S.wl2[nn][16 * g] : &S.zrow[0];
   const int8_t* wb1 = nn < 4 ? &S.wl1[nn][16 * g] : &S.zrow[0];
   const int8_t* wb4 = nn < 4 ? &S.wl4[nn][16 * g] : &S.zrow[0];
+  const int8_t* wb1b = nn < 4 ? &S.wl1b[nn][16 * g] : &S.zrow[0];
 
   auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale; };
   auto key_logit = [&](uint32_t m, const Outl<NO2>& o, uint32_t slot, int bits, float dotq) {
@@ -475,6 +480,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
     const int n32K = cK.n32(), n32V = cV.n32();
     const int first8V = n32V + cV.n4;
+    const int first1K = H1 ? cK.first1() : n_tok, first1V = H1 ? cV.first1() : n_tok;
 
     // ---- keys: logits ----------------------------------------------------------------------------
     // Every lane owns slot `tid`; the wavefront runs one contraction chain per width class that
@@ -503,7 +509,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         if (tid >= n32K) dotq = d4;
       }
       const int s8_0 = max(first8K, w0);                 // first 8-bit slot among this wavefront's
-      const int n8w = min(n_tok, w1) - s8_0;             // and how many there are
+      const int n8w = min(first1K, w1) - s8_0;           // and how many there are
       if (n8w > 0 && n8w <= 4) {
         // a few 8-bit keys: every group of 16 lanes takes one, a lane 8 of its bytes (fetched
         // with the rest of the tile), fp32 products with the query in a fixed order
@@ -537,8 +543,15 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         const v4i cc = k_contract<D, 8>(w, abase2);
         if (tid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
       }
+      if (H1 && cK.n1 > 0 && w1 > first1K) {
+        // 1-bit keys (only with a width set that has 1): the record is fetched here
+        uint32_t k1[KRec<D, 1>::RDW];
+        KRec<D, 1>::load(baseK + rK.r1b, min(max(tid - first1K, 0), cK.n1 - 1), k1);
+        const float d1 = real_of(k_contract<D, 1>(k1, abase1));
+        if (tid >= first1K) dotq = d1;
+      }
       if (tid < n_tok) {
-        const float lg = key_logit(kr.mm, kr.o, slot, cK.bits_of_slot(tid), dotq);
+        const float lg = key_logit(kr.mm, kr.o, slot, H1 ? cK.bits_of_slot(tid) : cK.bits_of_slot4(tid), dotq);
         S.logit[(kr.pos >> (8u * (slot & 3u))) & 0xffu] = lg;
         vmax = lg;
       }
@@ -571,7 +584,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         pt = __expf(S.logit[(vr.pos >> (8u * (slot & 3u))) & 0xffu] - M);
         const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
         const float range = mx - mn;
-        const int bits = cV.bits_of_slot(s);
+        const int bits = H1 ? cV.bits_of_slot(s) : cV.bits_of_slot4(s);
         const float scale = ldexpf(range, -bits);
         w = pt * scale;
         bias_l = pt * mn + 0.5f * w;
@@ -587,7 +600,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
             atomicAdd(&S.xc[och][(lane + 4 * (och >> 1)) & 15], (int)rintf(ldexpf(cval, 25 - wexp)));
           }
         }
-        if (s >= first8V) S.w8[s - first8V] = w;
+        if (s >= first8V && (!H1 || s < first1V)) S.w8[s - first8V] = w;
       }
       l_run = l_run * keep + pt;
       bias_run = bias_run * keep + bias_l;
@@ -613,6 +626,12 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         const uint32_t W4 = (fx && s >= n32V && s < first8V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp)) : 0u;
         S.wl4[0][i4] = (int8_t)(W4 & 127u); S.wl4[1][i4] = (int8_t)((W4 >> 7) & 127u);
         S.wl4[2][i4] = (int8_t)((W4 >> 14) & 127u); S.wl4[3][i4] = (int8_t)(W4 >> 21);
+      }
+      if (H1 && cV.n1 > 0) {
+        const int i1 = (s - first1V) & (QAQ_TT - 1);
+        const uint32_t W1 = (fx && s >= first1V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift1((i1 & 15) >> 2))) : 0u;
+        S.wl1b[0][i1] = (int8_t)(W1 & 127u); S.wl1b[1][i1] = (int8_t)((W1 >> 7) & 127u);
+        S.wl1b[2][i1] = (int8_t)((W1 >> 14) & 127u); S.wl1b[3][i1] = (int8_t)(W1 >> 21);
       }
     }
     lds_barrier();
@@ -661,6 +680,14 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         const uint32_t pr[2] = {w0[j], w1d[j]};
         cv[j] = mma(wa, spread<4>(pr, 0), cv[j]);
       }
+    }
+    for (int blk = 0; H1 && blk * 64 < cV.n1; ++blk) {     // 1-bit tokens: units in the format of the 1-bit fields
+      const int nu = (cV.n1 + 15) >> 4;
+      const uint32_t w1b = *(const uint32_t*)(baseV + rV.r1b + (uint32_t)min(blk * 4 + g, nu - 1) * (2u * D) +
+                                              (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+      const v4i wa = *(const v4i*)(wb1b + 64 * blk);
+#pragma unroll
+      for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&w1b, (CGW * wave + j) & 1), cv[j]);
     }
     // 8-bit codes: token-major bytes, plain fp32 multiply-add; this wavefront's D/4 channels,
     // lane = (token sub-index, 4 channels)
@@ -854,9 +881,15 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
 template <int D, int P>
 void launch_tile_p(const QaqAttnArgs& a, dim3 grid, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const dim3 block((P ? P : 1) * kThreads);
-  if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P>), grid, block, lds, s, e0, e1, 0, a);
-  else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P>), grid, block, lds, s, e0, e1, 0, a);
-  else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P>), grid, block, lds, s, e0, e1, 0, a);
+  if (a.v.has1) {
+    if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, true>), grid, block, lds, s, e0, e1, 0, a);
+    else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P, true>), grid, block, lds, s, e0, e1, 0, a);
+    else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P, true>), grid, block, lds, s, e0, e1, 0, a);
+    return;
+  }
+  if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, false>), grid, block, lds, s, e0, e1, 0, a);
+  else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P, false>), grid, block, lds, s, e0, e1, 0, a);
+  else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P, false>), grid, block, lds, s, e0, e1, 0, a);
 }
 template <int D>
 void launch_tile(const QaqAttnArgs& a, int fused_parts, int BQ, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {

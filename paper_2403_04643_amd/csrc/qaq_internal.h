@@ -27,6 +27,7 @@ struct QaqView {
   long long* statbuf;
   unsigned int* refused;   // [0] widenings refused for want of the unquantized copy, [1] widenings served
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
+  int has1;                // the width set contains 1: kernels take their five-class variants
   uint32_t cap[2];
 };
 
@@ -48,10 +49,12 @@ __device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, i
 __device__ __forceinline__ size_t qaq_slot_index(const QaqView& v, int b, int h, int tile, int slot) {
   return qaq_bh(v, b, h) * v.Tmax + (size_t)tile * QAQ_TT + slot;
 }
-__device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side, int b, int h, int tile) {
+// n_tok: tokens the tile holds (the 1-bit class is what the four stored counts leave of them)
+__device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side, int b, int h, int tile, int n_tok) {
   const uint16_t* p = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
   QaqCounts c;
   c.n3 = p[QC3]; c.n2 = p[QC2]; c.n4 = p[QC4]; c.n8 = p[QC8];
+  c.n1 = n_tok - (c.n3 + c.n2 + c.n4 + c.n8);
   return c;
 }
 
@@ -63,7 +66,7 @@ struct QaqRuleArgs {
   int new_row;             // ring row that receives `scores` (ignored if null)
   int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
   int nbits;
-  int bit_set[4];
+  int bit_set[5];
   float tau_k[QAQ_MAX_KV_HEADS];
   float c_v;
   uint8_t* out_bits[2];    // [B,Hkv,len] or null
@@ -90,7 +93,7 @@ struct QaqSelectArgs {
   int new_row;             // ring row that receives `scores` (ignored if null)
   int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
   int nbits;
-  int bit_set[4];
+  int bit_set[5];
   float tau_k[QAQ_MAX_KV_HEADS];
   float c_v;
   uint8_t* out_bits[2];    // [B,Hkv,len]

@@ -2,7 +2,7 @@
 //
 // The sequence of one (batch, KV head) is cut into tiles of TT = 256 positions.
 // Inside a tile, separately for keys and for values, tokens are ordered by code
-// width: first the 3-bit tokens, then the 2-bit, 4-bit and 8-bit ones ("slots";
+// width: first the 3-bit tokens, then the 2-bit, 4-bit, 8-bit and 1-bit ones ("slots";
 // perm[slot] = position inside the tile).  Per-token metadata (min/max, perm,
 // outlier side store) is stored in slot order, so a kernel that walks the slots
 // reads it coalesced.  Codes are stored per width class in operand-ready form for
@@ -12,6 +12,9 @@
 //       token's code (slots [0, n3+n2))
 //   R1  1-bit fields: the low bit of every 3-bit token (slots [0, n3))
 //   R4  4-bit codes, R8 8-bit codes
+//   R1b 1-bit codes of the 1-bit tokens, in the format of R1 (its index starts at the
+//       first 1-bit slot); the class sits last so that a cache whose width set has no 1
+//       is laid out as if the class did not exist
 //
 // A 3-bit code c is thus 2*top + low, which makes narrowing 3 -> 2 a matter of
 // dropping R1, and lets the attention kernels treat the planes as two separate
@@ -45,24 +48,32 @@
 #endif
 
 // class order inside a tile
-enum { QC3 = 0, QC2 = 1, QC4 = 2, QC8 = 3 };
+enum { QC3 = 0, QC2 = 1, QC4 = 2, QC8 = 3, QC1 = 4, QAQ_NCLASS = 5 };
 
-QAQ_HD int qaq_class_of_bits(int b) { return b == 3 ? QC3 : b == 2 ? QC2 : b == 4 ? QC4 : QC8; }
-QAQ_HD int qaq_bits_of_class(int c) { return c == QC3 ? 3 : c == QC2 ? 2 : c == QC4 ? 4 : 8; }
+QAQ_HD int qaq_class_of_bits(int b) { return b == 3 ? QC3 : b == 2 ? QC2 : b == 4 ? QC4 : b == 8 ? QC8 : QC1; }
+QAQ_HD int qaq_bits_of_class(int c) { return c == QC3 ? 3 : c == QC2 ? 2 : c == QC4 ? 4 : c == QC8 ? 8 : 1; }
 
+// Tokens per class.  Only the first four are stored per tile side; n1 is what remains of
+// the tile's tokens.
 struct QaqCounts {
-  int n3, n2, n4, n8;
+  int n3, n2, n4, n8, n1;
   QAQ_HD int n32() const { return n3 + n2; }
-  QAQ_HD int total() const { return n3 + n2 + n4 + n8; }
-  QAQ_HD int start(int cls) const { return cls == QC3 ? 0 : cls == QC2 ? n3 : cls == QC4 ? n3 + n2 : n3 + n2 + n4; }
-  QAQ_HD int bits_of_slot(int s) const { return s < n3 ? 3 : s < n3 + n2 ? 2 : s < n3 + n2 + n4 ? 4 : 8; }
+  QAQ_HD int first1() const { return n3 + n2 + n4 + n8; }
+  QAQ_HD int total() const { return n3 + n2 + n4 + n8 + n1; }
+  QAQ_HD int count(int cls) const { return cls == QC3 ? n3 : cls == QC2 ? n2 : cls == QC4 ? n4 : cls == QC8 ? n8 : n1; }
+  QAQ_HD int start(int cls) const {
+    return cls == QC3 ? 0 : cls == QC2 ? n3 : cls == QC4 ? n3 + n2 : cls == QC8 ? n3 + n2 + n4 : n3 + n2 + n4 + n8;
+  }
+  QAQ_HD int bits_of_slot(int s) const { return s < n3 ? 3 : s < n3 + n2 ? 2 : s < n3 + n2 + n4 ? 4 : s < n3 + n2 + n4 + n8 ? 8 : 1; }
+  // the same where the width set is known to have no 1 (kernels specialised on that)
+  QAQ_HD int bits_of_slot4(int s) const { return s < n3 ? 3 : s < n3 + n2 ? 2 : s < n3 + n2 + n4 ? 4 : 8; }
 };
 
 QAQ_HD uint32_t qaq_align16(uint32_t x) { return (x + 15u) & ~15u; }
 
 // ---- K side region offsets (bytes from the tile-side base) -------------------
 struct QaqKRegions {
-  uint32_t r2, r1, r4, r8, end;
+  uint32_t r2, r1, r4, r8, r1b, end;
 };
 QAQ_HD QaqKRegions qaq_k_regions(const QaqCounts& c, int D) {
   QaqKRegions r;
@@ -72,15 +83,16 @@ QAQ_HD QaqKRegions qaq_k_regions(const QaqCounts& c, int D) {
   r.r1 = (uint32_t)((c.n32() + 15) / 16) * 16u * (D / 4);
   r.r4 = r.r1 + (uint32_t)((c.n3 + 15) / 16) * 16u * (D / 8);
   r.r8 = r.r4 + (uint32_t)((c.n4 + 15) / 16) * 16u * (D / 2);
-  r.end = r.r8 + (uint32_t)c.n8 * D;
+  r.r1b = r.r8 + (uint32_t)c.n8 * D;
+  r.end = r.r1b + (uint32_t)((c.n1 + 15) / 16) * 16u * (D / 8);
   return r;
 }
-// worst case: 253 8-bit records and one partly filled group of 16 in each other region
+// worst case: 252 8-bit records and one partly filled group of 16 in each other region
 QAQ_HD uint32_t qaq_k_cap(int D) { return QAQ_TT * D + 16 * D; }
 
 // ---- V side region offsets ----------------------------------------------------
 struct QaqVRegions {
-  uint32_t r2, r1, r4, r8, end;
+  uint32_t r2, r1, r4, r8, r1b, end;
 };
 QAQ_HD QaqVRegions qaq_v_regions(const QaqCounts& c, int D) {
   QaqVRegions r;
@@ -88,7 +100,8 @@ QAQ_HD QaqVRegions qaq_v_regions(const QaqCounts& c, int D) {
   r.r1 = (uint32_t)((c.n32() + 15) / 16) * (4 * D);
   r.r4 = r.r1 + (uint32_t)((c.n3 + 15) / 16) * (2 * D);
   r.r8 = r.r4 + (uint32_t)((c.n4 + 7) / 8) * (4 * D);
-  r.end = r.r8 + (uint32_t)c.n8 * D;
+  r.r1b = r.r8 + (uint32_t)c.n8 * D;
+  r.end = r.r1b + (uint32_t)((c.n1 + 15) / 16) * (2 * D);
   return r;
 }
 QAQ_HD uint32_t qaq_v_cap(int D) { return QAQ_TT * D + 16 * D; }

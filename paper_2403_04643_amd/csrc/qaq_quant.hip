@@ -30,10 +30,14 @@ __device__ __forceinline__ uint32_t rd_field(const uint8_t* base, QaqFieldPos p,
 }
 
 // Code of (slot, channel d) as stored for this tile side.
-template <int D>
+template <int D, bool HAS1 = true>
 __device__ __forceinline__ uint32_t load_code(int side, const uint8_t* base, const QaqCounts& c, uint32_t r2,
-                                              uint32_t r1, uint32_t r4, uint32_t r8, int slot, int d) {
+                                              uint32_t r1, uint32_t r4, uint32_t r8, uint32_t r1b, int slot, int d) {
   const int n32 = c.n32();
+  if (HAS1 && slot >= c.first1()) {
+    const int i1 = slot - c.first1();
+    return side == 0 ? rd_field(base, qaq_k_field(r1b, 1, i1, d, D), 1u) : rd_field(base, qaq_v_field(r1b, 1, i1, d, D), 1u);
+  }
   if (slot < n32) {
     uint32_t f = side == 0 ? rd_field(base, qaq_k_field(r2, 2, slot, d, D), 3u)
                            : rd_field(base, qaq_v_field(r2, 2, slot, d, D), 3u);
@@ -58,10 +62,10 @@ __device__ __forceinline__ uint32_t load_code(int side, const uint8_t* base, con
 template <int D>
 __device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, int n_tok, TileLds<D>& L) {
   const int tid = threadIdx.x;
-  const QaqCounts c = qaq_load_counts(v, side, b, h, tile);
-  uint32_t r2, r1, r4, r8;
-  if (side == 0) { QaqKRegions r = qaq_k_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; }
-  else { QaqVRegions r = qaq_v_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; }
+  const QaqCounts c = qaq_load_counts(v, side, b, h, tile, n_tok);
+  uint32_t r2, r1, r4, r8, r1b;
+  if (side == 0) { QaqKRegions r = qaq_k_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; r1b = r.r1b; }
+  else { QaqVRegions r = qaq_v_regions(c, D); r2 = r.r2; r1 = r.r1; r4 = r.r4; r8 = r.r8; r1b = r.r1b; }
   if (tid < n_tok) {
     const int s = tid;
     const size_t gi = qaq_slot_index(v, b, h, tile, s);
@@ -78,7 +82,7 @@ __device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, in
   const uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
   for (int e = tid; e < n_tok * D; e += kThreads) {
     const int pos = e / D, d = e % D;
-    L.stage[pos][d] = (uint8_t)load_code<D>(side, base, c, r2, r1, r4, r8, L.slot_of_pos[pos], d);
+    L.stage[pos][d] = (uint8_t)load_code<D>(side, base, c, r2, r1, r4, r8, r1b, L.slot_of_pos[pos], d);
   }
   __syncthreads();
 }
@@ -110,9 +114,10 @@ struct BuildLds {
   uint32_t mask2[16];                      // value side, per unit of 16 slots of the 2-bit field region: slots whose
                                            // fields are written (bit i = slot 16u+i)
   uint32_t mask4[32];                      // ... per half-unit of 8 slots of the 4-bit region
-  int wave_cnt[4][4];
-  int wave_need[4][4];
-  int wave_free[4][4];
+  uint32_t mask1b[16];                     // ... per unit of 16 slots of the 1-bit tokens' region
+  int wave_cnt[QAQ_NCLASS][4];
+  int wave_need[QAQ_NCLASS][4];
+  int wave_free[QAQ_NCLASS][4];
   float wave_bound[4];
   float wave_bound2[4];
 };
@@ -284,7 +289,7 @@ struct TokenEncoder {
 // Stored code planes of one tile side -> staged bytes (old widths, nothing dropped yet), for
 // the cached tokens whose codes are read again (L.need == 1); whole words / units that hold
 // none of them are not touched.
-template <int D, int MAXO>
+template <int D, int MAXO, bool HAS1>
 __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, BuildLds<D, MAXO>& L) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW, NQ = D / 16, KS = D / 64;
   const int tid = threadIdx.x;
@@ -323,6 +328,19 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
       const uint32_t w = *(const uint32_t*)(base + r.r8 + 4u * (uint32_t)it);
       L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] = w ^ 0x80808080u;
     }
+    for (int it = tid; HAS1 && it < c.n1 * (D / 32); it += kThreads) {
+      const int i1 = it / (D / 32), jj = it % (D / 32);
+      const int pos = L.pos_old[c.first1() + i1];
+      if (L.need[pos] != 1) continue;
+      const uint32_t w = *(const uint32_t*)(base + r.r1b + 4u * (uint32_t)it);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int q = 2 * jj + hh;
+        uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) row[v] = (w >> (4 * hh + v)) & 0x01010101u;
+      }
+    }
   }
   // (value side: unpack_moved_v)
 }
@@ -331,7 +349,7 @@ __device__ void unpack_tile(int side, const uint8_t* base, const QaqCounts& c, B
 // positions (L.freeslot) and the slots they had (L.kept, reused); a work item is (token, four
 // channels), and every code is read with the per-element accessor of the layout -- a tile in
 // a decode step moves a handful of tokens, far fewer than its units hold.
-template <int D, int MAXO>
+template <int D, int MAXO, bool HAS1>
 __device__ void unpack_moved_v(const uint8_t* base, const QaqCounts& c, int n_moved, BuildLds<D, MAXO>& L) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW;
   const QaqVRegions r = qaq_v_regions(c, D);
@@ -340,7 +358,7 @@ __device__ void unpack_moved_v(const uint8_t* base, const QaqCounts& c, int n_mo
     const int pos = L.freeslot[m], slot = L.kept[m];
     uint32_t w = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) w |= load_code<D>(1, base, c, r.r2, r.r1, r.r4, r.r8, slot, 4 * c4 + k) << (8 * k);
+    for (int k = 0; k < 4; ++k) w |= load_code<D, HAS1>(1, base, c, r.r2, r.r1, r.r4, r.r8, r.r1b, slot, 4 * c4 + k) << (8 * k);
     L.stage[pos * SROW + c4] = w;
   }
 }
@@ -349,7 +367,7 @@ __device__ void unpack_moved_v(const uint8_t* base, const QaqCounts& c, int n_mo
 // narrow drop their low bits here (the coarser grid's segments contain the finer one's).
 // c0 = the class counts the tile had before (all zero for a tile that did not exist): a
 // word whose tokens all keep slot and width, in a region that has not moved, is left alone.
-template <int D, int MAXO>
+template <int D, int MAXO, bool HAS1>
 __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D, MAXO>& L) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW, NQ = D / 16, KS = D / 64;
   const int tid = threadIdx.x;
@@ -403,6 +421,23 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
       const int pos = L.pos_of_slot[n32 + c.n4 + i8];
       if (same8 && (L.shf[pos] & kKeptFlag)) continue;
       *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] ^ 0x80808080u;
+    }
+    const bool same1b = same8 && c0.n8 == c.n8;           // then r1b has not moved either
+    for (int it = tid; HAS1 && it < c.n1 * (D / 32); it += kThreads) {
+      const int i1 = it / (D / 32), jj = it % (D / 32);
+      const int pos = L.pos_of_slot[c.first1() + i1];
+      const int f = L.shf[pos];
+      if (same1b && (f & kKeptFlag)) continue;
+      const int sh = f & 7;
+      uint32_t w = 0;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int q = 2 * jj + hh;
+        const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) w |= ((row[v] >> sh) & 0x01010101u) << (4 * hh + v);
+      }
+      *(uint32_t*)(base + r.r1b + 4u * (uint32_t)it) = w;
     }
     return;
   }
@@ -488,6 +523,33 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
     if (same8 && (L.shf[pos] & kKeptFlag)) continue;
     *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
   }
+  for (int it = tid; HAS1 && it < ((c.n1 + 15) / 16) * (D / 8); it += kThreads) {
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int c4 = 4 * (2 * cgp + hh) + n4;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        uint32_t w[4], t[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int i1 = 16 * u + 4 * v + j;
+          w[j] = 0;
+          if (i1 < c.n1) {
+            const int pos = L.pos_of_slot[c.first1() + i1];
+            w[j] = (L.stage[pos * SROW + c4] >> (L.shf[pos] & 7)) & 0x01010101u;
+          }
+        }
+        transpose4(w, t);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] |= t[k] << (4 * hh + v);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *(uint32_t*)(base + r.r1b + (uint32_t)u * (2 * D) + 4u * (uint32_t)((4 * n4 + k) * (D / 32) + cgp)) = o[k];
+  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -497,7 +559,7 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
 // into the words as they are stored (read-modify-write; a word of a unit that did not exist,
 // or whose region has moved, starts from zero -- then the masks hold all its slots).  Fields
 // of slots past the end of a region are left as they are: no reader looks at them.
-template <int D, int MAXO>
+template <int D, int MAXO, bool HAS1>
 __device__ void pack_masked_v(uint8_t* base, const QaqCounts& c, const QaqCounts& c0, const BuildLds<D, MAXO>& L) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW;
   const int tid = threadIdx.x;
@@ -581,6 +643,32 @@ __device__ void pack_masked_v(uint8_t* base, const QaqCounts& c, const QaqCounts
     if (same8 && (L.shf[pos] & kKeptFlag)) continue;
     *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
   }
+  const bool same1b = same8 && c0.n8 == c.n8;
+  const int units1b_old = same1b ? (c0.n1 + 15) / 16 : 0;
+  for (int it = tid; HAS1 && it < ((c.n1 + 15) / 16) * (D / 8); it += kThreads) {
+    const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+    uint32_t m = L.mask1b[u];
+    if (!m) continue;
+    uint32_t* wp = (uint32_t*)(base + r.r1b + (uint32_t)u * (2 * D)) + (4 * n4) * (D / 32) + cgp;
+    uint32_t o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) o[k] = u < units1b_old ? wp[k * (D / 32)] : 0u;
+    while (m) {
+      const int i = __ffs(m) - 1;
+      m &= m - 1;
+      const int pos = L.pos_of_slot[c.first1() + 16 * u + i];
+      const int sh = L.shf[pos] & 7;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const uint32_t w = (L.stage[pos * SROW + 4 * (2 * cgp + hh) + n4] >> sh) & 0x01010101u;
+        const int bp = 8 * (i & 3) + 4 * hh + (i >> 2);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(1u << bp)) | (((w >> (8 * k)) & 1u) << bp);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wp[k * (D / 32)] = o[k];
+  }
 }
 
 // ---------------------------------------------------------------------------------
@@ -594,9 +682,12 @@ __device__ __forceinline__ void count_widenings(const QaqView& v, bool wider, bo
               (unsigned int)__popcll(bal));
 }
 
-template <int D, bool ONE>
+// HAS1: the width set contains 1 (five classes); without it the fifth class costs nothing.
+template <int D, bool ONE, bool HAS1>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   constexpr int MAXO = ONE ? 2 : QAQ_MAX_NO2;
+  constexpr int NC = HAS1 ? QAQ_NCLASS : 4;
+  auto bits_at = [](const QaqCounts& c, int s) { return HAS1 ? c.bits_of_slot(s) : c.bits_of_slot4(s); };
   __shared__ BuildLds<D, MAXO> L;
   constexpr int SROW = BuildLds<D, MAXO>::SROW;
 
@@ -629,13 +720,14 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   // touched at all), so that a rebuild costs two dependent round trips to memory, not three
   uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
   QaqCounts c_old;
-  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = 0;
+  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = c_old.n1 = 0;
   int pos_old = 0;
   uint32_t mm_old = 0;
   uint8_t oi_old[MAXO];
   uint16_t ov_old[MAXO];
   if (n_before > 0) {
-    c_old = qaq_load_counts(v, side, b, h, tile);
+    c_old = qaq_load_counts(v, side, b, h, tile, n_before);
+    if (!HAS1) c_old.n1 = 0;
     if (tid < n_before) {
       const size_t gi = qaq_slot_index(v, b, h, tile, tid);
       pos_old = v.perm[side][gi];
@@ -684,7 +776,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     L.pos_of_slot[tid] = (uint16_t)pos_old;
     L.pos_old[tid] = (uint16_t)pos_old;
     L.slot_of_pos[pos_old] = (uint16_t)tid;
-    L.bits_old[pos_old] = (uint8_t)c_old.bits_of_slot(tid);
+    L.bits_old[pos_old] = (uint8_t)bits_at(c_old, tid);
 #pragma unroll
     for (int k = 0; k < MAXO; ++k)
       if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
@@ -876,26 +968,28 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   // is stored for the tokens that stay is not written again.
   const int cls = tid < n_after ? qaq_class_of_bits(L.bits_new[tid]) : -1;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < NC; ++c) {
     const unsigned long long bal = __ballot(cls == c);
     if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
   }
   L.kept[tid] = 0;
   if (tid < 32) L.mask4[tid] = 0;
+  if (HAS1 && tid < 16) L.mask1b[tid] = 0;
   __syncthreads();
   QaqCounts cn;
   {
-    int n[4];
+    int n[QAQ_NCLASS];
+    n[QC1] = 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
-    cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8];
+    for (int c = 0; c < NC; ++c) n[c] = L.wave_cnt[c][0] + L.wave_cnt[c][1] + L.wave_cnt[c][2] + L.wave_cnt[c][3];
+    cn.n3 = n[QC3]; cn.n2 = n[QC2]; cn.n4 = n[QC4]; cn.n8 = n[QC8]; cn.n1 = n[QC1];
   }
   int old_slot = -1;              // cached tokens: the slot held so far
   if (n_before == 0) {
     // nothing cached: a plain stable counting sort (rank inside the wavefront + wavefront offsets)
     int my_rank = 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const unsigned long long bal = __ballot(cls == c);
       if (cls == c) my_rank = __popcll(bal & ((1ull << lane) - 1ull));
     }
@@ -912,18 +1006,17 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     bool keep = false;
     if (was_cached && cls == qaq_class_of_bits(L.bits_old[tid])) {
       const int lo = cn.start(cls);
-      const int cnt = cls == QC3 ? cn.n3 : cls == QC2 ? cn.n2 : cls == QC4 ? cn.n4 : cn.n8;
-      keep = old_slot >= lo && old_slot < lo + cnt;
+      keep = old_slot >= lo && old_slot < lo + cn.count(cls);
     }
     if (keep) L.kept[old_slot] = 1;
     __syncthreads();
     // ranks: of the tokens that need a slot (by position), of the free slots (by slot)
     const bool need = cls >= 0 && !keep;
-    const int slot_cls = tid < n_after ? qaq_class_of_bits(cn.bits_of_slot(tid)) : -1;   // class owning slot `tid`
+    const int slot_cls = tid < n_after ? qaq_class_of_bits(bits_at(cn, tid)) : -1;   // class owning slot `tid`
     const bool is_free = slot_cls >= 0 && !L.kept[tid];
     int need_rank = 0, free_rank = 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const unsigned long long bn = __ballot(need && cls == c);
       const unsigned long long bf = __ballot(is_free && slot_cls == c);
       if (lane == 0) { L.wave_need[c][wave] = __popcll(bn); L.wave_free[c][wave] = __popcll(bf); }
@@ -972,15 +1065,18 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       same4 = had && n32 == n32o && r.r4 == r0.r4;
       same8 = same4 && c_old.n4 == cn.n4 && r.r8 == r0.r8;
     }
+    const bool same1b = same8 && c_old.n8 == cn.n8;
     auto written = [&](int pos, int c) {
-      return !(L.shf[pos] & kKeptFlag) || (c == QC3 && !same1) || (c == QC4 && !same4) || (c == QC8 && !same8);
+      return !(L.shf[pos] & kKeptFlag) || (c == QC3 && !same1) || (c == QC4 && !same4) || (c == QC8 && !same8) ||
+             (HAS1 && c == QC1 && !same1b);
     };
     if (side == 1 && had) {
       // by slot of the new layout
-      const bool wr = tid < n_after && written(L.pos_of_slot[tid], qaq_class_of_bits(cn.bits_of_slot(tid)));
+      const bool wr = tid < n_after && written(L.pos_of_slot[tid], qaq_class_of_bits(bits_at(cn, tid)));
       const unsigned long long bal = __ballot(wr && tid < n32);
       if (lane < 4) L.mask2[4 * wave + lane] = (uint32_t)(bal >> (16 * lane)) & 0xffffu;
       if (wr && tid >= n32 && tid < n32 + cn.n4) atomicOr(&L.mask4[(tid - n32) >> 3], 1u << ((tid - n32) & 7));
+      if (HAS1 && wr && tid >= cn.first1()) atomicOr(&L.mask1b[(tid - cn.first1()) >> 4], 1u << ((tid - cn.first1()) & 15));
     }
     // by position
     int nd = 0;
@@ -1001,8 +1097,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     }
     __syncthreads();
     if (had) {
-      if (side == 0) unpack_tile<D, MAXO>(side, base, c_old, L);
-      else unpack_moved_v<D, MAXO>(base, c_old, n_moved, L);
+      if (side == 0) unpack_tile<D, MAXO, HAS1>(side, base, c_old, L);
+      else unpack_moved_v<D, MAXO, HAS1>(base, c_old, n_moved, L);
       __syncthreads();
     }
   }
@@ -1029,8 +1125,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
           make_float2(fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3])),
                       fminf(fminf(L.wave_bound2[0], L.wave_bound2[1]), fminf(L.wave_bound2[2], L.wave_bound2[3])));
   }
-  if (side == 1 && n_before > 0) pack_masked_v<D, MAXO>(base, cn, c_old, L);
-  else pack_tile<D, MAXO>(side, base, cn, c_old, L);
+  if (side == 1 && n_before > 0) pack_masked_v<D, MAXO, HAS1>(base, cn, c_old, L);
+  else pack_tile<D, MAXO, HAS1>(side, base, cn, c_old, L);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1157,31 +1253,33 @@ __global__ __launch_bounds__(kThreads) void k_dequant(QaqDequantArgs a) {
 
 // ---------------------------------------------------------------------------------
 // Accounting.
-// statbuf: [0..3] hist K (2,3,4,8), [4..7] hist V, [8] layout code bytes, [9] meta bytes
+// statbuf: [0..3] hist K (2,3,4,8), [4..7] hist V, [8] layout code bytes, [9] meta bytes,
+// [10], [11] 1-bit token-heads K, V
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
-  __shared__ unsigned long long acc[10];
+  __shared__ unsigned long long acc[12];
   const int tid = threadIdx.x;
-  if (tid < 10) acc[tid] = 0;
+  if (tid < 12) acc[tid] = 0;
   __syncthreads();
   const int ntile = (len + QAQ_TT - 1) / QAQ_TT;
   const long long total = (long long)v.B * v.Hkv * ntile * 2;
-  unsigned long long loc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long loc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   for (long long i = (long long)blockIdx.x * kThreads + tid; i < total; i += (long long)gridDim.x * kThreads) {
     const int side = (int)(i & 1);
     const long long j = i >> 1;
     const int tile = (int)(j % ntile);
     const int bh = (int)(j / ntile);
-    const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile);
+    const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile, min(len - tile * QAQ_TT, QAQ_TT));
     loc[side * 4 + 0] += c.n2; loc[side * 4 + 1] += c.n3; loc[side * 4 + 2] += c.n4; loc[side * 4 + 3] += c.n8;
+    loc[10 + side] += c.n1;
     // bytes a scan reads: key records one by one, value planes in whole units
-    loc[8] += side == 0 ? (unsigned long long)c.n32() * (v.D / 4) + c.n3 * (v.D / 8) + c.n4 * (v.D / 2) + c.n8 * v.D
+    loc[8] += side == 0 ? (unsigned long long)c.n32() * (v.D / 4) + (c.n3 + c.n1) * (v.D / 8) + c.n4 * (v.D / 2) + c.n8 * v.D
                         : qaq_v_regions(c, v.D).end;
     loc[9] += (unsigned long long)c.total() * (4 + 1 + 3 * v.no2);
   }
-  for (int k = 0; k < 10; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
+  for (int k = 0; k < 12; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
   __syncthreads();
-  if (tid < 10 && acc[tid]) atomicAdd((unsigned long long*)&v.statbuf[tid], acc[tid]);
+  if (tid < 12 && acc[tid]) atomicAdd((unsigned long long*)&v.statbuf[tid], acc[tid]);
 }
 
 __global__ void k_init(QaqView v) {
@@ -1207,11 +1305,21 @@ hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
   dim3 grid(a.v.B * a.v.Hkv, ntiles, 2);
   const bool one = a.v.no2 == 2;
   if (a.v.D == 128) {
-    if (one) hipLaunchKernelGGL((k_build<128, true>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((k_build<128, false>), grid, dim3(kThreads), 0, s, a);
+    if (a.v.has1) {
+      if (one) hipLaunchKernelGGL((k_build<128, true, true>), grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL((k_build<128, false, true>), grid, dim3(kThreads), 0, s, a);
+    } else {
+      if (one) hipLaunchKernelGGL((k_build<128, true, false>), grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL((k_build<128, false, false>), grid, dim3(kThreads), 0, s, a);
+    }
   } else {
-    if (one) hipLaunchKernelGGL((k_build<64, true>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((k_build<64, false>), grid, dim3(kThreads), 0, s, a);
+    if (a.v.has1) {
+      if (one) hipLaunchKernelGGL((k_build<64, true, true>), grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL((k_build<64, false, true>), grid, dim3(kThreads), 0, s, a);
+    } else {
+      if (one) hipLaunchKernelGGL((k_build<64, true, false>), grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL((k_build<64, false, false>), grid, dim3(kThreads), 0, s, a);
+    }
   }
   return hipGetLastError();
 }

@@ -22,7 +22,7 @@ class Config(C.Structure):
     _fields_ = [
         ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
         ("head_dim", C.c_int32), ("max_tokens", C.c_int32),
-        ("bit_set", C.c_int32 * 4), ("n_bits", C.c_int32),
+        ("bit_set", C.c_int32 * 5), ("n_bits", C.c_int32),
         ("outlier_frac", C.c_float), ("n_outlier_per_side", C.c_int32),
         ("window", C.c_int32), ("window_fp16", C.c_int32),
         ("sigma_s_max", C.c_double), ("sigma_x_max", C.c_double),
@@ -32,7 +32,7 @@ class Config(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [
-        ("tokens", C.c_int64), ("hist_k", C.c_int64 * 4), ("hist_v", C.c_int64 * 4),
+        ("tokens", C.c_int64), ("hist_k", C.c_int64 * 5), ("hist_v", C.c_int64 * 5),
         ("code_bytes", C.c_int64), ("layout_code_bytes", C.c_int64), ("meta_bytes", C.c_int64),
         ("fp16_bytes", C.c_int64), ("refused_upgrades", C.c_int64), ("served_upgrades", C.c_int64),
     ]

@@ -25,7 +25,7 @@ def test_random_run(seed):
     steps = int(rng.integers(3, 8))
     window = int(rng.integers(1, 7))
     n_o = int(rng.choice([0, 1, 1, 2, 4]))
-    sets = [(2, 3, 4, 8), (2, 3, 4, 8), (2, 4, 8), (3, 8), (2, 3), (4,), (2, 8)]
+    sets = [(2, 3, 4, 8), (2, 3, 4, 8), (2, 4, 8), (3, 8), (2, 3), (4,), (2, 8), (1, 2, 3, 4, 8), (1, 2, 3, 4, 8), (1, 3), (1, 4, 8), (1,)]
     bit_set = sets[int(rng.integers(len(sets)))]
     sh = W.shape(3, batch=int(rng.choice([1, 2])), n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D, context=T0)
     kw = dict(max_tokens=T0 + steps, window=window, n_outlier_per_side=n_o, bit_set=bit_set,
