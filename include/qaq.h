@@ -255,11 +255,12 @@ int qaq_outliers_per_side(const qaq_config* cfg);
 const char* qaq_last_error(void);
 
 /* Host-only helpers for layout tests (no device access): where the device layout keeps
- * the bf-bit field (bf = 1, 2, 4, 8) of token `idx` of its width region, channel d, for
- * a tile side with the given class counts: byte offset of the 32-bit word from the start
- * of the tile side, bit position inside it, and the end of the last region.  And the
- * bytes reserved per tile side. */
-int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8,
+ * the bf-bit field (bf = 2, 4, 8; 1 = the low bit of a 3-bit token; 0 = the code of a
+ * 1-bit token) of token `idx` of its region, channel d, for a tile side with the given
+ * class counts: byte offset of the 32-bit word from the start of the tile side, bit
+ * position inside it, and the end of the last region.  And the bytes reserved per tile
+ * side. */
+int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8, int32_t n1,
                     int32_t bf, int32_t idx, int32_t d, uint32_t* byte_off, int32_t* shift,
                     uint32_t* region_end);
 uint32_t qaq_debug_tile_capacity(int32_t side, int32_t D);

@@ -557,20 +557,21 @@ int qaq_stream_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stre
 // Host-only view of the code layout, for layout tests: where the field of width
 // `bf` (1, 2, 4 or 8) of token `idx` of its region, channel d, is stored, relative to the
 // start of the tile side; the region offsets follow from the class counts.
-int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8, int32_t bf,
+int qaq_debug_field(int32_t side, int32_t D, int32_t n3, int32_t n2, int32_t n4, int32_t n8, int32_t n1, int32_t bf,
                     int32_t idx, int32_t d, uint32_t* byte_off, int32_t* shift, uint32_t* region_end) {
   if ((D != 64 && D != 128) || d < 0 || d >= D || idx < 0) return fail(QAQ_ERR_INVALID_ARG, "bad layout query");
-  QaqCounts c; c.n3 = n3; c.n2 = n2; c.n4 = n4; c.n8 = n8;
+  QaqCounts c; c.n3 = n3; c.n2 = n2; c.n4 = n4; c.n8 = n8; c.n1 = n1;
   QaqFieldPos p;
+  const int fw = bf == 0 ? 1 : bf;      // field width; bf 0 = the region of the 1-bit tokens
   if (side == 0) {
     const QaqKRegions r = qaq_k_regions(c, D);
-    const uint32_t ro = bf == 2 ? r.r2 : bf == 1 ? r.r1 : bf == 4 ? r.r4 : r.r8;
-    p = qaq_k_field(ro, bf, idx, d, D);
+    const uint32_t ro = bf == 2 ? r.r2 : bf == 1 ? r.r1 : bf == 4 ? r.r4 : bf == 8 ? r.r8 : r.r1b;
+    p = qaq_k_field(ro, fw, idx, d, D);
     *region_end = r.end;
   } else {
     const QaqVRegions r = qaq_v_regions(c, D);
     if (bf == 8) { p.byte_off = (r.r8 + (uint32_t)idx * D + d) & ~3u; p.shift = 8 * (d & 3); }
-    else p = qaq_v_field(bf == 2 ? r.r2 : bf == 1 ? r.r1 : r.r4, bf, idx, d, D);
+    else p = qaq_v_field(bf == 2 ? r.r2 : bf == 1 ? r.r1 : bf == 4 ? r.r4 : r.r1b, fw, idx, d, D);
     *region_end = r.end;
   }
   *byte_off = p.byte_off;

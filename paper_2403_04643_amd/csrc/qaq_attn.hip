@@ -280,6 +280,7 @@ struct KeyRegs {
   uint32_t k8[2];
   uint32_t mm, pos;
   Outl<NO2> o;
+  template <bool H1>
   __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& ck, int tid) {
     c = ck;
     n_tok = min(len - tile * QAQ_TT, QAQ_TT);
@@ -296,7 +297,9 @@ struct KeyRegs {
     const bool is3 = tid < c.n3, is23 = tid < n32, is4 = !is23 && tid < n32 + c.n4;
     const uint32_t rec4 = rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
     const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : is4 ? rec4 : 0u;
-    const uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    if (H1 && c.n1 > 0 && tid >= c.first1())          // a 1-bit token's record (lanes past the tile's tokens: the last one)
+      off_b0 = rK.r1b + (uint32_t)min(tid - c.first1(), c.n1 - 1) * (uint32_t)KRec<D, 1>::REC;
     const uint32_t off_b1 = is4 ? rec4 + 4u * HALF + 2u * HALF : 0u;
     const gbytes_t ubase = uniform_ptr(base);
     gload_dwords<HALF>(ubase + off_a, ka);
@@ -321,6 +324,9 @@ struct ValRegs {
   uint32_t mm, pos;
   Outl<NO2> o;
   uint32_t vw2[4][CGW], vw1[4];
+  // vw1: blocks (of 4 units) of the 3-bit tokens' low planes from entry 0 up; with a width set
+  // that has 1, blocks of the 1-bit tokens' units from entry 3 down as far as entries are free
+  template <bool H1>
   __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& cv, int tid, int wave, int nn, int g) {
     c = cv;
     const int n_tok = min(len - tile * QAQ_TT, QAQ_TT);
@@ -333,13 +339,21 @@ struct ValRegs {
     o.load(v, 1, gi0, slot, v.no2);
     const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);
+    for (int blk = 0; blk < 4; ++blk)
+      if (!H1 || blk * 64 < c.n32()) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);   // (blocks past the region are not used)
     const QaqVRegions rV = qaq_v_regions(c, D);
     const int nu1 = (c.n3 + 15) >> 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
       if (blk * 4 < nu1)
         vw1[blk] = *(const uint32_t*)(base + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+    if (H1) {
+      const int nb3 = (nu1 + 3) >> 2, nu1b = (c.n1 + 15) >> 4;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+        if (blk * 4 < nu1b && 3 - blk >= nb3)
+          vw1[3 - blk] = *(const uint32_t*)(base + rV.r1b + (uint32_t)min(blk * 4 + g, nu1b - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+    }
   }
 };
 
@@ -408,8 +422,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   };
   KeyRegs<D, NO2> kr;
   ValRegs<D, NO2> vr;
-  kr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
-  vr.load(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+  kr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
+  vr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
   int qexp = 0;
@@ -544,9 +558,11 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         if (tid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
       }
       if (H1 && cK.n1 > 0 && w1 > first1K) {
-        // 1-bit keys (only with a width set that has 1): the record is fetched here
+        // 1-bit keys (only with a width set that has 1): the record came with the tile, where
+        // a 3-bit token has its low bits
         uint32_t k1[KRec<D, 1>::RDW];
-        KRec<D, 1>::load(baseK + rK.r1b, min(max(tid - first1K, 0), cK.n1 - 1), k1);
+#pragma unroll
+        for (int i = 0; i < KRec<D, 1>::RDW; ++i) k1[i] = kr.kb[i];
         const float d1 = real_of(k_contract<D, 1>(k1, abase1));
         if (tid >= first1K) dotq = d1;
       }
@@ -557,7 +573,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       }
     }
     // the key registers are free: request the next tile's keys
-    if (tile + 1 < tile_end) kr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid);
+    if (tile + 1 < tile_end) kr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid);
 
     vmax = wave_max(vmax);
     if (lane == 0) S.red[8 + wave] = vmax;
@@ -681,13 +697,20 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         cv[j] = mma(wa, spread<4>(pr, 0), cv[j]);
       }
     }
-    for (int blk = 0; H1 && blk * 64 < cV.n1; ++blk) {     // 1-bit tokens: units in the format of the 1-bit fields
-      const int nu = (cV.n1 + 15) >> 4;
-      const uint32_t w1b = *(const uint32_t*)(baseV + rV.r1b + (uint32_t)min(blk * 4 + g, nu - 1) * (2u * D) +
-                                              (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
-      const v4i wa = *(const v4i*)(wb1b + 64 * blk);
+    if (H1) {                                              // 1-bit tokens: units in the format of the 1-bit fields
+      const int nu = (cV.n1 + 15) >> 4, nb3 = (((cV.n3 + 15) >> 4) + 3) >> 2;
 #pragma unroll
-      for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&w1b, (CGW * wave + j) & 1), cv[j]);
+      for (int blk = 0; blk < 4; ++blk) {
+        if (blk * 64 < cV.n1) {
+          uint32_t w1b = vr.vw1[3 - blk];                  // came with the tile if the entry was free, else fetched here
+          if (3 - blk < nb3)
+            w1b = *(const uint32_t*)(baseV + rV.r1b + (uint32_t)min(blk * 4 + g, nu - 1) * (2u * D) +
+                                     (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+          const v4i wa = *(const v4i*)(wb1b + 64 * blk);
+#pragma unroll
+          for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&w1b, (CGW * wave + j) & 1), cv[j]);
+        }
+      }
     }
     // 8-bit codes: token-major bytes, plain fp32 multiply-add; this wavefront's D/4 channels,
     // lane = (token sub-index, 4 channels)
@@ -723,7 +746,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       }
     }
     // the value registers are free: request the next tile's values
-    if (tile + 1 < tile_end) vr.load(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
+    if (tile + 1 < tile_end) vr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
   }
 
   // ---- one partial per workgroup -----------------------------------------------------------------

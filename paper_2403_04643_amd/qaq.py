@@ -66,7 +66,7 @@ SIGNATURES = {
     "qaq_stats": (C.c_int, [_vp, C.POINTER(Stats), _vp]),
     "qaq_outliers_per_side": (C.c_int, [C.POINTER(Config)]),
     "qaq_last_error": (C.c_char_p, []),
-    "qaq_debug_field": (C.c_int, [_i32] * 9 + [C.POINTER(C.c_uint32), C.POINTER(C.c_int32), C.POINTER(C.c_uint32)]),
+    "qaq_debug_field": (C.c_int, [_i32] * 10 + [C.POINTER(C.c_uint32), C.POINTER(C.c_int32), C.POINTER(C.c_uint32)]),
     "qaq_debug_tile_capacity": (C.c_uint32, [_i32, _i32]),
 }
 
@@ -355,6 +355,6 @@ def debug_field(side, D, counts, bf, idx, d):
     """Host-only layout query: (byte offset of the 32-bit word, bit shift, end of regions)."""
     lib = load()
     off, sh, end = C.c_uint32(), C.c_int32(), C.c_uint32()
-    n3, n2, n4, n8 = counts
-    _check(lib.qaq_debug_field(side, D, n3, n2, n4, n8, bf, idx, d, C.byref(off), C.byref(sh), C.byref(end)))
+    n3, n2, n4, n8, n1 = counts
+    _check(lib.qaq_debug_field(side, D, n3, n2, n4, n8, n1, bf, idx, d, C.byref(off), C.byref(sh), C.byref(end)))
     return off.value, sh.value, end.value

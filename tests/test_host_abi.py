@@ -35,7 +35,8 @@ def test_config_validation_without_gpu():
     n = lib.qaq_arena_bytes(C.byref(good))
     assert n > 2 * 2 * 8 * 1024 * 128          # at least the 8-bit codes of K and V
     assert lib.qaq_outliers_per_side(C.byref(good)) == 1
-    for kw in (dict(head_dim=96), dict(bit_set=(2, 5)), dict(bit_set=(3, 2)), dict(window=0),
+    assert lib.qaq_arena_bytes(C.byref(qaq.make_config(2, 8, 8, 128, 1000, [0.01] * 8, bit_set=(1, 2, 3, 4, 8)))) == n
+    for kw in (dict(head_dim=96), dict(bit_set=(2, 5)), dict(bit_set=(0, 2)), dict(bit_set=(3, 2)), dict(window=0),
                dict(n_outlier_per_side=5), dict(sigma_s_max=0.0), dict(n_q_heads=7)):
         args = dict(batch=2, n_q_heads=8, n_kv_heads=8, head_dim=128, max_tokens=1000, qnorm2=[0.01] * 8)
         args.update(kw)
@@ -62,12 +63,15 @@ def test_layout_is_a_bijection(side, D):
     documented padding."""
     rng = np.random.default_rng(D + side)
     cap = qaq.load().qaq_debug_tile_capacity(side, D)
-    cases = [(256, 0, 0, 0), (0, 256, 0, 0), (0, 0, 256, 0), (0, 0, 0, 256), (1, 1, 1, 1), (17, 9, 3, 33)]
-    for _ in range(4):
-        cut = np.sort(rng.integers(0, 257, 3))
-        cases.append((cut[0], cut[1] - cut[0], cut[2] - cut[1], 256 - cut[2]))
-    for n3, n2, n4, n8 in cases:
-        counts = (int(n3), int(n2), int(n4), int(n8))
+    cases = [(256, 0, 0, 0, 0), (0, 256, 0, 0, 0), (0, 0, 256, 0, 0), (0, 0, 0, 256, 0), (0, 0, 0, 0, 256),
+             (1, 1, 1, 1, 1), (17, 9, 3, 33, 21), (1, 1, 1, 252, 1)]
+    for k in range(6):
+        cut = np.sort(rng.integers(0, 257, 4))
+        if k < 3:
+            cut[3] = 256                      # no 1-bit tokens: the layout of the paper's width set
+        cases.append((cut[0], cut[1] - cut[0], cut[2] - cut[1], cut[3] - cut[2], 256 - cut[3]))
+    for n3, n2, n4, n8, n1 in cases:
+        counts = (int(n3), int(n2), int(n4), int(n8), int(n1))
         used = np.zeros(cap * 8, dtype=np.uint8)
         end = None
         def mark(bf, idx, width_mask_bits):
@@ -87,10 +91,12 @@ def test_layout_is_a_bijection(side, D):
             mark(4, s, 4)
         for s in range(n8):
             mark(8, s, 8)
-        total_bits = D * (3 * n3 + 2 * n2 + 4 * n4 + 8 * n8)
+        for s in range(n1):
+            mark(0, s, 1)
+        total_bits = D * (3 * n3 + 2 * n2 + 4 * n4 + 8 * n8 + n1)
         assert used.sum() == total_bits
         if end is not None:
             pad = end * 8 - total_bits
-            # at most one partly filled group per region: keys 15 records of D/4 + D/8 + D/2 bytes,
-            # values 15/16 of a 4D- and of a 2D-byte unit and 7/8 of a 4D-byte half-unit
-            assert pad <= 8 * (14 * D)
+            # at most one partly filled group per region: keys 15 records of D/4 + D/8 + D/2 + D/8
+            # bytes, values 15/16 of a 4D- and of two 2D-byte units and 7/8 of a 4D-byte half-unit
+            assert pad <= 8 * (15 * D)

@@ -181,7 +181,7 @@ def _textbook_uniform(x, B):
     return c, lo + (c + 0.5) * w
 
 
-@pytest.mark.parametrize("B", [2, 3, 4, 8])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 8])
 def test_uniform_special_case_matches_textbook(B):
     """alpha = 0 and one width for all tokens is the paper's "uniform" comparison
     method (Section 5.3): an ordinary per-row min/max quantizer."""
@@ -204,7 +204,7 @@ def test_uniform_special_case_matches_textbook(B):
     np.testing.assert_allclose(xh[safe], xt[safe], rtol=2e-6, atol=2e-6)
 
 
-@pytest.mark.parametrize("B", [2, 3, 4, 8])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 8])
 def test_error_bound_and_uniform_error_law(B):
     """|x - x^| <= Delta = range / 2^(B+1), and on dense data the error is uniform
     on [-Delta, Delta], std Delta/sqrt(3) (Section 4.1)."""
@@ -235,7 +235,7 @@ def test_error_bound_halves_per_bit():
     om = O.outlier_split(x, 1)
     mn, mx = O.token_range(x, om)
     prev = None
-    for B in (2, 3, 4, 8):
+    for B in (1, 2, 3, 4, 8):
         bits = np.full(300, B)
         xh = O.dequantize(O.encode(x, mn, mx, bits), mn, mx, bits, om, x)
         worst = np.abs(xh - x.astype(F32)).max(1) / O.range_f32(mn, mx)
@@ -306,6 +306,26 @@ def test_outliers_shrink_range_and_restore_exactly():
     assert O.outliers_per_side(0.0, 128) == 0 and O.outliers_per_side(0.05, 128) == 4
 
 
+def test_one_bit_is_a_comparison_with_the_midpoint():
+    """Width 1 (a variant; Section 4.1's quantizer with 2 levels): the code says on which
+    side of the middle of [min, max] the value lies, the reconstruction is the quarter point
+    of that side.  Written out on exactly representable numbers."""
+    x = np.array([[0.0, 0.25, 0.5, 0.75, 0.99, 1.0, 1.5, 2.0, -3.0, 5.0] + [1.0] * 54], F16)
+    om = O.outlier_split(x, 1)
+    assert om[0, 8] and om[0, 9] and om.sum() == 2       # -3 and 5 leave; the rest spans [0, 2]
+    mn, mx = O.token_range(x, om)
+    assert float(mn[0]) == 0.0 and float(mx[0]) == 2.0
+    c = O.encode(x, mn, mx, np.array([1]))
+    np.testing.assert_array_equal(c[0, :10], [0, 0, 0, 0, 0, 1, 1, 1, 0, 1])   # x >= 1 <=> code 1; outliers clamp
+    xh = O.dequantize(c, mn, mx, np.array([1]), om, x)
+    np.testing.assert_array_equal(xh[0, :10], [0.5, 0.5, 0.5, 0.5, 0.5, 1.5, 1.5, 1.5, -3.0, 5.0])
+    assert O.pack_canonical(c[0], 1).shape == (8,)
+    assert O.pack_canonical(c[0], 1)[0] == 0b11100000 and O.pack_canonical(c[0], 1)[1] == 0b11111110
+    # the rules pick it where the range fits twice the threshold
+    r = np.array([0.5, 2.0, 2.0001, 4.0, 100.0], F32)
+    np.testing.assert_array_equal(O.select_bits_key(r, np.float32(1.0), (1, 2, 3, 4, 8)), [1, 1, 2, 2, 8])
+
+
 # ----------------------------------------------------------------- requantize
 def test_requantize_down_equals_direct_quantization():
     """Section 4.2: lower widths are reached from higher ones without the
@@ -320,9 +340,9 @@ def test_requantize_down_equals_direct_quantization():
     om = O.outlier_split(x, 1)
     mn, mx = O.token_range(x, om)
     N = x.shape[0]
-    for hi in (8, 4, 3):
+    for hi in (8, 4, 3, 2):
         ch = O.encode(x, mn, mx, np.full(N, hi))
-        for lo in (4, 3, 2):
+        for lo in (4, 3, 2, 1):
             if lo >= hi:
                 continue
             direct = O.encode(x, mn, mx, np.full(N, lo))
