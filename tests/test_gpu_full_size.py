@@ -69,17 +69,19 @@ def _sample_units(sh, n, seed):
 @pytest.mark.parametrize("cfgno,p_k,p_v", [
     (2, (0.49, 0.50, 0.007, 0.003), (0.89, 0.10, 0.007, 0.003)),   # the benchmark's operating point, plus a few wide tokens
     (5, (0.3, 0.3, 0.3, 0.1), (0.5, 0.3, 0.15, 0.05)),              # 8 query heads per KV head
+    (2, (0.45, 0.03, 0.01, 0.01, 0.5), (0.18, 0.01, 0.005, 0.005, 0.8)),   # width set with 1: the bench's point of that kind
 ])
 def test_full_size_given_widths(cfgno, p_k, p_v):
     sh = W.shape(cfgno)
-    _log(f"full size cfg={cfgno} shape={sh}")
+    _log(f"full size cfg={cfgno} shape={sh} width classes={len(p_k)}")
     K, V = W.make_kv(cfgno, sh)
     rng = np.random.default_rng(97 + cfgno)
-    widths = np.array([2, 3, 4, 8], np.uint8)
+    widths = np.array([2, 3, 4, 8, 1][:len(p_k)], np.uint8)
     bk = rng.choice(widths, size=K.shape[:3], p=p_k)
     bv = rng.choice(widths, size=K.shape[:3], p=p_v)
     qn = np.full(sh.n_kv_heads, 0.01, F32)
-    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context + 1, qn.tolist()))
+    bit_set = tuple(sorted(int(w) for w in widths))
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context + 1, qn.tolist(), bit_set=bit_set))
     gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
     q = W.make_queries(cfgno, sh)[0]
     kn, vn = W.make_new_token(cfgno, sh)
@@ -90,7 +92,7 @@ def test_full_size_given_widths(cfgno, p_k, p_v):
     exV = {k: v.cpu().numpy() for k, v in gc.export_canonical(1).items()}
     worst = 0.0
     for b, h in _sample_units(sh, 5, 11 + cfgno):
-        oc, G = _unit_oracle(sh, qn, b, h)
+        oc, G = _unit_oracle(sh, qn, b, h, bit_set=bit_set)
         oc.append(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], bk[b:b + 1, h:h + 1], bv[b:b + 1, h:h + 1])
         _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"K b={b} h={h}")
         _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"V b={b} h={h}")
