@@ -385,7 +385,13 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   TileLds<D>& S = S_all[P ? chunk : 0];
   const int tid = threadIdx.x & (kThreads - 1), lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 15, g = lane >> 4;
-  const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
+  // Grouped queries, fused form: workgroups are dealt to the eight dies round-robin, so the G
+  // query heads of a KV head, which read the same codes, are given indices that land on one
+  // die (the reads after the first are served by that die's L2): die x takes the x-th eighth
+  // of the (sequence, query head) pairs.
+  int bq = blockIdx.y;
+  if (P && a.G > 1 && (gridDim.y & 7) == 0) bq = (int)(blockIdx.y & 7) * (int)(gridDim.y >> 3) + (int)(blockIdx.y >> 3);
+  const int b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int tile_begin = (int)((long long)chunk * ntile / a.nparts);
   const int tile_end = (int)((long long)(chunk + 1) * ntile / a.nparts);
