@@ -43,6 +43,8 @@ typedef enum {
 
 typedef struct qaq_cache qaq_cache; /* opaque host-side descriptor */
 
+enum { QAQ_WINDOW_FP32 = 0, QAQ_WINDOW_FP16 = 1, QAQ_WINDOW_BF16 = 2 };
+
 typedef struct {
   int32_t batch;          /* B, number of sequences                                   */
   int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                             */
@@ -56,10 +58,11 @@ typedef struct {
                              the paper's experiments use 0.01                        */
   int32_t n_outlier_per_side; /* <0: ceil(outlier_frac/2 * D); 0: none; at most 4     */
   int32_t window;         /* n of the attention window (Section 3.2); 1..8; paper: 5  */
-  int32_t window_fp16;    /* 0: the window keeps its score rows in fp32; 1 (variant): in
-                             fp16, rounded to nearest even when they are stored -- the
-                             predicted score is the maximum of the stored values, the
-                             current step's included                                  */
+  int32_t window_store;   /* how the window keeps its score rows: QAQ_WINDOW_FP32, or
+                             (variants) QAQ_WINDOW_FP16 / QAQ_WINDOW_BF16: rounded to
+                             nearest even when they are stored -- the predicted score is
+                             the maximum of the stored values, the current step's
+                             included                                                 */
   double  sigma_s_max;    /* bound on the std of a score   (Section 4.1, key rule)    */
   double  sigma_x_max;    /* bound on the std of an output (Section 4.1, value rule)  */
   const float* qnorm2;    /* host [n_kv_heads]: statistic of sum_d Q_d^2 used by the key

@@ -232,6 +232,15 @@ def value_threshold(T: int, sigma_x_max: float) -> np.float32:
     return F32(2.0 * math.sqrt(3.0) * sigma_x_max / math.sqrt(T))
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Finite fp32 numbers rounded to bfloat16 (8 significant bits, fp32's exponent range),
+    ties to even, returned as fp32: on the bit pattern, add half a unit of the kept part
+    (one less when the kept part is even) and clear the 16 dropped bits."""
+    u = np.ascontiguousarray(x, dtype=F32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return r.astype(np.uint32).view(F32).reshape(np.shape(x))
+
+
 def window_predict(history: Sequence[np.ndarray], n: int, T: int) -> np.ndarray:
     """Section 3.2 / 4.2 "attention window": predicted score of a token = max of
     its last n observed scores.  history: list of score rows (oldest first), row
@@ -374,6 +383,7 @@ class Config:
     sigma_x_max: float = 1e-2
     qnorm2: Optional[np.ndarray] = None   # [n_kv_heads]
     window_fp16: bool = False             # variant: the window keeps its score rows in fp16
+    window_bf16: bool = False             # variant: ... in bfloat16
 
     def n_o(self) -> int:
         if self.n_outlier_per_side >= 0:
@@ -418,6 +428,8 @@ class OracleCache:
             # as fp16 (round to nearest even); the predicted score is the maximum of the
             # stored values, this step's included.
             row = row.astype(F16)
+        elif cfg.window_bf16:
+            row = round_to_bf16(row)
         self.history.append(row.astype(F32))
         self.history = self.history[-cfg.window:]
 

@@ -71,7 +71,8 @@ bool valid_config(const qaq_config* c, QaqDims* d) {
   d->Tmax = d->NT * QAQ_TT;
   d->no2 = 2 * no;
   d->window = c->window;
-  d->ring_half = c->window_fp16 ? 1 : 0;
+  if (c->window_store < QAQ_WINDOW_FP32 || c->window_store > QAQ_WINDOW_BF16) { fail(QAQ_ERR_INVALID_ARG, "window_store must be 0 (fp32), 1 (fp16) or 2 (bf16)"); return false; }
+  d->ring_half = c->window_store;
   return true;
 }
 

@@ -21,7 +21,7 @@ struct QaqView {
   uint16_t* counts;
   float* vbound;
   float* kthr;
-  void* ring;               // score rows of the window, fp32 or (ring_half) fp16
+  void* ring;               // score rows of the window: fp32, or (ring_half 1) fp16, or (2) bf16
   int ring_half;
   float* partial;
   long long* statbuf;
@@ -33,14 +33,22 @@ struct QaqView {
 
 __host__ __device__ __forceinline__ size_t qaq_bh(const QaqView& v, int b, int h) { return (size_t)b * v.Hkv + h; }
 // The window's rows: value as stored (what the predicted score is taken over), load, store.
+// bf16 of a finite float, round to nearest even: the upper 16 bits after adding half an ulp
+// (one less on an even upper half)
+__device__ __forceinline__ uint16_t qaq_bf16_bits(float s) {
+  const uint32_t u = __float_as_uint(s);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
 __device__ __forceinline__ float qaq_ring_value(const QaqView& v, float s) {
-  return v.ring_half ? __half2float(__float2half_rn(s)) : s;
+  return v.ring_half == 1 ? __half2float(__float2half_rn(s)) : v.ring_half == 2 ? __uint_as_float((uint32_t)qaq_bf16_bits(s) << 16) : s;
 }
 __device__ __forceinline__ float qaq_ring_load(const QaqView& v, size_t i) {
-  return v.ring_half ? __half2float(((const __half*)v.ring)[i]) : ((const float*)v.ring)[i];
+  return v.ring_half == 1 ? __half2float(((const __half*)v.ring)[i])
+       : v.ring_half == 2 ? __uint_as_float((uint32_t)((const uint16_t*)v.ring)[i] << 16) : ((const float*)v.ring)[i];
 }
 __device__ __forceinline__ void qaq_ring_store(const QaqView& v, size_t i, float s) {
-  if (v.ring_half) ((__half*)v.ring)[i] = __float2half_rn(s);
+  if (v.ring_half == 1) ((__half*)v.ring)[i] = __float2half_rn(s);
+  else if (v.ring_half == 2) ((uint16_t*)v.ring)[i] = qaq_bf16_bits(s);
   else ((float*)v.ring)[i] = s;
 }
 __device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, int b, int h, int tile) {

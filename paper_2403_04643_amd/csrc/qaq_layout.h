@@ -164,7 +164,7 @@ QAQ_HD QaqFieldPos qaq_v_field(uint32_t roff, int bf, int idx, int d, int D) {
 // ---- arena carving --------------------------------------------------------------
 struct QaqDims {
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
-  int ring_half;      // the window's rows are fp16
+  int ring_half;      // the window's rows: 0 fp32, 1 fp16, 2 bf16
 };
 
 struct QaqArena {

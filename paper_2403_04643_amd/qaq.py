@@ -24,7 +24,7 @@ class Config(C.Structure):
         ("head_dim", C.c_int32), ("max_tokens", C.c_int32),
         ("bit_set", C.c_int32 * 5), ("n_bits", C.c_int32),
         ("outlier_frac", C.c_float), ("n_outlier_per_side", C.c_int32),
-        ("window", C.c_int32), ("window_fp16", C.c_int32),
+        ("window", C.c_int32), ("window_store", C.c_int32),
         ("sigma_s_max", C.c_double), ("sigma_x_max", C.c_double),
         ("qnorm2", C.POINTER(C.c_float)),
     ]
@@ -102,7 +102,7 @@ def _check(rc: int) -> None:
 
 def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequence[float],
                 bit_set=(2, 3, 4, 8), outlier_frac=0.01, n_outlier_per_side=-1, window=5,
-                sigma_s_max=1e-3, sigma_x_max=1e-2, window_fp16=False):
+                sigma_s_max=1e-3, sigma_x_max=1e-2, window_fp16=False, window_bf16=False):
     cfg = Config()
     cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens = batch, n_q_heads, n_kv_heads, head_dim, max_tokens
     for i, b in enumerate(bit_set):
@@ -111,7 +111,8 @@ def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequ
     cfg.outlier_frac = outlier_frac
     cfg.n_outlier_per_side = n_outlier_per_side
     cfg.window = window
-    cfg.window_fp16 = 1 if window_fp16 else 0
+    assert not (window_fp16 and window_bf16)
+    cfg.window_store = 1 if window_fp16 else 2 if window_bf16 else 0
     cfg.sigma_s_max, cfg.sigma_x_max = sigma_s_max, sigma_x_max
     arr = (C.c_float * len(qnorm2))(*[float(x) for x in qnorm2])
     cfg.qnorm2 = C.cast(arr, C.POINTER(C.c_float))

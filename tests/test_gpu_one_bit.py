@@ -67,14 +67,14 @@ def test_append_requantize_export_dequantize(head_dim, context, n_o):
     _check_attention(oc, gc, q, tag="all one bit")
 
 
-@pytest.mark.parametrize("G,window_fp16", [(1, False), (4, True)])
-def test_decode_steps_with_one_bit_in_the_set(G, window_fp16):
+@pytest.mark.parametrize("G,window_kw", [(1, dict()), (4, dict(window_fp16=True)), (2, dict(window_bf16=True))])
+def test_decode_steps_with_one_bit_in_the_set(G, window_kw):
     sh = W.shape(3, batch=2, n_q_heads=2 * G, n_kv_heads=2, head_dim=128, context=500)
     steps = 14          # crosses into the third tile
     K, V = W.make_kv(3, sh)
     qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
     oc, gc = make_pair(sh, qn, max_tokens=sh.context + steps, window=3, bit_set=SET5,
-                       sigma_s_max=6e-4, sigma_x_max=0.12, window_fp16=window_fp16)
+                       sigma_s_max=6e-4, sigma_x_max=0.12, **window_kw)
     oc.append(K, V); gc.quantize_append(dev(K), dev(V))
     Korig, Vorig = K.copy(), V.copy()
     qs = W.make_queries(3, sh, n=steps)

@@ -163,17 +163,18 @@ def test_append_selected_to_a_partly_filled_tile():
     compare_canonical(oc, gc, "after the append")
 
 
-def test_window_kept_in_fp16():
-    """The variant that keeps the window's score rows in fp16: prompt encoding, separate
-    selection and fused decode steps all take the predicted score over the rounded rows."""
+@pytest.mark.parametrize("store", ["window_fp16", "window_bf16"])
+def test_window_kept_in_fp16(store):
+    """The variants that keep the window's score rows in fp16 or bfloat16: prompt encoding,
+    separate selection and fused decode steps all take the predicted score over the rounded rows."""
     sh = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=4, context=520)
     T, n, steps = sh.context, 4, 6
     K, V = W.make_kv(3, sh)
     q_last = np.ascontiguousarray(W.make_queries(3, sh, n=n, seed_offset=8).transpose(1, 2, 0, 3))
     qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
-    kw = dict(window=5, sigma_s_max=4e-4, sigma_x_max=6e-3, window_fp16=True)
-    oc, gc = make_pair(sh, qn, max_tokens=T + steps, **kw)
-    oc32, _ = make_pair(sh, qn, max_tokens=T + steps, **dict(kw, window_fp16=False))
+    kw = dict(window=5, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    oc, gc = make_pair(sh, qn, max_tokens=T + steps, **dict(kw, **{store: True}))
+    oc32, _ = make_pair(sh, qn, max_tokens=T + steps, **kw)
     rows = gc.prefill_window(dev(q_last), dev(K)).cpu().numpy()
     bk_g, bv_g = gc.quantize_append_selected(dev(K), dev(V), want_bits=True)
     given = [rows[i][..., : T - n + i + 1] for i in range(n)]

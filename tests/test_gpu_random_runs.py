@@ -30,7 +30,7 @@ def test_random_run(seed):
     sh = W.shape(3, batch=int(rng.choice([1, 2])), n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=D, context=T0)
     kw = dict(max_tokens=T0 + steps, window=window, n_outlier_per_side=n_o, bit_set=bit_set,
               sigma_s_max=float(10 ** rng.uniform(-4.3, -3.2)), sigma_x_max=float(10 ** rng.uniform(-2.6, -1.2)),
-              window_fp16=bool(rng.integers(2)))
+              **[dict(), dict(window_fp16=True), dict(window_bf16=True)][int(rng.integers(3))])
     print(f"seed {seed}: {sh} steps={steps} {kw}", flush=True)
     K, V = W.make_kv(3, sh, seed_offset=seed)
     qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)

@@ -490,6 +490,31 @@ def test_window_in_fp16_rounds_what_it_keeps():
     assert float(np.float16(0.625)) == 0.625 and pred[2] == np.float32(np.float16(0.7))
 
 
+def test_window_in_bf16_rounds_to_eight_significant_bits():
+    """bfloat16 keeps fp32's sign, exponent and the top 7 fraction bits, ties to even:
+    written-out cases, and the two defining properties on random numbers."""
+    cases = {1.0: 1.0, 1.0 + 2.0 ** -8: 1.0,                 # tie, kept part even: down
+             1.0 + 3 * 2.0 ** -8: 1.0 + 2.0 ** -6,           # tie, kept part odd: up
+             1.0 + 2.0 ** -8 + 2.0 ** -20: 1.0 + 2.0 ** -7,  # just above the tie
+             0.1: 0.10009765625, 1.0 / 3.0: 0.333984375, 0.0: 0.0, 2.0 ** -30: 2.0 ** -30}
+    x = np.array(list(cases), F32)
+    np.testing.assert_array_equal(O.round_to_bf16(x), np.array(list(cases.values()), F32))
+    rng = np.random.default_rng(3)
+    r = rng.random(20000).astype(F32) * np.float32(2.0) ** rng.integers(-20, 1, 20000).astype(F32)
+    q = O.round_to_bf16(r)
+    assert (q.view(np.uint32) & 0xFFFF == 0).all()                       # representable
+    assert (np.abs(q.astype(np.float64) - r) <= np.abs(r) * 2.0 ** -8).all()   # within half a unit of the 8th bit
+    np.testing.assert_array_equal(O.round_to_bf16(q), q)                 # idempotent
+    assert (np.diff(O.round_to_bf16(np.sort(r))) >= 0).all()             # monotone
+    cfg = O.Config(1, 1, 1, 8, window=2, window_bf16=True, qnorm2=np.ones(1, F32))
+    oc = O.OracleCache(cfg)
+    xk = np.zeros((1, 1, 2, 8), F16); xk[..., 0] = 1
+    oc.append(xk, xk)
+    oc.observe(np.array([[[0.1, 0.9]]], F32)); oc.observe(np.array([[[1.0 / 3.0, 2.0 / 3.0]]], F32))
+    pred = O.window_predict([r[0, 0] for r in oc.history], 2, 2)
+    np.testing.assert_array_equal(pred, np.array([0.333984375, 0.8984375], F32))    # 0.9 -> 0.8984375 (0x3f66)
+
+
 def test_accounting_and_canonical_pack():
     g = _golden("opt175b_sizing.txt")
     assert round(float(g["kv_gb"][0] / g["weights_gb"][0]), 2) == float(g["ratio"][0])
