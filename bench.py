@@ -164,7 +164,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (every (sequence, KV head) "
-              "is independent, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "is independent and would be sharded by KV head); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2403_04643_amd import qaq, workloads as W
