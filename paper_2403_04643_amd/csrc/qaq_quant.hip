@@ -169,6 +169,25 @@ __device__ __forceinline__ float key_value(uint32_t key) {
   key &= ~0x7fu;
   return key >= 0x80000000u ? __uint_as_float(key - 0x80000000u) : __uint_as_float((0x80000000u - key) | 0x80000000u);
 }
+// The same order on the fp16 bit patterns themselves, two at a time: per 16-bit half,
+// 0x8000 + magnitude for a positive number, 0x8000 - magnitude for a negative one (both zeros
+// give 0x8000).  Shifted into the upper half of a word such a key leaves 16 low bits for the
+// channel number.
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef short ss2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t order_keys_pair(uint32_t two_halves) {
+  const us2 b = __builtin_bit_cast(us2, two_halves);
+  const us2 sg = __builtin_bit_cast(us2, __builtin_bit_cast(ss2, b) >> (ss2)15);    // 0xffff where negative
+  const us2 mag = b & (us2)0x7fffu;
+  const us2 t = (mag ^ sg) - sg;                                                      // +-magnitude, two's complement
+  return __builtin_bit_cast(uint32_t, (us2)(t + (us2)0x8000u));
+}
+// value of a key made from order_keys_pair (upper 16 bits; the low bits carry a channel number)
+__device__ __forceinline__ float key16_value(uint32_t key) {
+  const uint32_t k = key >> 16;
+  const uint32_t hb = k >= 0x8000u ? k - 0x8000u : ((0x8000u - k) | 0x8000u);
+  return h2f((uint16_t)hb);
+}
 
 // ---------------------------------------------------------------------------------
 // Encoder for one token vector, run by the four lanes of a quad; lane c holds the 8-channel
@@ -212,11 +231,17 @@ struct TokenEncoder {
 #pragma unroll
         for (int i = 0; i < NCH; ++i)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const uint32_t k = order_key(h2f((uint16_t)half_bits(raw, i, e)));
-            const uint32_t kx = k + (uint32_t)(127 - channel(c, i, e)), kn = k + (uint32_t)channel(c, i, e);
-            a2 = umed3(a1, a2, kx); a1 = a1 > kx ? a1 : kx;
-            b2 = umed3(b1, b2, kn); b1 = b1 < kn ? b1 : kn;
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t w = e2 == 0 ? raw[i].x : e2 == 1 ? raw[i].y : e2 == 2 ? raw[i].z : raw[i].w;
+            const uint32_t kk = order_keys_pair(w);     // keys of elements 2*e2 (low half) and 2*e2+1 (high half)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+              const uint32_t k = hf ? (kk & 0xffff0000u) : (kk << 16);
+              const int ch = channel(c, i, 2 * e2 + hf);
+              const uint32_t kx = k | (uint32_t)(127 - ch), kn = k | (uint32_t)ch;
+              a2 = umed3(a1, a2, kx); a1 = a1 > kx ? a1 : kx;
+              b2 = umed3(b1, b2, kn); b1 = b1 < kn ? b1 : kn;
+            }
           }
         const uint32_t A1 = quad_umax(a1), A2 = quad_umax(a1 == A1 ? a2 : a1);
         const uint32_t B1 = quad_umin(b1), B2 = quad_umin(b1 == B1 ? b2 : b1);
@@ -225,11 +250,11 @@ struct TokenEncoder {
         // itself (all values equal): then it is the runner-up
         const uint32_t Bb = (int)(B1 & 127u) == ch_top ? B2 : B1;
         const int ch_bot = (int)(Bb & 127u);
-        if (((ch_top >> 3) & 3) == c) { oidx_row[0] = (uint8_t)ch_top; oval_row[0] = outlier_bits(raw, c, ch_top, key_value(A1)); }
-        if (((ch_bot >> 3) & 3) == c) { oidx_row[1] = (uint8_t)ch_bot; oval_row[1] = outlier_bits(raw, c, ch_bot, key_value(Bb)); }
+        if (((ch_top >> 3) & 3) == c) { oidx_row[0] = (uint8_t)ch_top; oval_row[0] = outlier_bits(raw, c, ch_top, key16_value(A1)); }
+        if (((ch_bot >> 3) & 3) == c) { oidx_row[1] = (uint8_t)ch_bot; oval_row[1] = outlier_bits(raw, c, ch_bot, key16_value(Bb)); }
         // what remains: its largest value is the runner-up of the maximum search, its smallest
         // the runner-up of the minimum search (equal values make the choice of element moot)
-        key_mx = A2; key_mn = B2;
+        mx = key16_value(A2); mn = key16_value(B2);
       } else {
         uint32_t kx[EPL], kn[EPL];
 #pragma unroll
@@ -258,8 +283,8 @@ struct TokenEncoder {
 #pragma unroll
         for (int j = 0; j < EPL; ++j) { m1 = m1 > kx[j] ? m1 : kx[j]; m0 = m0 < kn[j] ? m0 : kn[j]; }
         key_mx = quad_umax(m1); key_mn = quad_umin(m0);
+        mx = key_value(key_mx); mn = key_value(key_mn);
       }
-      mx = key_value(key_mx); mn = key_value(key_mn);
       if (c == 0) *mm_pos = (uint32_t)f2h(mn) | ((uint32_t)f2h(mx) << 16);
     } else {
       const uint32_t m = *mm_pos;
