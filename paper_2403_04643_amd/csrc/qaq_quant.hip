@@ -441,11 +441,13 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
       const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + 2 * dw];
       *(uint32_t*)(base + r.r4 + 4u * (uint32_t)it) = ((row[0] >> sh) & 0x0f0f0f0fu) | (((row[1] >> sh) & 0x0f0f0f0fu) << 4);
     }
-    for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
-      const int i8 = it / (D / 4), jj = it % (D / 4), q = jj >> 2, v = jj & 3;
+    for (int it = tid; it < c.n8 * NQ; it += kThreads) {        // one slice (16 bytes) per item
+      const int i8 = it / NQ, q = it % NQ;
       const int pos = L.pos_of_slot[n32 + c.n4 + i8];
       if (same8 && (L.shf[pos] & kKeptFlag)) continue;
-      *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS) + v] ^ 0x80808080u;
+      const uint32_t* row = &L.stage[pos * SROW + 16 * (q % KS) + 4 * (q / KS)];
+      *(uint4*)(base + r.r8 + 16u * (uint32_t)it) =
+          make_uint4(row[0] ^ 0x80808080u, row[1] ^ 0x80808080u, row[2] ^ 0x80808080u, row[3] ^ 0x80808080u);
     }
     const bool same1b = same8 && c0.n8 == c.n8;           // then r1b has not moved either
     for (int it = tid; HAS1 && it < c.n1 * (D / 32); it += kThreads) {
@@ -542,11 +544,12 @@ __device__ void pack_tile(int side, uint8_t* base, const QaqCounts& c, const Qaq
     for (int k = 0; k < 4; ++k)
       *(uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D) + 4u * (uint32_t)((4 * (c4 & 3) + k) * (D / 16) + cg)) = o[k];
   }
-  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
-    const int i8 = it / (D / 4), dq = it % (D / 4);
+  for (int it = tid; it < c.n8 * (D / 16); it += kThreads) {    // 16 bytes per item
+    const int i8 = it / (D / 16), dq = 4 * (it % (D / 16));
     const int pos = L.pos_of_slot[n32 + c.n4 + i8];
     if (same8 && (L.shf[pos] & kKeptFlag)) continue;
-    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
+    const uint32_t* row = &L.stage[pos * SROW + dq];
+    *(uint4*)(base + r.r8 + 16u * (uint32_t)it) = make_uint4(row[0], row[1], row[2], row[3]);
   }
   for (int it = tid; HAS1 && it < ((c.n1 + 15) / 16) * (D / 8); it += kThreads) {
     const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
@@ -662,11 +665,12 @@ __device__ void pack_masked_v(uint8_t* base, const QaqCounts& c, const QaqCounts
 #pragma unroll
     for (int k = 0; k < 4; ++k) wp[k * (D / 16)] = o[k];
   }
-  for (int it = tid; it < c.n8 * (D / 4); it += kThreads) {
-    const int i8 = it / (D / 4), dq = it % (D / 4);
+  for (int it = tid; it < c.n8 * (D / 16); it += kThreads) {    // 16 bytes per item
+    const int i8 = it / (D / 16), dq = 4 * (it % (D / 16));
     const int pos = L.pos_of_slot[n32 + c.n4 + i8];
     if (same8 && (L.shf[pos] & kKeptFlag)) continue;
-    *(uint32_t*)(base + r.r8 + 4u * (uint32_t)it) = L.stage[pos * SROW + dq];
+    const uint32_t* row = &L.stage[pos * SROW + dq];
+    *(uint4*)(base + r.r8 + 16u * (uint32_t)it) = make_uint4(row[0], row[1], row[2], row[3]);
   }
   const bool same1b = same8 && c0.n8 == c.n8;
   const int units1b_old = same1b ? (c0.n1 + 15) / 16 : 0;
