@@ -86,3 +86,42 @@ def test_random_run(seed):
     Ko, Vo = oc.dequantize()
     np.testing.assert_array_equal(Kd.cpu().numpy().view(np.uint16), Ko.astype(np.float16).view(np.uint16))
     np.testing.assert_array_equal(Vd.cpu().numpy().view(np.uint16), Vo.astype(np.float16).view(np.uint16))
+
+
+@pytest.mark.parametrize("bit_set,with_orig", [((2, 3, 4, 8), True), ((1, 2, 3, 4, 8), True), ((1, 2, 3, 4, 8), False)])
+def test_long_decode_run(bit_set, with_orig):
+    """400 decode steps from a 200-token prompt (the cache grows through two tile boundaries, class
+    counts cross many multiples of 16, so regions move again and again; with the unquantized
+    copies widths go up and down, without them only down): widths at every step, the whole
+    cache every 20 steps."""
+    sh = W.shape(3, batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, context=200)
+    steps = 400
+    K, V = W.make_kv(3, sh, seed_offset=5)
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    oc, gc = make_pair(sh, qn, max_tokens=sh.context + steps, window=3, bit_set=bit_set,
+                       sigma_s_max=2.5e-4, sigma_x_max=0.05)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps, seed_offset=2)
+    seen = set()
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        if s % 20 == 0:
+            Xo, So = oc.decode_attention(qs[s], kn, vn)
+            ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+            assert ex.max() < TOL and es.max() < TOL, f"step {s}"
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig if with_orig else None, Vorig if with_orig else None)
+        bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), dev(Korig) if with_orig else None,
+                                      dev(Vorig) if with_orig else None, want_bits=True)
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o, err_msg=f"step {s}")
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o, err_msg=f"step {s}")
+        seen |= set(np.unique(bk_o)) | set(np.unique(bv_o))
+        if s % 20 == 19:
+            compare_canonical(oc, gc, f"step {s}")
+            assert gc.stats().refused_upgrades == oc.refused
+    assert len(seen) >= 3, seen
