@@ -492,6 +492,40 @@ def main():
             "tokens_per_s": B * Tctx / ((ms_w + ms_a) * 1e-3),
             "fp16_key_bytes_read": B * Hkv * Tctx * D * 2, "window_GBps": B * Hkv * Tctx * D * 2 / (ms_w * 1e-3) / 1e9,
             "hist_k": list(stp.hist_k), "hist_v": list(stp.hist_v)}
+        # The paper's premise (Section 3.2) is that a token's importance persists from step to
+        # step; the timed steps above draw an independent query every step, the worst case for
+        # the update (every step re-draws every score).  The same steps with queries that follow
+        # q_j = rho q_{j-1} + sqrt(1 - rho^2) noise, rho = 0 (independent) and 0.98, from the
+        # same encoded prompt: time per step and token-heads widened per step.
+        persist = {}
+        n_p = min(per_layer, 8)
+        gen = torch.Generator(device="cuda"); gen.manual_seed(20240304)
+        q_std = float(q_last.float().std())
+        for rho in (0.0, 0.98):
+            for l, c in enumerate(caches):
+                Kd, Vd = origK[l][:, :, :T0].contiguous(), origV[l][:, :, :T0].contiguous()
+                c.reset(); c.set_sigmas(ss, sx)
+                c.prefill_window(q_last, Kd); c.quantize_append_selected(Kd, Vd)
+                del Kd, Vd
+            qp = q_last[:, :, -1].float()
+            chain = []
+            for j in range(n_p):
+                qp = rho * qp + float(np.sqrt(1.0 - rho * rho)) * q_std * torch.randn(qp.shape, generator=gen, device="cuda")
+                chain.append(qp.half().contiguous())
+            served_0 = sum(c.stats().served_upgrades for c in caches)
+            e0, e1 = ev(), ev()
+            torch.cuda.synchronize(); e0.record()
+            for j in range(n_p):
+                for l, c in enumerate(caches):
+                    rc = lib.qaq_decode_attention(c.h, P(chain[j]), P(newk[l][j]), P(newv[l][j]), P(out), 1, P(scores), stream)
+                    rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(origK[l]), P(origV[l]), Tcap,
+                                                None, None, stream)
+                    assert rc == 0, lib.qaq_last_error()
+            e1.record(); torch.cuda.synchronize()
+            served_1 = sum(c.stats().served_upgrades for c in caches)
+            persist[f"rho {rho}"] = {"ms_per_step": e0.elapsed_time(e1) / (n_p * L),
+                                     "served_upgrades_per_step": (served_1 - served_0) / (n_p * L)}
+        rec["query_persistence"] = persist
         # every token at one width (the uniform baseline of the paper's comparison): where the
         # tile kernel sits between instruction issue and HBM as the bytes per token grow
         sweep = {}
