@@ -95,3 +95,20 @@ def test_decode_steps_with_one_bit_in_the_set(G, window_kw):
         assert gc.stats().refused_upgrades == oc.refused
     assert 1 in seen and len(seen) >= 3, seen       # the hyper-parameters spread the widths, one bit included
     compare_canonical(oc, gc, "after decode steps")
+
+
+@pytest.mark.parametrize("G,context", [(1, 9000), (2, 3000)])
+def test_long_context_in_the_two_kernel_form(G, context):
+    """Few heads and a long context: one workgroup per part and the merge kernel, with the
+    fifth class present (and grouped queries in the second case)."""
+    sh = W.shape(4, batch=1, n_q_heads=G, n_kv_heads=1, context=context)
+    K, V = W.make_kv(4, sh)
+    rng = np.random.default_rng(29)
+    bk, bv = _rand_bits(rng, K.shape[:3]), _rand_bits(rng, K.shape[:3], p=(0.6, 0.2, 0.1, 0.05, 0.05))
+    oc, gc = make_pair(sh, 0.01, bit_set=SET5)
+    oc.append(K, V, bk, bv); gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(4, sh)[0]
+    kn, vn = W.make_new_token(4, sh)
+    S = _check_attention(oc, gc, q, kn, vn, tag="two-kernel form")
+    np.testing.assert_allclose(S.cpu().numpy().sum(-1, dtype=np.float64), 1.0, rtol=2e-5)
+    compare_canonical(oc, gc, "long context")
