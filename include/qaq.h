@@ -69,6 +69,14 @@ typedef struct {
                              rule (the paper takes the upper-10% quantile), with the
                              query already carrying the softmax's 1/sqrt(D), i.e.
                              quantile(|q|^2) / D.  Copied by qaq_create.              */
+  const float* outlier_thresholds; /* NULL: the count rule above.  Else (variant, Section 4.2
+                             "Outliers" read literally) host [2 (K, V)][n_kv_heads][2 (lo, hi)],
+                             lo <= hi, copied by qaq_create: the outliers of a token are its
+                             values above hi or below lo, so their number varies per token;
+                             a token keeps at most n_outlier_per_side per end (1..4; the
+                             largest above hi, the smallest below lo), the others widen its
+                             [min,max].  The side store is then variable-length: per token an
+                             offset and a count into a per-tile pool of (channel, value).   */
 } qaq_config;
 
 typedef struct {

@@ -116,6 +116,38 @@ def outlier_split(x: np.ndarray, n_o: int) -> np.ndarray:
     return mask
 
 
+def outlier_split_threshold(x: np.ndarray, lo: float, hi: float, cap: int) -> np.ndarray:
+    """Variant of Section 4.2 "Outliers" read literally: an outlier is a value outside fixed
+    thresholds [lo, hi] (calibrated once as the alpha/2 and 1 - alpha/2 quantiles of a
+    population, see calibrate_outlier_thresholds), so a token has a variable number of them.
+    A token keeps at most `cap` per end: the `cap` largest of those above hi and the `cap`
+    smallest of those below lo (equal values: lower channel first).  x: fp16 [N, D];
+    thresholds are compared as fp32 numbers, strictly.  Returns the bool mask [N, D]."""
+    x = np.asarray(x, dtype=F16)
+    N, D = x.shape
+    assert D - 2 * cap >= 1 and lo <= hi
+    xf = x.astype(F32)
+    mask = np.zeros((N, D), dtype=bool)
+    if cap == 0:
+        return mask
+    rows = np.arange(N)[:, None]
+    top = np.argsort(-xf.astype(np.float64), axis=1, kind="stable")[:, :cap]
+    mask[rows, top] = xf[rows, top] > F32(hi)
+    bot = np.argsort(xf.astype(np.float64), axis=1, kind="stable")[:, :cap]
+    mask[rows, bot] |= xf[rows, bot] < F32(lo)
+    return mask
+
+
+def calibrate_outlier_thresholds(population: np.ndarray, alpha: float) -> Tuple[np.float32, np.float32]:
+    """The two thresholds that make a fraction alpha (alpha/2 per end) of a calibration
+    population outliers: the lower and upper empirical quantiles, taken as order statistics
+    (elements of the population, hence fp16 numbers): exactly floor(alpha/2 * N) values lie
+    strictly above hi, and as many strictly below lo, unless equal values straddle the cut."""
+    v = np.sort(np.asarray(population, dtype=F16).astype(F32).reshape(-1))
+    k = int(math.floor(alpha / 2.0 * v.size))
+    return F32(v[k]), F32(v[v.size - 1 - k])
+
+
 def token_range(x: np.ndarray, omask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """min_t and max_t over the non-outlier entries of each token (Section 4.1,
     "Determining quantization bits"; Section 4.2 benefit 2).  fp16 in, fp16 out
@@ -295,7 +327,8 @@ def bits_formula_f64(range_, sigma) -> np.ndarray:
 @dataclass
 class HeadCache:
     D: int
-    n_o: int
+    n_o: int                               # outliers per end; with thresholds: the most a token keeps per end
+    thr: Optional[Tuple[float, float]] = None   # (lo, hi): the threshold variant of the outlier rule
     bits: np.ndarray = field(default_factory=lambda: np.zeros(0, np.uint8))
     mn: np.ndarray = field(default_factory=lambda: np.zeros(0, F16))
     mx: np.ndarray = field(default_factory=lambda: np.zeros(0, F16))
@@ -316,7 +349,7 @@ class HeadCache:
     def append(self, x: np.ndarray, bits: np.ndarray) -> None:
         x = np.asarray(x, dtype=F16).reshape(-1, self.D)
         bits = np.asarray(bits, dtype=np.uint8).reshape(-1)
-        om = outlier_split(x, self.n_o)
+        om = outlier_split(x, self.n_o) if self.thr is None else outlier_split_threshold(x, self.thr[0], self.thr[1], self.n_o)
         mn, mx = token_range(x, om)
         c = encode(x, mn, mx, bits)
         self.bits = np.concatenate([self.bits, bits])
@@ -355,14 +388,15 @@ class HeadCache:
         return range_f32(self.mn, self.mx)
 
     def outlier_lists(self) -> Tuple[np.ndarray, np.ndarray]:
-        """Side store as sorted-by-channel lists: idx uint8 [T, 2 n_o], val fp16 [T, 2 n_o]."""
+        """Side store as sorted-by-channel lists: idx uint8 [T, 2 n_o], val fp16 [T, 2 n_o].
+        With thresholds a token may have fewer: the rest of its row is (255, 0)."""
         k = 2 * self.n_o
-        idx = np.zeros((self.T, k), np.uint8)
+        idx = np.full((self.T, k), 255 if self.thr is not None else 0, np.uint8)
         val = np.zeros((self.T, k), F16)
         for t in range(self.T):
             ch = np.nonzero(self.omask[t])[0]
-            idx[t] = ch
-            val[t] = self.oval[t, ch]
+            idx[t, : len(ch)] = ch
+            val[t, : len(ch)] = self.oval[t, ch]
         return idx, val
 
     def packed(self, t: int) -> np.ndarray:
@@ -384,6 +418,8 @@ class Config:
     qnorm2: Optional[np.ndarray] = None   # [n_kv_heads]
     window_fp16: bool = False             # variant: the window keeps its score rows in fp16
     window_bf16: bool = False             # variant: ... in bfloat16
+    outlier_thresholds: Optional[np.ndarray] = None   # variant: fp32 [2 (K, V), n_kv_heads, 2 (lo, hi)]; then
+                                                      # n_outlier_per_side (or the count alpha gives) caps a token's outliers per end
 
     def n_o(self) -> int:
         if self.n_outlier_per_side >= 0:
@@ -398,8 +434,10 @@ class OracleCache:
     def __init__(self, cfg: Config):
         self.cfg = cfg
         B, H, D = cfg.batch, cfg.n_kv_heads, cfg.head_dim
-        self.K = [[HeadCache(D, cfg.n_o()) for _ in range(H)] for _ in range(B)]
-        self.V = [[HeadCache(D, cfg.n_o()) for _ in range(H)] for _ in range(B)]
+        thr = cfg.outlier_thresholds
+        pair = lambda side, h: None if thr is None else (float(thr[side][h][0]), float(thr[side][h][1]))
+        self.K = [[HeadCache(D, cfg.n_o(), pair(0, h)) for h in range(H)] for _ in range(B)]
+        self.V = [[HeadCache(D, cfg.n_o(), pair(1, h)) for h in range(H)] for _ in range(B)]
         self.history: List[np.ndarray] = []     # rows [B, Hkv, T_row], oldest first
         self.refused = 0
 
@@ -532,7 +570,11 @@ class OracleCache:
         per side, and (u8 channel, fp16 value) per outlier."""
         cfg = self.cfg
         n_tok = cfg.batch * cfg.n_kv_heads * self.T
-        meta = n_tok * (8 + 2 + 2 * 2 * cfg.n_o() * 3)
+        if cfg.outlier_thresholds is None:
+            meta = n_tok * (8 + 2 + 2 * 2 * cfg.n_o() * 3)
+        else:   # a variable number of entries per token, plus (u16 offset, u8 count) per token and side
+            entries = sum(int(hc.omask.sum()) for side in (self.K, self.V) for row in side for hc in row)
+            meta = n_tok * (8 + 2 + 2 * 3) + entries * 3
         return (n_tok * cfg.head_dim * 2 * 2) / (self.code_bytes() + meta)
 
 

@@ -11,6 +11,7 @@
 struct qaq_cache {
   qaq_config cfg;
   std::vector<float> qnorm2;
+  std::vector<float> othr;
   QaqDims dims;
   QaqArena arena;
   QaqView view;
@@ -73,6 +74,13 @@ bool valid_config(const qaq_config* c, QaqDims* d) {
   d->window = c->window;
   if (c->window_store < QAQ_WINDOW_FP32 || c->window_store > QAQ_WINDOW_BF16) { fail(QAQ_ERR_INVALID_ARG, "window_store must be 0 (fp32), 1 (fp16) or 2 (bf16)"); return false; }
   d->ring_half = c->window_store;
+  d->csr = c->outlier_thresholds != nullptr;
+  if (d->csr) {
+    if (no < 1) { fail(QAQ_ERR_INVALID_ARG, "outlier thresholds need a cap of 1..4 outliers per end"); return false; }
+    for (int i = 0; i < 2 * c->n_kv_heads; ++i)
+      if (!(c->outlier_thresholds[2 * i] <= c->outlier_thresholds[2 * i + 1])) {
+        fail(QAQ_ERR_INVALID_ARG, "outlier thresholds must satisfy lo <= hi"); return false; }
+  }
   return true;
 }
 
@@ -146,6 +154,10 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   c->cfg = *cfg;
   c->qnorm2.assign(cfg->qnorm2, cfg->qnorm2 + cfg->n_kv_heads);
   c->cfg.qnorm2 = c->qnorm2.data();
+  if (d.csr) {
+    c->othr.assign(cfg->outlier_thresholds, cfg->outlier_thresholds + 4 * cfg->n_kv_heads);
+    c->cfg.outlier_thresholds = c->othr.data();
+  }
   c->dims = d;
   c->arena = a;
   c->n_o = d.no2 / 2;
@@ -175,6 +187,16 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.refused = (unsigned int*)(base + a.refused);
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
   v.has1 = cfg->bit_set[0] == 1;
+  v.csr = d.csr;
+  for (int s = 0; s < 2; ++s) {
+    v.ostart[s] = d.csr ? (uint16_t*)(base + a.ostart[s]) : nullptr;
+    v.ocnt[s] = d.csr ? base + a.ocnt[s] : nullptr;
+  }
+  v.othr = d.csr ? (const float*)(base + a.othr) : nullptr;
+  if (d.csr) {
+    hipError_t e0 = hipMemcpy(base + a.othr, c->othr.data(), c->othr.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e0 != hipSuccess) { delete c; return hip_fail(e0, "qaq_create: thresholds"); }
+  }
   v.cap[0] = qaq_k_cap(d.D);
   v.cap[1] = qaq_v_cap(d.D);
   hipError_t e = qaq_launch_init(v, nullptr);

@@ -245,11 +245,29 @@ struct Outl {
       i2 = gload32(uniform_ptr(v.oidx[side] + gi0 * 2), (2u * slot) & ~3u);
       v2 = gload32(uniform_ptr(v.oval[side] + gi0 * 2), 4u * slot);
     } else if constexpr (NO2 > 2) {
+      if (v.csr) return;              // variable-length side store: fetched when the position is known (load_csr)
       const size_t gi = gi0 + slot;
 #pragma unroll
       for (int j = 0; j < NO2; ++j)
         if (j < no2) { idx8[j] = v.oidx[side][gi * no2 + j]; val8[j] = v.oval[side][gi * no2 + j]; }
     }
+  }
+  // Variable-length side store (outliers by thresholds): the tile's pool is in position order;
+  // `pos` = the token's position inside the tile.  Unused places get channel 255.
+  __device__ __forceinline__ void load_csr(const QaqView& v, int side, size_t gi0, uint32_t pos, int no2) {
+    if constexpr (NO2 > 2) {
+      const int cnt = v.ocnt[side][gi0 + pos], st = v.ostart[side][gi0 + pos];
+#pragma unroll
+      for (int j = 0; j < NO2; ++j) {
+        const bool have = j < cnt && j < no2;
+        idx8[j] = have ? v.oidx[side][gi0 * no2 + st + j] : (uint8_t)0xffu;
+        val8[j] = have ? v.oval[side][gi0 * no2 + st + j] : (uint16_t)0;
+      }
+    }
+  }
+  __device__ __forceinline__ bool used(int j) const {
+    if constexpr (NO2 > 2) return idx8[j] != 0xffu;
+    else return true;
   }
   // slot: the slot the store was loaded for (selects the half of the channel word)
   __device__ __forceinline__ int idx(int j, uint32_t slot) const {
@@ -469,7 +487,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const float hs = 0.5f * scale;
 #pragma unroll
     for (int j = 0; j < Outl<NO2>::CAP; ++j) {
-      if (j < NO2 && j < no2) {
+      if (j < NO2 && j < no2 && o.used(j)) {
         const float ov = o.val(j);
         const bool top = ov >= mx;
         val += S.qf[o.idx(j, slot)] * ((ov - (top ? mx : mn)) + (top ? hs : -hs));
@@ -573,6 +591,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         if (tid >= first1K) dotq = d1;
       }
       if (tid < n_tok) {
+        if constexpr (NO2 > 2)
+          if (v.csr) kr.o.load_csr(v, 0, qaq_slot_index(v, b, h, tile, 0), (kr.pos >> (8u * (slot & 3u))) & 0xffu, no2);
         const float lg = key_logit(kr.mm, kr.o, slot, H1 ? cK.bits_of_slot(tid) : cK.bits_of_slot4(tid), dotq);
         S.logit[(kr.pos >> (8u * (slot & 3u))) & 0xffu] = lg;
         vmax = lg;
@@ -603,6 +623,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       const bool live = s < n_tok;
       float pt = 0.0f, bias_l = 0.0f, w = 0.0f;
       if (live) {
+        if constexpr (NO2 > 2)
+          if (v.csr) vr.o.load_csr(v, 1, qaq_slot_index(v, b, h, tile, 0), (vr.pos >> (8u * (slot & 3u))) & 0xffu, no2);
         pt = __expf(S.logit[(vr.pos >> (8u * (slot & 3u))) & 0xffu] - M);
         const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
         const float range = mx - mn;
@@ -613,7 +635,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         const float hs = 0.5f * scale;
 #pragma unroll
         for (int j = 0; j < Outl<NO2>::CAP; ++j) {
-          if (j < NO2 && j < no2) {
+          if (j < NO2 && j < no2 && vr.o.used(j)) {
             const float ov = vr.o.val(j);
             const bool top = ov >= mx;
             // |correction| < 2^wexp, at most 32 arrive per copy: units of 2^(wexp-25) cannot overflow
@@ -911,12 +933,12 @@ template <int D, int P>
 void launch_tile_p(const QaqAttnArgs& a, dim3 grid, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const dim3 block((P ? P : 1) * kThreads);
   if (a.v.has1) {
-    if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, true>), grid, block, lds, s, e0, e1, 0, a);
+    if (a.v.no2 == 2 && !a.v.csr) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, true>), grid, block, lds, s, e0, e1, 0, a);
     else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P, true>), grid, block, lds, s, e0, e1, 0, a);
     else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P, true>), grid, block, lds, s, e0, e1, 0, a);
     return;
   }
-  if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, false>), grid, block, lds, s, e0, e1, 0, a);
+  if (a.v.no2 == 2 && !a.v.csr) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, false>), grid, block, lds, s, e0, e1, 0, a);   // (the variable-length side store runs in the general form)
   else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P, false>), grid, block, lds, s, e0, e1, 0, a);
   else hipExtLaunchKernelGGL((k_attn_tile<D, 8, P, false>), grid, block, lds, s, e0, e1, 0, a);
 }

@@ -28,6 +28,10 @@ struct QaqView {
   unsigned int* refused;   // [0] widenings refused for want of the unquantized copy, [1] widenings served
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
   int has1;                // the width set contains 1: kernels take their five-class variants
+  int csr;                 // outliers by thresholds: oidx / oval are per-tile pools in position order, addressed
+  uint16_t* ostart[2];     // ... through (first entry, count) per position
+  uint8_t* ocnt[2];
+  const float* othr;       // [2][Hkv][2] thresholds (lo, hi)
   uint32_t cap[2];
 };
 

@@ -165,6 +165,7 @@ QAQ_HD QaqFieldPos qaq_v_field(uint32_t roff, int bf, int idx, int d, int D) {
 struct QaqDims {
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
   int ring_half;      // the window's rows: 0 fp32, 1 fp16, 2 bf16
+  int csr;            // outliers by thresholds: variable-length side store
 };
 
 struct QaqArena {
@@ -182,6 +183,11 @@ struct QaqArena {
   size_t partial;     // f32  [B][Hq][NT][D+4]
   size_t statbuf;     // i64  [32]
   size_t refused;     // u32  [2][QAQ_NCOUNT] widenings refused / served, partial counts
+  // variable-length side store (outliers by thresholds) only: oidx / oval are then per-tile pools
+  // of 256 * no2 entries filled in position order
+  size_t ostart[2];   // u16  [B][Hkv][Tmax]  by position: first entry of the token in its tile's pool
+  size_t ocnt[2];     // u8   [B][Hkv][Tmax]  by position: entries of the token
+  size_t othr;        // f32  [2][Hkv][2]     thresholds (lo, hi) per side and KV head
   size_t total;
 };
 
@@ -205,6 +211,12 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
   a.statbuf = off; off = qaq_up256(off + 32 * 8);
   a.refused = off; off = qaq_up256(off + 2 * QAQ_NCOUNT * 4);
+  a.ostart[0] = a.ostart[1] = a.ocnt[0] = a.ocnt[1] = a.othr = 0;
+  if (d.csr) {
+    for (int s = 0; s < 2; ++s) { a.ostart[s] = off; off = qaq_up256(off + bh * d.Tmax * 2); }
+    for (int s = 0; s < 2; ++s) { a.ocnt[s] = off; off = qaq_up256(off + bh * d.Tmax); }
+    a.othr = off; off = qaq_up256(off + (size_t)2 * d.Hkv * 2 * 4);
+  }
   a.total = off;
   return a;
 }

@@ -73,9 +73,18 @@ __device__ void tile_load(const QaqView& v, int side, int b, int h, int tile, in
     L.mm[pos] = v.mm[side][gi];
     L.slot_of_pos[pos] = (uint16_t)s;
     L.bits_old[pos] = (uint8_t)c.bits_of_slot(s);
-    for (int k = 0; k < v.no2; ++k) {
+    for (int k = 0; k < v.no2 && !v.csr; ++k) {
       L.oidx[pos][k] = v.oidx[side][gi * v.no2 + k];
       L.oval[pos][k] = v.oval[side][gi * v.no2 + k];
+    }
+  }
+  if (v.csr && tid < n_tok) {       // variable-length side store: by position; unused places of the row = channel 255
+    const size_t pi = qaq_slot_index(v, b, h, tile, tid);
+    const size_t pool0 = qaq_slot_index(v, b, h, tile, 0) * (size_t)v.no2;
+    const int cnt = v.ocnt[side][pi], st = v.ostart[side][pi];
+    for (int k = 0; k < v.no2; ++k) {
+      L.oidx[tid][k] = k < cnt ? v.oidx[side][pool0 + st + k] : (uint8_t)0xffu;
+      L.oval[tid][k] = k < cnt ? v.oval[side][pool0 + st + k] : (uint16_t)0;
     }
   }
   __syncthreads();
@@ -120,6 +129,7 @@ struct BuildLds {
   int wave_free[QAQ_NCLASS][4];
   float wave_bound[4];
   float wave_bound2[4];
+  int wave_ocnt[4];                        // variable-length side store: entries of the new tokens per wavefront
 };
 constexpr int kKeptFlag = 0x80;
 
@@ -220,8 +230,12 @@ struct TokenEncoder {
     return (uint16_t)hv;
   }
 
+  // thr_lo, thr_hi: an outlier must lie below thr_lo resp. above thr_hi (+inf, -inf: the count
+  // rule, every candidate passes); a side stops at its first candidate that does not, and the
+  // rows of the side store are filled from the front, the rest marked unused (channel 255)
   __device__ static __forceinline__ void run(const uint4 (&raw)[NCH], int c, bool fresh, int bits, int n_o, uint32_t* mm_pos,
-                                             uint8_t* oidx_row, uint16_t* oval_row, uint32_t* stage_row) {
+                                             uint8_t* oidx_row, uint16_t* oval_row, uint32_t* stage_row,
+                                             float thr_lo = INFINITY, float thr_hi = -INFINITY) {
     float mn, mx;
     if (fresh) {
       uint32_t key_mx, key_mn;
@@ -265,20 +279,30 @@ struct TokenEncoder {
             kx[8 * i + e] = k + (uint32_t)(127 - channel(c, i, e));
             kn[8 * i + e] = k + (uint32_t)channel(c, i, e);
           }
+        int n_rec = 0;
+        bool alive = true;
         for (int k = 0; k < 2 * n_o; ++k) {
           const bool top = k < n_o;
+          if (k == n_o) alive = true;
           uint32_t m = top ? 0u : 0xffffffffu;
 #pragma unroll
           for (int j = 0; j < EPL; ++j) m = top ? (m > kx[j] ? m : kx[j]) : (m < kn[j] ? m : kn[j]);
           const uint32_t M = top ? quad_umax(m) : quad_umin(m);
           const int ch = top ? 127 - (int)(M & 127u) : (int)(M & 127u);
+          const float val = key_value(M);
+          alive = alive && (top ? val > thr_hi : val < thr_lo);      // the same for the four lanes of the quad
+          if (alive) {
 #pragma unroll
-          for (int j = 0; j < EPL; ++j) {
-            const bool dead = top ? kx[j] == M : kn[j] == M;
-            if (dead) { kx[j] = 0u; kn[j] = 0xffffffffu; }
+            for (int j = 0; j < EPL; ++j) {
+              const bool dead = top ? kx[j] == M : kn[j] == M;
+              if (dead) { kx[j] = 0u; kn[j] = 0xffffffffu; }
+            }
+            if (((ch >> 3) & 3) == c) { oidx_row[n_rec] = (uint8_t)ch; oval_row[n_rec] = outlier_bits(raw, c, ch, val); }
+            ++n_rec;
           }
-          if (((ch >> 3) & 3) == c) { oidx_row[k] = (uint8_t)ch; oval_row[k] = outlier_bits(raw, c, ch, key_value(M)); }
         }
+        if (c == 0)
+          for (int k = n_rec; k < 2 * n_o; ++k) { oidx_row[k] = 0xffu; oval_row[k] = 0; }
         uint32_t m1 = 0u, m0 = 0xffffffffu;
 #pragma unroll
         for (int j = 0; j < EPL; ++j) { m1 = m1 > kx[j] ? m1 : kx[j]; m0 = m0 < kn[j] ? m0 : kn[j]; }
@@ -763,7 +787,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       mm_old = v.mm[side][gi];
 #pragma unroll
       for (int k = 0; k < MAXO; ++k)
-        if (k < v.no2) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
+        if (k < v.no2 && !v.csr) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
     }
   }
   // decode-step update: the inputs of the width rules that are indexed by position (this
@@ -808,7 +832,20 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     L.bits_old[pos_old] = (uint8_t)bits_at(c_old, tid);
 #pragma unroll
     for (int k = 0; k < MAXO; ++k)
-      if (k < v.no2) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
+      if (k < v.no2 && !v.csr) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
+  }
+  // variable-length side store: the tile's pool is in position order and a token's entries never
+  // move; thread `tid` fetches those of position tid (unused places of its row: channel 255)
+  const size_t pool0 = qaq_slot_index(v, b, h, tile, 0) * (size_t)v.no2;
+  if (v.csr && tid < n_before) {
+    const size_t pi = qaq_slot_index(v, b, h, tile, tid);
+    const int cnt = v.ocnt[side][pi], st = v.ostart[side][pi];
+#pragma unroll
+    for (int k = 0; k < MAXO; ++k) {
+      const bool have = k < cnt;
+      L.oidx[tid][k] = have ? v.oidx[side][pool0 + st + k] : (uint8_t)0xffu;
+      L.oval[tid][k] = have ? v.oval[side][pool0 + st + k] : (uint16_t)0;
+    }
   }
   __syncthreads();
 
@@ -885,6 +922,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   if (n_enc > 0) {
     typedef TokenEncoder<D, ONE> Enc;
+    const float thr_lo = v.csr ? v.othr[(side * v.Hkv + h) * 2] : INFINITY;
+    const float thr_hi = v.csr ? v.othr[(side * v.Hkv + h) * 2 + 1] : -INFINITY;
     constexpr int TPP = kThreads / 4;     // tokens per pass
     const int NP = (n_enc + TPP - 1) / TPP;
     const int c = tid & 3, gt = tid >> 2;
@@ -915,7 +954,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       const int kind_next = fetch(pass + 1, nxt);
       if (kind) {                          // whole quads drop out together
         const int p = position(pass);
-        Enc::run(cur, c, kind == 1, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW]);
+        Enc::run(cur, c, kind == 1, L.bits_new[p], n_o, &L.mm[p], L.oidx[p], L.oval[p], &L.stage[p * SROW], thr_lo, thr_hi);
       }
 #pragma unroll
       for (int i = 0; i < Enc::NCH; ++i) cur[i] = nxt[i];
@@ -963,6 +1002,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       const float range = mx - mn;
       bnd = ldexpf(range, bits == 3 ? -2 : -bits);
       for (int k = 0; k < v.no2; ++k) {
+        if (L.oidx[tid][k] == 0xffu) continue;        // (variable-length side store: an unused place)
         const float ov = h2f(L.oval[tid][k]);
         bnd = fmaxf(bnd, fmaxf(fabsf(ov - mx), fabsf(ov - mn)) + range);
       }
@@ -1138,11 +1178,42 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     const size_t gi = qaq_slot_index(v, b, h, tile, s);
     v.mm[side][gi] = L.mm[tid];
     v.perm[side][gi] = (uint8_t)tid;
-    for (int k = 0; k < v.no2; ++k) {
+    for (int k = 0; k < v.no2 && !v.csr; ++k) {
       v.oidx[side][gi * v.no2 + k] = L.oidx[tid][k];
       v.oval[side][gi * v.no2 + k] = L.oval[tid][k];
     }
     v.tags[side][qaq_slot_index(v, b, h, tile, tid)] = L.bits_new[tid];
+  }
+  if (v.csr && n_after > n_before) {
+    // variable-length side store: the new tokens' entries go behind the tile's last one, in
+    // position order (a prefix sum of their counts)
+    const bool fresh = tid >= n_before && tid < n_after;
+    int cnt = 0;
+    if (fresh)
+      for (int k = 0; k < v.no2; ++k) cnt += L.oidx[tid][k] != 0xffu;
+    int inc = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(inc, o);
+      if (lane >= o) inc += y;
+    }
+    if (lane == 63) L.wave_ocnt[wave] = inc;
+    __syncthreads();
+    int start = inc - cnt;
+    for (int w = 0; w < wave; ++w) start += L.wave_ocnt[w];
+    if (n_before > 0) {
+      const size_t pl = qaq_slot_index(v, b, h, tile, n_before - 1);
+      start += (int)v.ostart[side][pl] + (int)v.ocnt[side][pl];
+    }
+    if (fresh) {
+      const size_t pi = qaq_slot_index(v, b, h, tile, tid);
+      v.ostart[side][pi] = (uint16_t)start;
+      v.ocnt[side][pi] = (uint8_t)cnt;
+      for (int k = 0; k < cnt; ++k) {          // the row is sorted by channel, unused places last
+        v.oidx[side][pool0 + start + k] = L.oidx[tid][k];
+        v.oval[side][pool0 + start + k] = L.oval[tid][k];
+      }
+    }
   }
   if (tid == 0) {
     uint16_t* cp = v.counts + (((qaq_bh(v, b, h) * v.NT + tile) * 2 + side) * 4);
@@ -1304,7 +1375,11 @@ __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
     // bytes a scan reads: key records one by one, value planes in whole units
     loc[8] += side == 0 ? (unsigned long long)c.n32() * (v.D / 4) + (c.n3 + c.n1) * (v.D / 8) + c.n4 * (v.D / 2) + c.n8 * v.D
                         : qaq_v_regions(c, v.D).end;
-    loc[9] += (unsigned long long)c.total() * (4 + 1 + 3 * v.no2);
+    if (!v.csr) loc[9] += (unsigned long long)c.total() * (4 + 1 + 3 * v.no2);
+    else {   // min/max, order byte, (offset, count), and the entries the tile's pool holds
+      const size_t pl = qaq_slot_index(v, bh / v.Hkv, bh % v.Hkv, tile, c.total() - 1);
+      loc[9] += (unsigned long long)c.total() * (4 + 1 + 3) + 3ull * ((unsigned)v.ostart[side][pl] + (unsigned)v.ocnt[side][pl]);
+    }
   }
   for (int k = 0; k < 12; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
   __syncthreads();
@@ -1332,7 +1407,7 @@ hipError_t qaq_launch_init(const QaqView& v, hipStream_t s) {
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   dim3 grid(a.v.B * a.v.Hkv, ntiles, 2);
-  const bool one = a.v.no2 == 2;
+  const bool one = a.v.no2 == 2 && !a.v.csr;      // (the one-per-end search has no threshold test)
   if (a.v.D == 128) {
     if (a.v.has1) {
       if (one) hipLaunchKernelGGL((k_build<128, true, true>), grid, dim3(kThreads), 0, s, a);

@@ -27,6 +27,7 @@ class Config(C.Structure):
         ("window", C.c_int32), ("window_store", C.c_int32),
         ("sigma_s_max", C.c_double), ("sigma_x_max", C.c_double),
         ("qnorm2", C.POINTER(C.c_float)),
+        ("outlier_thresholds", C.POINTER(C.c_float)),
     ]
 
 
@@ -102,7 +103,8 @@ def _check(rc: int) -> None:
 
 def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequence[float],
                 bit_set=(2, 3, 4, 8), outlier_frac=0.01, n_outlier_per_side=-1, window=5,
-                sigma_s_max=1e-3, sigma_x_max=1e-2, window_fp16=False, window_bf16=False):
+                sigma_s_max=1e-3, sigma_x_max=1e-2, window_fp16=False, window_bf16=False,
+                outlier_thresholds=None):
     cfg = Config()
     cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.max_tokens = batch, n_q_heads, n_kv_heads, head_dim, max_tokens
     for i, b in enumerate(bit_set):
@@ -117,6 +119,12 @@ def make_config(batch, n_q_heads, n_kv_heads, head_dim, max_tokens, qnorm2: Sequ
     arr = (C.c_float * len(qnorm2))(*[float(x) for x in qnorm2])
     cfg.qnorm2 = C.cast(arr, C.POINTER(C.c_float))
     cfg._keepalive = arr
+    if outlier_thresholds is not None:     # [2 (K, V)][n_kv_heads][2 (lo, hi)]
+        flat = [float(x) for side in outlier_thresholds for pair in side for x in pair]
+        assert len(flat) == 4 * n_kv_heads
+        arr2 = (C.c_float * len(flat))(*flat)
+        cfg.outlier_thresholds = C.cast(arr2, C.POINTER(C.c_float))
+        cfg._keepalive2 = arr2
     return cfg
 
 

@@ -22,7 +22,8 @@ def make_pair(sh, qnorm2, max_tokens=None, **kw):
     okw = dict(window=kw.get("window", 5), sigma_s_max=kw.get("sigma_s_max", 1e-3),
                sigma_x_max=kw.get("sigma_x_max", 1e-2), outlier_frac=kw.get("outlier_frac", 0.01),
                n_outlier_per_side=kw.get("n_outlier_per_side", -1), bit_set=tuple(kw.get("bit_set", (2, 3, 4, 8))),
-               window_fp16=bool(kw.get("window_fp16", False)), window_bf16=bool(kw.get("window_bf16", False)))
+               window_fp16=bool(kw.get("window_fp16", False)), window_bf16=bool(kw.get("window_bf16", False)),
+               outlier_thresholds=None if kw.get("outlier_thresholds") is None else np.asarray(kw["outlier_thresholds"], F32))
     ocfg = O.Config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, qnorm2=qn, **okw)
     gcfg = qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
                            max_tokens or sh.context, qn.tolist(), **okw)

@@ -31,8 +31,12 @@ def test_random_run(seed):
     kw = dict(max_tokens=T0 + steps, window=window, n_outlier_per_side=n_o, bit_set=bit_set,
               sigma_s_max=float(10 ** rng.uniform(-4.3, -3.2)), sigma_x_max=float(10 ** rng.uniform(-2.6, -1.2)),
               **[dict(), dict(window_fp16=True), dict(window_bf16=True)][int(rng.integers(3))])
-    print(f"seed {seed}: {sh} steps={steps} {kw}", flush=True)
     K, V = W.make_kv(3, sh, seed_offset=seed)
+    if n_o > 0 and rng.integers(3) == 0:       # outliers by thresholds, calibrated per KV head on the prompt
+        alpha = float(rng.choice([0.005, 0.02, 0.1]))
+        kw["outlier_thresholds"] = np.array([[O.calibrate_outlier_thresholds(X[:, h], alpha) for h in range(Hkv)]
+                                             for X in (K, V)], np.float32)
+    print(f"seed {seed}: {sh} steps={steps} {kw}", flush=True)
     qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
     oc, gc = make_pair(sh, qn, **kw)
     n_rows = min(window, T0, int(rng.integers(1, 9)))

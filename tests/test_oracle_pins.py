@@ -288,6 +288,56 @@ def test_outlier_split_brute_force_and_ties():
         assert (om.sum(1) == 2 * n_o).all()
 
 
+def test_threshold_outliers_brute_force_and_calibration():
+    """The threshold variant of the outlier rule (Section 4.2 "Outliers" read literally):
+    brute force per element, the cap, ties, the degenerate thresholds, and the calibration
+    that makes exactly a fraction alpha of a population outliers."""
+    rng = np.random.default_rng(21)
+    x = (rng.standard_normal((50, 64)) * 2).astype(F16)
+    x[0, :12] = 7.0            # more above hi than the cap keeps: the lowest channels win the ties
+    x[1, 5:20] = -9.0
+    x[2] = 0.25                # nothing outside
+    lo, hi, cap = -2.5, 3.0, 4
+    m = O.outlier_split_threshold(x, lo, hi, cap)
+    for t in range(x.shape[0]):
+        xt = x[t].astype(np.float64)
+        above = sorted([d for d in range(64) if xt[d] > hi], key=lambda d: (-xt[d], d))[:cap]
+        below = sorted([d for d in range(64) if xt[d] < lo], key=lambda d: (xt[d], d))[:cap]
+        assert sorted(np.nonzero(m[t])[0]) == sorted(above + below), t
+    assert list(np.nonzero(m[0])[0][:4]) == [0, 1, 2, 3] and m[0, :12].sum() == 4
+    assert list(np.nonzero(m[1])[0][:4]) == [5, 6, 7, 8] and not m[2].any()
+    # the values a token keeps beyond the cap widen its range instead
+    mn, mx = O.token_range(x, m)
+    assert float(mx[0]) == 7.0 and float(mn[1]) == -9.0
+    # thresholds that nothing passes; thresholds at the 2nd largest / 2nd smallest value of a row
+    # of distinct values reproduce the count rule with one outlier per end
+    assert not O.outlier_split_threshold(x, -np.inf, np.inf, cap).any()
+    z = rng.permutation(64).astype(F16)[None]
+    np.testing.assert_array_equal(O.outlier_split_threshold(z, 1.0, 62.0, 4), O.outlier_split(z, 1))
+    # strict comparison: a value equal to the threshold is not an outlier
+    y = np.zeros((1, 64), F16); y[0, 3] = 3.0; y[0, 4] = 3.002
+    assert list(np.nonzero(O.outlier_split_threshold(y, -1.0, 3.0, 4)[0])[0]) == [4]
+    # calibration: alpha of the population lies outside, alpha/2 per end
+    pop = (rng.standard_normal((400, 128)) * rng.uniform(0.5, 3, size=(1, 128))).astype(F16)
+    alpha = 0.01
+    lo_c, hi_c = O.calibrate_outlier_thresholds(pop, alpha)
+    pf = pop.astype(F32)
+    k = int(alpha / 2 * pop.size)
+    assert abs(int((pf > hi_c).sum()) - k) <= 2 and abs(int((pf < lo_c).sum()) - k) <= 2      # fp16 ties at the cut
+    counts = O.outlier_split_threshold(pop, lo_c, hi_c, 4).sum(1)
+    assert counts.min() == 0 and counts.max() > 2                                     # a variable number per token
+    assert abs(counts.sum() / pop.size - alpha) < 0.1 * alpha                         # the cap rarely bites
+    # a cache built with thresholds keeps them through append / requantize / dequantize
+    hc = O.HeadCache(64, 4, (lo, hi))
+    hc.append(x, np.full(50, 4, np.uint8))
+    np.testing.assert_array_equal(hc.omask, m)
+    idx, val = hc.outlier_lists()
+    assert idx.shape == (50, 8) and (idx[2] == 255).all() and list(idx[0, :4]) == [0, 1, 2, 3]
+    assert (idx[0, m[0].sum():] == 255).all() and (np.diff(idx[0, : m[0].sum()].astype(int)) > 0).all()
+    xh = hc.dequantize()
+    assert (xh[m] == x[m].astype(F32)).all()
+
+
 def test_outliers_shrink_range_and_restore_exactly():
     rng = np.random.default_rng(8)
     x = rng.standard_normal((500, 128)).astype(np.float32)
