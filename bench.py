@@ -577,6 +577,35 @@ def main():
             "us_tile_kernel": us5, "algorithmic_bytes": b5, "GBps": b5 / (us5 * 1e-6) / 1e9,
             "frac_of_hbm_peak": b5 / (us5 * 1e-6) / 1e9 / HBM_PEAK_GBS, "output_rel_l2_error": output_error(0, c5s)}
         del c5s
+        # Variant: outliers by thresholds (the 0.5 % and 99.5 % quantiles of each KV head's keys /
+        # values over the prompt; at most 4 per end and token) in the variable-length side store;
+        # the widths of the benchmark's operating point.
+        thr = []
+        for src in (origK[0], origV[0]):
+            per_head = []
+            for hh in range(Hkv):
+                flat = src[:, hh, :Tctx].float().reshape(-1)
+                k_cut = int(0.005 * flat.numel())
+                per_head.append((float(torch.kthvalue(flat, k_cut + 1).values), float(torch.kthvalue(flat, flat.numel() - k_cut).values)))
+            thr.append(per_head)
+        cts = []
+        for l in range(L):
+            ct = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=5, n_outlier_per_side=4, outlier_thresholds=thr))
+            Kd, Vd = origK[l][:, :, :Tctx].contiguous(), origV[l][:, :, :Tctx].contiguous()
+            ct.set_sigmas(ss, sx)
+            ct.prefill_window(q_last, Kd); ct.quantize_append_selected(Kd, Vd)
+            del Kd, Vd
+            cts.append(ct)
+        us_t = time_tile_kernel(2 * L, cts)
+        stt = cts[0].stats()
+        tht = B * Hkv * stt.tokens
+        entries = (stt.meta_bytes - 2 * tht * 8) / 3.0
+        bt = stt.code_bytes + stt.meta_bytes + B * Hq * D * 2 + B * Hq * stt.tokens * 4
+        rec["outliers_by_thresholds"] = {
+            "alpha": 0.01, "cap_per_end": 4, "outliers_per_token_side": entries / (2 * tht),
+            "ratio_codes": stt.fp16_bytes / stt.code_bytes, "ratio_all": stt.fp16_bytes / (stt.code_bytes + stt.meta_bytes),
+            "us_tile_kernel": us_t, "bytes": bt, "GBps": bt / (us_t * 1e-6) / 1e9, "output_rel_l2_error": output_error(0, cts)}
+        del cts
     # attention-output error against fp32 attention over the unquantized tokens, by compression
     # ratio: the adaptive widths of the two operating points next to uniform widths
     rec["quality_on_synthetic_data"] = quality

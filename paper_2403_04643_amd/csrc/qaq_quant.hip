@@ -745,6 +745,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   constexpr int SROW = BuildLds<D, MAXO>::SROW;
 
   const QaqView& v = a.v;
+  const bool csr = !ONE && v.csr;     // (the one-per-end build never has the variable-length side store)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // heads are the fastest grid dimension: with tiles fastest and a tile count that is a multiple
   // of eight, every die would see the same two tile indices of every head, which ran 30 % slower
@@ -787,7 +788,7 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       mm_old = v.mm[side][gi];
 #pragma unroll
       for (int k = 0; k < MAXO; ++k)
-        if (k < v.no2 && !v.csr) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
+        if (k < v.no2 && !csr) { oi_old[k] = v.oidx[side][gi * v.no2 + k]; ov_old[k] = v.oval[side][gi * v.no2 + k]; }
     }
   }
   // decode-step update: the inputs of the width rules that are indexed by position (this
@@ -832,12 +833,12 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     L.bits_old[pos_old] = (uint8_t)bits_at(c_old, tid);
 #pragma unroll
     for (int k = 0; k < MAXO; ++k)
-      if (k < v.no2 && !v.csr) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
+      if (k < v.no2 && !csr) { L.oidx[pos_old][k] = oi_old[k]; L.oval[pos_old][k] = ov_old[k]; }
   }
   // variable-length side store: the tile's pool is in position order and a token's entries never
   // move; thread `tid` fetches those of position tid (unused places of its row: channel 255)
   const size_t pool0 = qaq_slot_index(v, b, h, tile, 0) * (size_t)v.no2;
-  if (v.csr && tid < n_before) {
+  if (csr && tid < n_before) {
     const size_t pi = qaq_slot_index(v, b, h, tile, tid);
     const int cnt = v.ocnt[side][pi], st = v.ostart[side][pi];
 #pragma unroll
@@ -922,8 +923,8 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   }
   if (n_enc > 0) {
     typedef TokenEncoder<D, ONE> Enc;
-    const float thr_lo = v.csr ? v.othr[(side * v.Hkv + h) * 2] : INFINITY;
-    const float thr_hi = v.csr ? v.othr[(side * v.Hkv + h) * 2 + 1] : -INFINITY;
+    const float thr_lo = csr ? v.othr[(side * v.Hkv + h) * 2] : INFINITY;
+    const float thr_hi = csr ? v.othr[(side * v.Hkv + h) * 2 + 1] : -INFINITY;
     constexpr int TPP = kThreads / 4;     // tokens per pass
     const int NP = (n_enc + TPP - 1) / TPP;
     const int c = tid & 3, gt = tid >> 2;
@@ -1178,13 +1179,13 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
     const size_t gi = qaq_slot_index(v, b, h, tile, s);
     v.mm[side][gi] = L.mm[tid];
     v.perm[side][gi] = (uint8_t)tid;
-    for (int k = 0; k < v.no2 && !v.csr; ++k) {
+    for (int k = 0; k < v.no2 && !csr; ++k) {
       v.oidx[side][gi * v.no2 + k] = L.oidx[tid][k];
       v.oval[side][gi * v.no2 + k] = L.oval[tid][k];
     }
     v.tags[side][qaq_slot_index(v, b, h, tile, tid)] = L.bits_new[tid];
   }
-  if (v.csr && n_after > n_before) {
+  if (csr && n_after > n_before) {
     // variable-length side store: the new tokens' entries go behind the tile's last one, in
     // position order (a prefix sum of their counts)
     const bool fresh = tid >= n_before && tid < n_after;
