@@ -234,9 +234,20 @@ __device__ __forceinline__ v4i k_contract(const uint32_t (&w)[KRec<D, BF>::RDW],
 template <int NO2>
 struct Outl {
   static constexpr int CAP = NO2 ? NO2 : 1;
+  static constexpr int NI = (CAP + 3) / 4, NV = (CAP + 1) / 2;
   uint32_t i2, v2;            // NO2 == 2: word holding the two channel bytes, two fp16 values
-  uint8_t idx8[CAP];          // NO2 > 2
-  uint16_t val8[CAP];
+  int nmax = CAP;             // NO2 > 2: places any lane of the wavefront uses (uniform)
+  uint32_t ip[NI], vp[NV];    // NO2 > 2: channel bytes and fp16 values, packed (place j: byte j, half j)
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int k = 0; k < NI; ++k) ip[k] = 0xffffffffu;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) vp[k] = 0u;
+  }
+  __device__ __forceinline__ void put(int j, uint32_t ch, uint32_t hv) {      // j is a compile-time constant at every call
+    ip[j >> 2] = (ip[j >> 2] & ~(0xffu << (8 * (j & 3)))) | (ch << (8 * (j & 3)));
+    vp[j >> 1] = (vp[j >> 1] & ~(0xffffu << (16 * (j & 1)))) | (hv << (16 * (j & 1)));
+  }
   // gi0: first slot of the tile (uniform), slot: the lane's slot inside the tile
   __device__ __forceinline__ void load(const QaqView& v, int side, size_t gi0, uint32_t slot, int no2) {
     if constexpr (NO2 == 2) {
@@ -247,36 +258,41 @@ struct Outl {
     } else if constexpr (NO2 > 2) {
       if (v.csr) return;              // variable-length side store: fetched when the position is known (load_csr)
       const size_t gi = gi0 + slot;
+      clear();
 #pragma unroll
       for (int j = 0; j < NO2; ++j)
-        if (j < no2) { idx8[j] = v.oidx[side][gi * no2 + j]; val8[j] = v.oval[side][gi * no2 + j]; }
+        if (j < no2) put(j, v.oidx[side][gi * no2 + j], v.oval[side][gi * no2 + j]);
     }
   }
   // Variable-length side store (outliers by thresholds): the tile's pool is in position order;
-  // `pos` = the token's position inside the tile.  Unused places get channel 255.
+  // `pos` = the token's position inside the tile.  Unused places keep channel 255.
   __device__ __forceinline__ void load_csr(const QaqView& v, int side, size_t gi0, uint32_t pos, int no2) {
     if constexpr (NO2 > 2) {
       const int cnt = v.ocnt[side][gi0 + pos], st = v.ostart[side][gi0 + pos];
+      nmax = 0;
+      clear();
 #pragma unroll
       for (int j = 0; j < NO2; ++j) {
         const bool have = j < cnt && j < no2;
-        idx8[j] = have ? v.oidx[side][gi0 * no2 + st + j] : (uint8_t)0xffu;
-        val8[j] = have ? v.oval[side][gi0 * no2 + st + j] : (uint16_t)0;
+        if (__ballot(have) != 0ull) {        // uniform: most tokens have one or two, the row has room for eight
+          nmax = j + 1;
+          if (have) put(j, v.oidx[side][gi0 * no2 + st + j], v.oval[side][gi0 * no2 + st + j]);
+        }
       }
     }
-  }
-  __device__ __forceinline__ bool used(int j) const {
-    if constexpr (NO2 > 2) return idx8[j] != 0xffu;
-    else return true;
   }
   // slot: the slot the store was loaded for (selects the half of the channel word)
   __device__ __forceinline__ int idx(int j, uint32_t slot) const {
     if constexpr (NO2 == 2) return (int)((i2 >> (16 * (slot & 1u) + 8 * j)) & 0xffu);
-    else return idx8[j];
+    else return (int)((ip[j >> 2] >> (8 * (j & 3))) & 0xffu);
+  }
+  __device__ __forceinline__ bool used(int j) const {
+    if constexpr (NO2 > 2) return j < nmax && ((ip[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0xffu;
+    else return true;
   }
   __device__ __forceinline__ float val(int j) const {
     if constexpr (NO2 == 2) return h2f((uint16_t)(v2 >> (16 * j)));
-    else return h2f(val8[j]);
+    else return h2f((uint16_t)(vp[j >> 1] >> (16 * (j & 1))));
   }
 };
 
