@@ -259,9 +259,20 @@ struct Outl {
       if (v.csr) return;              // variable-length side store: fetched when the position is known (load_csr)
       const size_t gi = gi0 + slot;
       clear();
+      if (no2 == 8) {                 // a row is two aligned words of channels and four of values
+        const uint2 ci = *(const uint2*)(v.oidx[side] + gi * 8);
+        const uint4 cv = *(const uint4*)(v.oval[side] + gi * 8);
+        ip[0] = ci.x; ip[NI - 1] = ci.y;
+        vp[0] = cv.x; vp[1 % NV] = cv.y; vp[2 % NV] = cv.z; vp[NV - 1] = cv.w;
+      } else if (no2 == 4) {          // one word of channels, two of values
+        ip[0] = *(const uint32_t*)(v.oidx[side] + gi * 4);
+        const uint2 cv = *(const uint2*)(v.oval[side] + gi * 4);
+        vp[0] = cv.x; vp[1 % NV] = cv.y;
+      } else {
 #pragma unroll
-      for (int j = 0; j < NO2; ++j)
-        if (j < no2) put(j, v.oidx[side][gi * no2 + j], v.oval[side][gi * no2 + j]);
+        for (int j = 0; j < NO2; ++j)
+          if (j < no2) put(j, v.oidx[side][gi * no2 + j], v.oval[side][gi * no2 + j]);
+      }
     }
   }
   // Variable-length side store (outliers by thresholds): the tile's pool is in position order;
