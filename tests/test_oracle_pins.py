@@ -590,6 +590,101 @@ def test_accounting_and_canonical_pack():
     assert O.pack_canonical(np.array([200, 7], np.uint8), 8).tolist() == [200, 7]
 
 
+def test_everything_counted_ratio_against_a_hand_count():
+    """ratio_all = fp16 bytes over every stored byte, counted here by hand for a cache small
+    enough to list (Section 2.1: memory "calculated by the quantized bit"; Section 4.2: the
+    outliers are kept beside the codes).  Count rule: B1, 1 KV head, D 64, 3 tokens, one
+    outlier per end.  Per side and token: codes 64*b/8 bytes, min and max as fp16 (4 bytes),
+    one width tag (1 byte), two outliers of (u8 channel, fp16 value) (6 bytes)."""
+    rng = np.random.default_rng(31)
+    k = rng.standard_normal((1, 1, 3, 64)).astype(F16)
+    cfg = O.Config(1, 1, 1, 64, qnorm2=np.ones(1))
+    oc = O.OracleCache(cfg)
+    bk = np.array([[[2, 3, 8]]], np.uint8)
+    bv = np.array([[[4, 2, 2]]], np.uint8)
+    oc.append(k, k, bk, bv)
+    # keys: 16 + 24 + 64 code bytes, values: 32 + 16 + 16; metadata 3 tokens x 2 sides x (4 + 1 + 6)
+    assert oc.code_bytes() == 104 + 64
+    assert oc.ratio_all() == pytest.approx((3 * 64 * 2 * 2) / (168 + 66), rel=1e-15)
+    # Threshold rule: a token keeps the values outside [lo, hi] (at most 2 per end), so the number
+    # of entries varies; per side and token a u16 offset and a u8 count replace the fixed rows.
+    x = np.zeros((1, 1, 3, 64), F16)
+    x[0, 0, :, :8] = np.linspace(-1, 1, 8)
+    x[0, 0, 0, 9] = 50.0                      # token 0: one above hi
+    x[0, 0, 1, 10] = -50.0; x[0, 0, 1, 11] = 60.0; x[0, 0, 1, 12] = 70.0   # token 1: one below lo, two above hi
+    #                                          token 2: none
+    thr = np.array([[[-10.0, 10.0]], [[-10.0, 10.0]]], F32)
+    cfg2 = O.Config(1, 1, 1, 64, qnorm2=np.ones(1), n_outlier_per_side=2, outlier_thresholds=thr)
+    oc2 = O.OracleCache(cfg2)
+    two = np.full((1, 1, 3), 2, np.uint8)
+    oc2.append(x, x, two, two)
+    # codes 2 sides x 3 tokens x 16; per side and token min/max 4 + tag 1 + (offset, count) 3;
+    # entries (1 + 3 + 0) per side x 3 bytes
+    assert oc2.ratio_all() == pytest.approx(768 / (96 + 2 * 3 * 8 + 2 * 4 * 3), rel=1e-15)
+    # a third outlier above hi on one token exceeds the cap of two per end: it stays in the token
+    x[0, 0, 1, 13] = 80.0
+    oc3 = O.OracleCache(cfg2)
+    oc3.append(x, x, two, two)
+    assert oc3.ratio_all() == pytest.approx(768 / (96 + 48 + 24), rel=1e-15)
+
+
+def test_key_widths_use_each_heads_own_query_statistic_and_the_cache_length():
+    """OracleCache.select_bits, key side (Section 4.1 "Key cache quantization" + "Determining
+    quantization bits"): the noise bound of a key depends on its head's query statistic and on
+    the number of tokens attended, not on the token or its score.  The same key rows in three
+    heads with different statistics must get different widths, and every chosen width must be
+    the narrowest allowed one that keeps the modelled score variance
+    (1/T^2)(1 - 1/T)(exp(qnorm2 * sigma_K^2) - 1), sigma_K = range / (2 sqrt(3) 2^b), within
+    sigma_S_max^2 -- the constraint itself, evaluated here per head in double precision."""
+    D, T = 16, 4
+    ranges = np.array([0.11, 0.37, 1.3, 4.9], np.float64)       # fp16 rounds these; the stored range is what counts
+    k = np.zeros((1, 3, T, D), F16)
+    k[0, :, :, 1] = ranges.astype(F16)[None, :]
+    r16 = k[0, 0, :, 1].astype(np.float64)
+    qn = np.array([0.25, 1.0, 9.0], F32)
+    ss = 0.04
+    cfg = O.Config(1, 3, 3, D, n_outlier_per_side=0, window=1, sigma_s_max=ss, sigma_x_max=1.0, qnorm2=qn)
+    oc = O.OracleCache(cfg)
+    oc.append(k, k)
+    oc.observe(np.full((1, 3, T), 0.25, F32))
+    bk, _ = oc.select_bits()
+
+    def model_var(b, r, q, t):
+        sig = r / (2.0 * math.sqrt(3.0) * 2.0 ** b)
+        return (1.0 / t ** 2) * (1.0 - 1.0 / t) * math.expm1(q * sig * sig)
+
+    allowed = (2, 3, 4, 8)
+    for h in range(3):
+        for t in range(T):
+            b = int(bk[0, h, t])
+            assert b in allowed
+            ok = model_var(b, r16[t], float(qn[h]), T) <= ss * ss
+            assert ok or b == 8
+            i = allowed.index(b)
+            if i > 0:     # the next narrower width would break the budget
+                assert model_var(allowed[i - 1], r16[t], float(qn[h]), T) > ss * ss
+    # worked by hand from the same constraint (T = 4: sigma_K^2 <= log(1 + 64/3 * 0.0016) / qnorm2):
+    # head 0 (0.25): sigma_K <= 0.3663 -> 2^b >= range / 1.2690 ; head 1: / 0.6345 ; head 2: / 0.2115
+    np.testing.assert_array_equal(bk[0, 0], [2, 2, 2, 2])
+    np.testing.assert_array_equal(bk[0, 1], [2, 2, 2, 3])
+    np.testing.assert_array_equal(bk[0, 2], [2, 2, 3, 8])
+    # more tokens attended loosen every bound (it grows with T): the same four keys inside a cache of
+    # 40 tokens need no more bits than before, and some need fewer
+    k40 = np.zeros((1, 3, 40, D), F16)
+    k40[0, :, :T, 1] = ranges.astype(F16)[None, :]
+    oc40 = O.OracleCache(cfg)
+    oc40.append(k40, k40)
+    bk40, _ = oc40.select_bits()
+    for h in range(3):
+        for t in range(T):
+            b = int(bk40[0, h, t])
+            assert model_var(b, r16[t], float(qn[h]), 40) <= ss * ss or b == 8
+            i = allowed.index(b)
+            if i > 0:
+                assert model_var(allowed[i - 1], r16[t], float(qn[h]), 40) > ss * ss
+    assert (bk40[0, :, :T] <= bk[0]).all() and (bk40[0, :, :T] < bk[0]).any()
+
+
 def test_query_norm_statistic():
     rng = np.random.default_rng(16)
     q = rng.standard_normal((4000, 128)) / math.sqrt(128)
