@@ -284,17 +284,18 @@ int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits, 
   a.G = c->dims.Hq / c->dims.Hkv;
   a.scores = dev_scores;
   a.new_row = c->ring_next;
-  if (dev_scores) {
-    c->row_len[c->ring_next] = c->len;
-    c->ring_next = (c->ring_next + 1) % c->dims.window;
-  }
   for (int r = 0; r < QAQ_MAX_WINDOW; ++r) a.row_len[r] = r < c->dims.window ? c->row_len[r] : 0;
+  if (dev_scores) a.row_len[a.new_row] = c->len;     // the row this call writes (kept by the cache only if the launch succeeds)
   a.nbits = c->cfg.n_bits;
   for (int i = 0; i < 5; ++i) a.bit_set[i] = c->cfg.bit_set[i < a.nbits ? i : a.nbits - 1];
   thresholds(c, c->len, a.tau_k, &a.c_v);
   a.out_bits[0] = dev_k_bits; a.out_bits[1] = dev_v_bits;
   hipError_t e = qaq_launch_select(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_select_bits");
+  if (dev_scores) {
+    c->row_len[a.new_row] = c->len;
+    c->ring_next = (a.new_row + 1) % c->dims.window;
+  }
   return QAQ_OK;
 }
 
@@ -349,15 +350,16 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   r.scores = dev_scores;
   r.score_stride = a.len_after;
   r.new_row = c->ring_next;
-  c->row_len[c->ring_next] = a.len_after;
-  c->ring_next = (c->ring_next + 1) % c->dims.window;
   for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
+  r.row_len[r.new_row] = a.len_after;               // the row this call writes (kept by the cache only if the launch succeeds)
   r.nbits = c->cfg.n_bits;
   for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
   thresholds(c, a.len_after, r.tau_k, &r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
   hipError_t e = qaq_launch_build(a, (a.len_after + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_update");
+  c->row_len[r.new_row] = a.len_after;
+  c->ring_next = (r.new_row + 1) % c->dims.window;
   c->len = a.len_after;
   return QAQ_OK;
 }

@@ -227,3 +227,79 @@ def test_attention_with_two_and_three_parts_per_head(batch, parts):
         ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
         _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
         assert ex.max() < TOL and es.max() < TOL
+
+
+def test_full_size_decode_update_across_a_tile_border():
+    """Config 2 at full size through the call the benchmark times for the second half of a
+    step: qaq_decode_update on all 256 (sequence, head) units at once, four consecutive decode
+    steps from 4094 cached tokens (the third one opens a 17th tile per head), the unquantized
+    copies resident so that tokens widen, without the width outputs in two of the steps (the
+    form the benchmark runs: key tiles inside their threshold interval are skipped).  The
+    cache starts from prompt encoding at hyper-parameters close to the benchmark's operating
+    point.  Sampled units follow the oracle at every step: scores and outputs of the attention
+    within 2e-3, widths, [min,max], outlier lists and packed codes bit for bit."""
+    import torch
+    sh = W.shape(2)
+    steps, T0, n = 4, 4094, 5
+    Tcap = T0 + steps
+    G = sh.n_q_heads // sh.n_kv_heads
+    _log(f"full size decode update cfg=2 shape={sh} prompt={T0} steps={steps}")
+    K, V = W.make_kv(2, sh, n_tokens=T0)
+    q_last = np.ascontiguousarray(W.make_queries(2, sh, n=n, seed_offset=3).transpose(1, 2, 0, 3))
+    qcal = W.make_queries(2, sh, n=4, seed_offset=7).astype(np.float64)
+    qn = np.full(sh.n_kv_heads, float(np.quantile((qcal ** 2).sum(-1).reshape(-1), 0.9)) / sh.head_dim, F32)
+    kw = dict(sigma_s_max=1.8e-5, sigma_x_max=1.85e-2, window=5)
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, Tcap, qn.tolist(), **kw))
+    Kd, Vd = dev(K), dev(V)
+    rows = gc.prefill_window(dev(q_last), Kd).cpu().numpy()
+    gc.quantize_append_selected(Kd, Vd)
+    oK = torch.zeros((sh.batch, sh.n_kv_heads, Tcap, sh.head_dim), dtype=torch.float16, device="cuda")
+    oV = torch.zeros_like(oK)
+    oK[:, :, :T0] = Kd; oV[:, :, :T0] = Vd
+    del Kd, Vd
+    units = _sample_units(sh, 4, 41)
+    oracles = {}
+    for b, h in units:
+        oc, _ = _unit_oracle(sh, qn, b, h, **kw)
+        unit_rows = [rows[i][b:b + 1, h * G:(h + 1) * G, : T0 - n + i + 1] for i in range(n)]
+        oc.prefill(q_last[b:b + 1, h * G:(h + 1) * G], K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], score_rows=unit_rows)
+        oracles[(b, h)] = (oc, K[b:b + 1, h:h + 1].copy(), V[b:b + 1, h:h + 1].copy())
+    qs = W.make_queries(2, sh, n=steps, seed_offset=1)
+    served0 = gc.stats().served_upgrades
+    for s in range(steps):
+        kn, vn = W.make_new_token(2, sh, step=s)
+        X, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Xg, Sg = X.cpu().numpy(), S.cpu().numpy()
+        want_bits = s % 2 == 0
+        bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), oK, oV, want_bits=want_bits)
+        torch.cuda.synchronize()
+        assert gc.length() == T0 + s + 1
+        # the call wrote the new token into the copies
+        np.testing.assert_array_equal(oK[:, :, T0 + s].cpu().numpy(), kn)
+        np.testing.assert_array_equal(oV[:, :, T0 + s].cpu().numpy(), vn)
+        exK = {k: v.cpu().numpy() for k, v in gc.export_canonical(0).items()}
+        exV = {k: v.cpu().numpy() for k, v in gc.export_canonical(1).items()}
+        widened = 0
+        for b, h in units:
+            oc, Ko, Vo = oracles[(b, h)]
+            Xo, So = oc.decode_attention(qs[s][b:b + 1, h * G:(h + 1) * G], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+            ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
+            assert ex.max() < TOL and es.max() < TOL, (s, b, h, ex.max(), es.max())
+            Ko = np.concatenate([Ko, kn[b:b + 1, h:h + 1, None]], 2); Vo = np.concatenate([Vo, vn[b:b + 1, h:h + 1, None]], 2)
+            before = oc.V[0][0].bits.copy()
+            oc.append(kn[b:b + 1, h:h + 1, None], vn[b:b + 1, h:h + 1, None])
+            oc.observe(Sg[b:b + 1, h * G:(h + 1) * G])
+            bko, bvo = oc.select_bits()
+            oc.requantize(bko, bvo, Ko, Vo)
+            widened += int((bvo[0, 0, :-1] > before).sum())
+            oracles[(b, h)] = (oc, Ko, Vo)
+            if want_bits:
+                np.testing.assert_array_equal(bk_g[b, h].cpu().numpy(), bko[0, 0])
+                np.testing.assert_array_equal(bv_g[b, h].cpu().numpy(), bvo[0, 0])
+            _compare_unit(exK, oc.K[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"step {s} K b={b} h={h}")
+            _compare_unit(exV, oc.V[0][0], b, h, sh.head_dim, oc.cfg.n_o(), f"step {s} V b={b} h={h}")
+        _log(f"  step {s}: {T0 + s + 1} cached tokens, {widened} value tokens widened in the {len(units)} sampled units")
+        assert widened > 0, "the case must exercise widening from the unquantized copies"
+    st = gc.stats()
+    assert st.refused_upgrades == 0 and st.served_upgrades > served0
+    assert sum(st.hist_k) == sum(st.hist_v) == sh.batch * sh.n_kv_heads * Tcap
