@@ -222,6 +222,25 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
                          const void* dev_v_new, void* dev_out, int32_t out_is_fp32,
                          float* dev_scores_out, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace at the moment of the
+ * call (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * qaq_decode_attention with the same arguments, results and errors, except that where a
+ * head's tiles are scanned by more than four workgroups (long contexts with few heads: the
+ * scan kernel is then followed by a merge kernel) the partial results (max, sum, output per
+ * part, fp32) go to a file-scope device array of the library instead of the cache's arena.
+ * That array has qaq_static_scratch_limit() bytes (1 MiB; every GPU the library runs on
+ * holds one copy until the process ends) and needs B*Hq*parts*(D+4)*4 of them.  The library
+ * cuts a call into at most four parts per compute unit (1024 on MI355X: 528 KiB at D = 128)
+ * unless a part would then hold more than 64 tiles of 256 tokens; QAQ_ERR_CAPACITY, nothing
+ * launched, if such a shape needs more than the array has.  The call itself allocates nothing and calls no allocating routine.  All calls on
+ * one GPU share the array (nothing in it has to start at zero: every entry a call reads it
+ * has written before), so two such calls that overlap on one GPU -- different streams,
+ * different caches -- race; order them. */
+int qaq_decode_attention_static(qaq_cache* c, const void* dev_q, const void* dev_k_new,
+                                const void* dev_v_new, void* dev_out, int32_t out_is_fp32,
+                                float* dev_scores_out, void* stream);
+size_t qaq_static_scratch_limit(void);
+
 /* Midpoint reconstruction of positions [t0, t1) with outliers restored exactly
  * (Section 4.1 / 4.2), rounded to fp16.  dev_k_out/dev_v_out: fp16 [B, Hkv, t1-t0, D],
  * either may be NULL. */

@@ -423,8 +423,8 @@ int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* de
   return QAQ_OK;
 }
 
-int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
-                         void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
+static int decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
+                            void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream, bool static_scratch) {
   if (!c || !dev_q || !dev_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   if ((dev_k_new == nullptr) != (dev_v_new == nullptr)) return fail(QAQ_ERR_INVALID_ARG, "k_new and v_new must be given together");
   if (c->len == 0 && !dev_k_new) return fail(QAQ_ERR_INVALID_ARG, "empty cache and no new token");
@@ -444,11 +444,28 @@ int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new,
   int kernels = 0;
   const bool timed = !c->prof_ev.empty() && (size_t)(4 * c->prof_n + 4) <= c->prof_ev.size();
   if (timed) ev = &c->prof_ev[4 * c->prof_n];
-  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev, &kernels);
+  bool too_big = false;
+  hipError_t e = qaq_launch_attention(a, (hipStream_t)stream, ev, &kernels, static_scratch, &too_big);
+  if (too_big)
+    return fail(QAQ_ERR_CAPACITY, "qaq_decode_attention_static: the partial results of this shape (%d query heads x %d tiles) "
+                "exceed the library's %zu-byte scratch array; use qaq_decode_attention", c->dims.B * c->dims.Hq,
+                (c->len + QAQ_TT - 1) / QAQ_TT, qaq_static_scratch_bytes());
   if (timed && e == hipSuccess) c->prof_kernels[c->prof_n++] = kernels;
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_attention");
   return QAQ_OK;
 }
+
+int qaq_decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
+                         void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
+  return decode_attention(c, dev_q, dev_k_new, dev_v_new, dev_out, out_is_fp32, dev_scores_out, stream, false);
+}
+
+int qaq_decode_attention_static(qaq_cache* c, const void* dev_q, const void* dev_k_new, const void* dev_v_new,
+                                void* dev_out, int32_t out_is_fp32, float* dev_scores_out, void* stream) {
+  return decode_attention(c, dev_q, dev_k_new, dev_v_new, dev_out, out_is_fp32, dev_scores_out, stream, true);
+}
+
+size_t qaq_static_scratch_limit(void) { return qaq_static_scratch_bytes(); }
 
 int qaq_profile_begin(qaq_cache* c, int32_t max_calls) {
   if (!c || max_calls < 0 || max_calls > 4096) return fail(QAQ_ERR_INVALID_ARG, "bad profile request");

@@ -819,7 +819,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   lds_barrier();
   const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
   const float bias = (S.red[4] + S.red[5]) + (S.red[6] + S.red[7]);
-  float* part = P ? &S.part[0] : v.partial + ((size_t)bq * v.NT + chunk) * (D + 4);
+  float* part = P ? &S.part[0] : a.partial + ((size_t)bq * a.part_stride + chunk) * (D + 4);
   if (g == 0) {
 #pragma unroll
     for (int j = 0; j < CGW; ++j) part[(D / 4) * wave + 16 * j + nn] = xrun[j] + bias + S.xcorr[(D / 4) * wave + 16 * j + nn];
@@ -872,7 +872,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
   const int nparts = a.nparts;
-  const float* part = v.partial + (size_t)bq * v.NT * (D + 4);
+  const float* part = a.partial + (size_t)bq * a.part_stride * (D + 4);
   float* sc = a.scores ? a.scores + (size_t)bq * a.score_stride : nullptr;
   const int t0 = blockIdx.x * (4 * kThreads);
   float raw[4] = {0.f, 0.f, 0.f, 0.f};
@@ -980,10 +980,40 @@ void launch_tile(const QaqAttnArgs& a, int fused_parts, int BQ, size_t lds, hipS
   }
 }
 
+// Scratch for callers that must not allocate (qaq_decode_attention_static): the partial results
+// of the two-kernel form.  One copy per GPU the library runs on, held until the process ends;
+// host code reaches it only through the address hipGetSymbolAddress returns for the current
+// device (the array's name is a host-side stand-in, not a device address).
+constexpr size_t kStaticScratchBytes = 1u << 20;
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];        // per device, filled at the first use on that device
+
+hipError_t static_scratch_ptr(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
 
-hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent_t* ev, int* kernels) {
+size_t qaq_static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent_t* ev, int* kernels,
+                                bool static_scratch, bool* too_big) {
   QaqAttnArgs a = a_in;
+  a.partial = a.v.partial;
+  a.part_stride = a.v.NT;
+  if (too_big) *too_big = false;
   const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
   const int BQ = a.v.B * a.v.Hq;
   // parts per (sequence, query head): as many as keep the whole grid resident at once (four
@@ -1006,6 +1036,17 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   // logits fit its LDS next to the parts' working blocks.
   const bool fused = ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;
   if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
+  if (static_scratch && !fused) {
+    if ((size_t)BQ * (size_t)(a.nparts > 0 ? a.nparts : 1) * (a.v.D + 4) * sizeof(float) > kStaticScratchBytes) {
+      if (too_big) *too_big = true;
+      return hipSuccess;
+    }
+    void* p = nullptr;
+    const hipError_t e = static_scratch_ptr(&p);
+    if (e != hipSuccess) return e;
+    a.partial = (float*)p;
+    a.part_stride = a.nparts > 0 ? a.nparts : 1;
+  }
   if (ntile > 0) {
     const int fp = fused ? a.nparts : 0;
     const size_t lds = fused && a.scores ? (size_t)a.nparts * a.ntc * QAQ_TT * sizeof(float) : 0;

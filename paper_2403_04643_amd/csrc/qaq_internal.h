@@ -123,6 +123,8 @@ struct QaqAttnArgs {
   int score_stride;       // len (+1)
   int ntc;                // most tiles any workgroup of the tile kernel gets (set by the launcher)
   int nparts;             // partials per (sequence, query head)
+  float* partial;         // two-kernel form: [B*Hq][part_stride][D+4] partial results (max, sum, X) of the parts
+  int part_stride;        // partials reserved per (sequence, query head)
 };
 
 struct QaqPrefillArgs {
@@ -156,7 +158,11 @@ hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
 // ev: NULL, or four events that take the start and the end of the dispatch of the tile kernel
 // ([0], [1]) and of the merge kernel ([2], [3], two-kernel form only); *kernels = dispatches
 // made (0 for an empty cache without timing, 1 fused, 2 tile + merge)
-hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev, int* kernels);
+// static_scratch: the partial results of the two-kernel form go to the library's file-scope device
+// array instead of the cache's arena; *too_big is set (and nothing launched) if they do not fit it
+hipError_t qaq_launch_attention(const QaqAttnArgs& a, hipStream_t s, hipEvent_t* ev, int* kernels,
+                                bool static_scratch = false, bool* too_big = nullptr);
+size_t qaq_static_scratch_bytes();
 hipError_t qaq_launch_prefill_window(const QaqPrefillArgs& a, hipStream_t s);
 hipError_t qaq_launch_export(const QaqExportArgs& a, hipStream_t s);
 hipError_t qaq_launch_dequant(const QaqDequantArgs& a, hipStream_t s);

@@ -62,6 +62,8 @@ SIGNATURES = {
     "qaq_stream_read": (C.c_int, [_vp, C.c_size_t, _vp, _vp]),
     "qaq_stream_copy": (C.c_int, [_vp, _vp, C.c_size_t, _vp]),
     "qaq_decode_attention": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _f32p, _vp]),
+    "qaq_decode_attention_static": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _f32p, _vp]),
+    "qaq_static_scratch_limit": (C.c_size_t, []),
     "qaq_dequantize": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp]),
     "qaq_export_canonical": (C.c_int, [_vp, _i32, _u8p, _vp, _u8p, _vp, _u8p, _vp]),
     "qaq_stats": (C.c_int, [_vp, C.POINTER(Stats), _vp]),
@@ -305,6 +307,12 @@ class Cache:
         b = (C.c_float * max(self._prof_cap, 1))()
         _check(self.lib.qaq_profile_read(self.h, a, b, C.byref(n)))
         return list(a[: n.value]), list(b[: n.value])
+
+    def decode_attention_static(self, q, k_new, v_new, out, scores_out=None):
+        """qaq_decode_attention_static: every buffer is the caller's, nothing is allocated."""
+        import torch
+        _check(self.lib.qaq_decode_attention_static(self.h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                    1 if out.dtype == torch.float32 else 0, _ptr(scores_out), _stream()))
 
     def decode_attention(self, q, k_new=None, v_new=None, out=None, scores_out=None, want_scores=False, out_fp32=True):
         """q: fp16 [B, Hq, D]; k_new, v_new: fp16 [B, Hkv, D] or None.
