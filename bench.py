@@ -347,6 +347,7 @@ def main():
     quality = {args.op: {"output_rel_l2_error": output_error(0), "ratio_codes": st1[0].fp16_bytes / st1[0].code_bytes}}
     served_main = sum(b_.served_upgrades - a_.served_upgrades for a_, b_ in zip(st0, st1)) / total_steps
     rec["served_upgrades_per_step"] = served_main
+    rec["update_handovers_last_step"] = [int(x.update_handovers) for x in st1]
     if not args.no_extras:
         # Unquantized copies in page-locked host memory instead of HBM: the update kernel writes
         # the new token there and reads the rows of the tokens that widen, over the host link.

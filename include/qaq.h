@@ -91,6 +91,10 @@ typedef struct {
   int64_t refused_upgrades;  /* widenings asked for without an unquantized copy       */
   int64_t served_upgrades;   /* widenings done from the unquantized copy (each one reads
                                 one fp16 token vector of it), since qaq_create           */
+  int64_t update_handovers;  /* tile sides (of 2 * B * Hkv * tiles) that the last
+                                qaq_decode_update rebuilt with the general kernel instead
+                                of its decode-step kernel (too many tokens moved at once,
+                                or a code region had to move with tokens in it)          */
 } qaq_stats_t;
 
 /* Bytes of device memory the cache needs for this configuration (worst case: every

@@ -18,6 +18,7 @@ struct qaq_cache {
   int len;                         // cached positions per sequence
   int n_o;
   int ring_next;                   // ring row that the next score row goes to
+  int update_parity;               // which of the two hand-over counters the next decode-step update uses
   int row_len[QAQ_MAX_WINDOW];     // tokens covered by each ring row (0 = empty)
   double sigma_s, sigma_x;
   std::vector<hipEvent_t> prof_ev;  // 4 events per profiled attention call
@@ -163,6 +164,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   c->n_o = d.no2 / 2;
   c->len = 0;
   c->ring_next = 0;
+  c->update_parity = 0;
   std::memset(c->row_len, 0, sizeof(c->row_len));
   c->sigma_s = cfg->sigma_s_max;
   c->sigma_x = cfg->sigma_x_max;
@@ -185,6 +187,8 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.partial = (float*)(base + a.partial);
   v.statbuf = (long long*)(base + a.statbuf);
   v.refused = (unsigned int*)(base + a.refused);
+  v.todo = (uint32_t*)(base + a.todo);
+  v.todo_count = (uint32_t*)(base + a.todo_count);
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
   v.has1 = cfg->bit_set[0] == 1;
   v.csr = d.csr;
@@ -356,8 +360,12 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
   thresholds(c, a.len_after, r.tau_k, &r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
-  hipError_t e = qaq_launch_build(a, (a.len_after + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
+  a.todo = c->view.todo;
+  a.todo_count = c->view.todo_count + c->update_parity;
+  a.todo_count_next = c->view.todo_count + (1 - c->update_parity);
+  hipError_t e = qaq_launch_update(a, (a.len_after + QAQ_TT - 1) / QAQ_TT, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_decode_update");
+  c->update_parity ^= 1;
   c->row_len[r.new_row] = a.len_after;
   c->ring_next = (r.new_row + 1) % c->dims.window;
   c->len = a.len_after;
@@ -532,10 +540,10 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   std::memset(out, 0, sizeof(*out));
   out->tokens = c->len;
   long long buf[16] = {0};
-  unsigned int refused[2 * QAQ_NCOUNT] = {0};
+  uint32_t handed[2] = {0, 0};
   hipError_t e = qaq_launch_stats(c->view, c->len, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(handed, c->view.todo_count, sizeof(handed), hipMemcpyDeviceToHost, (hipStream_t)stream);
   if (e == hipSuccess) e = hipMemcpyAsync(buf, c->view.statbuf, sizeof(buf), hipMemcpyDeviceToHost, (hipStream_t)stream);
-  if (e == hipSuccess) e = hipMemcpyAsync(refused, c->view.refused, sizeof(refused), hipMemcpyDeviceToHost, (hipStream_t)stream);
   if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_stats");
   static const int widths[4] = {2, 3, 4, 8};
@@ -551,10 +559,9 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   out->layout_code_bytes = buf[8];
   out->meta_bytes = buf[9];
   out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
-  for (int i = 0; i < QAQ_NCOUNT; ++i) {
-    out->refused_upgrades += refused[i];
-    out->served_upgrades += refused[QAQ_NCOUNT + i];
-  }
+  out->update_handovers = (long long)handed[0] + handed[1];     // (the counter of the step to come is zero)
+  out->refused_upgrades = buf[12];
+  out->served_upgrades = buf[13];
   return QAQ_OK;
 }
 

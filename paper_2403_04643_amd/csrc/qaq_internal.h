@@ -25,7 +25,9 @@ struct QaqView {
   int ring_half;
   float* partial;
   long long* statbuf;
-  unsigned int* refused;   // [0] widenings refused for want of the unquantized copy, [1] widenings served
+  unsigned int* refused;   // per tile side: [0] widenings refused for want of the unquantized copy, [1] widenings served
+  uint32_t* todo;          // [B][Hkv][NT][2] list of tile sides a decode-step update hands to the general kernel
+  uint32_t* todo_count;    // [2] entries of the list; the two counters serve alternate steps
   int B, Hq, Hkv, D, Tmax, NT, no2, window;
   int has1;                // the width set contains 1: kernels take their five-class variants
   int csr;                 // outliers by thresholds: oidx / oval are per-tile pools in position order, addressed
@@ -95,6 +97,10 @@ struct QaqBuildArgs {
   const __half* orig[2];       // requantize: [B,Hkv,orig_tokens,D] or null
   __half* orig_put[2];         // same buffers when the appended tokens are to be written into them, else null
   int orig_tokens;             // token extent of the unquantized copies (>= len)
+  // decode-step update: tile sides the fast kernel leaves to the general one, (unit * NT + tile) * 2 + side
+  uint32_t* todo;
+  uint32_t* todo_count;        // the counter this step appends through (zero when the step starts)
+  uint32_t* todo_count_next;   // the next step's counter (this step clears it)
 };
 
 struct QaqSelectArgs {
@@ -154,6 +160,9 @@ struct QaqDequantArgs {
 // launchers (each returns the hipError_t of the launch)
 hipError_t qaq_launch_init(const QaqView& v, hipStream_t s);
 hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s);
+// decode-step update (a.mode == 2): the fast kernel where the configuration has one, followed by the
+// general kernel on the tile sides it handed over; else the general kernel on every tile side
+hipError_t qaq_launch_update(const QaqBuildArgs& a, int ntiles, hipStream_t s);
 hipError_t qaq_launch_select(const QaqSelectArgs& a, hipStream_t s);
 // ev: NULL, or four events that take the start and the end of the dispatch of the tile kernel
 // ([0], [1]) and of the merge kernel ([2], [3], two-kernel form only); *kernels = dispatches

@@ -39,7 +39,6 @@
 
 #define QAQ_TT 256           // positions per tile
 #define QAQ_MAX_NO2 8        // 2 * max outliers per side
-#define QAQ_NCOUNT 64         // partial counters per kind of widening (spreads the atomics)
 
 #if defined(__HIPCC__)
 #define QAQ_HD __host__ __device__ __forceinline__
@@ -182,7 +181,10 @@ struct QaqArena {
   size_t ring;        // f32 (or fp16) [window][B][Hkv][Tmax]
   size_t partial;     // f32  [B][Hq][NT][D+4]
   size_t statbuf;     // i64  [32]
-  size_t refused;     // u32  [2][QAQ_NCOUNT] widenings refused / served, partial counts
+  size_t refused;     // u32  [B][Hkv][NT][2 sides][2] widenings refused / served, counted per tile side by the
+                      // workgroup that owns it (plain read-modify-write: no atomics)
+  size_t todo;        // u32  [B][Hkv][NT][2] tile sides a decode-step update leaves to the general build kernel
+  size_t todo_count;  // u32  [2]
   // variable-length side store (outliers by thresholds) only: oidx / oval are then per-tile pools
   // of 256 * no2 entries filled in position order
   size_t ostart[2];   // u16  [B][Hkv][Tmax]  by position: first entry of the token in its tile's pool
@@ -210,7 +212,9 @@ inline QaqArena qaq_carve(const QaqDims& d) {
   a.ring = off; off = qaq_up256(off + (size_t)d.window * bh * d.Tmax * (d.ring_half ? 2 : 4));
   a.partial = off; off = qaq_up256(off + (size_t)d.B * d.Hq * d.NT * (d.D + 4) * 4);
   a.statbuf = off; off = qaq_up256(off + 32 * 8);
-  a.refused = off; off = qaq_up256(off + 2 * QAQ_NCOUNT * 4);
+  a.refused = off; off = qaq_up256(off + bh * d.NT * 2 * 2 * 4);
+  a.todo = off; off = qaq_up256(off + bh * d.NT * 2 * 4);
+  a.todo_count = off; off = qaq_up256(off + 2 * 4);
   a.ostart[0] = a.ostart[1] = a.ocnt[0] = a.ocnt[1] = a.othr = 0;
   if (d.csr) {
     for (int s = 0; s < 2; ++s) { a.ostart[s] = off; off = qaq_up256(off + bh * d.Tmax * 2); }

@@ -130,6 +130,7 @@ struct BuildLds {
   float wave_bound[4];
   float wave_bound2[4];
   int wave_ocnt[4];                        // variable-length side store: entries of the new tokens per wavefront
+  int wave_wide[4];                        // widenings asked for, per wavefront
 };
 constexpr int kKeptFlag = 0x80;
 
@@ -725,33 +726,34 @@ __device__ void pack_masked_v(uint8_t* base, const QaqCounts& c, const QaqCounts
 }
 
 // ---------------------------------------------------------------------------------
-// Widenings asked for in this wavefront: one atomic per wavefront that has any, spread over
-// QAQ_NCOUNT counters per kind (v.refused[kind * QAQ_NCOUNT + i]; kind 0 = refused for want of
-// the unquantized copy, 1 = served); the host sums them.
-__device__ __forceinline__ void count_widenings(const QaqView& v, bool wider, bool served) {
+// Widenings asked for in a tile side: every wavefront leaves its count in LDS (`per_wave`,
+// four entries); after the next barrier add_widenings, called by one thread, adds them to the
+// tile side's own counters (kind 0 = refused for want of the unquantized copy, 1 = served).
+// A tile side is only ever written by the workgroup that owns it, so no atomics are needed;
+// the accounting kernel sums the counters.
+__device__ __forceinline__ void note_widenings(int* per_wave, bool wider) {
   const unsigned long long bal = __ballot(wider);
-  if (bal != 0ull && (threadIdx.x & 63) == 0)
-    atomicAdd(v.refused + (served ? QAQ_NCOUNT : 0) + ((blockIdx.y + 5 * blockIdx.x + (threadIdx.x >> 6)) & (QAQ_NCOUNT - 1)),
-              (unsigned int)__popcll(bal));
+  if ((threadIdx.x & 63) == 0) per_wave[threadIdx.x >> 6] = __popcll(bal);
+}
+__device__ __forceinline__ void add_widenings(const QaqView& v, size_t tile_side, const int* per_wave, bool served) {
+  const int n = per_wave[0] + per_wave[1] + per_wave[2] + per_wave[3];
+  if (n) v.refused[tile_side * 2 + (served ? 1 : 0)] += (unsigned int)n;
 }
 
 // HAS1: the width set contains 1 (five classes); without it the fifth class costs nothing.
+// One tile side (unit bh, tile, side) of a build.
 template <int D, bool ONE, bool HAS1>
-__global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
+__device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, const int tile, const int side) {
   constexpr int MAXO = ONE ? 2 : QAQ_MAX_NO2;
+  __shared__ BuildLds<D, MAXO> L;
   constexpr int NC = HAS1 ? QAQ_NCLASS : 4;
   auto bits_at = [](const QaqCounts& c, int s) { return HAS1 ? c.bits_of_slot(s) : c.bits_of_slot4(s); };
-  __shared__ BuildLds<D, MAXO> L;
   constexpr int SROW = BuildLds<D, MAXO>::SROW;
 
   const QaqView& v = a.v;
   const bool csr = !ONE && v.csr;     // (the one-per-end build never has the variable-length side store)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // heads are the fastest grid dimension: with tiles fastest and a tile count that is a multiple
-  // of eight, every die would see the same two tile indices of every head, which ran 30 % slower
-  const int tile = a.tile0 + blockIdx.y;
-  const int bh = blockIdx.x, b = bh / v.Hkv, h = bh % v.Hkv;
-  const int side = blockIdx.z;
+  const int b = bh / v.Hkv, h = bh % v.Hkv;
   const int t0 = tile * QAQ_TT;
   const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
   const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
@@ -820,8 +822,10 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (req < oldb) changed = true;
       else if (req > oldb) { wider = true; if (a.orig[side]) changed = true; }
     }
-    count_widenings(v, wider, a.orig[side] != nullptr);
-    if (!__syncthreads_or(changed ? 1 : 0)) return;
+    note_widenings(L.wave_wide, wider);
+    const bool any = __syncthreads_or(changed ? 1 : 0) != 0;
+    if (tid == 0) add_widenings(v, (qaq_bh(v, b, h) * v.NT + tile) * 2 + side, L.wave_wide, a.orig[side] != nullptr);
+    if (!any) return;
   }
 
   // metadata by position
@@ -872,9 +876,11 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
       if (req_rule < oldb) changed = true;
       else if (req_rule > oldb) { wider = true; if (a.orig[side]) changed = true; }
     }
-    count_widenings(v, wider, a.orig[side] != nullptr);
+    note_widenings(L.wave_wide, wider);
     const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
-    if (!__syncthreads_or(changed ? 1 : 0) && !has_new) return;
+    const bool any = __syncthreads_or(changed ? 1 : 0) != 0;
+    if (tid == 0) add_widenings(v, (qaq_bh(v, b, h) * v.NT + tile) * 2 + side, L.wave_wide, a.orig[side] != nullptr);
+    if (!any && !has_new) return;
   }
 
   // final width of every position; whether it is encoded in this pass (new tokens, and
@@ -1230,6 +1236,567 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
   else pack_tile<D, MAXO, HAS1>(side, base, cn, c_old, L);
 }
 
+// Grid (units, tiles, 2 sides) -- heads are the fastest grid dimension: with tiles fastest and a
+// tile count that is a multiple of eight, every die would see the same two tile indices of every
+// head, which ran 30 % slower.  Or, given a list (a.todo: entries (unit * NT + tile) * 2 + side,
+// a.todo_count of them, both in device memory), a one-dimensional grid whose workgroups share
+// out the listed tile sides.
+template <int D, bool ONE, bool HAS1>
+__global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
+  const bool listed = a.todo != nullptr;
+  const uint32_t n = listed ? *a.todo_count : 1u;
+  for (uint32_t i = listed ? blockIdx.x : 0u; i < n; i += listed ? gridDim.x : 1u) {
+    int bh = (int)blockIdx.x, tile = a.tile0 + (int)blockIdx.y, side = (int)blockIdx.z;
+    if (listed) {
+      const uint32_t e = a.todo[i];
+      bh = (int)((e >> 1) / (uint32_t)a.v.NT); tile = (int)((e >> 1) % (uint32_t)a.v.NT); side = (int)(e & 1u);
+    }
+    build_tile<D, ONE, HAS1>(a, bh, tile, side);
+    if (listed) __syncthreads();        // the next tile side reuses the staging memory
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Decode-step update, fast kernel (Section 4.2 "Integration in text generation process": the
+// part of a step after the attention).  Same result as build_tile in mode 2, for the common
+// configuration (one outlier per end, fixed-length side store, widths within {2,3,4,8}), built
+// for what a decode step does to a tile: a few tokens change width, one token is appended to
+// the last tile, everything else stays.  A workgroup evaluates the rules for its tile side,
+// leaves at once if nothing moves, re-assigns slots so that as few tokens move as possible
+// (a token keeps its place inside its region; regions whose start would move with tokens still
+// in them, and tiles in which more than kMaxMoved tokens move, are handed to the general
+// kernel through a list), and carries only the moved tokens' codes through LDS.  A fifth of
+// the general kernel's LDS and half its registers: eight workgroups per compute unit hide its
+// two dependent round trips to memory.
+// ---------------------------------------------------------------------------------
+constexpr int kMaxMoved = 64;
+
+template <int D>
+struct UpdLds {
+  static constexpr int SROW = D / 4 + 1;   // dwords per staged row (odd stride: rows spread over the banks)
+  float pred[QAQ_TT];                      // value side: predicted score by position
+  uint32_t stage[kMaxMoved * SROW];        // codes of the moved tokens at their new width, byte d = channel d
+  uint32_t mv_a[kMaxMoved];                // moved list: token (thread) index | new slot << 16
+  uint32_t mv_b[kMaxMoved];                // ... old width | new width << 8 | position << 16
+  uint32_t mv_mm[kMaxMoved];               // ... fp16 min | max << 16
+  uint8_t cls_new[QAQ_TT];                 // by token: class after this step (0xff: no token)
+  uint8_t m_of_slot[QAQ_TT];               // by new slot: index in the moved list, 0xff = what is stored stays
+  uint8_t freeslot[QAQ_TT];                // per class, in slot order: the slots no token keeps
+  uint32_t mask2[16], mask4[32];           // value side: slots to write per unit of 16 (2-bit fields) / half-unit of 8 (4-bit)
+  int wave_cnt[4][4], wave_need[4][4], wave_free[4][4];
+  int wave_moved[4];
+  int wave_wide[4];                        // widenings asked for, per wavefront
+  float wave_bound[4], wave_bound2[4];
+  uint32_t new_mm, new_oi, new_ov;         // the appended token: min | max, outlier channels, outlier values
+  uint32_t newrow[D / 4];                  // ... its codes at the widest width, byte d = channel d
+};
+
+// unsigned wavefront reductions on the data-parallel-primitive path
+__device__ __forceinline__ uint32_t wave_umax(uint32_t x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = (uint32_t)__shfl_xor((int)x, o); x = x > y ? x : y; }
+  return x;
+}
+__device__ __forceinline__ uint32_t wave_umin(uint32_t x) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = (uint32_t)__shfl_xor((int)x, o); x = x < y ? x : y; }
+  return x;
+}
+__device__ __forceinline__ uint16_t key16_bits(uint32_t key) {     // fp16 bits of a key made by order_keys_pair (upper half)
+  const uint32_t k = key >> 16;
+  return (uint16_t)(k >= 0x8000u ? k - 0x8000u : ((0x8000u - k) | 0x8000u));
+}
+__device__ __forceinline__ uint32_t width_mask(int bits) { return 0x01010101u * ((1u << bits) - 1u); }
+
+// Four codes (channels 4*c4 .. 4*c4+3, one per byte) of the token in old slot `slot`, keys.  The
+// class only selects addresses, shifts and masks: the loads themselves are unconditional (two, the
+// second one repeating the first where the token has no low-bit plane), so that they are in
+// flight together.
+template <int D>
+__device__ __forceinline__ uint32_t k_old_codes(const uint8_t* base, const QaqCounts& c, const QaqKRegions& r, int slot, int c4) {
+  constexpr int KS = D / 64;
+  const int d = 4 * c4, ks = d / 64, g = (d % 64) / 16, vq = (d % 16) / 4;
+  const int q = g * KS + ks;
+  const int n32 = c.n32();
+  const bool f2 = slot < n32, f3 = slot < c.n3, f4 = !f2 && slot < n32 + c.n4;
+  const uint32_t off = f2 ? r.r2 + (uint32_t)slot * (D / 4) + 4u * (uint32_t)q
+                     : f4 ? r.r4 + (uint32_t)(slot - n32) * (D / 2) + 4u * (uint32_t)(2 * q + (vq >> 1))
+                          : r.r8 + (uint32_t)(slot - n32 - c.n4) * D + 4u * (uint32_t)(4 * q + vq);
+  const uint32_t offl = f3 ? r.r1 + (uint32_t)slot * (D / 8) + 4u * (uint32_t)(q >> 1) : off;
+  const uint32_t w = *(const uint32_t*)(base + off);
+  const uint32_t wl = *(const uint32_t*)(base + offl);
+  const int sh = f2 ? 2 * vq : f4 ? 4 * (vq & 1) : 0;
+  const uint32_t msk = f2 ? 0x03030303u : f4 ? 0x0f0f0f0fu : 0xffffffffu;
+  uint32_t code = ((w >> sh) & msk) ^ (f2 || f4 ? 0u : 0x80808080u);
+  if (f3) code = (code << 1) | ((wl >> (4 * (q & 1) + vq)) & 0x01010101u);
+  return code;
+}
+
+// The same for values (transposed units: one load per channel, and one more per channel for the
+// low-bit plane of a 3-bit token; eight unconditional loads, or one for an 8-bit token).
+template <int D>
+__device__ __forceinline__ uint32_t v_old_codes(const uint8_t* base, const QaqCounts& c, const QaqVRegions& r, int slot, int c4) {
+  const int n32 = c.n32();
+  const int n0 = 4 * (c4 & 3), cg = c4 >> 2;
+  if (slot >= n32 + c.n4) return *(const uint32_t*)(base + r.r8 + (uint32_t)(slot - n32 - c.n4) * D + 4u * (uint32_t)c4);
+  const bool f2 = slot < n32, f3 = slot < c.n3;
+  const int idx = f2 ? slot : slot - n32;
+  const int u = f2 ? idx >> 4 : idx >> 3, i = f2 ? idx & 15 : idx & 7;
+  const uint32_t off = (f2 ? r.r2 : r.r4) + (uint32_t)u * (4u * D) + 4u * (uint32_t)(n0 * (D / 16) + cg);
+  const int sh = f2 ? 8 * (i & 3) + 2 * (i >> 2) : 8 * (i & 3) + 4 * (i >> 2);
+  const uint32_t msk = f2 ? 3u : 15u;
+  // low-bit plane of a 3-bit token: word (n, cg / 2) of unit u, bit 8*(i%4) + 4*(cg%2) + i/4
+  const uint32_t offl = f3 ? r.r1 + (uint32_t)u * (2u * D) + 4u * (uint32_t)(n0 * (D / 32) + (cg >> 1)) : off;
+  const uint32_t stl = f3 ? D / 8 : D / 4;
+  uint32_t w[4], l[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) w[k] = *(const uint32_t*)(base + off + (uint32_t)k * (D / 4));
+#pragma unroll
+  for (int k = 0; k < 4; ++k) l[k] = *(const uint32_t*)(base + offl + (uint32_t)k * stl);
+  uint32_t code = 0u;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) code |= ((w[k] >> sh) & msk) << (8 * k);
+  if (f3) {
+    const int shl = 8 * (i & 3) + 4 * (cg & 1) + (i >> 2);
+    uint32_t low = 0u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) low |= ((l[k] >> shl) & 1u) << (8 * k);
+    code = (code << 1) | low;
+  }
+  return code;
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
+  __shared__ UpdLds<D> L;
+  constexpr int SROW = UpdLds<D>::SROW, NQ = D / 16, KS = D / 64;
+  const QaqView& v = a.v;
+  const QaqRuleArgs& ru = a.rule;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int bh = blockIdx.x, b = bh / v.Hkv, h = bh % v.Hkv;
+  const int tile = blockIdx.y, side = blockIdx.z;
+  const int t0 = tile * QAQ_TT;
+  const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
+  const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
+  if (bh == 0 && tile == 0 && side == 0 && tid == 0) *a.todo_count_next = 0u;
+  if (n_after == 0) return;
+  const bool has_new = n_after > n_before;           // the appended token is position n_before of this tile
+  const size_t tile_id = qaq_bh(v, b, h) * v.NT + tile;
+  // keys: the tile recorded, when it was built, the interval of thresholds for which none of its
+  // tokens changes width (one 8-byte load decides)
+  if (side == 0 && !has_new && !ru.out_bits[0]) {
+    const float2 keep = ((const float2*)v.kthr)[tile_id];
+    const float tau = ru.tau_k[h];
+    if (tau >= keep.x && tau < keep.y) return;
+  }
+
+  // ---- everything whose address is known up front ------------------------------------------------
+  uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
+  QaqCounts c_old;
+  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = c_old.n1 = 0;
+  if (n_before > 0) { c_old = qaq_load_counts(v, side, b, h, tile, n_before); c_old.n1 = 0; }
+  const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+  // thread t is token t: the cached token in old slot t, or (t == n_before) the appended one
+  uint32_t mm = 0, oi = 0, ov = 0;
+  int pos = tid;
+  if (tid < n_before) {
+    mm = v.mm[side][gi0 + tid];
+    pos = v.perm[side][gi0 + tid];
+    oi = *(const uint16_t*)(v.oidx[side] + (gi0 + tid) * 2);
+    ov = *(const uint32_t*)(v.oval[side] + (gi0 + tid) * 2);
+  }
+  if (side == 1 && tid < n_after) {      // thread t as position t: the window (Section 4.2), this step's row stored
+    const int t = t0 + tid;
+    const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
+    const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
+    float s = 0.0f;
+    for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
+    s = qaq_ring_value(v, s);
+    float pred = s;
+    for (int r = 0; r < v.window; ++r) {
+      if (r == ru.new_row) continue;
+      if (t < ru.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
+    }
+    qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
+    L.pred[tid] = pred;
+  }
+  L.cls_new[tid] = 0xffu;
+  L.m_of_slot[tid] = 0xffu;
+  if (tid < 32) L.mask4[tid] = 0u;
+
+  // ---- the appended token: outliers, range, codes at the widest width (Section 4.2 "Outliers",
+  // Section 4.1 quantizer), by the last wavefront, two channels per lane -------------------------------
+  if (has_new && wave == 3) {
+    const bool act = 2 * lane < D;
+    const uint32_t* src = (const uint32_t*)(a.newx[side] + (size_t)bh * a.n_new * D);
+    const uint32_t w = act ? src[lane] : 0u;
+    if (act && a.orig_put[side]) ((uint32_t*)(a.orig_put[side] + ((size_t)bh * a.orig_tokens + a.len_before) * D))[lane] = w;
+    const uint32_t kk = order_keys_pair(w);
+    const int ch0 = 2 * lane, ch1 = 2 * lane + 1;
+    const uint32_t k0 = kk << 16, k1 = kk & 0xffff0000u;
+    // largest value, lowest channel first; then the smallest of the rest, lowest channel first
+    const uint32_t A1 = wave_umax(act ? max(k0 | (uint32_t)(127 - ch0), k1 | (uint32_t)(127 - ch1)) : 0u);
+    const int ch_top = 127 - (int)(A1 & 127u);
+    const uint32_t n0 = act && ch0 != ch_top ? (k0 | (uint32_t)ch0) : 0xffffffffu;
+    const uint32_t n1 = act && ch1 != ch_top ? (k1 | (uint32_t)ch1) : 0xffffffffu;
+    const uint32_t B1 = wave_umin(min(n0, n1));
+    const int ch_bot = (int)(B1 & 127u);
+    // [min, max] of what remains
+    const bool in0 = act && ch0 != ch_top && ch0 != ch_bot, in1 = act && ch1 != ch_top && ch1 != ch_bot;
+    const uint32_t A2 = wave_umax(max(in0 ? k0 : 0u, in1 ? k1 : 0u));
+    const uint32_t B2 = wave_umin(min(in0 ? k0 : 0xffffffffu, in1 ? k1 : 0xffffffffu));
+    const uint32_t mn_b = key16_bits(B2), mx_b = key16_bits(A2);
+    const uint32_t wt = (uint32_t)__shfl((int)w, ch_top >> 1), wb = (uint32_t)__shfl((int)w, ch_bot >> 1);
+    const uint32_t v_top = (wt >> (16 * (ch_top & 1))) & 0xffffu, v_bot = (wb >> (16 * (ch_bot & 1))) & 0xffffu;
+    const float mn = h2f((uint16_t)mn_b), mx = h2f((uint16_t)mx_b);
+    const float range = mx - mn;
+    const float levels = (float)(1 << a.widest);
+    const float inv = range > 0.0f ? levels / range : 0.0f;
+    const float top_code = levels - 1.0f;
+    uint32_t cw = 0u;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const float diff = h2f((uint16_t)(w >> (16 * e))) - mn;
+      const float prod = diff * inv;
+      cw = __builtin_amdgcn_cvt_pk_u8_f32(fminf(floorf(prod), top_code), e, cw);
+    }
+    if (act) ((uint16_t*)L.newrow)[lane] = (uint16_t)cw;
+    if (lane == 0) {
+      L.new_mm = mn_b | (mx_b << 16);
+      const bool top_first = ch_top < ch_bot;                 // the side store is ordered by channel
+      L.new_oi = top_first ? ((uint32_t)ch_top | ((uint32_t)ch_bot << 8)) : ((uint32_t)ch_bot | ((uint32_t)ch_top << 8));
+      L.new_ov = top_first ? (v_top | (v_bot << 16)) : (v_bot | (v_top << 16));
+    }
+  }
+  __syncthreads();
+  const bool is_new = has_new && tid == n_before;
+  if (is_new) { mm = L.new_mm; oi = L.new_oi; ov = L.new_ov; pos = n_before; }
+
+  // ---- widths by the rules of Section 4.1 -----------------------------------------------------------
+  const float mnf = h2f((uint16_t)(mm & 0xffffu)), mxf = h2f((uint16_t)(mm >> 16));
+  const float range = mxf - mnf;
+  int ob = 0, nb = 0;
+  bool changed = false, wider = false;
+  if (tid < n_after) {
+    const float lhs = side == 0 ? range : range * L.pred[pos];
+    const float thr = side == 0 ? ru.tau_k[h] : ru.c_v;
+    int req = ru.bit_set[ru.nbits - 1];
+    for (int i = ru.nbits - 1; i >= 0; --i)
+      if (lhs <= ldexpf(thr, ru.bit_set[i])) req = ru.bit_set[i];
+    if (ru.out_bits[side]) ru.out_bits[side][(size_t)bh * a.len_after + t0 + pos] = (uint8_t)req;
+    if (is_new) {
+      ob = a.widest; nb = req; changed = true;       // encoded at the widest width; narrowing drops low bits
+    } else {
+      ob = c_old.bits_of_slot4(tid);
+      nb = ob;
+      if (req < ob) nb = req;
+      else if (req > ob) { wider = true; if (a.orig[side]) nb = req; }
+      changed = nb != ob;
+    }
+  }
+  const bool served = a.orig[side] != nullptr;
+  note_widenings(L.wave_wide, wider);
+  if (!__syncthreads_or(changed ? 1 : 0)) {          // nothing moves and nothing is appended
+    if (tid == 0) add_widenings(v, tile_id * 2 + side, L.wave_wide, served);
+    return;
+  }
+
+  // ---- new class counts; what the attention kernel and the next step's skip test need of the tile ------
+  const int cls = tid < n_after ? qaq_class_of_bits(nb) : -1;
+  const int ocls = (tid < n_before) ? qaq_class_of_bits(ob) : -1;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const unsigned long long bal = __ballot(cls == c);
+    if (lane == 0) L.wave_cnt[c][wave] = __popcll(bal);
+  }
+  if (tid < n_after) L.cls_new[tid] = (uint8_t)cls;
+  if (side == 1) {
+    float bnd = 0.0f;
+    if (tid < n_after) {
+      bnd = ldexpf(range, nb == 3 ? -2 : -nb);
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const float o = h2f((uint16_t)(ov >> (16 * k)));
+        bnd = fmaxf(bnd, fmaxf(fabsf(o - mxf), fabsf(o - mnf)) + range);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) bnd = fmaxf(bnd, __shfl_xor(bnd, o));
+    if (lane == 0) L.wave_bound[wave] = bnd;
+  } else {
+    float lo = 0.0f, hi = INFINITY;
+    if (tid < n_after) {
+      int narrower = 0;
+      for (int i = 0; i < ru.nbits; ++i)
+        if (ru.bit_set[i] < nb) narrower = ru.bit_set[i];
+      if (nb < ru.bit_set[ru.nbits - 1]) lo = ldexpf(range, -nb);
+      if (narrower > 0) hi = ldexpf(range, -narrower);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { lo = fmaxf(lo, __shfl_xor(lo, o)); hi = fminf(hi, __shfl_xor(hi, o)); }
+    if (lane == 0) { L.wave_bound[wave] = lo; L.wave_bound2[wave] = hi; }
+  }
+  __syncthreads();
+  QaqCounts cn;
+  cn.n3 = L.wave_cnt[QC3][0] + L.wave_cnt[QC3][1] + L.wave_cnt[QC3][2] + L.wave_cnt[QC3][3];
+  cn.n2 = L.wave_cnt[QC2][0] + L.wave_cnt[QC2][1] + L.wave_cnt[QC2][2] + L.wave_cnt[QC2][3];
+  cn.n4 = L.wave_cnt[QC4][0] + L.wave_cnt[QC4][1] + L.wave_cnt[QC4][2] + L.wave_cnt[QC4][3];
+  cn.n8 = L.wave_cnt[QC8][0] + L.wave_cnt[QC8][1] + L.wave_cnt[QC8][2] + L.wave_cnt[QC8][3];
+  cn.n1 = 0;
+
+  // ---- slots.  A token's codes sit at an index inside its class's region (2- and 3-bit tokens: the
+  // slot; 4-bit: slot minus the 2/3-bit tokens; 8-bit: minus the 4-bit ones as well).  A cached token
+  // that stays in its class keeps that index if the region still reaches it; the others -- tokens that
+  // change class, tokens squeezed out, the appended one -- take the free indices of their class in order.
+  const int n32o = c_old.n32(), n32n = cn.n32();
+  bool mv3, mv4, mv8;       // the region a class alone owns starts elsewhere than before (the 2-bit fields start the tile side)
+  if (side == 0) {
+    const QaqKRegions r0 = qaq_k_regions(c_old, D), r1 = qaq_k_regions(cn, D);
+    mv3 = r0.r1 != r1.r1; mv4 = r0.r4 != r1.r4; mv8 = r0.r8 != r1.r8;
+  } else {
+    const QaqVRegions r0 = qaq_v_regions(c_old, D), r1 = qaq_v_regions(cn, D);
+    mv3 = r0.r1 != r1.r1; mv4 = r0.r4 != r1.r4; mv8 = r0.r8 != r1.r8;
+  }
+  auto old_index = [&](int c, int slot) { return c == QC4 ? slot - n32o : c == QC8 ? slot - n32o - c_old.n4 : slot; };
+  auto new_slot_of = [&](int c, int idx) { return c == QC4 ? n32n + idx : c == QC8 ? n32n + cn.n4 + idx : idx; };
+  bool keep = false;
+  int my_slot = -1;
+  if (ocls >= 0 && cls == ocls) {
+    const int idx = old_index(cls, tid);
+    keep = cls == QC3 ? idx < cn.n3 : cls == QC2 ? (idx >= cn.n3 && idx < n32n) : cls == QC4 ? idx < cn.n4 : idx < cn.n8;
+    if (keep) my_slot = new_slot_of(cls, idx);
+  }
+  // a kept token whose region starts elsewhere than before would have to be copied: such tiles (rare: a
+  // region start moves when a count crosses a multiple of 16) go to the general kernel
+  const bool stranded = keep && ((cls == QC3 && mv3) || (cls == QC4 && mv4) || (cls == QC8 && mv8));
+  const bool need = cls >= 0 && !keep;
+  // thread s as slot s of the new order: free unless the token that could keep it does
+  int slot_cls = -1;
+  bool is_free = false;
+  if (tid < n_after) {
+    slot_cls = qaq_class_of_bits(cn.bits_of_slot4(tid));
+    const int idx = slot_cls == QC4 ? tid - n32n : slot_cls == QC8 ? tid - n32n - cn.n4 : tid;
+    const int cand = slot_cls == QC4 ? idx + n32o : slot_cls == QC8 ? idx + n32o + c_old.n4 : idx;    // the old slot with that index
+    const bool taken = cand < n_before && qaq_class_of_bits(c_old.bits_of_slot4(cand)) == slot_cls && L.cls_new[cand] == slot_cls;
+    is_free = !taken;
+  }
+  int need_rank = 0, free_rank = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const unsigned long long bn = __ballot(need && cls == c);
+    const unsigned long long bf = __ballot(is_free && slot_cls == c);
+    if (lane == 0) { L.wave_need[c][wave] = __popcll(bn); L.wave_free[c][wave] = __popcll(bf); }
+    if (need && cls == c) need_rank = __popcll(bn & ((1ull << lane) - 1ull));
+    if (is_free && slot_cls == c) free_rank = __popcll(bf & ((1ull << lane) - 1ull));
+  }
+  const unsigned long long bal_need = __ballot(need);
+  if (lane == 0) L.wave_moved[wave] = __popcll(bal_need);
+  const bool hand_over = __syncthreads_or(stranded ? 1 : 0) != 0;
+  const int n_moved = L.wave_moved[0] + L.wave_moved[1] + L.wave_moved[2] + L.wave_moved[3];
+  if (hand_over || n_moved > kMaxMoved) {
+    // nothing of the cache has been written yet (the window row and the width outputs are the same
+    // numbers when the general kernel writes them again)
+    if (tid == 0) a.todo[atomicAdd(a.todo_count, 1u)] = (uint32_t)(tile_id * 2 + side);
+    return;
+  }
+  if (is_free) {
+    int r = cn.start(slot_cls) + free_rank;
+    for (int w = 0; w < wave; ++w) r += L.wave_free[slot_cls][w];
+    L.freeslot[r] = (uint8_t)tid;
+  }
+  __syncthreads();
+  int m_idx = -1;
+  if (need) {
+    int r = cn.start(cls) + need_rank;
+    for (int w = 0; w < wave; ++w) r += L.wave_need[cls][w];
+    my_slot = L.freeslot[r];
+    m_idx = __popcll(bal_need & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) m_idx += L.wave_moved[w];
+    L.mv_a[m_idx] = (uint32_t)tid | ((uint32_t)my_slot << 16);
+    L.mv_b[m_idx] = (uint32_t)ob | ((uint32_t)nb << 8) | ((uint32_t)pos << 16);
+    L.mv_mm[m_idx] = mm;
+    L.m_of_slot[my_slot] = (uint8_t)m_idx;
+  }
+  __syncthreads();
+
+  // ---- value side: which slots of which units are written ---------------------------------------------
+  if (side == 1) {
+    const bool wr = tid < n_after && L.m_of_slot[tid] != 0xffu;
+    const unsigned long long bal = __ballot(wr && tid < n32n);
+    if (lane < 4) L.mask2[4 * wave + lane] = (uint32_t)(bal >> (16 * lane)) & 0xffffu;
+    if (wr && tid >= n32n && tid < n32n + cn.n4) atomicOr(&L.mask4[(tid - n32n) >> 3], 1u << ((tid - n32n) & 7));
+  }
+
+  // ---- codes of the moved tokens -> LDS, at the new width: four channels per work item -----------------
+  {
+    const QaqKRegions rk0 = qaq_k_regions(c_old, D);
+    const QaqVRegions rv0 = qaq_v_regions(c_old, D);
+    for (int it = tid; it < n_moved * (D / 4); it += kThreads) {
+      const int m = it / (D / 4), c4 = it % (D / 4);
+      const uint32_t ma = L.mv_a[m], mb = L.mv_b[m];
+      const int tok = (int)(ma & 0xffffu), o_b = (int)(mb & 0xffu), n_b = (int)((mb >> 8) & 0xffu), p = (int)(mb >> 16);
+      uint32_t codes;
+      if (has_new && tok == n_before) {
+        codes = (L.newrow[c4] >> (o_b - n_b)) & width_mask(n_b);
+      } else if (n_b > o_b) {
+        // wider: from the unquantized copy, with the stored [min, max] (Section 4.2 "Integration")
+        const uint2 raw = *(const uint2*)(a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D + 4 * c4);
+        const uint32_t m2 = L.mv_mm[m];
+        const float mn = h2f((uint16_t)(m2 & 0xffffu)), mx = h2f((uint16_t)(m2 >> 16));
+        const float rg = mx - mn;
+        const float levels = (float)(1 << n_b);
+        const float inv = rg > 0.0f ? levels / rg : 0.0f;
+        const float top_code = levels - 1.0f;
+        codes = 0u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t hw = e < 2 ? raw.x : raw.y;
+          const float diff = h2f((uint16_t)(hw >> (16 * (e & 1)))) - mn;
+          const float prod = diff * inv;
+          codes = __builtin_amdgcn_cvt_pk_u8_f32(fminf(floorf(prod), top_code), e, codes);
+        }
+      } else {
+        codes = side == 0 ? k_old_codes<D>(base, c_old, rk0, tok, c4) : v_old_codes<D>(base, c_old, rv0, tok, c4);
+        codes = (codes >> (o_b - n_b)) & width_mask(n_b);
+      }
+      L.stage[m * SROW + c4] = codes;
+    }
+  }
+  __syncthreads();      // every read of the old layout is done
+
+  // ---- metadata: tokens whose slot changed (moved ones, and 4-/8-bit tokens behind a moved class
+  // border), widths by position, class counts, the tile's bounds --------------------------------------
+  if (tid < n_after && (my_slot != tid || need)) {
+    const size_t gi = gi0 + my_slot;
+    v.mm[side][gi] = mm;
+    v.perm[side][gi] = (uint8_t)pos;
+    *(uint16_t*)(v.oidx[side] + gi * 2) = (uint16_t)oi;
+    *(uint32_t*)(v.oval[side] + gi * 2) = ov;
+  }
+  if (tid < n_after && (changed || is_new)) v.tags[side][gi0 + pos] = (uint8_t)nb;
+  if (tid == 0) {
+    uint16_t* cp = v.counts + ((tile_id * 2 + side) * 4);
+    cp[QC3] = (uint16_t)cn.n3; cp[QC2] = (uint16_t)cn.n2; cp[QC4] = (uint16_t)cn.n4; cp[QC8] = (uint16_t)cn.n8;
+    if (side == 1)
+      v.vbound[tile_id] = fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3]));
+    else
+      ((float2*)v.kthr)[tile_id] = make_float2(fmaxf(fmaxf(L.wave_bound[0], L.wave_bound[1]), fmaxf(L.wave_bound[2], L.wave_bound[3])),
+                                               fminf(fminf(L.wave_bound2[0], L.wave_bound2[1]), fminf(L.wave_bound2[2], L.wave_bound2[3])));
+  }
+  if (tid == 0) add_widenings(v, tile_id * 2 + side, L.wave_wide, served);
+
+  // ---- codes of the moved tokens -> their new places ----------------------------------------------------
+  if (side == 0) {
+    const QaqKRegions r = qaq_k_regions(cn, D);
+    for (int it = tid; it < n_moved * NQ; it += kThreads) {
+      const int m = it / NQ, q = it % NQ;
+      const uint32_t ma = L.mv_a[m];
+      const int sl = (int)(ma >> 16), n_b = (int)((L.mv_b[m] >> 8) & 0xffu);
+      const uint32_t* row = &L.stage[m * SROW + 16 * (q % KS) + 4 * (q / KS)];
+      if (n_b <= 3) {
+        const int sh = n_b == 3 ? 1 : 0;
+        uint32_t w = 0;
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) w |= ((row[vq] >> sh) & 0x03030303u) << (2 * vq);
+        *(uint32_t*)(base + r.r2 + (uint32_t)sl * (D / 4) + 4u * (uint32_t)q) = w;
+        if (n_b == 3 && !(q & 1)) {       // the low bits of slices q and q+1 share a word
+          const uint32_t* row1 = &L.stage[m * SROW + 16 * ((q + 1) % KS) + 4 * ((q + 1) / KS)];
+          uint32_t w1 = 0;
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) w1 |= ((row[vq] & 0x01010101u) << vq) | ((row1[vq] & 0x01010101u) << (4 + vq));
+          *(uint32_t*)(base + r.r1 + (uint32_t)sl * (D / 8) + 4u * (uint32_t)(q >> 1)) = w1;
+        }
+      } else if (n_b == 4) {
+        const uint2 w = make_uint2((row[0] & 0x0f0f0f0fu) | ((row[1] & 0x0f0f0f0fu) << 4), (row[2] & 0x0f0f0f0fu) | ((row[3] & 0x0f0f0f0fu) << 4));
+        *(uint2*)(base + r.r4 + (uint32_t)(sl - n32n) * (D / 2) + 8u * (uint32_t)q) = w;
+      } else {
+        *(uint4*)(base + r.r8 + (uint32_t)(sl - n32n - cn.n4) * D + 16u * (uint32_t)q) =
+            make_uint4(row[0] ^ 0x80808080u, row[1] ^ 0x80808080u, row[2] ^ 0x80808080u, row[3] ^ 0x80808080u);
+      }
+    }
+    return;
+  }
+  // value side: a stored word holds one channel of up to 16 tokens, so the fields of the written slots
+  // are put into the words as they are stored (a word of a unit that did not exist starts from zero;
+  // so does one whose region moved: then no token was kept in it and every slot of it is written)
+  {
+    const QaqVRegions r = qaq_v_regions(cn, D), r0 = qaq_v_regions(c_old, D);
+    const int units2_old = (n32o + 15) / 16;
+    const int units1_old = r.r1 == r0.r1 ? (c_old.n3 + 15) / 16 : 0;
+    const int half4_old = r.r4 == r0.r4 ? (c_old.n4 + 7) / 8 : 0;
+    for (int it = tid; it < ((n32n + 15) / 16) * (D / 4); it += kThreads) {
+      const int u = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+      uint32_t msk = L.mask2[u];
+      if (!msk) continue;
+      uint32_t* wp = (uint32_t*)(base + r.r2 + (uint32_t)u * (4 * D)) + (4 * (c4 & 3)) * (D / 16) + cg;
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = u < units2_old ? wp[k * (D / 16)] : 0u;
+      while (msk) {
+        const int i = __ffs(msk) - 1;
+        msk &= msk - 1;
+        const int sl = 16 * u + i;
+        const uint32_t w = (L.stage[L.m_of_slot[sl] * SROW + c4] >> (sl < cn.n3 ? 1 : 0)) & 0x03030303u;
+        const int bp = 8 * (i & 3) + 2 * (i >> 2);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(3u << bp)) | (((w >> (8 * k)) & 3u) << bp);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wp[k * (D / 16)] = o[k];
+    }
+    for (int it = tid; it < ((cn.n3 + 15) / 16) * (D / 8); it += kThreads) {
+      const int u = it / (D / 8), rest = it % (D / 8), cgp = rest >> 2, n4 = rest & 3;
+      const int in3 = cn.n3 - 16 * u;                      // slots of this unit inside the 3-bit class
+      uint32_t msk = L.mask2[u] & (in3 >= 16 ? 0xffffu : (1u << in3) - 1u);
+      if (!msk) continue;
+      uint32_t* wp = (uint32_t*)(base + r.r1 + (uint32_t)u * (2 * D)) + (4 * n4) * (D / 32) + cgp;
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = u < units1_old ? wp[k * (D / 32)] : 0u;
+      while (msk) {
+        const int i = __ffs(msk) - 1;
+        msk &= msk - 1;
+        const int mi = L.m_of_slot[16 * u + i];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const uint32_t w = L.stage[mi * SROW + 4 * (2 * cgp + hh) + n4] & 0x01010101u;
+          const int bp = 8 * (i & 3) + 4 * hh + (i >> 2);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(1u << bp)) | (((w >> (8 * k)) & 1u) << bp);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wp[k * (D / 32)] = o[k];
+    }
+    for (int it = tid; it < ((cn.n4 + 7) / 8) * (D / 4); it += kThreads) {
+      const int hu = it / (D / 4), c4 = it % (D / 4), cg = c4 >> 2;
+      uint32_t msk = L.mask4[hu];
+      if (!msk) continue;
+      uint32_t* wp = (uint32_t*)(base + r.r4 + (uint32_t)hu * (4 * D)) + (4 * (c4 & 3)) * (D / 16) + cg;
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = hu < half4_old ? wp[k * (D / 16)] : 0u;
+      while (msk) {
+        const int i = __ffs(msk) - 1;
+        msk &= msk - 1;
+        const uint32_t w = L.stage[L.m_of_slot[n32n + 8 * hu + i] * SROW + c4] & 0x0f0f0f0fu;
+        const int bp = 8 * (i & 3) + 4 * (i >> 2);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (o[k] & ~(15u << bp)) | (((w >> (8 * k)) & 15u) << bp);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) wp[k * (D / 16)] = o[k];
+    }
+    for (int it = tid; it < n_moved * (D / 16); it += kThreads) {        // 8-bit tokens: token-major bytes, 16 per item
+      const int m = it / (D / 16), dq = 4 * (it % (D / 16));
+      if (((L.mv_b[m] >> 8) & 0xffu) != 8u) continue;
+      const int sl = (int)(L.mv_a[m] >> 16);
+      const uint32_t* row = &L.stage[m * SROW + dq];
+      *(uint4*)(base + r.r8 + (uint32_t)(sl - n32n - cn.n4) * D + 4u * (uint32_t)dq) = make_uint4(row[0], row[1], row[2], row[3]);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------
 // Width selection (Section 4.1 bit rules written as comparisons, Section 4.2 window).
 // ---------------------------------------------------------------------------------
@@ -1355,16 +1922,16 @@ __global__ __launch_bounds__(kThreads) void k_dequant(QaqDequantArgs a) {
 // ---------------------------------------------------------------------------------
 // Accounting.
 // statbuf: [0..3] hist K (2,3,4,8), [4..7] hist V, [8] layout code bytes, [9] meta bytes,
-// [10], [11] 1-bit token-heads K, V
+// [10], [11] 1-bit token-heads K, V, [12], [13] widenings refused / served since the cache was made
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
-  __shared__ unsigned long long acc[12];
+  __shared__ unsigned long long acc[14];
   const int tid = threadIdx.x;
-  if (tid < 12) acc[tid] = 0;
+  if (tid < 14) acc[tid] = 0;
   __syncthreads();
   const int ntile = (len + QAQ_TT - 1) / QAQ_TT;
   const long long total = (long long)v.B * v.Hkv * ntile * 2;
-  unsigned long long loc[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned long long loc[14] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   for (long long i = (long long)blockIdx.x * kThreads + tid; i < total; i += (long long)gridDim.x * kThreads) {
     const int side = (int)(i & 1);
     const long long j = i >> 1;
@@ -1373,6 +1940,7 @@ __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
     const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile, min(len - tile * QAQ_TT, QAQ_TT));
     loc[side * 4 + 0] += c.n2; loc[side * 4 + 1] += c.n3; loc[side * 4 + 2] += c.n4; loc[side * 4 + 3] += c.n8;
     loc[10 + side] += c.n1;
+
     // bytes a scan reads: key records one by one, value planes in whole units
     loc[8] += side == 0 ? (unsigned long long)c.n32() * (v.D / 4) + (c.n3 + c.n1) * (v.D / 8) + c.n4 * (v.D / 2) + c.n8 * v.D
                         : qaq_v_regions(c, v.D).end;
@@ -1382,16 +1950,22 @@ __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
       loc[9] += (unsigned long long)c.total() * (4 + 1 + 3) + 3ull * ((unsigned)v.ostart[side][pl] + (unsigned)v.ocnt[side][pl]);
     }
   }
-  for (int k = 0; k < 12; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
+  // widenings: every tile side the cache has room for (a cache that was reset keeps its history)
+  const long long sides = (long long)v.B * v.Hkv * v.NT * 2;
+  for (long long i = (long long)blockIdx.x * kThreads + tid; i < sides; i += (long long)gridDim.x * kThreads) {
+    loc[12] += v.refused[2 * i]; loc[13] += v.refused[2 * i + 1];
+  }
+  for (int k = 0; k < 14; ++k) if (loc[k]) atomicAdd(&acc[k], loc[k]);
   __syncthreads();
-  if (tid < 12 && acc[tid]) atomicAdd((unsigned long long*)&v.statbuf[tid], acc[tid]);
+  if (tid < 14 && acc[tid]) atomicAdd((unsigned long long*)&v.statbuf[tid], acc[tid]);
 }
 
 __global__ void k_init(QaqView v) {
   const size_t n = (size_t)v.B * v.Hkv * v.NT * 2 * 4;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) v.counts[i] = 0;
   if (blockIdx.x == 0 && threadIdx.x < 32) v.statbuf[threadIdx.x] = 0;
-  if (blockIdx.x == 0 && threadIdx.x < 2 * QAQ_NCOUNT) v.refused[threadIdx.x] = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)v.B * v.Hkv * v.NT * 4; i += (size_t)gridDim.x * blockDim.x) v.refused[i] = 0;
+  if (blockIdx.x == 0 && threadIdx.x < 2) v.todo_count[threadIdx.x] = 0;
 }
 
 __global__ void k_clear_stats(QaqView v) {
@@ -1426,6 +2000,27 @@ hipError_t qaq_launch_build(const QaqBuildArgs& a, int ntiles, hipStream_t s) {
       else hipLaunchKernelGGL((k_build<64, false, false>), grid, dim3(kThreads), 0, s, a);
     }
   }
+  return hipGetLastError();
+}
+
+hipError_t qaq_launch_update(const QaqBuildArgs& a_in, int ntiles, hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  QaqBuildArgs a = a_in;
+  const bool fast = a.mode == 2 && a.v.no2 == 2 && !a.v.csr && !a.v.has1 && a.todo && a.todo_count && a.todo_count_next;
+  if (!fast) {
+    a.todo = nullptr;
+    return qaq_launch_build(a, ntiles, s);
+  }
+  const dim3 grid(a.v.B * a.v.Hkv, ntiles, 2);
+  if (a.v.D == 128) hipLaunchKernelGGL(k_update<128>, grid, dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(k_update<64>, grid, dim3(kThreads), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // the tile sides the fast kernel handed over (their number is only known on the device)
+  const long long sides = (long long)a.v.B * a.v.Hkv * ntiles * 2;
+  const dim3 grid2((unsigned)(sides < 512 ? sides : 512));
+  if (a.v.D == 128) hipLaunchKernelGGL((k_build<128, true, false>), grid2, dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL((k_build<64, true, false>), grid2, dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

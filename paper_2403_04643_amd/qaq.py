@@ -36,6 +36,7 @@ class Stats(C.Structure):
         ("tokens", C.c_int64), ("hist_k", C.c_int64 * 5), ("hist_v", C.c_int64 * 5),
         ("code_bytes", C.c_int64), ("layout_code_bytes", C.c_int64), ("meta_bytes", C.c_int64),
         ("fp16_bytes", C.c_int64), ("refused_upgrades", C.c_int64), ("served_upgrades", C.c_int64),
+        ("update_handovers", C.c_int64),
     ]
 
 
