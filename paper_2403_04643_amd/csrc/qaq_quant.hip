@@ -1238,21 +1238,22 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
 
 // Grid (units, tiles, 2 sides) -- heads are the fastest grid dimension: with tiles fastest and a
 // tile count that is a multiple of eight, every die would see the same two tile indices of every
-// head, which ran 30 % slower.  Or, given a list (a.todo: entries (unit * NT + tile) * 2 + side,
-// a.todo_count of them, both in device memory), a one-dimensional grid whose workgroups share
-// out the listed tile sides.
+// head, which ran 30 % slower.
 template <int D, bool ONE, bool HAS1>
 __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
-  const bool listed = a.todo != nullptr;
-  const uint32_t n = listed ? *a.todo_count : 1u;
-  for (uint32_t i = listed ? blockIdx.x : 0u; i < n; i += listed ? gridDim.x : 1u) {
-    int bh = (int)blockIdx.x, tile = a.tile0 + (int)blockIdx.y, side = (int)blockIdx.z;
-    if (listed) {
-      const uint32_t e = a.todo[i];
-      bh = (int)((e >> 1) / (uint32_t)a.v.NT); tile = (int)((e >> 1) % (uint32_t)a.v.NT); side = (int)(e & 1u);
-    }
-    build_tile<D, ONE, HAS1>(a, bh, tile, side);
-    if (listed) __syncthreads();        // the next tile side reuses the staging memory
+  build_tile<D, ONE, HAS1>(a, (int)blockIdx.x, a.tile0 + (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// The same for a list of tile sides (a.todo: entries (unit * NT + tile) * 2 + side, a.todo_count of
+// them, both in device memory): a one-dimensional grid whose workgroups share out the entries.
+template <int D, bool ONE, bool HAS1>
+__global__ __launch_bounds__(kThreads) void k_build_listed(QaqBuildArgs a) {
+  const uint32_t n = *a.todo_count;
+#pragma unroll 1
+  for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+    const uint32_t e = a.todo[i];
+    build_tile<D, ONE, HAS1>(a, (int)((e >> 1) / (uint32_t)a.v.NT), (int)((e >> 1) % (uint32_t)a.v.NT), (int)(e & 1u));
+    __syncthreads();        // the next tile side reuses the staging memory
   }
 }
 
@@ -1263,9 +1264,9 @@ __global__ __launch_bounds__(kThreads) void k_build(QaqBuildArgs a) {
 // for what a decode step does to a tile: a few tokens change width, one token is appended to
 // the last tile, everything else stays.  A workgroup evaluates the rules for its tile side,
 // leaves at once if nothing moves, re-assigns slots so that as few tokens move as possible
-// (a token keeps its place inside its region; regions whose start would move with tokens still
-// in them, and tiles in which more than kMaxMoved tokens move, are handed to the general
-// kernel through a list), and carries only the moved tokens' codes through LDS.  A fifth of
+// (a token keeps its place inside its region; tiles in which more than kMaxMoved tokens move
+// are handed to the general kernel through a list), and carries only the moved tokens' codes
+// through LDS.  A fifth of
 // the general kernel's LDS and half its registers: eight workgroups per compute unit hide its
 // two dependent round trips to memory.
 // ---------------------------------------------------------------------------------
@@ -1374,7 +1375,9 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   const QaqRuleArgs& ru = a.rule;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bh = blockIdx.x, b = bh / v.Hkv, h = bh % v.Hkv;
-  const int tile = blockIdx.y, side = blockIdx.z;
+  // value sides first: nearly every one of them has work (a token's predicted score moves every
+  // step), most key sides leave after one load and fill in behind
+  const int tile = blockIdx.y, side = 1 - (int)blockIdx.z;
   const int t0 = tile * QAQ_TT;
   const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
   const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
@@ -1559,16 +1562,16 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   }
   auto old_index = [&](int c, int slot) { return c == QC4 ? slot - n32o : c == QC8 ? slot - n32o - c_old.n4 : slot; };
   auto new_slot_of = [&](int c, int idx) { return c == QC4 ? n32n + idx : c == QC8 ? n32n + cn.n4 + idx : idx; };
+  // (a region whose start moves -- a count before it crossed a multiple of 16 -- keeps nobody: its
+  // tokens are written again at the new place like any other moved token)
+  auto region_moved = [&](int c) { return (c == QC3 && mv3) || (c == QC4 && mv4) || (c == QC8 && mv8); };
   bool keep = false;
   int my_slot = -1;
-  if (ocls >= 0 && cls == ocls) {
+  if (ocls >= 0 && cls == ocls && !region_moved(cls)) {
     const int idx = old_index(cls, tid);
     keep = cls == QC3 ? idx < cn.n3 : cls == QC2 ? (idx >= cn.n3 && idx < n32n) : cls == QC4 ? idx < cn.n4 : idx < cn.n8;
     if (keep) my_slot = new_slot_of(cls, idx);
   }
-  // a kept token whose region starts elsewhere than before would have to be copied: such tiles (rare: a
-  // region start moves when a count crosses a multiple of 16) go to the general kernel
-  const bool stranded = keep && ((cls == QC3 && mv3) || (cls == QC4 && mv4) || (cls == QC8 && mv8));
   const bool need = cls >= 0 && !keep;
   // thread s as slot s of the new order: free unless the token that could keep it does
   int slot_cls = -1;
@@ -1577,7 +1580,8 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     slot_cls = qaq_class_of_bits(cn.bits_of_slot4(tid));
     const int idx = slot_cls == QC4 ? tid - n32n : slot_cls == QC8 ? tid - n32n - cn.n4 : tid;
     const int cand = slot_cls == QC4 ? idx + n32o : slot_cls == QC8 ? idx + n32o + c_old.n4 : idx;    // the old slot with that index
-    const bool taken = cand < n_before && qaq_class_of_bits(c_old.bits_of_slot4(cand)) == slot_cls && L.cls_new[cand] == slot_cls;
+    const bool taken = cand < n_before && !region_moved(slot_cls) && qaq_class_of_bits(c_old.bits_of_slot4(cand)) == slot_cls &&
+                       L.cls_new[cand] == slot_cls;
     is_free = !taken;
   }
   int need_rank = 0, free_rank = 0;
@@ -1591,9 +1595,9 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   }
   const unsigned long long bal_need = __ballot(need);
   if (lane == 0) L.wave_moved[wave] = __popcll(bal_need);
-  const bool hand_over = __syncthreads_or(stranded ? 1 : 0) != 0;
+  __syncthreads();
   const int n_moved = L.wave_moved[0] + L.wave_moved[1] + L.wave_moved[2] + L.wave_moved[3];
-  if (hand_over || n_moved > kMaxMoved) {
+  if (n_moved > kMaxMoved) {
     // nothing of the cache has been written yet (the window row and the width outputs are the same
     // numbers when the general kernel writes them again)
     if (tid == 0) a.todo[atomicAdd(a.todo_count, 1u)] = (uint32_t)(tile_id * 2 + side);
@@ -2019,8 +2023,8 @@ hipError_t qaq_launch_update(const QaqBuildArgs& a_in, int ntiles, hipStream_t s
   // the tile sides the fast kernel handed over (their number is only known on the device)
   const long long sides = (long long)a.v.B * a.v.Hkv * ntiles * 2;
   const dim3 grid2((unsigned)(sides < 512 ? sides : 512));
-  if (a.v.D == 128) hipLaunchKernelGGL((k_build<128, true, false>), grid2, dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL((k_build<64, true, false>), grid2, dim3(kThreads), 0, s, a);
+  if (a.v.D == 128) hipLaunchKernelGGL((k_build_listed<128, true, false>), grid2, dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL((k_build_listed<64, true, false>), grid2, dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 
