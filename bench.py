@@ -125,6 +125,60 @@ def algorithmic_bytes(st, sh, n_o, T_scores):
     return cache, io
 
 
+def _cpu_unit(args):
+    """One worker of the all-cores figure: the oracle, one thread, on one sequence of the sample
+    (its own seed): quantization + one decode attention.  Returns (seconds, seconds, bytes)."""
+    seq, context, n_q, n_kv, hist_k, hist_v, qn, n_o = args
+    from threadpoolctl import threadpool_limits
+    from oracle import qaq_oracle as O
+    from paper_2403_04643_amd import workloads as W
+    s1 = W.shape(2, batch=1, context=context, n_q_heads=n_q, n_kv_heads=n_kv)
+    K, V = W.make_kv(2, s1, seed_offset=100 + seq)
+    rng = np.random.default_rng(990 + seq)
+    widths = np.array([2, 3, 4, 8, 1], np.uint8)
+    bk = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_k) / np.sum(hist_k))
+    bv = rng.choice(widths, size=K.shape[:3], p=np.asarray(hist_v) / np.sum(hist_v))
+    oc = O.OracleCache(O.Config(1, n_q, n_kv, s1.head_dim, qnorm2=np.asarray(qn, np.float32)))
+    q = W.make_queries(2, s1, seed_offset=100 + seq)[0]
+    kn, vn = W.make_new_token(2, s1, step=seq)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter(); oc.append(K, V, bk, bv); t_quant = time.perf_counter() - t0
+        t0 = time.perf_counter(); oc.decode_attention(q, kn, vn); t_attn = time.perf_counter() - t0
+    return t_quant, t_attn, oc.code_bytes() + n_kv * context * (8 + 2 + 12 * n_o)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_all_cores(sh, hist_k, hist_v, qn, n_o, workers):
+    """The same oracle on all host cores: a process pool, one sequence of the sample per worker
+    (every (sequence, head) unit is independent), started with `spawn` so that no worker
+    inherits the GPU context.  Rates are whole-pool work over the pool's wall time."""
+    import multiprocessing as mp
+    args = [(i, sh.context, sh.n_q_heads, sh.n_kv_heads, list(hist_k), list(hist_v), [float(x) for x in qn], n_o) for i in range(workers)]
+    t0 = time.perf_counter()
+    pool = mp.get_context("spawn").Pool(workers)
+    try:
+        res = pool.map_async(_cpu_unit, args).get(timeout=300)      # (a worker that cannot start must not hang the run)
+    except Exception as e:
+        pool.terminate()
+        return {"workers": workers, "error": f"{type(e).__name__}: {e}"}
+    pool.close(); pool.join()
+    wall = time.perf_counter() - t0
+    t_quant = max(r[0] for r in res); t_attn = max(r[1] for r in res)
+    nbytes = sum(r[2] for r in res)
+    return {"workers": workers, "GBps_attention": nbytes / t_attn / 1e9, "tokens_quantized_per_s": workers * sh.context / t_quant,
+            "wall_s_with_start_up": wall, "sample": f"{workers} sequences (one per worker), all {sh.n_kv_heads} heads, context {sh.context}"}
+
+
 def cpu_baseline(sh, hist_k, hist_v, qn, n_o, n_seq):
     """The CPU oracle (numpy, as it stands) on a bounded sample of the same workload: the
     first `n_seq` sequences of layer 0 (all KV heads, full context), widths drawn i.i.d.
@@ -151,13 +205,146 @@ def cpu_baseline(sh, hist_k, hist_v, qn, n_o, n_seq):
         t_attn = time.perf_counter() - t0
     th = n_seq * s1.n_kv_heads * s1.context
     nbytes = oc.code_bytes() + th * (8 + 2 + 12 * n_o)
+    workers = max(1, min(16, os.cpu_count() or 1))      # (a one-GPU machine's share of its host is 16 cores)
     return {
         "value": nbytes / t_attn / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "nproc": os.cpu_count(), "cpu_model": cpu_model(),
+        "all_cores": cpu_all_cores(sh, hist_k, hist_v, qn, n_o, workers),
         "sample": f"{n_seq} of {sh.batch} sequences of one layer, all {s1.n_kv_heads} heads, context {s1.context}, widths "
                   f"i.i.d. with the GPU run's histogram: quantization {t_quant:.1f} s + one decode attention {t_attn:.2f} s",
         "tokens_quantized_per_s": n_seq * s1.context / t_quant,
         "us_per_attention_call_scaled_to_full_batch": t_attn * sh.batch / n_seq * 1e6,
     }
+
+
+def other_configs(lib, qaq, W, torch, n_inst=3):
+    """The decode-attention call at BASELINE configs[3] (long context: batch 1, 32 heads, 32768
+    tokens, widths from the Zipf(1.1) importance profile) and configs[4] (grouped queries: batch
+    16, 64 query heads on 8 KV heads, 8192 tokens), both at operating point A's mean widths: time of
+    the call's kernels (events attached to the dispatches), algorithmic bytes (a KV head's cache
+    counted once), rate.  `n_inst` cache instances with the same contents are rotated so that the
+    codes are streamed from HBM."""
+    out = {}
+    for cfgno in (4, 5):
+        sh = W.shape(cfgno)
+        B, Hq, Hkv, D, T = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+        K, V = W.make_kv(cfgno, sh)
+        Kd, Vd = torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda()
+        del K, V
+        qcal = W.make_queries(cfgno, sh, n=max(1, 1024 // (B * Hq)), seed_offset=7).astype(np.float64)
+        qn = np.full(Hkv, float(np.quantile((qcal ** 2).sum(-1).reshape(-1), 0.9)) / D, np.float32)
+        q = torch.from_numpy(W.make_queries(cfgno, sh, n=4, seed_offset=1)).cuda()
+        kn, vn = W.make_new_token(cfgno, sh)
+        kn, vn = torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
+        caches = []
+        for i in range(n_inst):
+            c = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, T + 1, qn.tolist(), window=5))
+            c.quantize_append(Kd, Vd)
+            if cfgno == 4:      # the importance profile of the configuration is the score history
+                rows = torch.from_numpy(W.zipf_score_rows(sh, T)).cuda()
+                c.select_bits(rows)
+                del rows
+            else:               # the scores of one query per query head; the rule takes the maximum over a KV head's group
+                _, S = c.decode_attention(q[3], want_scores=True)
+                c.select_bits(S)
+                del S
+            caches.append(c)
+        ss, sx = calibrate(caches[0], *OPERATING_POINTS["A"], torch)
+        for c in caches:
+            c.set_sigmas(ss, sx)
+            kb, vb = c.select_bits(None)
+            c.requantize(kb, vb)
+        del Kd, Vd
+        torch.cuda.synchronize()
+        n_calls = 8
+        scores = torch.empty((B, Hq, T + 1), dtype=torch.float32, device="cuda")
+        for c in caches:
+            c.profile_begin(n_calls + 1)
+        for i in range((n_calls + 1) * n_inst):
+            caches[i % n_inst].decode_attention(q[i % 3], kn, vn, scores_out=scores)
+        torch.cuda.synchronize()
+        t_tile, t_merge = [], []
+        for c in caches:
+            a_ms, b_ms = c.profile_read()
+            t_tile += a_ms[1:]; t_merge += b_ms[1:]
+            c.profile_begin(0)
+        st = caches[0].stats()
+        n_o = caches[0].n_o
+        cb, io = algorithmic_bytes(st, sh, n_o, T + 1)
+        us_t, us_m = 1e3 * float(np.mean(t_tile)), 1e3 * float(np.mean(t_merge))
+        th = B * Hkv * st.tokens
+        out[f"configs[{cfgno - 1}]"] = {
+            "shape": f"batch {B}, {Hq} query heads on {Hkv} KV heads, head_dim {D}, context {T}",
+            "us_attention_call": us_t + us_m, "us_tile_kernel": us_t, "us_merge_kernel": us_m,
+            "algorithmic_bytes": cb + io, "GBps": (cb + io) / ((us_t + us_m) * 1e-6) / 1e9,
+            "frac_of_hbm_peak": (cb + io) / ((us_t + us_m) * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8, 1), st.hist_k)) / th,
+            "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8, 1), st.hist_v)) / th,
+            "hist_k": list(st.hist_k), "hist_v": list(st.hist_v)}
+        del caches
+    return out
+
+
+def config_3_as_stated(lib, qaq, torch, sh, qn, ss, sx, n_layers=32, steps=64):
+    """BASELINE configs[2] at its stated size: `n_layers` independent cache instances of config
+    2's shape (the layers of a LLaMA-7B stack), `steps` consecutive decode steps from the
+    configured context, each step one attention call and one update call per layer (append,
+    widths, requantization) with a fresh query per step, layer and head, the unquantized
+    copies resident in HBM.  The layers' K/V are drawn on the device (torch generator, the law
+    of config 2: per-channel scale log-uniform in [0.5, 4], 0.5 % of the channels Student-t(3)):
+    drawing 32 layers with numpy on the host would take minutes."""
+    B, Hq, Hkv, D, T0 = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+    Tcap = T0 + steps
+    gen = torch.Generator(device="cuda")
+
+    def draw(seed):
+        gen.manual_seed(seed)
+        std = torch.exp(torch.empty((Hkv, D), device="cuda").uniform_(float(np.log(0.5)), float(np.log(4.0)), generator=gen))
+        heavy = torch.rand((Hkv, D), device="cuda", generator=gen) < 0.005
+        x = torch.randn((B, Hkv, Tcap, D), device="cuda", generator=gen)
+        chi = torch.randn((3, B, Hkv, Tcap, 1), device="cuda", generator=gen).square().sum(0) / 3.0
+        x = torch.where(heavy[None, :, None, :], x / chi.sqrt(), x)          # a Student-t(3) draw where the channel is heavy-tailed
+        return (x * std[None, :, None, :]).clamp_(-65504.0, 65504.0).half()
+
+    q_last = (torch.randn((B, Hq, 5, D), device="cuda", generator=gen.manual_seed(20240304 + 33)) / float(np.sqrt(D))).half()
+    caches, oKs, oVs, newk, newv = [], [], [], [], []
+    for l in range(n_layers):
+        oK, oV = draw(20240304 + 3 + 1000 * l), draw(20240304 + 3 + 1000 * l + 500)
+        c = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, Tcap, qn.tolist(), window=5, sigma_s_max=ss, sigma_x_max=sx))
+        Kd, Vd = oK[:, :, :T0].contiguous(), oV[:, :, :T0].contiguous()
+        c.prefill_window(q_last, Kd); c.quantize_append_selected(Kd, Vd)
+        del Kd, Vd
+        newk.append(oK[:, :, T0:].permute(2, 0, 1, 3).contiguous()); newv.append(oV[:, :, T0:].permute(2, 0, 1, 3).contiguous())
+        caches.append(c); oKs.append(oK); oVs.append(oV)
+    qs = (torch.randn((steps, n_layers, B, Hq, D), device="cuda", generator=gen.manual_seed(20240304 + 34)) / float(np.sqrt(D))).half()
+    out = torch.empty((B, Hq, D), dtype=torch.float32, device="cuda")
+    scores = torch.empty(B * Hq * (Tcap + 1), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    P = lambda t: C.c_void_p(t.data_ptr())
+    served0 = sum(c.stats().served_upgrades for c in caches)
+    st_a = caches[0].stats()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(steps):
+        for l, c in enumerate(caches):
+            rc = lib.qaq_decode_attention(c.h, P(qs[j, l]), P(newk[l][j]), P(newv[l][j]), P(out), 1, P(scores), stream)
+            rc |= lib.qaq_decode_update(c.h, P(scores), P(newk[l][j]), P(newv[l][j]), P(oKs[l]), P(oVs[l]), Tcap, None, None, stream)
+            assert rc == 0, lib.qaq_last_error()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    sts = [c.stats() for c in caches]
+    served1 = sum(s_.served_upgrades for s_ in sts)
+    hist = lambda name: [int(sum(getattr(s_, name)[i] for s_ in sts)) for i in range(4)]
+    th = B * Hkv * sts[0].tokens * n_layers
+    return {"layers": n_layers, "steps": steps, "cached_tokens": [int(st_a.tokens), int(sts[0].tokens)],
+            "ms_per_layer_step": 1e3 * el / (steps * n_layers), "ms_per_token_all_layers": 1e3 * el / steps,
+            "served_upgrades_per_layer_step": (served1 - served0) / (steps * n_layers),
+            "refused_upgrades": int(sum(s_.refused_upgrades for s_ in sts)),
+            "update_handovers_last_step": int(sum(s_.update_handovers for s_ in sts)),
+            "hist_k_2_3_4_8": hist("hist_k"), "hist_v_2_3_4_8": hist("hist_v"),
+            "mean_bits_k": sum(w * n for w, n in zip((2, 3, 4, 8), hist("hist_k"))) / th,
+            "mean_bits_v": sum(w * n for w, n in zip((2, 3, 4, 8), hist("hist_v"))) / th,
+            "hbm_bytes_held": int(sum(c.arena_bytes for c in caches) + sum(t.numel() * 2 for t in oKs + oVs))}
 
 
 def main():
@@ -340,6 +527,7 @@ def main():
         "refused_upgrades": int(sum(x.refused_upgrades for x in st1)),
         "roofline": {"bound": "hbm", "kernel": "k_attn_tile", "achieved": gbs_main, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": gbs_main / HBM_PEAK_GBS, "traffic": measured_traffic(args.op),
+                     "traffic_source": f"profiles/k_attn_tile_cfg2_op{args.op}_hbm_traffic.txt (rocprofv3 --pmc runs of this command, committed)",
                      "algorithmic_bytes": bytes_main,
                      "stream_read_GBps": read_gbs, "frac_of_stream_read": gbs_main / read_gbs,
                      "stream_copy_GBps": copy_gbs, "yardstick_bytes": yard_bytes},
@@ -493,6 +681,9 @@ def main():
             "tokens_per_s": B * Tctx / ((ms_w + ms_a) * 1e-3),
             "fp16_key_bytes_read": B * Hkv * Tctx * D * 2, "window_GBps": B * Hkv * Tctx * D * 2 / (ms_w * 1e-3) / 1e9,
             "hist_k": list(stp.hist_k), "hist_v": list(stp.hist_v)}
+        # tokens quantized per second through the selected-width call alone (the headline figure is the
+        # bulk append at the widest width)
+        rec["tokens_quantized_per_s_selected_widths"] = B * Tctx / (ms_a * 1e-3)
         # The paper's premise (Section 3.2) is that a token's importance persists from step to
         # step; the timed steps above draw an independent query every step, the worst case for
         # the update (every step re-draws every score).  The same steps with queries that follow
@@ -607,6 +798,15 @@ def main():
             "ratio_codes": stt.fp16_bytes / stt.code_bytes, "ratio_all": stt.fp16_bytes / (stt.code_bytes + stt.meta_bytes),
             "us_tile_kernel": us_t, "bytes": bt, "GBps": bt / (us_t * 1e-6) / 1e9, "output_rel_l2_error": output_error(0, cts)}
         del cts
+    if not args.no_extras:
+        # free the benchmark's own instances first: the stated configurations bring their own
+        for lst in (caches, origK, origV, newk, newv):
+            lst.clear()
+        torch.cuda.empty_cache()
+        rec["other_configs"] = other_configs(lib, qaq, W, torch)
+        torch.cuda.empty_cache()
+        rec["config_3_as_stated"] = config_3_as_stated(lib, qaq, torch, sh, qn, ss, sx)
+        torch.cuda.empty_cache()
     # attention-output error against fp32 attention over the unquantized tokens, by compression
     # ratio: the adaptive widths of the two operating points next to uniform widths
     rec["quality_on_synthetic_data"] = quality
