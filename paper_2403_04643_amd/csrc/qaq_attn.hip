@@ -860,6 +860,452 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Grouped queries: one pass over a KV head's codes for four query heads at a time.
+//
+// k_attn_tile gives every query head its own scan, so the G heads that share a KV head unpack
+// the same codes and decode the same per-token metadata G times.  Here a part (256 threads)
+// serves kHG = 4 query heads of one KV head: the 16 rows of the A operand are 4 heads x
+// (3 query digits + an empty row) on the key side and 4 heads x 4 weight digits on the value
+// side, the B operand -- the unpacked codes -- is shared, and so are min/scale, order bytes
+// and outlier entries of every token.  On the key side column n of a product is token n of a
+// group of 16, lane (n, g) supplies 16 channels of it (its k-range) and receives head g's
+// digit sums for it; on the value side the rows are summed over 64 slots and lane (n, g)
+// receives head g's digit sums for channel n.  Parts write partials (max, sum, X) per query
+// head and raw logits; k_attn_combine merges them.  Width sets without 1, the fixed-length
+// side store with one outlier per end or none; G a multiple of 4 (a KV head with 8 query
+// heads is scanned twice, by two workgroups that run side by side).
+// ---------------------------------------------------------------------------------------
+constexpr int kHG = 4;
+
+template <int D>
+struct GqaLds {
+  float qf[kHG][D];
+  alignas(16) int8_t ql[3][kHG][3][D + 16];     // query digits [format][head][digit][position in record order]
+  alignas(16) int8_t zrow[256];                // zeros: the fourth row of every head on the key side
+  alignas(16) uint16_t cnt[QAQ_MAX_NTC][8];
+  float vb[QAQ_MAX_NTC];
+  float logit[kHG][QAQ_TT];                    // raw logits by position; at the very end: outlier corrections by channel
+  alignas(16) int8_t wl2[kHG][4][QAQ_TT + 16];  // weight digits [head][digit][slot of the 2-bit field region]
+  alignas(16) int8_t wl1[kHG][4][QAQ_TT + 16];
+  alignas(16) int8_t wl4[kHG][4][QAQ_TT + 16];
+  float w8[kHG][QAQ_TT];                       // fp32 weights of the 8-bit slots
+  float xw[4][kHG][D / 4];                     // per wavefront: 8-bit-class outputs of its own channels
+  alignas(16) int xc[kHG][D][4];               // outlier corrections of one tile, fixed point, four copies per channel
+  alignas(16) float red[4][kHG];               // per wavefront and head
+  alignas(16) float red2[4][kHG];
+};
+
+template <int D, int NO2>
+__global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
+  constexpr int KS = D / 64;
+  constexpr int NCG = D / 16;
+  constexpr int CGW = NCG / 4;
+  __shared__ GqaLds<D> S;
+  const QaqView& v = a.v;
+  const int chunk = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nn = lane & 15, g = lane >> 4;
+  const int NG = a.G / kHG;
+  const int unit = blockIdx.y;
+  const int b = unit / (v.Hkv * NG), h = (unit / NG) % v.Hkv, hg = unit % NG;
+  const int bq0 = b * v.Hq + h * a.G + kHG * hg;           // first of the four query heads
+  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  const int tile_begin = (int)((long long)chunk * ntile / a.nparts);
+  const int tile_end = (int)((long long)(chunk + 1) * ntile / a.nparts);
+  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+  const v4i zero4 = {0, 0, 0, 0};
+
+  float qv[kHG];
+#pragma unroll
+  for (int j = 0; j < kHG; ++j) qv[j] = tid < D ? __half2float(a.q[(size_t)(bq0 + j) * D + tid]) : 0.0f;
+  if (tid < tile_end - tile_begin) {
+    *(uint4*)&S.cnt[tid][0] = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + tile_begin + tid) * 2) * 4);
+    S.vb[tid] = v.vbound[qaq_bh(v, b, h) * v.NT + tile_begin + tid];
+  }
+  if (wave < KS) {
+#pragma unroll
+    for (int j = 0; j < kHG; ++j) {
+      const float am = wave_max(fabsf(qv[j]));
+      const float sm = wave_sum(qv[j]);
+      if (lane == 0) { S.red[wave][j] = am; S.red2[wave][j] = sm; }
+      S.qf[j][tid] = qv[j];
+    }
+  }
+  S.zrow[tid] = 0;
+  for (int e = tid; e < kHG * D * 4; e += kThreads) (&S.xc[0][0][0])[e] = 0;
+  lds_barrier();
+
+  auto counts_of = [&](int t, int side) {
+    const uint2 c = *(const uint2*)&S.cnt[t - tile_begin][4 * side];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
+    QaqCounts r;
+    r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16; r.n1 = 0;
+    return r;
+  };
+
+  // ---- what is loaded ahead for the key side: lane (n, g) holds, for each of its wavefront's four
+  // groups of 16 slots, the slices g*KS .. g*KS+KS-1 of slot 16*tg + n and that slot's metadata ------
+  uint32_t ka[4][KS], kb[4][KS], kmm[4], kpos[4], koi[4], kov[4];
+  QaqCounts cKn;
+  int n_tok_n = 0;
+  auto load_keys = [&](int tile) {
+    cKn = counts_of(tile, 0);
+    n_tok_n = min(a.len - tile * QAQ_TT, QAQ_TT);
+    const gbytes_t ubase = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const QaqKRegions rK = qaq_k_regions(cKn, D);
+    const int n32 = cKn.n32();
+#pragma unroll
+    for (int tg = 0; tg < 4; ++tg) {
+      const int s = min(64 * wave + 16 * tg + nn, n_tok_n - 1);
+      kmm[tg] = gload32(uniform_ptr(v.mm[0] + gi0), 4u * (uint32_t)s);
+      kpos[tg] = gload32(uniform_ptr(v.perm[0] + gi0), (uint32_t)s & ~3u);
+      if (NO2 == 2) {
+        koi[tg] = gload32(uniform_ptr(v.oidx[0] + gi0 * 2), (2u * (uint32_t)s) & ~3u);
+        kov[tg] = gload32(uniform_ptr(v.oval[0] + gi0 * 2), 4u * (uint32_t)s);
+      }
+      const bool is3 = s < cKn.n3, is23 = s < n32, is4 = !is23 && s < n32 + cKn.n4;
+      const uint32_t rec4 = rK.r4 + (uint32_t)(s - n32) * (uint32_t)(D / 2) + (uint32_t)g * (8u * KS);
+      const uint32_t off_a = is23 ? (uint32_t)s * (uint32_t)(D / 4) + (uint32_t)g * (4u * KS) : is4 ? rec4 : 0u;
+      // the low bits of a 3-bit token: the word that holds the lane's slices (KS = 2: both halves of
+      // word g; KS = 1: one half of word g / 2); a 4-bit token: the second half of its slices
+      const uint32_t off_b = is3 ? rK.r1 + (uint32_t)s * (uint32_t)(D / 8) + 4u * (uint32_t)((g * KS) >> 1) : is4 ? rec4 + 4u * KS : 0u;
+      gload_dwords<KS>(ubase + off_a, ka[tg]);
+      gload_dwords<KS>(ubase + off_b, kb[tg]);
+    }
+  };
+  ValRegs<D, NO2> vr;
+  load_keys(tile_begin);
+  vr.template load<false>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+
+  // ---- query digits: 22-bit fixed point per head, three signed base-256 digits, one table per
+  // spreading format ---------------------------------------------------------------------------------
+  float qscale_g = 0.0f, sumq_g = 0.0f;        // of the lane's own head g
+#pragma unroll
+  for (int j = 0; j < kHG; ++j) {
+    const float qmax = KS == 1 ? S.red[0][j] : fmaxf(S.red[0][j], S.red[1][j]);
+    const float sumq = KS == 1 ? S.red2[0][j] : S.red2[0][j] + S.red2[1][j];
+    int qexp = 0;
+    if (qmax > 0.0f) (void)frexpf(qmax, &qexp);
+    const float qscale = qmax > 0.0f ? ldexpf(1.0f, qexp - 22) : 0.0f;
+    if (j == g) { qscale_g = qscale; sumq_g = sumq; }
+    if (wave < KS) {
+      const int i = tid & 15, vgr = i >> 2;
+      const int pos = 16 * (((tid & 63) >> 4) * KS + (tid >> 6)) + i;
+#pragma unroll
+      for (int f = 0; f < 3; ++f) {
+        const int sh = f == 0 ? shift2(vgr) : f == 1 ? shift1(vgr) : 0;
+        const int x = qmax > 0.0f ? (int)rintf(ldexpf(qv[j], 22 - qexp - sh)) : 0;
+        const uint32_t dg = digits_packed(x);
+        S.ql[f][j][0][pos] = (int8_t)dg; S.ql[f][j][1][pos] = (int8_t)(dg >> 8); S.ql[f][j][2][pos] = (int8_t)(dg >> 16);
+      }
+    }
+  }
+  lds_barrier();
+  // A rows: row r = 4 * head + digit; the lane's k-range is slices g*KS ..
+  const int arow_h = nn >> 2, arow_d = nn & 3;
+  const int8_t* abase0 = arow_d < 3 ? &S.ql[0][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
+  const int8_t* abase1 = arow_d < 3 ? &S.ql[1][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
+  const int8_t* abase2 = arow_d < 3 ? &S.ql[2][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
+  const int8_t* wb2 = &S.wl2[arow_h][arow_d][16 * g];
+  const int8_t* wb1 = &S.wl1[arow_h][arow_d][16 * g];
+  const int8_t* wb4 = &S.wl4[arow_h][arow_d][16 * g];
+  auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale_g; };
+
+  float m_run[kHG], l_run[kHG], bias_run[kHG];
+#pragma unroll
+  for (int j = 0; j < kHG; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.0f; bias_run[j] = 0.0f; }
+  constexpr int NCR = (kHG * D + kThreads - 1) / kThreads;      // (head, channel) pairs per thread for the outlier corrections
+  float c_run[NCR];
+#pragma unroll
+  for (int r = 0; r < NCR; ++r) c_run[r] = 0.0f;
+  float xrun[CGW];                 // head g, channel 16*(CGW*wave + j) + n
+#pragma unroll
+  for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const QaqCounts cK = cKn, cV = vr.c;
+    const int n_tok = n_tok_n;
+    const QaqKRegions rK = qaq_k_regions(cK, D);
+    const QaqVRegions rV = qaq_v_regions(cV, D);
+    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
+    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    const int n32K = cK.n32(), n32V = cV.n32();
+    const int first8K = n32K + cK.n4, first8V = n32V + cV.n4;
+
+    // ---- keys: logits of the lane's head for the four tokens 16*tg + n of its wavefront ---------------
+    float vmax = -INFINITY;
+#pragma unroll
+    for (int tg = 0; tg < 4; ++tg) {
+      const int s0 = 64 * wave + 16 * tg;           // uniform
+      if (s0 >= n_tok) continue;
+      const int s = s0 + nn;
+      float dotq = 0.0f;
+      if (s0 < n32K) {
+        v4i c = zero4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) c = mma(*(const v4i*)(abase0 + 16 * ks), spread<2>(&ka[tg][ks], 0), c);
+        dotq = real_of(c);
+        if (s0 < cK.n3) {
+          v4i c1 = zero4;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) c1 = mma(*(const v4i*)(abase1 + 16 * ks), spread<1>(&kb[tg][0], (g * KS + ks) & 1), c1);
+          const float low = real_of(c1);
+          dotq = s < cK.n3 ? 2.0f * dotq + low : dotq;
+        }
+      }
+      if (s0 + 16 > n32K && s0 < first8K) {
+        uint32_t k4[2 * KS];
+#pragma unroll
+        for (int i = 0; i < KS; ++i) { k4[i] = ka[tg][i]; k4[KS + i] = kb[tg][i]; }
+        v4i c = zero4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) c = mma(*(const v4i*)(abase2 + 16 * ks), spread<4>(&k4[2 * ks], 0), c);
+        const float d4 = real_of(c);
+        if (s >= n32K) dotq = d4;
+      }
+      if (cK.n8 > 0 && s0 + 16 > first8K) {
+        // 8-bit keys (rare): fetched here; stored as code - 128, so the product gets 128 * (sum of the
+        // head's query integers) back, rebuilt from the digits
+        const int i8 = min(max(s - first8K, 0), max(cK.n8 - 1, 0));
+        uint32_t w8r[4 * KS];
+        load_dwords<4 * KS>(baseK + rK.r8 + (uint32_t)i8 * D + (uint32_t)g * (16u * KS), w8r);
+        v4i c = zero4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) c = mma(*(const v4i*)(abase2 + 16 * ks), spread<8>(&w8r[4 * ks], 0), c);
+        int sq = 0;
+        for (int d = nn; d < D; d += 16) sq += (int)S.ql[2][g][0][d] + 256 * (int)S.ql[2][g][1][d] + 65536 * (int)S.ql[2][g][2][d];
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
+        if (s >= first8K) dotq = ((((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) + 128.0f * (float)sq) * qscale_g;
+      }
+      if (s < n_tok) {
+        const uint32_t m = kmm[tg];
+        const float mn = h2f((uint16_t)(m & 0xffffu)), mx = h2f((uint16_t)(m >> 16));
+        const float range = mx - mn;
+        const float scale = ldexpf(range, -cK.bits_of_slot4(s));
+        float val = mn * sumq_g + scale * (dotq + 0.5f * sumq_g);
+        if (NO2 == 2) {
+          const float hs = 0.5f * scale;
+          const uint32_t oi = koi[tg] >> (16 * (s & 1));
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const float ovf = h2f((uint16_t)(kov[tg] >> (16 * j)));
+            const bool top = ovf >= mx;
+            val += S.qf[g][(oi >> (8 * j)) & 0xffu] * ((ovf - (top ? mx : mn)) + (top ? hs : -hs));
+          }
+        }
+        const float lg = val * inv_sqrt_d;
+        S.logit[g][(kpos[tg] >> (8u * ((uint32_t)s & 3u))) & 0xffu] = lg;
+        vmax = vmaxf(vmax, lg);
+      }
+    }
+    if (tile + 1 < tile_end) load_keys(tile + 1);
+
+    // maximum of the lane's head over its row of 16 lanes, then over the wavefronts
+    asm volatile(QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+                 QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+                 QAQ_DPP_STEP("v_max_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+                 QAQ_DPP_STEP("v_max_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+                 "s_nop 1"
+                 : "+v"(vmax));
+    if (nn == 0) S.red[wave][g] = vmax;
+    lds_barrier();
+    float M[kHG], keep[kHG];
+    {
+      const float4 r0 = *(const float4*)&S.red[0][0], r1 = *(const float4*)&S.red[1][0];
+      const float4 r2 = *(const float4*)&S.red[2][0], r3 = *(const float4*)&S.red[3][0];
+      const float mt[kHG] = {vmaxf(vmaxf(r0.x, r1.x), vmaxf(r2.x, r3.x)), vmaxf(vmaxf(r0.y, r1.y), vmaxf(r2.y, r3.y)),
+                             vmaxf(vmaxf(r0.z, r1.z), vmaxf(r2.z, r3.z)), vmaxf(vmaxf(r0.w, r1.w), vmaxf(r2.w, r3.w))};
+#pragma unroll
+      for (int j = 0; j < kHG; ++j) {
+        M[j] = vmaxf(m_run[j], mt[j]);
+        keep[j] = __expf(m_run[j] - M[j]);
+        m_run[j] = M[j];
+      }
+    }
+    const float smax = S.vb[tile - tile_begin];
+    int wexp = 0;
+    if (smax > 0.0f) (void)frexpf(smax, &wexp);
+    const float wscale = smax > 0.0f ? ldexpf(1.0f, wexp - 28) : 0.0f;
+    if (a.scores && tid < n_tok) {
+#pragma unroll
+      for (int j = 0; j < kHG; ++j) a.scores[(size_t)(bq0 + j) * a.score_stride + tile * QAQ_TT + tid] = S.logit[j][tid];
+    }
+
+    // ---- values: the four heads' weights of slot `tid`, as digits ---------------------------------------
+    {
+      const int s = tid;
+      const bool live = s < n_tok;
+      const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
+      const int posv = (int)((vr.pos >> (8u * (slot & 3u))) & 0xffu);
+      const float mn = h2f((uint16_t)(vr.mm & 0xffffu)), mx = h2f((uint16_t)(vr.mm >> 16));
+      const float range = mx - mn;
+      const float scale = ldexpf(range, -cV.bits_of_slot4(s));
+      const float hs = 0.5f * scale;
+      float corr[2] = {0.0f, 0.0f};
+      int och[2] = {0, 0};
+      if (NO2 == 2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const float ovf = vr.o.val(j);
+          const bool top = ovf >= mx;
+          corr[j] = (ovf - (top ? mx : mn)) + (top ? hs : -hs);
+          och[j] = vr.o.idx(j, slot);
+        }
+      }
+      const bool fx = live && smax > 0.0f;
+      const int vg = (s & 15) >> 2;
+      const int i4 = (s - n32V) & (QAQ_TT - 1);
+#pragma unroll
+      for (int j = 0; j < kHG; ++j) {
+        float pt = 0.0f, w = 0.0f;
+        if (live) {
+          pt = __expf(S.logit[j][posv] - M[j]);
+          w = pt * scale;
+          if (NO2 == 2) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+              atomicAdd(&S.xc[j][och[k]][lane & 3], (int)rintf(ldexpf(pt * corr[k], 25 - wexp)));
+          }
+          if (s >= first8V) S.w8[j][s - first8V] = w;
+        }
+        l_run[j] = l_run[j] * keep[j] + pt;
+        bias_run[j] = bias_run[j] * keep[j] + (pt * mn + 0.5f * w);
+        const uint32_t W2 = (fx && s < n32V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0u;
+        S.wl2[j][0][s] = (int8_t)(W2 & 127u); S.wl2[j][1][s] = (int8_t)((W2 >> 7) & 127u);
+        S.wl2[j][2][s] = (int8_t)((W2 >> 14) & 127u); S.wl2[j][3][s] = (int8_t)(W2 >> 21);
+        if (cV.n3 > 0) {
+          const uint32_t W1 = (fx && s < cV.n3) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift1(vg))) : 0u;
+          S.wl1[j][0][s] = (int8_t)(W1 & 127u); S.wl1[j][1][s] = (int8_t)((W1 >> 7) & 127u);
+          S.wl1[j][2][s] = (int8_t)((W1 >> 14) & 127u); S.wl1[j][3][s] = (int8_t)(W1 >> 21);
+        }
+        if (cV.n4 > 0) {
+          const uint32_t W4 = (fx && s >= n32V && s < first8V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp)) : 0u;
+          S.wl4[j][0][i4] = (int8_t)(W4 & 127u); S.wl4[j][1][i4] = (int8_t)((W4 >> 7) & 127u);
+          S.wl4[j][2][i4] = (int8_t)((W4 >> 14) & 127u); S.wl4[j][3][i4] = (int8_t)(W4 >> 21);
+        }
+      }
+    }
+    lds_barrier();
+    // outlier corrections of this tile: (head, channel) pairs sum their copies and clear them
+    if (NO2 == 2) {
+#pragma unroll
+      for (int r = 0; r < NCR; ++r) {
+        const int item = tid + kThreads * r;
+        if (item < kHG * D) {
+          const int j = item / D;
+          int4* c4 = (int4*)&S.xc[0][0][0] + item;
+          const int4 x = *c4;
+          *c4 = make_int4(0, 0, 0, 0);
+          const float kp = j == 0 ? keep[0] : j == 1 ? keep[1] : j == 2 ? keep[2] : keep[3];
+          c_run[r] = c_run[r] * kp + ((float)(x.x + x.y) + (float)(x.z + x.w)) * ldexpf(wscale, 3);
+        }
+      }
+    }
+
+    // ---- values: integer contractions, rows = 4 heads x 4 weight digits ----------------------------------
+    v4i cv[CGW];
+#pragma unroll
+    for (int j = 0; j < CGW; ++j) cv[j] = zero4;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      if (blk * 64 < n32V) {
+        const v4i wa = *(const v4i*)(wb2 + 64 * blk);
+#pragma unroll
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<2>(&vr.vw2[blk][j], 0), cv[j]);
+      }
+      if (blk * 64 < cV.n3) {
+        const v4i wa = *(const v4i*)(wb1 + 64 * blk);
+#pragma unroll
+        for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&vr.vw1[blk], (CGW * wave + j) & 1), cv[j]);
+      }
+    }
+    for (int blk = 0; blk * 64 < cV.n4; ++blk) {
+      const int u = blk * 4 + g;
+      const int nhu = (cV.n4 + 7) >> 3;
+      uint32_t w0[CGW], w1d[CGW];
+      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
+      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
+      const v4i wa = *(const v4i*)(wb4 + 64 * blk);
+#pragma unroll
+      for (int j = 0; j < CGW; ++j) {
+        const uint32_t pr[2] = {w0[j], w1d[j]};
+        cv[j] = mma(wa, spread<4>(pr, 0), cv[j]);
+      }
+    }
+    if (cV.n8 > 0) {
+      // 8-bit values: token-major bytes, fp32 multiply-add per head; this wavefront's D/4 channels
+      constexpr int LPT8 = D / 16;
+      constexpr int TPW = 64 / LPT8;
+      const int sub = lane / LPT8, ch4 = lane % LPT8;
+      float a8[kHG][4];
+#pragma unroll
+      for (int j = 0; j < kHG; ++j)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a8[j][k] = 0.0f;
+      for (int i8 = sub; i8 < cV.n8; i8 += TPW) {
+        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)i8 * D + (D / 4) * wave + 4 * ch4);
+#pragma unroll
+        for (int j = 0; j < kHG; ++j) {
+          const float w8v = S.w8[j][i8];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) a8[j][k] += w8v * (float)((dw >> (8 * k)) & 255u);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kHG; ++j)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float t = a8[j][k];
+#pragma unroll
+          for (int o = LPT8; o < 64; o <<= 1) t += __shfl_xor(t, o);
+          if (sub == 0) S.xw[wave][j][4 * ch4 + k] = t;
+        }
+    }
+    {
+      const float kp = g == 0 ? keep[0] : g == 1 ? keep[1] : g == 2 ? keep[2] : keep[3];
+#pragma unroll
+      for (int j = 0; j < CGW; ++j) {
+        const float hi = (float)cv[j][3] * 2097152.0f + (float)cv[j][2] * 16384.0f;
+        const float lo = (float)cv[j][1] * 128.0f + (float)cv[j][0];
+        float xt = (hi + lo) * wscale;
+        if (cV.n8 > 0) xt += S.xw[wave][g][16 * j + nn];
+        xrun[j] = xrun[j] * kp + xt;
+      }
+    }
+    if (tile + 1 < tile_end) vr.template load<false>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
+  }
+
+  // ---- one partial per query head -------------------------------------------------------------------------
+  lds_barrier();          // the last tile's logits and digits are done with
+#pragma unroll
+  for (int j = 0; j < kHG; ++j) {
+    const float ls = wave_sum(l_run[j]);
+    const float bs = wave_sum(bias_run[j]);
+    if (lane == 0) { S.red[wave][j] = ls; S.red2[wave][j] = bs; }
+  }
+#pragma unroll
+  for (int r = 0; r < NCR; ++r) {
+    const int item = tid + kThreads * r;
+    if (item < kHG * D) (&S.logit[0][0])[(item / D) * QAQ_TT + (item % D)] = c_run[r];
+  }
+  lds_barrier();
+  {
+    const float lsum = (S.red[0][g] + S.red[1][g]) + (S.red[2][g] + S.red[3][g]);
+    const float bias = (S.red2[0][g] + S.red2[1][g]) + (S.red2[2][g] + S.red2[3][g]);
+    float* part = a.partial + ((size_t)(bq0 + g) * a.part_stride + chunk) * (D + 4);
+#pragma unroll
+    for (int j = 0; j < CGW; ++j) {
+      const int ch = (D / 4) * wave + 16 * j + nn;
+      part[ch] = xrun[j] + bias + S.logit[g][ch];
+    }
+    const float mg = g == 0 ? m_run[0] : g == 1 ? m_run[1] : g == 2 ? m_run[2] : m_run[3];
+    if (wave == 0 && nn == 0) { part[D] = mg; part[D + 1] = lsum; }
+  }
+}
+
 // Merge the tiles of one (sequence, query head), add the unquantized new token and
 // normalise.  Block x = 0 writes the output vector; every block normalises its share of
 // the emitted scores (each recomputes the head's max and sum from the per-tile pairs).
@@ -1026,15 +1472,18 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
     if (n_cu <= 0) n_cu = 256;
   }
-  const int slots = 4 * n_cu;
-  const int per_head = slots / BQ > 0 ? slots / BQ : 1;
+  // grouped queries: four query heads of a KV head per pass (k_attn_gqa), where the cache has that form
+  const bool gqa = a.G >= kHG && a.G % kHG == 0 && !a.v.has1 && !a.v.csr && (a.v.no2 == 2 || a.v.no2 == 0);
+  const int units = gqa ? BQ / kHG : BQ;
+  const int slots = (gqa ? 3 : 4) * n_cu;
+  const int per_head = slots / units > 0 ? slots / units : 1;
   a.nparts = ntile < per_head ? ntile : per_head;
   const int least = (ntile + QAQ_MAX_NTC - 1) / QAQ_MAX_NTC;    // a part holds at most QAQ_MAX_NTC tiles
   if (a.nparts < least) a.nparts = least;
   a.ntc = a.nparts > 0 ? (ntile + a.nparts - 1) / a.nparts : 0;
   // Fused form (no second kernel) when the parts of a head fit one workgroup and their raw
   // logits fit its LDS next to the parts' working blocks.
-  const bool fused = ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;
+  const bool fused = !gqa && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;
   if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
   if (static_scratch && !fused) {
     if ((size_t)BQ * (size_t)(a.nparts > 0 ? a.nparts : 1) * (a.v.D + 4) * sizeof(float) > kStaticScratchBytes) {
@@ -1047,7 +1496,17 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
     a.partial = (float*)p;
     a.part_stride = a.nparts > 0 ? a.nparts : 1;
   }
-  if (ntile > 0) {
+  if (ntile > 0 && gqa) {
+    const dim3 grid(a.nparts, units), block(kThreads);
+    hipEvent_t e0 = ev ? ev[0] : nullptr, e1 = ev ? ev[1] : nullptr;
+    if (a.v.D == 128) {
+      if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_gqa<128, 2>), grid, block, 0, s, e0, e1, 0, a);
+      else hipExtLaunchKernelGGL((k_attn_gqa<128, 0>), grid, block, 0, s, e0, e1, 0, a);
+    } else {
+      if (a.v.no2 == 2) hipExtLaunchKernelGGL((k_attn_gqa<64, 2>), grid, block, 0, s, e0, e1, 0, a);
+      else hipExtLaunchKernelGGL((k_attn_gqa<64, 0>), grid, block, 0, s, e0, e1, 0, a);
+    }
+  } else if (ntile > 0) {
     const int fp = fused ? a.nparts : 0;
     const size_t lds = fused && a.scores ? (size_t)a.nparts * a.ntc * QAQ_TT * sizeof(float) : 0;
     if (a.v.D == 128) launch_tile<128>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);

@@ -234,6 +234,45 @@ def test_decode_attention_matches_oracle(cfgno, shape_kw, p_bits):
     assert exh.max() < TOL + 1e-3        # plus fp16 rounding of the output
 
 
+@pytest.mark.parametrize("shape_kw,p_bits,kw", [
+    (dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=64, context=700), (0.4, 0.3, 0.2, 0.1), dict()),          # G = 4, D = 64
+    (dict(batch=1, n_q_heads=16, n_kv_heads=2, head_dim=128, context=1500), (0.5, 0.45, 0.04, 0.01), dict()),    # G = 8: two passes per KV head
+    (dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, context=520), (0.3, 0.3, 0.2, 0.2), dict(n_outlier_per_side=0)),
+    (dict(batch=1, n_q_heads=12, n_kv_heads=1, head_dim=128, context=300), (0.0, 0.0, 0.0, 1.0), dict()),        # G = 12, every token at 8 bits
+    (dict(batch=3, n_q_heads=4, n_kv_heads=1, head_dim=64, context=17), (0.0, 0.0, 1.0, 0.0), dict()),
+])
+def test_grouped_query_attention_matches_oracle(shape_kw, p_bits, kw):
+    """Query heads that share a KV head, four at a time in one pass over its codes: outputs and
+    scores of every query head against the oracle, with and without the new token, and the
+    same call twice (the sums over outlier corrections are order-independent)."""
+    sh = W.shape(5, **shape_kw)
+    _log(f"grouped queries shape={sh} p={p_bits} {kw}")
+    K, V = W.make_kv(5, sh)
+    rng = np.random.default_rng(57)
+    bk, bv = _rand_bits(rng, K.shape[:3], p_bits), _rand_bits(rng, K.shape[:3], p_bits)
+    oc, gc = make_pair(sh, 0.01, **kw)
+    oc.append(K, V, bk, bv); gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    qs = W.make_queries(5, sh, n=2)
+    qs[1] = (qs[1].astype(F32) * 6.0).astype(F16)          # sharper scores for the second call
+    kn, vn = W.make_new_token(5, sh)
+    X, S = gc.decode_attention(dev(qs[0]), want_scores=True)
+    Xo, So = oc.decode_attention(qs[0])
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    _log(f"  cache only: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+    assert ex.max() < TOL and es.max() < TOL
+    X, S = gc.decode_attention(dev(qs[1]), dev(kn), dev(vn), want_scores=True)
+    Xo, So = oc.decode_attention(qs[1], kn, vn)
+    ex, es = attention_errors(X.cpu().numpy(), S.cpu().numpy(), Xo, So)
+    _log(f"  with new token: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+    assert ex.max() < TOL and es.max() < TOL
+    X2, S2 = gc.decode_attention(dev(qs[1]), dev(kn), dev(vn), want_scores=True)
+    np.testing.assert_array_equal(X2.cpu().numpy(), X.cpu().numpy())
+    np.testing.assert_array_equal(S2.cpu().numpy(), S.cpu().numpy())
+    Xn, none = gc.decode_attention(dev(qs[1]), dev(kn), dev(vn))       # without scores
+    assert none is None
+    np.testing.assert_array_equal(Xn.cpu().numpy(), X.cpu().numpy())
+
+
 def test_attention_with_peaked_scores():
     """A query aligned with one key: the softmax is dominated by a single token."""
     sh = W.shape(2, batch=1, n_q_heads=4, n_kv_heads=4, context=600)
