@@ -430,6 +430,12 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   TileLds<D>& S = S_all[P ? chunk : 0];
   const int tid = threadIdx.x & (kThreads - 1), lane = tid & 63, wave = tid >> 6;
   const int nn = lane & 15, g = lane >> 4;
+  // Key side: which quarter of a tile's slots a wavefront takes rotates with the part, so that the
+  // wavefronts one SIMD hosts (the same wavefront index of the parts that share a compute unit) do not
+  // all get the quarter with the widest keys: slots are sorted by width, and a quarter of 3-bit
+  // keys costs twice the contractions of a quarter of 2-bit keys.  The threads that sum the
+  // outlier corrections of the output rotate the same way.
+  const int kwave = (wave + chunk) & 3, ktid = 64 * kwave + lane;
   // Grouped queries, fused form: workgroups are dealt to the eight dies round-robin, so the G
   // query heads of a KV head, which read the same codes, are given indices that land on one
   // die (the reads after the first are served by that die's L2): die x takes the x-th eighth
@@ -473,7 +479,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   };
   KeyRegs<D, NO2> kr;
   ValRegs<D, NO2> vr;
-  kr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), tid);
+  kr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), ktid);
   vr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
@@ -527,7 +533,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   // carried across the tiles
   float m_run = -INFINITY;          // reference of everything below
   float l_run = 0.0f, bias_run = 0.0f;    // per thread: softmax sum and constant terms of its slots
-  float c_run = 0.0f;               // threads 0..D-1: outlier correction of channel tid
+  float c_run = 0.0f;               // threads with ktid < D: outlier correction of channel ktid
   float xrun[CGW];                  // lanes of group 0: output of channel 16*(CGW*wave+j)+n
 #pragma unroll
   for (int j = 0; j < CGW; ++j) xrun[j] = 0.0f;
@@ -538,7 +544,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const bool on = !P || tile < tile_end;       // uniform over the part's 256 threads
     const QaqCounts cK = kr.c, cV = vr.c;
     const int n_tok = kr.n_tok;
-    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);   // the slot this lane's metadata was loaded for
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);   // the value slot this lane's metadata was loaded for
+    const uint32_t kslot = (uint32_t)min(ktid, n_tok - 1); // ... the key slot
     const QaqKRegions rK = qaq_k_regions(cK, D);
     const QaqVRegions rV = qaq_v_regions(cV, D);
     const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
@@ -548,12 +555,12 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const int first1K = H1 ? cK.first1() : n_tok, first1V = H1 ? cV.first1() : n_tok;
 
     // ---- keys: logits ----------------------------------------------------------------------------
-    // Every lane owns slot `tid`; the wavefront runs one contraction chain per width class that
+    // Every lane owns key slot `ktid`; the wavefront runs one contraction chain per width class that
     // occurs among its 64 slots (one, except where a class boundary falls inside them) and
     // every lane keeps the result of its own class.
     float vmax = -INFINITY;
     if (on) {
-      const int w0 = wave * 64, w1 = w0 + 64;
+      const int w0 = kwave * 64, w1 = w0 + 64;
       const int first8K = n32K + cK.n4;
       float dotq = 0.0f;
       if (w0 < n32K) {
@@ -563,7 +570,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
 #pragma unroll
           for (int i = 0; i < KRec<D, 1>::RDW; ++i) k1[i] = kr.kb[i];
           const float low = real_of(k_contract<D, 1>(k1, abase1));
-          dotq = tid < cK.n3 ? 2.0f * dotq + low : dotq;
+          dotq = ktid < cK.n3 ? 2.0f * dotq + low : dotq;
         }
       }
       if (w1 > n32K && w0 < first8K) {
@@ -571,7 +578,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
 #pragma unroll
         for (int i = 0; i < KeyRegs<D, NO2>::HALF; ++i) { k4[i] = kr.ka[i]; k4[KeyRegs<D, NO2>::HALF + i] = kr.kb[i]; }
         const float d4 = real_of(k_contract<D, 4>(k4, abase2));
-        if (tid >= n32K) dotq = d4;
+        if (ktid >= n32K) dotq = d4;
       }
       const int s8_0 = max(first8K, w0);                 // first 8-bit slot among this wavefront's
       const int n8w = min(first1K, w1) - s8_0;           // and how many there are
@@ -593,7 +600,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         if (8 * (lane & 15) >= D) d = 0.0f;
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) d += __shfl_xor(d, o);
-        const int own = tid - s8_0;                        // the lane that owns the slot
+        const int own = ktid - s8_0;                       // the lane that owns the slot
         const float dd = __shfl(d, 16 * (own & 3));
         if (own >= 0 && own < n8w) dotq = dd;
       } else if (__builtin_expect(n8w > 4, 0)) {
@@ -604,9 +611,9 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
         uint32_t w[KRec<D, 8>::RDW];
-        KRec<D, 8>::load(baseK + rK.r8, min(max(tid - first8K, 0), cK.n8 - 1), w);
+        KRec<D, 8>::load(baseK + rK.r8, min(max(ktid - first8K, 0), cK.n8 - 1), w);
         const v4i cc = k_contract<D, 8>(w, abase2);
-        if (tid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
+        if (ktid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
       }
       if (H1 && cK.n1 > 0 && w1 > first1K) {
         // 1-bit keys (only with a width set that has 1): the record came with the tile, where
@@ -615,18 +622,18 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
 #pragma unroll
         for (int i = 0; i < KRec<D, 1>::RDW; ++i) k1[i] = kr.kb[i];
         const float d1 = real_of(k_contract<D, 1>(k1, abase1));
-        if (tid >= first1K) dotq = d1;
+        if (ktid >= first1K) dotq = d1;
       }
-      if (tid < n_tok) {
+      if (ktid < n_tok) {
         if constexpr (NO2 > 2)
-          if (v.csr) kr.o.load_csr(v, 0, qaq_slot_index(v, b, h, tile, 0), (kr.pos >> (8u * (slot & 3u))) & 0xffu, no2);
-        const float lg = key_logit(kr.mm, kr.o, slot, H1 ? cK.bits_of_slot(tid) : cK.bits_of_slot4(tid), dotq);
-        S.logit[(kr.pos >> (8u * (slot & 3u))) & 0xffu] = lg;
+          if (v.csr) kr.o.load_csr(v, 0, qaq_slot_index(v, b, h, tile, 0), (kr.pos >> (8u * (kslot & 3u))) & 0xffu, no2);
+        const float lg = key_logit(kr.mm, kr.o, kslot, H1 ? cK.bits_of_slot(ktid) : cK.bits_of_slot4(ktid), dotq);
+        S.logit[(kr.pos >> (8u * (kslot & 3u))) & 0xffu] = lg;
         vmax = lg;
       }
     }
     // the key registers are free: request the next tile's keys
-    if (tile + 1 < tile_end) kr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), tid);
+    if (tile + 1 < tile_end) kr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), ktid);
 
     vmax = wave_max(vmax);
     if (lane == 0) S.red[8 + wave] = vmax;
@@ -709,9 +716,9 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     if (!on) continue;
     // outlier corrections of this tile: channel tid sums its 16 copies in a fixed order,
     // carries the result like the output, and clears the copies for the next tile
-    if (wave < KS) {
-      int4* c4 = (int4*)&S.xc[tid][0];
-      const int r0 = (tid >> 1) & 3, r1 = (r0 + 1) & 3, r2 = (r0 + 2) & 3, r3 = (r0 + 3) & 3;   // bank-staggered order
+    if (kwave < KS) {
+      int4* c4 = (int4*)&S.xc[ktid][0];
+      const int r0 = (ktid >> 1) & 3, r1 = (r0 + 1) & 3, r2 = (r0 + 2) & 3, r3 = (r0 + 3) & 3;   // bank-staggered order
       const int4 x0 = c4[r0], x1 = c4[r1], x2 = c4[r2], x3 = c4[r3];
       const int4 z = {0, 0, 0, 0};
       c4[r0] = z; c4[r1] = z; c4[r2] = z; c4[r3] = z;
@@ -809,7 +816,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const float ls = wave_sum(l_run);
     const float bs = wave_sum(bias_run);
     if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
-    if (wave < KS) S.xcorr[tid] = c_run;
+    if (kwave < KS) S.xcorr[ktid] = c_run;
   }
   if (P && chunk == 0 && a.k_new) {      // fused form: the logit of the unquantized new token, by the first part
     float qk = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) * __half2float(a.k_new[((size_t)b * v.Hkv + h) * D + tid]) : 0.0f;
