@@ -106,11 +106,35 @@ size_t qaq_arena_bytes(const qaq_config* cfg);
 int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_cache** out);
 int qaq_destroy(qaq_cache* c);
 
-/* Forget all tokens and the score window (host bookkeeping only). */
+/* Forget all tokens and the score window (host bookkeeping only); the sequences have one
+ * length again (see qaq_set_shortfall). */
 int qaq_reset(qaq_cache* c);
 
-/* Number of cached positions per sequence. */
+/* Number of cached positions of the longest sequence (of every sequence, unless
+ * qaq_set_shortfall made them differ). */
 int qaq_length(const qaq_cache* c, int32_t* host_len);
+
+/* Number of cached positions of every sequence: host_len int32 [batch]. */
+int qaq_lengths(const qaq_cache* c, int32_t* host_len);
+
+/* Sequences of different lengths (Section 5.1 evaluates one prompt at a time; a served batch
+ * mixes prompt lengths, and the rules of Section 4.1 depend on each sequence's own token count T).
+ * Declares, for an EMPTY cache with an empty window, that sequence b will always be
+ * host_shortfall[b] tokens shorter than the longest one.  From then on every length that the
+ * caller passes or reads (n_new of the first append, T of qaq_prefill_window, qaq_length, the
+ * strides of bit, score and original-copy arrays) is the longest sequence's, and sequence b
+ * has max(length - host_shortfall[b], 0) tokens: of a [.., length, ..] input or output only
+ * its first that-many positions are read or written (the rest is padding and is left alone),
+ * its thresholds tau_K(T, h) and c_V(T) take its own T, its softmax runs over its own tokens, and
+ * in a score row with a new token that token's score sits right after its own cached tokens.
+ * Every later append and decode step adds the same number of tokens to all sequences.
+ *   host_shortfall  int32 [batch], >= 0, at least one 0, all < max_tokens; all 0 = one length
+ * The first append must be longer than the largest shortfall (no sequence stays empty), and
+ * a prompt must leave the shortest sequence at least n_rows tokens in qaq_prefill_window.
+ * Limits: batch <= 64 and batch * n_kv_heads <= 256 when any shortfall is positive (the
+ * per-sequence thresholds travel as kernel arguments).  Decode attention then always takes its
+ * two-kernel form.  QAQ_ERR_INVALID_ARG if the cache is not empty or a limit is exceeded. */
+int qaq_set_shortfall(qaq_cache* c, const int32_t* host_shortfall);
 
 /* Change the two hyper-parameters of Section 4.1 between calls. */
 int qaq_set_sigmas(qaq_cache* c, double sigma_s_max, double sigma_x_max);

@@ -15,7 +15,8 @@ struct qaq_cache {
   QaqDims dims;
   QaqArena arena;
   QaqView view;
-  int len;                         // cached positions per sequence
+  int len;                         // cached positions of the longest sequence
+  int max_shortfall;               // 0: every sequence has `len` positions; else sequence b has max(len - view.shortfall[b], 0)
   int n_o;
   int ring_next;                   // ring row that the next score row goes to
   int update_parity;               // which of the two hand-over counters the next decode-step update uses
@@ -94,6 +95,34 @@ void thresholds(const qaq_cache* c, int T, float* tau_k, float* c_v) {
   *c_v = (float)(2.0 * std::sqrt(3.0) * c->sigma_x / std::sqrt((double)(T < 1 ? 1 : T)));
 }
 
+int seq_len(const qaq_cache* c, int b, int len_longest) {
+  const int l = len_longest - (c->max_shortfall ? c->view.shortfall[b] : 0);
+  return l > 0 ? l : 0;
+}
+
+// The tables a kernel call gets: thresholds for T tokens in the longest sequence -- per KV head, or,
+// where lengths differ, per (sequence, KV head) for the key rule and per sequence for the value rule,
+// each from the sequence's own token count.
+void threshold_tables(const qaq_cache* c, int T, float* tau_k, float* c_v) {
+  if (!c->max_shortfall) { thresholds(c, T, tau_k, c_v); return; }
+  for (int b = 0; b < c->dims.B; ++b) thresholds(c, seq_len(c, b, T), tau_k + (size_t)b * c->dims.Hkv, c_v + b);
+}
+
+// first tile that holds the position after the end of any sequence
+int first_open_tile(const qaq_cache* c) {
+  const int shortest = c->len - c->max_shortfall;
+  return (shortest > 0 ? shortest : 0) / QAQ_TT;
+}
+
+// on an empty cache whose sequences differ in length, the first append must give every sequence a token
+bool first_append_too_short(const qaq_cache* c, int n_new) {
+  if (c->len == 0 && c->max_shortfall >= n_new) {
+    fail(QAQ_ERR_INVALID_ARG, "the first append of %d tokens leaves the sequence that is %d tokens shorter empty", n_new, c->max_shortfall);
+    return true;
+  }
+  return false;
+}
+
 }  // namespace
 
 // ---- streaming yardsticks ------------------------------------------------------------
@@ -163,6 +192,7 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   c->arena = a;
   c->n_o = d.no2 / 2;
   c->len = 0;
+  c->max_shortfall = 0;
   c->ring_next = 0;
   c->update_parity = 0;
   std::memset(c->row_len, 0, sizeof(c->row_len));
@@ -192,6 +222,8 @@ int qaq_create(const qaq_config* cfg, void* dev_arena, size_t arena_bytes, qaq_c
   v.B = d.B; v.Hq = d.Hq; v.Hkv = d.Hkv; v.D = d.D; v.Tmax = d.Tmax; v.NT = d.NT; v.no2 = d.no2; v.window = d.window;
   v.has1 = cfg->bit_set[0] == 1;
   v.csr = d.csr;
+  v.ragged = 0;
+  std::memset(v.shortfall, 0, sizeof(v.shortfall));
   for (int s = 0; s < 2; ++s) {
     v.ostart[s] = d.csr ? (uint16_t*)(base + a.ostart[s]) : nullptr;
     v.ocnt[s] = d.csr ? base + a.ocnt[s] : nullptr;
@@ -219,6 +251,9 @@ int qaq_destroy(qaq_cache* c) {
 int qaq_reset(qaq_cache* c) {
   if (!c) return fail(QAQ_ERR_INVALID_ARG, "cache is NULL");
   c->len = 0;
+  c->max_shortfall = 0;
+  c->view.ragged = 0;
+  std::memset(c->view.shortfall, 0, sizeof(c->view.shortfall));
   c->ring_next = 0;
   std::memset(c->row_len, 0, sizeof(c->row_len));
   return QAQ_OK;
@@ -227,6 +262,31 @@ int qaq_reset(qaq_cache* c) {
 int qaq_length(const qaq_cache* c, int32_t* host_len) {
   if (!c || !host_len) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   *host_len = c->len;
+  return QAQ_OK;
+}
+
+int qaq_lengths(const qaq_cache* c, int32_t* host_len) {
+  if (!c || !host_len) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  for (int b = 0; b < c->dims.B; ++b) host_len[b] = seq_len(c, b, c->len);
+  return QAQ_OK;
+}
+
+int qaq_set_shortfall(qaq_cache* c, const int32_t* host_shortfall) {
+  if (!c || !host_shortfall) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
+  if (c->len != 0) return fail(QAQ_ERR_INVALID_ARG, "the cache already holds %d tokens", c->len);
+  for (int r = 0; r < QAQ_MAX_WINDOW; ++r)
+    if (c->row_len[r]) return fail(QAQ_ERR_INVALID_ARG, "the attention window already holds score rows");
+  int lo = host_shortfall[0], hi = host_shortfall[0];
+  for (int b = 1; b < c->dims.B; ++b) { lo = host_shortfall[b] < lo ? host_shortfall[b] : lo; hi = host_shortfall[b] > hi ? host_shortfall[b] : hi; }
+  if (lo != 0) return fail(QAQ_ERR_INVALID_ARG, "the smallest shortfall must be 0 (the longest sequence), got %d", lo);
+  if (hi >= c->cfg.max_tokens) return fail(QAQ_ERR_CAPACITY, "a shortfall of %d tokens with max_tokens %d", hi, c->cfg.max_tokens);
+  if (hi > 0 && (c->dims.B > QAQ_MAX_RAGGED_BATCH || c->dims.B * c->dims.Hkv > QAQ_MAX_THR))
+    return fail(QAQ_ERR_INVALID_ARG, "sequences of different lengths: at most %d sequences and %d (sequence, KV head) pairs",
+                QAQ_MAX_RAGGED_BATCH, QAQ_MAX_THR);
+  c->max_shortfall = hi;
+  c->view.ragged = hi > 0;
+  std::memset(c->view.shortfall, 0, sizeof(c->view.shortfall));
+  if (hi > 0) for (int b = 0; b < c->dims.B; ++b) c->view.shortfall[b] = host_shortfall[b];
   return QAQ_OK;
 }
 
@@ -259,6 +319,7 @@ int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int3
   if (((uintptr_t)dev_k & 15) || ((uintptr_t)dev_v & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
   if ((long long)c->len + n_new > c->cfg.max_tokens)
     return fail(QAQ_ERR_CAPACITY, "%d cached + %d new tokens exceed max_tokens %d", c->len, n_new, c->cfg.max_tokens);
+  if (first_append_too_short(c, n_new)) return QAQ_ERR_INVALID_ARG;
   QaqBuildArgs a;
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
@@ -266,7 +327,7 @@ int qaq_quantize_append(qaq_cache* c, const void* dev_k, const void* dev_v, int3
   fill_bit_set(c, a.rule);
   a.len_before = c->len;
   a.len_after = c->len + n_new;
-  a.tile0 = c->len / QAQ_TT;
+  a.tile0 = first_open_tile(c);
   a.n_new = n_new;
   a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
   a.newx[0] = (const __half*)dev_k; a.newx[1] = (const __half*)dev_v;
@@ -292,7 +353,7 @@ int qaq_select_bits(qaq_cache* c, const float* dev_scores, uint8_t* dev_k_bits, 
   if (dev_scores) a.row_len[a.new_row] = c->len;     // the row this call writes (kept by the cache only if the launch succeeds)
   a.nbits = c->cfg.n_bits;
   for (int i = 0; i < 5; ++i) a.bit_set[i] = c->cfg.bit_set[i < a.nbits ? i : a.nbits - 1];
-  thresholds(c, c->len, a.tau_k, &a.c_v);
+  threshold_tables(c, c->len, a.tau_k, a.c_v);
   a.out_bits[0] = dev_k_bits; a.out_bits[1] = dev_v_bits;
   hipError_t e = qaq_launch_select(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "qaq_select_bits");
@@ -336,6 +397,7 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
     return fail(QAQ_ERR_CAPACITY, "%d cached + 1 new token exceed max_tokens %d", c->len, c->cfg.max_tokens);
   if ((dev_k_orig || dev_v_orig) && orig_tokens < c->len + 1)
     return fail(QAQ_ERR_INVALID_ARG, "unquantized copies hold %d tokens, cache will have %d", orig_tokens, c->len + 1);
+  if (first_append_too_short(c, 1)) return QAQ_ERR_INVALID_ARG;
   QaqBuildArgs a;
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
@@ -358,7 +420,7 @@ int qaq_decode_update(qaq_cache* c, const float* dev_scores, const void* dev_k_n
   r.row_len[r.new_row] = a.len_after;               // the row this call writes (kept by the cache only if the launch succeeds)
   r.nbits = c->cfg.n_bits;
   for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
-  thresholds(c, a.len_after, r.tau_k, &r.c_v);
+  threshold_tables(c, a.len_after, r.tau_k, r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
   a.todo = c->view.todo;
   a.todo_count = c->view.todo_count + c->update_parity;
@@ -377,7 +439,7 @@ int qaq_prefill_window(qaq_cache* c, const void* dev_q_last, int32_t n_rows, con
   if (!c || !dev_q_last || !dev_k || !dev_scores_out) return fail(QAQ_ERR_INVALID_ARG, "NULL argument");
   if (c->len != 0) return fail(QAQ_ERR_INVALID_ARG, "the cache already holds %d tokens", c->len);
   if (n_rows < 1 || n_rows > c->dims.window) return fail(QAQ_ERR_INVALID_ARG, "n_rows %d outside [1, window %d]", n_rows, c->dims.window);
-  if (T < n_rows) return fail(QAQ_ERR_INVALID_ARG, "prompt of %d tokens is shorter than %d rows", T, n_rows);
+  if (T - c->max_shortfall < n_rows) return fail(QAQ_ERR_INVALID_ARG, "prompt of %d tokens is shorter than %d rows", T - c->max_shortfall, n_rows);
   if (T > c->cfg.max_tokens) return fail(QAQ_ERR_CAPACITY, "prompt of %d tokens exceeds max_tokens %d", T, c->cfg.max_tokens);
   if (((uintptr_t)dev_q_last & 15) || ((uintptr_t)dev_k & 15)) return fail(QAQ_ERR_INVALID_ARG, "Q/K input must be 16-byte aligned");
   QaqPrefillArgs a;
@@ -406,13 +468,14 @@ int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* de
   if (((uintptr_t)dev_k & 15) || ((uintptr_t)dev_v & 15)) return fail(QAQ_ERR_INVALID_ARG, "K/V input must be 16-byte aligned");
   if ((long long)c->len + n_new > c->cfg.max_tokens)
     return fail(QAQ_ERR_CAPACITY, "%d cached + %d new tokens exceed max_tokens %d", c->len, n_new, c->cfg.max_tokens);
+  if (first_append_too_short(c, n_new)) return QAQ_ERR_INVALID_ARG;
   QaqBuildArgs a;
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
   a.mode = 3;
   a.len_before = c->len;
   a.len_after = c->len + n_new;
-  a.tile0 = c->len / QAQ_TT;
+  a.tile0 = first_open_tile(c);
   a.n_new = n_new;
   a.widest = c->cfg.bit_set[c->cfg.n_bits - 1];
   a.newx[0] = (const __half*)dev_k; a.newx[1] = (const __half*)dev_v;
@@ -422,7 +485,7 @@ int qaq_quantize_append_selected(qaq_cache* c, const void* dev_k, const void* de
   for (int i = 0; i < QAQ_MAX_WINDOW; ++i) r.row_len[i] = i < c->dims.window ? c->row_len[i] : 0;
   r.nbits = c->cfg.n_bits;
   for (int i = 0; i < 5; ++i) r.bit_set[i] = c->cfg.bit_set[i < r.nbits ? i : r.nbits - 1];
-  thresholds(c, a.len_after, r.tau_k, &r.c_v);
+  threshold_tables(c, a.len_after, r.tau_k, r.c_v);
   r.out_bits[0] = dev_k_bits; r.out_bits[1] = dev_v_bits;
   const int tile_last = (a.len_after - 1) / QAQ_TT;
   hipError_t e = qaq_launch_build(a, tile_last - a.tile0 + 1, (hipStream_t)stream);
@@ -558,7 +621,9 @@ int qaq_stats(qaq_cache* c, qaq_stats_t* out, void* stream) {
   out->code_bytes += (buf[10] + buf[11]) * D / 8;
   out->layout_code_bytes = buf[8];
   out->meta_bytes = buf[9];
-  out->fp16_bytes = (long long)c->dims.B * c->dims.Hkv * c->len * D * 2 * 2;
+  long long seq_tokens = 0;
+  for (int b = 0; b < c->dims.B; ++b) seq_tokens += seq_len(c, b, c->len);
+  out->fp16_bytes = seq_tokens * c->dims.Hkv * D * 2 * 2;
   out->update_handovers = (long long)handed[0] + handed[1];     // (the counter of the step to come is zero)
   out->refused_upgrades = buf[12];
   out->served_upgrades = buf[13];

@@ -443,9 +443,17 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
   int bq = blockIdx.y;
   if (P && a.G > 1 && (gridDim.y & 7) == 0) bq = (int)(blockIdx.y & 7) * (int)(gridDim.y >> 3) + (int)(blockIdx.y >> 3);
   const int b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
-  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  const int len = qaq_seq_len(v, b, a.len);          // cached tokens of this sequence
+  const int ntile = (len + QAQ_TT - 1) / QAQ_TT;
   const int tile_begin = (int)((long long)chunk * ntile / a.nparts);
   const int tile_end = (int)((long long)(chunk + 1) * ntile / a.nparts);
+  if (!P && tile_begin >= tile_end) {
+    // a sequence shorter than the longest can leave a part without tiles: a partial that the merge ignores
+    float* part = a.partial + ((size_t)bq * a.part_stride + chunk) * (D + 4);
+    if (tid < D) part[tid] = 0.0f;
+    if (tid == 0) { part[D] = -INFINITY; part[D + 1] = 0.0f; }
+    return;
+  }
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
@@ -474,13 +482,13 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
     QaqCounts r;
     r.n3 = lo & 0xffffu; r.n2 = lo >> 16; r.n4 = hi & 0xffffu; r.n8 = hi >> 16;
-    r.n1 = H1 ? min(a.len - t * QAQ_TT, QAQ_TT) - (r.n3 + r.n2 + r.n4 + r.n8) : 0;      // the 1-bit class is the rest of the tile
+    r.n1 = H1 ? min(len - t * QAQ_TT, QAQ_TT) - (r.n3 + r.n2 + r.n4 + r.n8) : 0;      // the 1-bit class is the rest of the tile
     return r;
   };
   KeyRegs<D, NO2> kr;
   ValRegs<D, NO2> vr;
-  kr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 0), ktid);
-  vr.template load<H1>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+  kr.template load<H1>(v, len, b, h, tile_begin, counts_of(tile_begin, 0), ktid);
+  vr.template load<H1>(v, len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
   int qexp = 0;
@@ -633,7 +641,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       }
     }
     // the key registers are free: request the next tile's keys
-    if (tile + 1 < tile_end) kr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 0), ktid);
+    if (tile + 1 < tile_end) kr.template load<H1>(v, len, b, h, tile + 1, counts_of(tile + 1, 0), ktid);
 
     vmax = wave_max(vmax);
     if (lane == 0) S.red[8 + wave] = vmax;
@@ -808,7 +816,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       }
     }
     // the value registers are free: request the next tile's values
-    if (tile + 1 < tile_end) vr.template load<H1>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
+    if (tile + 1 < tile_end) vr.template load<H1>(v, len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
   }
 
   // ---- one partial per workgroup -----------------------------------------------------------------
@@ -861,9 +869,9 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     float* sc = a.scores + (size_t)bq * a.score_stride;
     for (int it = 0; it < tile_end - tile_begin; ++it) {
       const int t = (tile_begin + it) * QAQ_TT + tid;
-      if (t < a.len) sc[t] = __expf(lg_all[((chunk * a.ntc + it) << 8) + tid] - Mx) * inv;
+      if (t < len) sc[t] = __expf(lg_all[((chunk * a.ntc + it) << 8) + tid] - Mx) * inv;
     }
-    if (a.k_new && chunk == 0 && tid == 0) sc[a.len] = e_new * inv;
+    if (a.k_new && chunk == 0 && tid == 0) sc[len] = e_new * inv;
   }
 }
 
@@ -917,9 +925,19 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   const int unit = blockIdx.y;
   const int b = unit / (v.Hkv * NG), h = (unit / NG) % v.Hkv, hg = unit % NG;
   const int bq0 = b * v.Hq + h * a.G + kHG * hg;           // first of the four query heads
-  const int ntile = (a.len + QAQ_TT - 1) / QAQ_TT;
+  const int len = qaq_seq_len(v, b, a.len);          // cached tokens of this sequence
+  const int ntile = (len + QAQ_TT - 1) / QAQ_TT;
   const int tile_begin = (int)((long long)chunk * ntile / a.nparts);
   const int tile_end = (int)((long long)(chunk + 1) * ntile / a.nparts);
+  if (tile_begin >= tile_end) {
+    // a sequence shorter than the longest can leave a part without tiles: partials that the merge ignores
+    for (int e = tid; e < kHG * (D + 2); e += kThreads) {
+      float* part = a.partial + ((size_t)(bq0 + e / (D + 2)) * a.part_stride + chunk) * (D + 4);
+      const int c = e % (D + 2);
+      part[c] = c == D ? -INFINITY : 0.0f;
+    }
+    return;
+  }
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const v4i zero4 = {0, 0, 0, 0};
 
@@ -958,7 +976,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   int n_tok_n = 0;
   auto load_keys = [&](int tile) {
     cKn = counts_of(tile, 0);
-    n_tok_n = min(a.len - tile * QAQ_TT, QAQ_TT);
+    n_tok_n = min(len - tile * QAQ_TT, QAQ_TT);
     const gbytes_t ubase = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
     const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const QaqKRegions rK = qaq_k_regions(cKn, D);
@@ -984,7 +1002,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   };
   ValRegs<D, NO2> vr;
   load_keys(tile_begin);
-  vr.template load<false>(v, a.len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+  vr.template load<false>(v, len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
 
   // ---- query digits: 22-bit fixed point per head, three signed base-256 digits, one table per
   // spreading format ---------------------------------------------------------------------------------
@@ -1282,7 +1300,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         xrun[j] = xrun[j] * kp + xt;
       }
     }
-    if (tile + 1 < tile_end) vr.template load<false>(v, a.len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
+    if (tile + 1 < tile_end) vr.template load<false>(v, len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
   }
 
   // ---- one partial per query head -------------------------------------------------------------------------
@@ -1325,6 +1343,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bq = blockIdx.y, b = bq / v.Hq, hq = bq % v.Hq, h = hq / a.G;
   const int nparts = a.nparts;
+  const int len = qaq_seq_len(v, b, a.len);          // cached tokens of this sequence
   const float* part = a.partial + (size_t)bq * a.part_stride * (D + 4);
   float* sc = a.scores ? a.scores + (size_t)bq * a.score_stride : nullptr;
   const int t0 = blockIdx.x * (4 * kThreads);
@@ -1333,7 +1352,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int t = t0 + k * kThreads + tid;
-      if (t < a.len) raw[k] = sc[t];
+      if (t < len) raw[k] = sc[t];
     }
   }
   float pm[MAXP], pl[MAXP];
@@ -1371,7 +1390,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int t = t0 + k * kThreads + tid;
-      if (t < a.len) sc[t] = __expf(raw[k] - M) * inv;
+      if (t < len) sc[t] = __expf(raw[k] - M) * inv;
     }
   }
   if (blockIdx.x == 0) {
@@ -1402,7 +1421,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
       if (a.out_is_fp32) ((float*)a.out)[(size_t)bq * D + tid] = x * inv;
       else ((__half*)a.out)[(size_t)bq * D + tid] = __float2half_rn(x * inv);
     }
-    if (sc && a.k_new && tid == 0) sc[a.len] = e_new * inv;
+    if (sc && a.k_new && tid == 0) sc[len] = e_new * inv;
   }
 }
 
@@ -1490,7 +1509,7 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   a.ntc = a.nparts > 0 ? (ntile + a.nparts - 1) / a.nparts : 0;
   // Fused form (no second kernel) when the parts of a head fit one workgroup and their raw
   // logits fit its LDS next to the parts' working blocks.
-  const bool fused = !gqa && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;
+  const bool fused = !gqa && !a.v.ragged && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;   // its parts run in lockstep: every one needs a tile
   if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
   if (static_scratch && !fused) {
     if ((size_t)BQ * (size_t)(a.nparts > 0 ? a.nparts : 1) * (a.v.D + 4) * sizeof(float) > kStaticScratchBytes) {

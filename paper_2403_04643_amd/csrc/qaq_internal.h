@@ -9,6 +9,8 @@
 
 #define QAQ_MAX_KV_HEADS 128
 #define QAQ_MAX_WINDOW 8
+#define QAQ_MAX_THR 256          // threshold table of a call: per KV head, or per (sequence, KV head) where lengths differ
+#define QAQ_MAX_RAGGED_BATCH 64  // sequences of a cache whose lengths differ
 
 // What every kernel sees of a cache: raw pointers into the arena plus the shape.
 struct QaqView {
@@ -35,7 +37,17 @@ struct QaqView {
   uint8_t* ocnt[2];
   const float* othr;       // [2][Hkv][2] thresholds (lo, hi)
   uint32_t cap[2];
+  // Sequences of different lengths: every length the host passes (cached tokens, tokens a window row
+  // covers) is that of the longest sequence, and sequence b is shortfall[b] tokens shorter -- a
+  // decode step adds one token to every sequence, so the differences stay what the first append made them.
+  int ragged;              // 0: all sequences have one length, kernels do not read the table
+  int shortfall[QAQ_MAX_RAGGED_BATCH];
 };
+
+// tokens of sequence b, given the longest sequence's count
+__device__ __forceinline__ int qaq_seq_len(const QaqView& v, int b, int len_longest) {
+  return v.ragged ? max(len_longest - v.shortfall[b], 0) : len_longest;
+}
 
 __host__ __device__ __forceinline__ size_t qaq_bh(const QaqView& v, int b, int h) { return (size_t)b * v.Hkv + h; }
 // The window's rows: value as stored (what the predicted score is taken over), load, store.
@@ -81,10 +93,12 @@ struct QaqRuleArgs {
   int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
   int nbits;
   int bit_set[5];
-  float tau_k[QAQ_MAX_KV_HEADS];
-  float c_v;
+  float tau_k[QAQ_MAX_THR];        // key-rule threshold per KV head; per (sequence, KV head) in a cache with different lengths
+  float c_v[QAQ_MAX_RAGGED_BATCH]; // value-rule threshold; per sequence in such a cache, else entry 0
   uint8_t* out_bits[2];    // [B,Hkv,len] or null
 };
+__device__ __forceinline__ float qaq_tau_k(const QaqRuleArgs& r, const QaqView& v, int b, int h) { return r.tau_k[v.ragged ? b * v.Hkv + h : h]; }
+__device__ __forceinline__ float qaq_c_v(const QaqRuleArgs& r, const QaqView& v, int b) { return r.c_v[v.ragged ? b : 0]; }
 
 struct QaqBuildArgs {
   QaqView v;
@@ -112,8 +126,8 @@ struct QaqSelectArgs {
   int row_len[QAQ_MAX_WINDOW];  // tokens covered by each ring row, 0 = unused
   int nbits;
   int bit_set[5];
-  float tau_k[QAQ_MAX_KV_HEADS];
-  float c_v;
+  float tau_k[QAQ_MAX_THR];        // as in QaqRuleArgs
+  float c_v[QAQ_MAX_RAGGED_BATCH];
   uint8_t* out_bits[2];    // [B,Hkv,len]
 };
 

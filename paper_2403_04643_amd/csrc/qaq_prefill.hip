@@ -18,7 +18,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
 constexpr int kKeep = 16;          // logits per thread the softmax kernel keeps in registers (a 4096-token row)
 
-// tokens a query row attends to: row i belongs to prompt position T - n + i
+// tokens a query row attends to: row i belongs to position T - n + i of a prompt of T tokens
 __device__ __forceinline__ int row_length(int T, int n, int i) { return T - n + i + 1; }
 
 template <int D>
@@ -30,6 +30,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_logits(QaqPrefillArgs a) {
   const int bh = blockIdx.x, b = bh / v.Hkv, h = bh % v.Hkv;     // heads fastest (see k_build)
   const int t_wave = blockIdx.y * QAQ_TT + 64 * wave;
   if (t_wave >= a.T) return;
+  const int T_seq = qaq_seq_len(v, b, a.T);      // tokens of this sequence's prompt (rows of K past them are padding)
 
   // 64 keys of this wavefront: lane (col, kb) holds channels 32s + 8kb .. +8 of key 16g + col
   h8 key[4][NS];
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_logits(QaqPrefillArgs a) {
           if (r < R) {
             const int hq = h * a.G + r / a.n_rows, i = r % a.n_rows;
             a.scores[(((size_t)i * v.B + b) * v.Hq + hq) * a.T + t] =
-                t < row_length(a.T, a.n_rows, i) ? acc[j] * scale : -INFINITY;
+                t < row_length(T_seq, a.n_rows, i) ? acc[j] * scale : -INFINITY;
           }
         }
       }
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void k_prefill_softmax(QaqPrefillArgs a) 
   const QaqView& v = a.v;
   const int tid = threadIdx.x;
   const int i = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
-  const int len = row_length(a.T, a.n_rows, i);
+  const int len = row_length(qaq_seq_len(v, b, a.T), a.n_rows, i);
   const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
   const size_t ring0 = (size_t)i * ring_row + qaq_bh(v, b, h) * v.Tmax;
   for (int g = 0; g < a.G; ++g) {

@@ -755,19 +755,23 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = bh / v.Hkv, h = bh % v.Hkv;
   const int t0 = tile * QAQ_TT;
-  const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
-  const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
+  const int len_before = qaq_seq_len(v, b, a.len_before), len_after = qaq_seq_len(v, b, a.len_after);   // of this sequence
+  const int n_before = min(max(len_before - t0, 0), QAQ_TT);
+  const int n_after = min(max(len_after - t0, 0), QAQ_TT);
   if (n_after == 0) return;
   const int n_o = v.no2 / 2;
 
   if (a.mode == 1 && a.newbits[side] == nullptr) return;   // requantize: nothing to do for this side
+  // an append, where sequences differ in length: the grid starts at the shortest sequence's open
+  // tile, which a longer sequence may have filled already
+  if ((a.mode == 0 || a.mode == 3) && n_before == n_after) return;
 
   // decode-step update, key side: the rule compares a token's range with one threshold per
   // (T, head); the tile keeps, from when it was built, the interval of thresholds for which
   // none of its tokens changes width, so a tile with nothing to do costs one 8-byte load
   if (a.mode == 2 && side == 0 && n_before == n_after && !a.rule.out_bits[0]) {
     const float2 keep = ((const float2*)v.kthr)[qaq_bh(v, b, h) * v.NT + tile];
-    const float tau = a.rule.tau_k[h];
+    const float tau = qaq_tau_k(a.rule, v, b, h);
     if (tau >= keep.x && tau < keep.y) return;
   }
 
@@ -809,7 +813,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     pred = s;
     for (int r = 0; r < v.window; ++r) {
       if (r == ru.new_row) continue;
-      if (t < ru.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
+      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
     }
     if (a.mode == 2) qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
   }
@@ -860,7 +864,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     const QaqRuleArgs& ru = a.rule;
     const float range = h2f((uint16_t)(m >> 16)) - h2f((uint16_t)(m & 0xffffu));
     const float lhs = side == 0 ? range : range * pred;
-    const float thr = side == 0 ? ru.tau_k[h] : ru.c_v;
+    const float thr = side == 0 ? qaq_tau_k(ru, v, b, h) : qaq_c_v(ru, v, b);
     int w = ru.bit_set[ru.nbits - 1];
     for (int i = ru.nbits - 1; i >= 0; --i)
       if (lhs <= ldexpf(thr, ru.bit_set[i])) w = ru.bit_set[i];
@@ -877,7 +881,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
       else if (req_rule > oldb) { wider = true; if (a.orig[side]) changed = true; }
     }
     note_widenings(L.wave_wide, wider);
-    const bool has_new = a.len_before >= t0 && a.len_before < t0 + QAQ_TT;
+    const bool has_new = len_before >= t0 && len_before < t0 + QAQ_TT;
     const bool any = __syncthreads_or(changed ? 1 : 0) != 0;
     if (tid == 0) add_widenings(v, (qaq_bh(v, b, h) * v.NT + tile) * 2 + side, L.wave_wide, a.orig[side] != nullptr);
     if (!any && !has_new) return;
@@ -898,7 +902,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
       }
       enc = nb > oldb;
     } else {
-      const int r = t0 + tid - a.len_before;
+      const int r = t0 + tid - len_before;
       nb = a.newbits[side] ? a.newbits[side][(size_t)bh * a.n_new + r] : a.widest;
       L.bits_old[tid] = (uint8_t)nb;
       enc = true;
@@ -939,7 +943,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
       if (pass >= NP || pass * TPP + gt >= n_enc) return 0;
       const int p = position(pass);
       const bool fresh = p >= n_before;
-      const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - a.len_before)) * D
+      const __half* src = fresh ? a.newx[side] + ((size_t)bh * a.n_new + (t0 + p - len_before)) * D
                                 : a.orig[side] + ((size_t)bh * a.orig_tokens + (t0 + p)) * D;
 #pragma unroll
       for (int i = 0; i < Enc::NCH; ++i) {      // read once: streaming loads
@@ -976,7 +980,7 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     const int w = rule_width(L.mm[tid]);
     if (a.rule.out_bits[side]) {
       if (a.mode == 2) a.rule.out_bits[side][(size_t)bh * a.len_after + t0 + tid] = (uint8_t)w;
-      else a.rule.out_bits[side][(size_t)bh * a.n_new + (t0 + tid - a.len_before)] = (uint8_t)w;
+      else a.rule.out_bits[side][(size_t)bh * a.n_new + (t0 + tid - len_before)] = (uint8_t)w;
     }
     L.shf[tid] = (uint8_t)(a.widest - w);
     L.bits_new[tid] = (uint8_t)w;
@@ -1379,8 +1383,9 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   // step), most key sides leave after one load and fill in behind
   const int tile = blockIdx.y, side = 1 - (int)blockIdx.z;
   const int t0 = tile * QAQ_TT;
-  const int n_before = min(max(a.len_before - t0, 0), QAQ_TT);
-  const int n_after = min(max(a.len_after - t0, 0), QAQ_TT);
+  const int len_before = qaq_seq_len(v, b, a.len_before), len_after = qaq_seq_len(v, b, a.len_after);   // of this sequence
+  const int n_before = min(max(len_before - t0, 0), QAQ_TT);
+  const int n_after = min(max(len_after - t0, 0), QAQ_TT);
   if (bh == 0 && tile == 0 && side == 0 && tid == 0) *a.todo_count_next = 0u;
   if (n_after == 0) return;
   const bool has_new = n_after > n_before;           // the appended token is position n_before of this tile
@@ -1389,7 +1394,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   // tokens changes width (one 8-byte load decides)
   if (side == 0 && !has_new && !ru.out_bits[0]) {
     const float2 keep = ((const float2*)v.kthr)[tile_id];
-    const float tau = ru.tau_k[h];
+    const float tau = qaq_tau_k(ru, v, b, h);
     if (tau >= keep.x && tau < keep.y) return;
   }
 
@@ -1418,7 +1423,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     float pred = s;
     for (int r = 0; r < v.window; ++r) {
       if (r == ru.new_row) continue;
-      if (t < ru.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
+      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
     }
     qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
     L.pred[tid] = pred;
@@ -1433,7 +1438,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     const bool act = 2 * lane < D;
     const uint32_t* src = (const uint32_t*)(a.newx[side] + (size_t)bh * a.n_new * D);
     const uint32_t w = act ? src[lane] : 0u;
-    if (act && a.orig_put[side]) ((uint32_t*)(a.orig_put[side] + ((size_t)bh * a.orig_tokens + a.len_before) * D))[lane] = w;
+    if (act && a.orig_put[side]) ((uint32_t*)(a.orig_put[side] + ((size_t)bh * a.orig_tokens + len_before) * D))[lane] = w;
     const uint32_t kk = order_keys_pair(w);
     const int ch0 = 2 * lane, ch1 = 2 * lane + 1;
     const uint32_t k0 = kk << 16, k1 = kk & 0xffff0000u;
@@ -1482,7 +1487,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   bool changed = false, wider = false;
   if (tid < n_after) {
     const float lhs = side == 0 ? range : range * L.pred[pos];
-    const float thr = side == 0 ? ru.tau_k[h] : ru.c_v;
+    const float thr = side == 0 ? qaq_tau_k(ru, v, b, h) : qaq_c_v(ru, v, b);
     int req = ru.bit_set[ru.nbits - 1];
     for (int i = ru.nbits - 1; i >= 0; --i)
       if (lhs <= ldexpf(thr, ru.bit_set[i])) req = ru.bit_set[i];
@@ -1810,7 +1815,7 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
   const int tid = threadIdx.x;
   const int tile = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
   const int t0 = tile * QAQ_TT;
-  const int n_tok = min(a.len - t0, QAQ_TT);
+  const int n_tok = min(qaq_seq_len(v, b, a.len) - t0, QAQ_TT);
   if (n_tok <= 0) return;
   // all loads first (slot-order ranges, this step's scores, the window rows), one barrier,
   // then the comparisons
@@ -1830,7 +1835,7 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
     }
     for (int r = 0; r < v.window; ++r) {
       if (a.scores && r == a.new_row) continue;
-      if (t < a.row_len[r]) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
+      if (t < qaq_seq_len(v, b, a.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
     }
     if (a.scores) qaq_ring_store(v, (size_t)a.new_row * ring_row + ri, s);
     rk[pk] = h2f((uint16_t)(mk >> 16)) - h2f((uint16_t)(mk & 0xffffu));
@@ -1838,13 +1843,14 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
   }
   __syncthreads();
   if (tid >= n_tok) return;
-  const float tau = a.tau_k[h];
+  const float tau = a.tau_k[v.ragged ? b * v.Hkv + h : h];
+  const float c_v = a.c_v[v.ragged ? b : 0];
   const float lhs_v = rv[tid] * pred;
   int bk = a.bit_set[a.nbits - 1], bv = a.bit_set[a.nbits - 1];
   for (int i = a.nbits - 1; i >= 0; --i) {
     const int bb = a.bit_set[i];
     if (rk[tid] <= ldexpf(tau, bb)) bk = bb;
-    if (lhs_v <= ldexpf(a.c_v, bb)) bv = bb;
+    if (lhs_v <= ldexpf(c_v, bb)) bv = bb;
   }
   a.out_bits[0][(size_t)bh * a.len + t] = (uint8_t)bk;
   a.out_bits[1][(size_t)bh * a.len + t] = (uint8_t)bv;
@@ -1861,7 +1867,7 @@ __global__ __launch_bounds__(kThreads) void k_export(QaqExportArgs a) {
   const int tid = threadIdx.x;
   const int tile = blockIdx.x, bh = blockIdx.y, b = bh / v.Hkv, h = bh % v.Hkv;
   const int t0 = tile * QAQ_TT;
-  const int n_tok = min(a.len - t0, QAQ_TT);
+  const int n_tok = min(qaq_seq_len(v, b, a.len) - t0, QAQ_TT);
   if (n_tok <= 0) return;
   tile_load<D>(v, a.side, b, h, tile, n_tok, L);
   if (tid < n_tok) {
@@ -1901,7 +1907,7 @@ __global__ __launch_bounds__(kThreads) void k_dequant(QaqDequantArgs a) {
   const int side = blockIdx.z;
   if (a.out[side] == nullptr) return;
   const int t0 = tile * QAQ_TT;
-  const int n_tok = min(a.len - t0, QAQ_TT);
+  const int n_tok = min(qaq_seq_len(v, b, a.len) - t0, QAQ_TT);
   if (n_tok <= 0) return;
   tile_load<D>(v, side, b, h, tile, n_tok, L);
   const int nt = a.t1 - a.t0;
@@ -1941,7 +1947,9 @@ __global__ __launch_bounds__(kThreads) void k_stats(QaqView v, int len) {
     const long long j = i >> 1;
     const int tile = (int)(j % ntile);
     const int bh = (int)(j / ntile);
-    const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile, min(len - tile * QAQ_TT, QAQ_TT));
+    const int n_tok = min(qaq_seq_len(v, bh / v.Hkv, len) - tile * QAQ_TT, QAQ_TT);
+    if (n_tok <= 0) continue;      // past the end of a shorter sequence
+    const QaqCounts c = qaq_load_counts(v, side, bh / v.Hkv, bh % v.Hkv, tile, n_tok);
     loc[side * 4 + 0] += c.n2; loc[side * 4 + 1] += c.n3; loc[side * 4 + 2] += c.n4; loc[side * 4 + 3] += c.n8;
     loc[10 + side] += c.n1;
 

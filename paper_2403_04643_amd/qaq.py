@@ -48,6 +48,8 @@ SIGNATURES = {
     "qaq_destroy": (C.c_int, [_vp]),
     "qaq_reset": (C.c_int, [_vp]),
     "qaq_length": (C.c_int, [_vp, C.POINTER(C.c_int32)]),
+    "qaq_lengths": (C.c_int, [_vp, C.POINTER(C.c_int32)]),
+    "qaq_set_shortfall": (C.c_int, [_vp, C.POINTER(C.c_int32)]),
     "qaq_set_sigmas": (C.c_int, [_vp, C.c_double, C.c_double]),
     "qaq_thresholds": (C.c_int, [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "qaq_quantize_append": (C.c_int, [_vp, _vp, _vp, _i32, _u8p, _u8p, _vp]),
@@ -212,6 +214,17 @@ class Cache:
         n = C.c_int32()
         _check(self.lib.qaq_length(self.h, C.byref(n)))
         return n.value
+
+    def lengths(self):
+        n = (C.c_int32 * self.cfg.batch)()
+        _check(self.lib.qaq_lengths(self.h, n))
+        return list(n)
+
+    def set_shortfall(self, shortfall):
+        s = (C.c_int32 * self.cfg.batch)(*[int(x) for x in shortfall])
+        if len(shortfall) != self.cfg.batch:
+            raise ValueError("one shortfall per sequence")
+        _check(self.lib.qaq_set_shortfall(self.h, s))
 
     def reset(self):
         _check(self.lib.qaq_reset(self.h))

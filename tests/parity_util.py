@@ -16,8 +16,7 @@ def dev(a, dtype=None):
     return t.cuda()
 
 
-def make_pair(sh, qnorm2, max_tokens=None, **kw):
-    """(oracle cache, GPU cache) with identical hyper-parameters."""
+def _configs(sh, qnorm2, max_tokens=None, **kw):
     qn = np.full(sh.n_kv_heads, qnorm2, F32) if np.isscalar(qnorm2) else np.asarray(qnorm2, F32)
     okw = dict(window=kw.get("window", 5), sigma_s_max=kw.get("sigma_s_max", 1e-3),
                sigma_x_max=kw.get("sigma_x_max", 1e-2), outlier_frac=kw.get("outlier_frac", 0.01),
@@ -27,7 +26,18 @@ def make_pair(sh, qnorm2, max_tokens=None, **kw):
     ocfg = O.Config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, qnorm2=qn, **okw)
     gcfg = qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim,
                            max_tokens or sh.context, qn.tolist(), **okw)
+    return ocfg, gcfg
+
+
+def make_pair(sh, qnorm2, max_tokens=None, **kw):
+    """(oracle cache, GPU cache) with identical hyper-parameters."""
+    ocfg, gcfg = _configs(sh, qnorm2, max_tokens, **kw)
     return O.OracleCache(ocfg), qaq.Cache(gcfg)
+
+
+def make_oracle(sh, qnorm2, max_tokens=None, **kw):
+    """The oracle cache of make_pair alone."""
+    return O.OracleCache(_configs(sh, qnorm2, max_tokens, **kw)[0])
 
 
 def compare_canonical(oc, gc, what=""):
