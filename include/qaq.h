@@ -14,7 +14,9 @@
  *     enqueue kernels on it and return; they do not synchronise, and after
  *     qaq_create they allocate nothing.  (qaq_create and qaq_stats do synchronise.)
  *   - Tensors are row-major with the head dimension D innermost.  fp16 is IEEE
- *     binary16.  All sequences of the batch have the same length.
+ *     binary16.  All sequences of the batch have the same length unless
+ *     qaq_set_shortfall says otherwise; a length argument is then the longest
+ *     sequence's, and arrays are padded to it.
  *   - Return value: QAQ_OK (0) or a negative qaq_status.  Arguments are validated on
  *     the host without reading device memory; nothing crosses the ABI as an
  *     exception or abort.  qaq_last_error() gives a thread-local description.
