@@ -618,9 +618,17 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
-        uint32_t w[KRec<D, 8>::RDW];
-        KRec<D, 8>::load(baseK + rK.r8, min(max(ktid - first8K, 0), cK.n8 - 1), w);
-        const v4i cc = k_contract<D, 8>(w, abase2);
+        // the record in pieces of two slices (eight registers at a time: the whole record in
+        // registers would make every tile of every call pay for this path with spills)
+        const uint8_t* rec = baseK + rK.r8 + (uint32_t)min(max(ktid - first8K, 0), cK.n8 - 1) * (uint32_t)D;
+        v4i cc = zero4;
+#pragma unroll 1
+        for (int q2 = 0; q2 < D / 32; ++q2) {
+          uint32_t w[8];
+          load_dwords<8>(rec + 32 * q2, w);
+          cc = mma(*(const v4i*)(abase2 + 32 * q2), spread<8>(&w[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 32 * q2 + 16), spread<8>(&w[4], 0), cc);
+        }
         if (ktid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
       }
       if (H1 && cK.n1 > 0 && w1 > first1K) {
