@@ -371,7 +371,14 @@ struct ValRegs {
   uint32_t vw2[4][CGW], vw1[4];
   // vw1: blocks (of 4 units) of the 3-bit tokens' low planes from entry 0 up; with a width set
   // that has 1, blocks of the 1-bit tokens' units from entry 3 down as far as entries are free
-  template <bool H1>
+  // PRE8 (the grouped-query kernel; in k_attn_tile the two registers cost the common case more than
+  // the rare classes gain):
+  uint32_t v4p;  // D = 128: one word of the first two half-units (16 slots) of the 4-bit region: lane
+                 // group g holds word g & 1 of half-unit g >> 1 (handed to the lanes that need it when it is used)
+  uint32_t v8;   // 8-bit values (token-major rows): this lane's four channels of row lane / (D/16), so
+                 // that the first 64 / (D/16) such tokens of a tile -- a tile of a cache the rules shaped rarely
+                 // has more -- cost no load inside the tile loop
+  template <bool H1, bool PRE8 = false>
   __device__ __forceinline__ void load(const QaqView& v, int len, int b, int h, int tile, const QaqCounts& cv, int tid, int wave, int nn, int g) {
     c = cv;
     const int n_tok = min(len - tile * QAQ_TT, QAQ_TT);
@@ -387,6 +394,14 @@ struct ValRegs {
     for (int blk = 0; blk < 4; ++blk)
       if (!H1 || blk * 64 < c.n32()) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);   // (blocks past the region are not used)
     const QaqVRegions rV = qaq_v_regions(c, D);
+    if (PRE8 && CGW == 2) {
+      const int nhu = (c.n4 + 7) >> 3;
+      v4p = gload32(ubase, c.n4 > 0 ? rV.r4 + (uint32_t)min(g >> 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * (uint32_t)(CGW * wave + (g & 1)) : 0u);
+    }
+    if (PRE8) {
+      const int lane = tid & 63;
+      v8 = gload32(ubase, c.n8 > 0 ? rV.r8 + (uint32_t)min(lane / (D / 16), c.n8 - 1) * D + (D / 4) * wave + 4 * (lane % (D / 16)) : 0u);
+    }
     const int nu1 = (c.n3 + 15) >> 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
@@ -797,11 +812,27 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       constexpr int TPW = 64 / LPT8;       // tokens per pass
       float a8[4] = {0.f, 0.f, 0.f, 0.f};
       const int sub = lane / LPT8, ch4 = lane % LPT8;
-      for (int i8 = sub; i8 < cV.n8; i8 += TPW) {
-        const float w8 = S.w8[i8];
-        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)i8 * D + (D / 4) * wave + 4 * ch4);
+      if (sub < cV.n8) {                  // a tile of a cache the rules shaped rarely has more than these rows
+        const float w8 = S.w8[sub];
+        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)sub * D + (D / 4) * wave + 4 * ch4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw >> (8 * j)) & 255u);
+      }
+      // the others: four rows requested at a time (a row past the end repeats the last one and gets weight 0)
+      constexpr int UB = 4;
+#pragma unroll 1
+      for (int i0 = sub + TPW; i0 < cV.n8; i0 += UB * TPW) {
+        uint32_t dw[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+          dw[u] = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)min(i0 + u * TPW, cV.n8 - 1) * D + (D / 4) * wave + 4 * ch4);
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          const int i8 = i0 + u * TPW;
+          const float w8 = i8 < cV.n8 ? S.w8[min(i8, QAQ_TT - 1)] : 0.0f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw[u] >> (8 * j)) & 255u);
+        }
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -914,9 +945,11 @@ struct GqaLds {
   alignas(16) int8_t wl4[kHG][4][QAQ_TT + 16];
   float w8[kHG][QAQ_TT];                       // fp32 weights of the 8-bit slots
   float xw[4][kHG][D / 4];                     // per wavefront: 8-bit-class outputs of its own channels
+  alignas(16) uint32_t v8[4][64];              // per wavefront: 64 / (D/16) rows of 8-bit values, its D/4 channels of each
   alignas(16) int xc[kHG][D][4];               // outlier corrections of one tile, fixed point, four copies per channel
   alignas(16) float red[4][kHG];               // per wavefront and head
   alignas(16) float red2[4][kHG];
+  int sq[kHG];                                 // per head: sum of the unscaled query integers (8-bit keys are stored as code - 128)
 };
 
 template <int D, int NO2>
@@ -966,6 +999,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
     }
   }
   S.zrow[tid] = 0;
+  if (tid < kHG) S.sq[tid] = 0;
   for (int e = tid; e < kHG * D * 4; e += kThreads) (&S.xc[0][0][0])[e] = 0;
   lds_barrier();
 
@@ -978,8 +1012,10 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   };
 
   // ---- what is loaded ahead for the key side: lane (n, g) holds, for each of its wavefront's four
-  // groups of 16 slots, the slices g*KS .. g*KS+KS-1 of slot 16*tg + n and that slot's metadata ------
-  uint32_t ka[4][KS], kb[4][KS], kmm[4], kpos[4], koi[4], kov[4];
+  // groups of 16 slots, the slices g*KS .. g*KS+KS-1 of slot 16*tg + n; the metadata of a slot is
+  // held once, by lane 16*tg + n (slot = lane index), and handed to the other three lanes that work
+  // on the token (one per head) when its group is processed ----------------------------------------
+  uint32_t ka[4][KS], kb[4][KS], kmm, kpos, koi, kov;
   QaqCounts cKn;
   int n_tok_n = 0;
   auto load_keys = [&](int tile) {
@@ -989,15 +1025,18 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
     const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
     const QaqKRegions rK = qaq_k_regions(cKn, D);
     const int n32 = cKn.n32();
+    {
+      const int so = min(64 * wave + lane, n_tok_n - 1);
+      kmm = gload32(uniform_ptr(v.mm[0] + gi0), 4u * (uint32_t)so);
+      kpos = gload32(uniform_ptr(v.perm[0] + gi0), (uint32_t)so & ~3u);
+      if (NO2 == 2) {
+        koi = gload32(uniform_ptr(v.oidx[0] + gi0 * 2), (2u * (uint32_t)so) & ~3u);
+        kov = gload32(uniform_ptr(v.oval[0] + gi0 * 2), 4u * (uint32_t)so);
+      }
+    }
 #pragma unroll
     for (int tg = 0; tg < 4; ++tg) {
       const int s = min(64 * wave + 16 * tg + nn, n_tok_n - 1);
-      kmm[tg] = gload32(uniform_ptr(v.mm[0] + gi0), 4u * (uint32_t)s);
-      kpos[tg] = gload32(uniform_ptr(v.perm[0] + gi0), (uint32_t)s & ~3u);
-      if (NO2 == 2) {
-        koi[tg] = gload32(uniform_ptr(v.oidx[0] + gi0 * 2), (2u * (uint32_t)s) & ~3u);
-        kov[tg] = gload32(uniform_ptr(v.oval[0] + gi0 * 2), 4u * (uint32_t)s);
-      }
       const bool is3 = s < cKn.n3, is23 = s < n32, is4 = !is23 && s < n32 + cKn.n4;
       const uint32_t rec4 = rK.r4 + (uint32_t)(s - n32) * (uint32_t)(D / 2) + (uint32_t)g * (8u * KS);
       const uint32_t off_a = is23 ? (uint32_t)s * (uint32_t)(D / 4) + (uint32_t)g * (4u * KS) : is4 ? rec4 : 0u;
@@ -1010,7 +1049,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   };
   ValRegs<D, NO2> vr;
   load_keys(tile_begin);
-  vr.template load<false>(v, len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+  vr.template load<false, true>(v, len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
 
   // ---- query digits: 22-bit fixed point per head, three signed base-256 digits, one table per
   // spreading format ---------------------------------------------------------------------------------
@@ -1032,6 +1071,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         const int x = qmax > 0.0f ? (int)rintf(ldexpf(qv[j], 22 - qexp - sh)) : 0;
         const uint32_t dg = digits_packed(x);
         S.ql[f][j][0][pos] = (int8_t)dg; S.ql[f][j][1][pos] = (int8_t)(dg >> 8); S.ql[f][j][2][pos] = (int8_t)(dg >> 16);
+        if (f == 2) atomicAdd(&S.sq[j], x);        // integers: the order of the additions does not matter
       }
     }
   }
@@ -1104,33 +1144,38 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         const int i8 = min(max(s - first8K, 0), max(cK.n8 - 1, 0));
         uint32_t w8r[4 * KS];
         load_dwords<4 * KS>(baseK + rK.r8 + (uint32_t)i8 * D + (uint32_t)g * (16u * KS), w8r);
+        const int sq = S.sq[g];
         v4i c = zero4;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) c = mma(*(const v4i*)(abase2 + 16 * ks), spread<8>(&w8r[4 * ks], 0), c);
-        int sq = 0;
-        for (int d = nn; d < D; d += 16) sq += (int)S.ql[2][g][0][d] + 256 * (int)S.ql[2][g][1][d] + 65536 * (int)S.ql[2][g][2][d];
-#pragma unroll
-        for (int o = 8; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
         if (s >= first8K) dotq = ((((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) + 128.0f * (float)sq) * qscale_g;
       }
+      // metadata of slot s from the lane that holds it (every lane takes part in the exchange)
+      const int src = 4 * (16 * tg + nn);
+      const uint32_t m = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kmm);
+      const uint32_t pos4 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kpos);
+      uint32_t oi4 = 0, ov2 = 0;
+      if (NO2 == 2) {
+        oi4 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)koi);
+        ov2 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kov);
+      }
       if (s < n_tok) {
-        const uint32_t m = kmm[tg];
         const float mn = h2f((uint16_t)(m & 0xffffu)), mx = h2f((uint16_t)(m >> 16));
         const float range = mx - mn;
         const float scale = ldexpf(range, -cK.bits_of_slot4(s));
         float val = mn * sumq_g + scale * (dotq + 0.5f * sumq_g);
         if (NO2 == 2) {
           const float hs = 0.5f * scale;
-          const uint32_t oi = koi[tg] >> (16 * (s & 1));
+          const uint32_t oi = oi4 >> (16 * (s & 1));
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
-            const float ovf = h2f((uint16_t)(kov[tg] >> (16 * j)));
+            const float ovf = h2f((uint16_t)(ov2 >> (16 * j)));
             const bool top = ovf >= mx;
             val += S.qf[g][(oi >> (8 * j)) & 0xffu] * ((ovf - (top ? mx : mn)) + (top ? hs : -hs));
           }
         }
         const float lg = val * inv_sqrt_d;
-        S.logit[g][(kpos[tg] >> (8u * ((uint32_t)s & 3u))) & 0xffu] = lg;
+        S.logit[g][(pos4 >> (8u * ((uint32_t)s & 3u))) & 0xffu] = lg;
         vmax = vmaxf(vmax, lg);
       }
     }
@@ -1255,7 +1300,24 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&vr.vw1[blk], (CGW * wave + j) & 1), cv[j]);
       }
     }
-    for (int blk = 0; blk * 64 < cV.n4; ++blk) {
+    // 4-bit values.  Up to 16 of them in a tile (the usual case where the rules chose the widths):
+    // their two half-units came with the tile, one word per lane; the lanes of group 0, whose 16
+    // slots these are, collect the four words (the other groups' slots carry zero digits, so what
+    // they pass as codes does not matter).  More: fetched here.
+    const bool few4 = CGW == 2 && cV.n4 <= 16;
+    if (few4 && cV.n4 > 0) {
+      if constexpr (CGW == 2) {
+        const uint32_t d00 = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * nn, (int)vr.v4p);
+        const uint32_t d10 = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (nn + 16), (int)vr.v4p);
+        const uint32_t d01 = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (nn + 32), (int)vr.v4p);
+        const uint32_t d11 = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (nn + 48), (int)vr.v4p);
+        const v4i wa = *(const v4i*)wb4;
+        const uint32_t p0[2] = {d00, d01}, p1[2] = {d10, d11};
+        cv[0] = mma(wa, spread<4>(p0, 0), cv[0]);
+        cv[1] = mma(wa, spread<4>(p1, 0), cv[1]);
+      }
+    }
+    for (int blk = 0; !few4 && blk * 64 < cV.n4; ++blk) {
       const int u = blk * 4 + g;
       const int nhu = (cV.n4 + 7) >> 3;
       uint32_t w0[CGW], w1d[CGW];
@@ -1269,33 +1331,34 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
       }
     }
     if (cV.n8 > 0) {
-      // 8-bit values: token-major bytes, fp32 multiply-add per head; this wavefront's D/4 channels
+      // 8-bit values: token-major bytes, fp32 multiply-add; this wavefront's D/4 channels.  Rows go
+      // through the wavefront's own LDS block, 64 / (D/16) at a time (the first batch came with the
+      // tile, further ones -- rare -- are fetched here), so that a lane can own a channel and sum
+      // over the rows by itself: lane (c, half) = channel c of heads 2*half and 2*half + 1.  (No
+      // reduction across lanes: a chain of cross-lane exchanges per head cost more than all the
+      // arithmetic of this class.)  Needs D/4 <= 32 channels per wavefront, i.e. D <= 128.
       constexpr int LPT8 = D / 16;
       constexpr int TPW = 64 / LPT8;
-      const int sub = lane / LPT8, ch4 = lane % LPT8;
-      float a8[kHG][4];
+      static_assert(D / 4 <= 32, "a wavefront's channels must fit half its lanes");
+      const int c8 = lane & 31, h0 = 2 * (lane >> 5);
+      const uint8_t* rows = (const uint8_t*)&S.v8[wave][0];
+      float acc0 = 0.0f, acc1 = 0.0f;
+      for (int r0 = 0; r0 < cV.n8; r0 += TPW) {
+        uint32_t dw = vr.v8;
+        if (r0 > 0) dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)min(r0 + lane / LPT8, cV.n8 - 1) * D + (D / 4) * wave + 4 * (lane % LPT8));
+        S.v8[wave][lane] = dw;        // row lane / LPT8, bytes 4 * (lane % LPT8) .. +3: a row is D/4 consecutive bytes
+        // (LDS operations of one wavefront complete in order: no barrier between the write and the reads)
+        const int nr = min(cV.n8 - r0, TPW);
 #pragma unroll
-      for (int j = 0; j < kHG; ++j)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) a8[j][k] = 0.0f;
-      for (int i8 = sub; i8 < cV.n8; i8 += TPW) {
-        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)i8 * D + (D / 4) * wave + 4 * ch4);
-#pragma unroll
-        for (int j = 0; j < kHG; ++j) {
-          const float w8v = S.w8[j][i8];
-#pragma unroll
-          for (int k = 0; k < 4; ++k) a8[j][k] += w8v * (float)((dw >> (8 * k)) & 255u);
+        for (int r = 0; r < TPW; ++r) {
+          if (r < nr && c8 < D / 4) {
+            const float x = (float)rows[r * (D / 4) + c8];
+            acc0 += S.w8[h0][r0 + r] * x;
+            acc1 += S.w8[h0 + 1][r0 + r] * x;
+          }
         }
       }
-#pragma unroll
-      for (int j = 0; j < kHG; ++j)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          float t = a8[j][k];
-#pragma unroll
-          for (int o = LPT8; o < 64; o <<= 1) t += __shfl_xor(t, o);
-          if (sub == 0) S.xw[wave][j][4 * ch4 + k] = t;
-        }
+      if (c8 < D / 4) { S.xw[wave][h0][c8] = acc0; S.xw[wave][h0 + 1][c8] = acc1; }
     }
     {
       const float kp = g == 0 ? keep[0] : g == 1 ? keep[1] : g == 2 ? keep[2] : keep[3];
@@ -1308,7 +1371,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         xrun[j] = xrun[j] * kp + xt;
       }
     }
-    if (tile + 1 < tile_end) vr.template load<false>(v, len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
+    if (tile + 1 < tile_end) vr.template load<false, true>(v, len, b, h, tile + 1, counts_of(tile + 1, 1), tid, wave, nn, g);
   }
 
   // ---- one partial per query head -------------------------------------------------------------------------
