@@ -1406,7 +1406,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
 // normalise.  Block x = 0 writes the output vector; every block normalises its share of
 // the emitted scores (each recomputes the head's max and sum from the per-tile pairs).
 // All global loads are issued before the first reduction.
-template <int D>
+template <int D, int EPT>      // EPT: scores per thread of a block
 __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   constexpr int MAXP = 4;                    // per-tile pairs held per lane (256 tiles); more: loop
   __shared__ float red[8];
@@ -1417,11 +1417,13 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   const int len = qaq_seq_len(v, b, a.len);          // cached tokens of this sequence
   const float* part = a.partial + (size_t)bq * a.part_stride * (D + 4);
   float* sc = a.scores ? a.scores + (size_t)bq * a.score_stride : nullptr;
-  const int t0 = blockIdx.x * (4 * kThreads);
-  float raw[4] = {0.f, 0.f, 0.f, 0.f};
+  const int t0 = blockIdx.x * (EPT * kThreads);
+  float raw[EPT];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) raw[k] = 0.0f;
   if (sc) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < EPT; ++k) {
       const int t = t0 + k * kThreads + tid;
       if (t < len) raw[k] = sc[t];
     }
@@ -1459,7 +1461,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
   const float inv = 1.0f / lsum;
   if (sc) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < EPT; ++k) {
       const int t = t0 + k * kThreads + tid;
       if (t < len) sc[t] = __expf(raw[k] - M) * inv;
     }
@@ -1610,10 +1612,18 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
     else launch_tile<64>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
   }
   if (fused) return hipGetLastError();
-  const int nblk = a.scores ? (a.len + 4 * kThreads - 1) / (4 * kThreads) : 1;
+  // scores per block: every block repeats the head's merge (partial maxima and sums, the new token's
+  // logit) before it normalises its share, so longer shares where there are blocks enough
+  const int ept = (long long)BQ * a.len >= 16ll * kThreads * 1024 ? 16 : 4;
+  const int nblk = a.scores ? (a.len + ept * kThreads - 1) / (ept * kThreads) : 1;
   dim3 grid(nblk < 1 ? 1 : nblk, BQ);
   hipEvent_t c0 = ev && ntile > 0 ? ev[2] : nullptr, c1 = ev && ntile > 0 ? ev[3] : nullptr;
-  if (a.v.D == 128) hipExtLaunchKernelGGL(k_attn_combine<128>, grid, dim3(kThreads), 0, s, c0, c1, 0, a);
-  else hipExtLaunchKernelGGL(k_attn_combine<64>, grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+  if (a.v.D == 128) {
+    if (ept == 16) hipExtLaunchKernelGGL((k_attn_combine<128, 16>), grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+    else hipExtLaunchKernelGGL((k_attn_combine<128, 4>), grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+  } else {
+    if (ept == 16) hipExtLaunchKernelGGL((k_attn_combine<64, 16>), grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+    else hipExtLaunchKernelGGL((k_attn_combine<64, 4>), grid, dim3(kThreads), 0, s, c0, c1, 0, a);
+  }
   return hipGetLastError();
 }
