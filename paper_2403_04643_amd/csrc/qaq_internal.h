@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/qaq.h"
+#include "../../include/qaq_aux.h"
 #include "qaq_layout.h"
 
 #define QAQ_MAX_KV_HEADS 128
