@@ -725,12 +725,14 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       const uint32_t W2 = (fx && s < n32V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0u;
       S.wl2[0][s] = (int8_t)(W2 & 127u); S.wl2[1][s] = (int8_t)((W2 >> 7) & 127u);
       S.wl2[2][s] = (int8_t)((W2 >> 14) & 127u); S.wl2[3][s] = (int8_t)(W2 >> 21);
-      if (cV.n3 > 0) {
+      // (the value phase reads these two tables in blocks of 64 slots, as far as the class reaches:
+      // slots of later blocks need no digits, not even zeros)
+      if (s < ((cV.n3 + 63) & ~63)) {
         const uint32_t W1 = (fx && s < cV.n3) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift1(vg))) : 0u;
         S.wl1[0][s] = (int8_t)(W1 & 127u); S.wl1[1][s] = (int8_t)((W1 >> 7) & 127u);
         S.wl1[2][s] = (int8_t)((W1 >> 14) & 127u); S.wl1[3][s] = (int8_t)(W1 >> 21);
       }
-      if (cV.n4 > 0) {
+      if (((s - n32V) & (QAQ_TT - 1)) < ((cV.n4 + 63) & ~63)) {
         const int i4 = (s - n32V) & (QAQ_TT - 1);
         const uint32_t W4 = (fx && s >= n32V && s < first8V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp)) : 0u;
         S.wl4[0][i4] = (int8_t)(W4 & 127u); S.wl4[1][i4] = (int8_t)((W4 >> 7) & 127u);
@@ -1254,12 +1256,14 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         const uint32_t W2 = (fx && s < n32V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift2(vg) + (s < cV.n3 ? 1 : 0))) : 0u;
         S.wl2[j][0][s] = (int8_t)(W2 & 127u); S.wl2[j][1][s] = (int8_t)((W2 >> 7) & 127u);
         S.wl2[j][2][s] = (int8_t)((W2 >> 14) & 127u); S.wl2[j][3][s] = (int8_t)(W2 >> 21);
-        if (cV.n3 > 0) {
+        // (the value phase reads these two tables in blocks of 64 slots, as far as the class reaches:
+        // slots of later blocks need no digits, not even zeros)
+        if (s < ((cV.n3 + 63) & ~63)) {
           const uint32_t W1 = (fx && s < cV.n3) ? (uint32_t)rintf(ldexpf(w, 28 - wexp - shift1(vg))) : 0u;
           S.wl1[j][0][s] = (int8_t)(W1 & 127u); S.wl1[j][1][s] = (int8_t)((W1 >> 7) & 127u);
           S.wl1[j][2][s] = (int8_t)((W1 >> 14) & 127u); S.wl1[j][3][s] = (int8_t)(W1 >> 21);
         }
-        if (cV.n4 > 0) {
+        if (i4 < ((cV.n4 + 63) & ~63)) {
           const uint32_t W4 = (fx && s >= n32V && s < first8V) ? (uint32_t)rintf(ldexpf(w, 28 - wexp)) : 0u;
           S.wl4[j][0][i4] = (int8_t)(W4 & 127u); S.wl4[j][1][i4] = (int8_t)((W4 >> 7) & 127u);
           S.wl4[j][2][i4] = (int8_t)((W4 >> 14) & 127u); S.wl4[j][3][i4] = (int8_t)(W4 >> 21);
