@@ -40,14 +40,17 @@ def test_static_scratch_entry_point_matches_the_arena_one():
     # scan kernel leaves partial results for the merge kernel (the form that needs scratch)
     big = W.shape(3, batch=1, n_q_heads=8, n_kv_heads=4, head_dim=128, context=5000)     # 20 tiles, 20 parts per head
     small = W.shape(3, batch=1, n_q_heads=4, n_kv_heads=4, head_dim=64, context=1700)    # 7 tiles, 7 parts per head
-    cases = [_cache(big, 1), _cache(small, 2)]
+    # grouped queries: four query heads per pass over a KV head's codes, also a form with partial results
+    grouped = W.shape(3, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, context=1300)
+    shapes = (big, small, grouped)
+    cases = [_cache(big, 1), _cache(small, 2), _cache(grouped, 3)]
     ref = []
-    for (gc, q, kn, vn), sh in zip(cases, (big, small)):
+    for (gc, q, kn, vn), sh in zip(cases, shapes):
         X, S = gc.decode_attention(q, kn, vn, want_scores=True)
         ref.append((X.clone(), S.clone()))
     torch.cuda.synchronize()
     for rep in range(2):
-        for i, ((gc, q, kn, vn), sh) in enumerate(zip(cases, (big, small))):
+        for i, ((gc, q, kn, vn), sh) in enumerate(zip(cases, shapes)):
             out = torch.full((sh.batch, sh.n_q_heads, sh.head_dim), float("nan"), dtype=torch.float32, device="cuda")
             sc = torch.full((sh.batch, sh.n_q_heads, sh.context + 1), float("nan"), dtype=torch.float32, device="cuda")
             gc.decode_attention_static(q, kn, vn, out, sc)
