@@ -1110,6 +1110,26 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
     const int first8K = n32K + cK.n4, first8V = n32V + cV.n4;
 
     // ---- keys: logits of the lane's head for the four tokens 16*tg + n of its wavefront ---------------
+    // What depends on the token only is worked out once, by the lane that holds the slot's metadata
+    // (slot = lane index), not by each of the four lanes that work on the token: min, scale, the two
+    // outlier corrections, and (one word) the outlier channels and the position.
+    float t_mn, t_scale, t_c0 = 0.0f, t_c1 = 0.0f;
+    uint32_t t_idx;
+    {
+      const int so = 64 * wave + lane;
+      const float mx = h2f((uint16_t)(kmm >> 16));
+      t_mn = h2f((uint16_t)(kmm & 0xffffu));
+      t_scale = ldexpf(mx - t_mn, -cK.bits_of_slot4(min(so, n_tok - 1)));
+      t_idx = ((kpos >> (8u * ((uint32_t)so & 3u))) & 0xffu) << 16;
+      if (NO2 == 2) {
+        const float hs = 0.5f * t_scale;
+        const float o0 = h2f((uint16_t)(kov & 0xffffu)), o1 = h2f((uint16_t)(kov >> 16));
+        const bool top0 = o0 >= mx, top1 = o1 >= mx;
+        t_c0 = (o0 - (top0 ? mx : t_mn)) + (top0 ? hs : -hs);
+        t_c1 = (o1 - (top1 ? mx : t_mn)) + (top1 ? hs : -hs);
+        t_idx |= (koi >> (16 * (so & 1))) & 0xffffu;
+      }
+    }
     float vmax = -INFINITY;
 #pragma unroll
     for (int tg = 0; tg < 4; ++tg) {
@@ -1154,30 +1174,22 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
       }
       // metadata of slot s from the lane that holds it (every lane takes part in the exchange)
       const int src = 4 * (16 * tg + nn);
-      const uint32_t m = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kmm);
-      const uint32_t pos4 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kpos);
-      uint32_t oi4 = 0, ov2 = 0;
+      const float mn = __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(t_mn)));
+      const float scale = __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(t_scale)));
+      const uint32_t idx = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)t_idx);
+      float c0 = 0.0f, c1 = 0.0f;
       if (NO2 == 2) {
-        oi4 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)koi);
-        ov2 = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kov);
+        c0 = __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(t_c0)));
+        c1 = __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(t_c1)));
       }
       if (s < n_tok) {
-        const float mn = h2f((uint16_t)(m & 0xffffu)), mx = h2f((uint16_t)(m >> 16));
-        const float range = mx - mn;
-        const float scale = ldexpf(range, -cK.bits_of_slot4(s));
         float val = mn * sumq_g + scale * (dotq + 0.5f * sumq_g);
         if (NO2 == 2) {
-          const float hs = 0.5f * scale;
-          const uint32_t oi = oi4 >> (16 * (s & 1));
-#pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const float ovf = h2f((uint16_t)(ov2 >> (16 * j)));
-            const bool top = ovf >= mx;
-            val += S.qf[g][(oi >> (8 * j)) & 0xffu] * ((ovf - (top ? mx : mn)) + (top ? hs : -hs));
-          }
+          val += S.qf[g][idx & 0xffu] * c0;
+          val += S.qf[g][(idx >> 8) & 0xffu] * c1;
         }
         const float lg = val * inv_sqrt_d;
-        S.logit[g][(pos4 >> (8u * ((uint32_t)s & 3u))) & 0xffu] = lg;
+        S.logit[g][idx >> 16] = lg;
         vmax = vmaxf(vmax, lg);
       }
     }
