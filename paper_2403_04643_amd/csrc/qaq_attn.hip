@@ -1104,8 +1104,9 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
     const int n_tok = n_tok_n;
     const QaqKRegions rK = qaq_k_regions(cK, D);
     const QaqVRegions rV = qaq_v_regions(cV, D);
-    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
-    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    // (scalar base + 32-bit lane offset: a 64-bit address per lane would cost the loop two registers each)
+    const gbytes_t baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    const gbytes_t baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
     const int n32K = cK.n32(), n32V = cV.n32();
     const int first8K = n32K + cK.n4, first8V = n32V + cV.n4;
 
@@ -1165,7 +1166,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
         // head's query integers) back, rebuilt from the digits
         const int i8 = min(max(s - first8K, 0), max(cK.n8 - 1, 0));
         uint32_t w8r[4 * KS];
-        load_dwords<4 * KS>(baseK + rK.r8 + (uint32_t)i8 * D + (uint32_t)g * (16u * KS), w8r);
+        gload_dwords<4 * KS>(baseK + (rK.r8 + (uint32_t)i8 * D + (uint32_t)g * (16u * KS)), w8r);
         const int sq = S.sq[g];
         v4i c = zero4;
 #pragma unroll
@@ -1337,8 +1338,8 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
       const int u = blk * 4 + g;
       const int nhu = (cV.n4 + 7) >> 3;
       uint32_t w0[CGW], w1d[CGW];
-      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
-      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
+      gload_dwords<CGW>(baseV + (rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave), w0);
+      gload_dwords<CGW>(baseV + (rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave), w1d);
       const v4i wa = *(const v4i*)(wb4 + 64 * blk);
 #pragma unroll
       for (int j = 0; j < CGW; ++j) {
@@ -1361,7 +1362,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
       float acc0 = 0.0f, acc1 = 0.0f;
       for (int r0 = 0; r0 < cV.n8; r0 += TPW) {
         uint32_t dw = vr.v8;
-        if (r0 > 0) dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)min(r0 + lane / LPT8, cV.n8 - 1) * D + (D / 4) * wave + 4 * (lane % LPT8));
+        if (r0 > 0) dw = gload32(baseV, rV.r8 + (uint32_t)min(r0 + lane / LPT8, cV.n8 - 1) * D + (D / 4) * wave + 4 * (lane % LPT8));
         S.v8[wave][lane] = dw;        // row lane / LPT8, bytes 4 * (lane % LPT8) .. +3: a row is D/4 consecutive bytes
         // (LDS operations of one wavefront complete in order: no barrier between the write and the reads)
         const int nr = min(cV.n8 - r0, TPW);
