@@ -571,8 +571,9 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     const uint32_t kslot = (uint32_t)min(ktid, n_tok - 1); // ... the key slot
     const QaqKRegions rK = qaq_k_regions(cK, D);
     const QaqVRegions rV = qaq_v_regions(cV, D);
-    const uint8_t* baseK = qaq_tile_codes(v, 0, b, h, tile);
-    const uint8_t* baseV = qaq_tile_codes(v, 1, b, h, tile);
+    // (scalar base + 32-bit lane offset for what is fetched inside the loop: no 64-bit lane addresses)
+    const gbytes_t baseK = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    const gbytes_t baseV = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
     const int n32K = cK.n32(), n32V = cV.n32();
     const int first8V = n32V + cV.n4;
     const int first1K = H1 ? cK.first1() : n_tok, first1V = H1 ? cV.first1() : n_tok;
@@ -635,12 +636,12 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
         // the record in pieces of two slices (eight registers at a time: the whole record in
         // registers would make every tile of every call pay for this path with spills)
-        const uint8_t* rec = baseK + rK.r8 + (uint32_t)min(max(ktid - first8K, 0), cK.n8 - 1) * (uint32_t)D;
+        const uint32_t rec = rK.r8 + (uint32_t)min(max(ktid - first8K, 0), cK.n8 - 1) * (uint32_t)D;
         v4i cc = zero4;
 #pragma unroll 1
         for (int q2 = 0; q2 < D / 32; ++q2) {
           uint32_t w[8];
-          load_dwords<8>(rec + 32 * q2, w);
+          gload_dwords<8>(baseK + (rec + 32u * (uint32_t)q2), w);
           cc = mma(*(const v4i*)(abase2 + 32 * q2), spread<8>(&w[0], 0), cc);
           cc = mma(*(const v4i*)(abase2 + 32 * q2 + 16), spread<8>(&w[4], 0), cc);
         }
@@ -783,8 +784,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       const int nhu = (cV.n4 + 7) >> 3;
       uint32_t w0[CGW], w1d[CGW];
       // a half-unit past the end repeats the last one; its slots carry zero digits
-      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w0);
-      load_dwords<CGW>(baseV + rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave, w1d);
+      gload_dwords<CGW>(baseV + (rV.r4 + (uint32_t)min(2 * u, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave), w0);
+      gload_dwords<CGW>(baseV + (rV.r4 + (uint32_t)min(2 * u + 1, nhu - 1) * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave), w1d);
       const v4i wa = *(const v4i*)(wb4 + 64 * blk);
 #pragma unroll
       for (int j = 0; j < CGW; ++j) {
@@ -799,8 +800,8 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         if (blk * 64 < cV.n1) {
           uint32_t w1b = vr.vw1[3 - blk];                  // came with the tile if the entry was free, else fetched here
           if (3 - blk < nb3)
-            w1b = *(const uint32_t*)(baseV + rV.r1b + (uint32_t)min(blk * 4 + g, nu - 1) * (2u * D) +
-                                     (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+            w1b = gload32(baseV, rV.r1b + (uint32_t)min(blk * 4 + g, nu - 1) * (2u * D) +
+                                 (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
           const v4i wa = *(const v4i*)(wb1b + 64 * blk);
 #pragma unroll
           for (int j = 0; j < CGW; ++j) cv[j] = mma(wa, spread<1>(&w1b, (CGW * wave + j) & 1), cv[j]);
@@ -816,7 +817,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
       const int sub = lane / LPT8, ch4 = lane % LPT8;
       if (sub < cV.n8) {                  // a tile of a cache the rules shaped rarely has more than these rows
         const float w8 = S.w8[sub];
-        const uint32_t dw = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)sub * D + (D / 4) * wave + 4 * ch4);
+        const uint32_t dw = gload32(baseV, rV.r8 + (uint32_t)sub * D + (D / 4) * wave + 4 * ch4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw >> (8 * j)) & 255u);
       }
@@ -827,7 +828,7 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
         uint32_t dw[UB];
 #pragma unroll
         for (int u = 0; u < UB; ++u)
-          dw[u] = *(const uint32_t*)(baseV + rV.r8 + (uint32_t)min(i0 + u * TPW, cV.n8 - 1) * D + (D / 4) * wave + 4 * ch4);
+          dw[u] = gload32(baseV, rV.r8 + (uint32_t)min(i0 + u * TPW, cV.n8 - 1) * D + (D / 4) * wave + 4 * ch4);
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
           const int i8 = i0 + u * TPW;
