@@ -938,8 +938,10 @@ constexpr int kHG = 4;
 template <int D>
 struct GqaLds {
   float qf[kHG][D];
-  alignas(16) int8_t ql[3][kHG][3][D + 16];     // query digits [format][head][digit][position in record order]
-  alignas(16) int8_t zrow[256];                // zeros: the fourth row of every head on the key side
+  // query digits [format][head][digit][position in record order]; "digit" 3 is a row of zeros, the fourth
+  // A row of every head on the key side, so that a lane's row has the same place in all three formats
+  // (one address register, the formats at constant offsets)
+  alignas(16) int8_t ql[3][kHG][4][D + 16];
   alignas(16) uint16_t cnt[QAQ_MAX_NTC][8];
   float vb[QAQ_MAX_NTC];
   float logit[kHG][QAQ_TT];                    // raw logits by position; at the very end: outlier corrections by channel
@@ -1001,7 +1003,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
       S.qf[j][tid] = qv[j];
     }
   }
-  S.zrow[tid] = 0;
+  for (int e = tid; e < 3 * kHG * (D + 16); e += kThreads) S.ql[e / (kHG * (D + 16))][(e / (D + 16)) % kHG][3][e % (D + 16)] = 0;
   if (tid < kHG) S.sq[tid] = 0;
   for (int e = tid; e < kHG * D * 4; e += kThreads) (&S.xc[0][0][0])[e] = 0;
   lds_barrier();
@@ -1081,12 +1083,14 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
   lds_barrier();
   // A rows: row r = 4 * head + digit; the lane's k-range is slices g*KS ..
   const int arow_h = nn >> 2, arow_d = nn & 3;
-  const int8_t* abase0 = arow_d < 3 ? &S.ql[0][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
-  const int8_t* abase1 = arow_d < 3 ? &S.ql[1][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
-  const int8_t* abase2 = arow_d < 3 ? &S.ql[2][arow_h][arow_d][16 * g * KS] : &S.zrow[0];
+  const int8_t* abase0 = &S.ql[0][arow_h][arow_d][16 * g * KS];
+  const int8_t* abase1 = abase0 + sizeof(S.ql[0]);
+  const int8_t* abase2 = abase0 + 2 * sizeof(S.ql[0]);
   const int8_t* wb2 = &S.wl2[arow_h][arow_d][16 * g];
-  const int8_t* wb1 = &S.wl1[arow_h][arow_d][16 * g];
-  const int8_t* wb4 = &S.wl4[arow_h][arow_d][16 * g];
+  const int8_t* wb1 = wb2 + sizeof(S.wl2);       // the three tables have one shape and follow one another
+  const int8_t* wb4 = wb2 + 2 * sizeof(S.wl2);
+  static_assert(offsetof(GqaLds<D>, wl1) - offsetof(GqaLds<D>, wl2) == sizeof(S.wl2) &&
+                offsetof(GqaLds<D>, wl4) - offsetof(GqaLds<D>, wl2) == 2 * sizeof(S.wl2), "weight digit tables are contiguous");
   auto real_of = [&](const v4i& c) { return (((float)c[2] * 65536.0f + (float)c[1] * 256.0f) + (float)c[0]) * qscale_g; };
 
   float m_run[kHG], l_run[kHG], bias_run[kHG];
