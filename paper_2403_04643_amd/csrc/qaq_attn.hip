@@ -937,14 +937,16 @@ constexpr int kHG = 4;
 
 template <int D>
 struct GqaLds {
-  float qf[kHG][D];
+  // (rows of the two tables that the four lanes of a token address together -- one head each, the same
+  // column -- are eight words longer than their payload, so that the four land in different banks)
+  float qf[kHG][D + 8];
   // query digits [format][head][digit][position in record order]; "digit" 3 is a row of zeros, the fourth
   // A row of every head on the key side, so that a lane's row has the same place in all three formats
   // (one address register, the formats at constant offsets)
   alignas(16) int8_t ql[3][kHG][4][D + 16];
   alignas(16) uint16_t cnt[QAQ_MAX_NTC][8];
   float vb[QAQ_MAX_NTC];
-  float logit[kHG][QAQ_TT];                    // raw logits by position; at the very end: outlier corrections by channel
+  float logit[kHG][QAQ_TT + 8];                // raw logits by position; at the very end: outlier corrections by channel
   alignas(16) int8_t wl2[kHG][4][QAQ_TT + 16];  // weight digits [head][digit][slot of the 2-bit field region]
   alignas(16) int8_t wl1[kHG][4][QAQ_TT + 16];
   alignas(16) int8_t wl4[kHG][4][QAQ_TT + 16];
@@ -1407,7 +1409,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_attn_gqa(QaqAttnArgs a) {
 #pragma unroll
   for (int r = 0; r < NCR; ++r) {
     const int item = tid + kThreads * r;
-    if (item < kHG * D) (&S.logit[0][0])[(item / D) * QAQ_TT + (item % D)] = c_run[r];
+    if (item < kHG * D) S.logit[item / D][item % D] = c_run[r];
   }
   lds_barrier();
   {
