@@ -285,6 +285,76 @@ def other_configs(lib, qaq, W, torch, n_inst=3):
     return out
 
 
+def different_lengths(lib, qaq, W, torch, sh, qn, ss, sx, n_inst=3, steps=8):
+    """The benchmark's shape with sequences of different lengths in one cache (qaq_set_shortfall):
+    sequence b is 384 * b tokens shorter than the first (4096 ... 1408 tokens at batch 8), the
+    hyper-parameters of the timed operating point, widths by the rules.  Time of the attention call's
+    kernels (such a cache takes the two-kernel form), algorithmic bytes of the tokens that exist,
+    and the time of a full decode step (attention + update, no unquantized copies)."""
+    B, Hq, Hkv, D, T = sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context
+    short = [min(384 * b, T - 512) for b in range(B)]
+    q = torch.from_numpy(W.make_queries(2, sh, n=5 + steps, seed_offset=11)).cuda()
+    caches = []
+    for i in range(n_inst):
+        K, V = W.make_kv(2, sh, seed_offset=20 + i)
+        c = qaq.Cache(qaq.make_config(B, Hq, Hkv, D, T + steps + 1, qn.tolist(), window=5))
+        c.set_shortfall(short)
+        c.quantize_append(torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+        del K, V
+        for r in range(5):                      # the window: five score rows of five queries
+            _, S = c.decode_attention(q[r], want_scores=True)
+            c.select_bits(S)
+        c.set_sigmas(ss, sx)
+        kb, vb = c.select_bits(None)
+        c.requantize(kb, vb)
+        caches.append(c)
+    torch.cuda.synchronize()
+    st = caches[0].stats()
+    lens = caches[0].lengths()
+    n_o = caches[0].n_o
+    token_heads = sum(lens) * Hkv
+    cache_bytes = st.code_bytes + token_heads * (8 + 2 + 12 * n_o)
+    io = B * Hq * D * (2 + 4) + Hq * sum(n + 1 for n in lens) * 4 + B * Hkv * D * 4
+    kn, vn = W.make_new_token(2, sh, step=77)
+    kn, vn = torch.from_numpy(kn).cuda(), torch.from_numpy(vn).cuda()
+    scores = torch.empty((B, Hq, T + steps + 1), dtype=torch.float32, device="cuda")
+    n_calls = 8
+    for c in caches:
+        c.profile_begin(n_calls + 1)
+    for i in range((n_calls + 1) * n_inst):
+        caches[i % n_inst].decode_attention(q[i % 5], kn, vn, scores_out=scores)
+    torch.cuda.synchronize()
+    t_tile, t_merge = [], []
+    for c in caches:
+        a_ms, b_ms = c.profile_read()
+        t_tile += a_ms[1:]; t_merge += b_ms[1:]
+        c.profile_begin(0)
+    us_t, us_m = 1e3 * float(np.mean(t_tile)), 1e3 * float(np.mean(t_merge))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    bufs = {}
+    def one_step_buf(j):
+        c = caches[j % n_inst]
+        n = c.length() + 1
+        if n not in bufs:
+            bufs[n] = torch.empty((B, Hq, n), dtype=torch.float32, device="cuda")
+        c.decode_attention(q[5 + j % steps], kn, vn, scores_out=bufs[n])
+        c.decode_update(bufs[n], kn, vn)
+    for n in range(T + 1, T + steps + 2):       # score buffers of every length the steps will need, before timing
+        bufs[n] = torch.empty((B, Hq, n), dtype=torch.float32, device="cuda")
+    for j in range(n_inst):                     # one untimed step per instance
+        one_step_buf(j)
+    torch.cuda.synchronize()
+    n_steps = n_inst * (steps - 1)
+    e0.record()
+    for j in range(n_steps):
+        one_step_buf(n_inst + j)
+    e1.record(); torch.cuda.synchronize()
+    return {"lengths_at_the_attention_timing": lens, "us_attention_call": us_t + us_m, "us_tile_kernel": us_t, "us_merge_kernel": us_m,
+            "algorithmic_bytes": cache_bytes + io, "GBps": (cache_bytes + io) / ((us_t + us_m) * 1e-6) / 1e9,
+            "frac_of_hbm_peak": (cache_bytes + io) / ((us_t + us_m) * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "ms_per_step": e0.elapsed_time(e1) / n_steps, "steps": n_steps}
+
+
 def config_3_as_stated(lib, qaq, torch, sh, qn, ss, sx, n_layers=32, steps=64):
     """BASELINE configs[2] at its stated size: `n_layers` independent cache instances of config
     2's shape (the layers of a LLaMA-7B stack), `steps` consecutive decode steps from the
@@ -804,6 +874,8 @@ def main():
             lst.clear()
         torch.cuda.empty_cache()
         rec["other_configs"] = other_configs(lib, qaq, W, torch)
+        torch.cuda.empty_cache()
+        rec["sequences_of_different_lengths"] = different_lengths(lib, qaq, W, torch, sh, qn, ss, sx)
         torch.cuda.empty_cache()
         rec["config_3_as_stated"] = config_3_as_stated(lib, qaq, torch, sh, qn, ss, sx)
         torch.cuda.empty_cache()
