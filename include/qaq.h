@@ -134,8 +134,8 @@ int qaq_lengths(const qaq_cache* c, int32_t* host_len);
  * The first append must be longer than the largest shortfall (no sequence stays empty), and
  * a prompt must leave the shortest sequence at least n_rows tokens in qaq_prefill_window.
  * Limits: batch <= 64 and batch * n_kv_heads <= 256 when any shortfall is positive (the
- * per-sequence thresholds travel as kernel arguments).  Decode attention then always takes its
- * two-kernel form.  QAQ_ERR_INVALID_ARG if the cache is not empty or a limit is exceeded. */
+ * per-sequence thresholds travel as kernel arguments).  QAQ_ERR_INVALID_ARG if the cache is not
+ * empty or a limit is exceeded. */
 int qaq_set_shortfall(qaq_cache* c, const int32_t* host_shortfall);
 
 /* Change the two hyper-parameters of Section 4.1 between calls. */

@@ -503,6 +503,7 @@ static int decode_attention(qaq_cache* c, const void* dev_q, const void* dev_k_n
   std::memset(&a, 0, sizeof(a));
   a.v = c->view;
   a.len = c->len;
+  a.len_shortest = c->len > c->max_shortfall ? c->len - c->max_shortfall : 0;
   a.G = c->dims.Hq / c->dims.Hkv;
   a.q = (const __half*)dev_q;
   a.k_new = (const __half*)dev_k_new;

@@ -1606,7 +1606,11 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   a.ntc = a.nparts > 0 ? (ntile + a.nparts - 1) / a.nparts : 0;
   // Fused form (no second kernel) when the parts of a head fit one workgroup and their raw
   // logits fit its LDS next to the parts' working blocks.
-  const bool fused = !gqa && !a.v.ragged && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles;   // its parts run in lockstep: every one needs a tile
+  // (its parts run in lockstep and every one needs a tile: where the sequences differ in length, the
+  // shortest must have as many tiles as a head has parts)
+  const int ntile_shortest = (a.len_shortest + QAQ_TT - 1) / QAQ_TT;
+  const bool fused = !gqa && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles &&
+                     (!a.v.ragged || ntile_shortest >= a.nparts);
   if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
   if (static_scratch && !fused) {
     if ((size_t)BQ * (size_t)(a.nparts > 0 ? a.nparts : 1) * (a.v.D + 4) * sizeof(float) > kStaticScratchBytes) {

@@ -144,6 +144,7 @@ struct QaqAttnArgs {
   int score_stride;       // len (+1)
   int ntc;                // most tiles any workgroup of the tile kernel gets (set by the launcher)
   int nparts;             // partials per (sequence, query head)
+  int len_shortest;       // cached tokens of the shortest sequence (= len unless the sequences differ in length)
   float* partial;         // two-kernel form: [B*Hq][part_stride][D+4] partial results (max, sum, X) of the parts
   int part_stride;        // partials reserved per (sequence, query head)
 };

@@ -67,14 +67,16 @@ def compare_all(ocs, gc, what):
         compare_sequence(oc, ex, b, what)
 
 
-@pytest.mark.parametrize("n_q_heads,n_kv_heads", [(8, 4), (8, 2)])
-def test_decode_steps_with_sequences_of_different_lengths(n_q_heads, n_kv_heads):
-    """Append prompts of 766, 300 and 511 tokens (padded to 766), then decode steps that take two of
-    the sequences across a tile border at different steps; the grouped-query attention kernel
-    serves the second shape.  Attention output and scores, the selected widths and the cache
-    contents of every sequence against its own oracle cache, at every step."""
+@pytest.mark.parametrize("n_q_heads,n_kv_heads,lens", [(8, 4, [766, 300, 511]), (8, 2, [766, 300, 511]),
+                                                        (8, 4, [1000, 780, 1021])])
+def test_decode_steps_with_sequences_of_different_lengths(n_q_heads, n_kv_heads, lens):
+    """Append prompts of different lengths (padded to the longest), then decode steps that take
+    sequences across a tile border at different steps; the grouped-query attention kernel serves the
+    second shape; in the third every sequence has as many tiles as a head has parts, so the
+    attention call is one kernel until the longest sequence grows a fifth tile.  Attention output
+    and scores, the selected widths and the cache contents of every sequence against its own
+    oracle cache, at every step."""
     import torch
-    lens = [766, 300, 511]
     B, Tmax = len(lens), max(lens)
     steps = 6
     sh = W.shape(3, batch=B, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, context=Tmax)
