@@ -433,8 +433,13 @@ struct ValRegs {
 // and the workgroup writes the output and the normalised scores itself: no second kernel.
 // H1: the width set contains 1 (a fifth class at the end of every tile); without it that
 // class costs nothing.
-template <int D, int NO2, int P, bool H1>
-__global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
+// PP = 5: the fused form with four parts whose raw logits wait in the score buffer instead of LDS
+// (a head with more tiles than the LDS store holds; a form of its own so that the common one carries
+// no test for it: as a run-time flag it cost the call 0.4 us).
+template <int D, int NO2, int PP, bool H1>
+__global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_attn_tile(QaqAttnArgs a) {   // four wavefronts per SIMD
+  constexpr int P = PP == 5 ? 4 : PP;
+  constexpr bool LDS_LOGITS = PP != 5;
   constexpr int KS = D / 64;
   constexpr int NCG = D / 16;
   constexpr int CGW = NCG / 4;              // channel groups per wavefront on the value side
@@ -681,7 +686,10 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
 
     // ---- values: weight of slot `tid`, as digits -------------------------------------------------
     if (a.scores && on && tid < n_tok) {
-      if (P) lg_all[((chunk * a.ntc + it) << 8) + tid] = S.logit[tid];
+      // fused form: in LDS if a head's logits fit, else in the score buffer, where the same thread finds
+      // them again at the end (through the L2: volatile); two-kernel form: for the merge kernel
+      if (P && LDS_LOGITS) lg_all[((chunk * a.ntc + it) << 8) + tid] = S.logit[tid];
+      else if (P) ((volatile float*)a.scores)[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
       else a.scores[(size_t)bq * a.score_stride + tile * QAQ_TT + tid] = S.logit[tid];
     }
     if (on) {
@@ -911,7 +919,10 @@ __global__ __launch_bounds__((P ? P : 1) * kThreads, 4) void k_attn_tile(QaqAttn
     float* sc = a.scores + (size_t)bq * a.score_stride;
     for (int it = 0; it < tile_end - tile_begin; ++it) {
       const int t = (tile_begin + it) * QAQ_TT + tid;
-      if (t < len) sc[t] = __expf(lg_all[((chunk * a.ntc + it) << 8) + tid] - Mx) * inv;
+      if (t < len) {
+        const float raw = LDS_LOGITS ? lg_all[((chunk * a.ntc + it) << 8) + tid] : ((volatile float*)sc)[t];
+        sc[t] = __expf(raw - Mx) * inv;
+      }
     }
     if (a.k_new && chunk == 0 && tid == 0) sc[len] = e_new * inv;
   }
@@ -1527,7 +1538,7 @@ __global__ __launch_bounds__(kThreads) void k_attn_combine(QaqAttnArgs a) {
 // e0, e1: NULL, or events that take the start and the end of this dispatch.
 template <int D, int P>
 void launch_tile_p(const QaqAttnArgs& a, dim3 grid, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  const dim3 block((P ? P : 1) * kThreads);
+  const dim3 block((P == 5 ? 4 : P ? P : 1) * kThreads);
   if (a.v.has1) {
     if (a.v.no2 == 2 && !a.v.csr) hipExtLaunchKernelGGL((k_attn_tile<D, 2, P, true>), grid, block, lds, s, e0, e1, 0, a);
     else if (a.v.no2 == 0) hipExtLaunchKernelGGL((k_attn_tile<D, 0, P, true>), grid, block, lds, s, e0, e1, 0, a);
@@ -1545,6 +1556,7 @@ void launch_tile(const QaqAttnArgs& a, int fused_parts, int BQ, size_t lds, hipS
     case 2: launch_tile_p<D, 2>(a, dim3(1, BQ), lds, s, e0, e1); break;
     case 3: launch_tile_p<D, 3>(a, dim3(1, BQ), lds, s, e0, e1); break;
     case 4: launch_tile_p<D, 4>(a, dim3(1, BQ), lds, s, e0, e1); break;
+    case 5: launch_tile_p<D, 5>(a, dim3(1, BQ), 0, s, e0, e1); break;      // four parts, raw logits in the score buffer
     default: launch_tile_p<D, 0>(a, dim3(a.nparts, BQ), 0, s, e0, e1); break;
   }
 }
@@ -1604,13 +1616,14 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
   const int least = (ntile + QAQ_MAX_NTC - 1) / QAQ_MAX_NTC;    // a part holds at most QAQ_MAX_NTC tiles
   if (a.nparts < least) a.nparts = least;
   a.ntc = a.nparts > 0 ? (ntile + a.nparts - 1) / a.nparts : 0;
-  // Fused form (no second kernel) when the parts of a head fit one workgroup and their raw
-  // logits fit its LDS next to the parts' working blocks.
+  // Fused form (no second kernel) when the parts of a head fit one workgroup; their raw logits stay
+  // in its LDS next to the parts' working blocks if they fit, else they wait in the score buffer.
   // (its parts run in lockstep and every one needs a tile: where the sequences differ in length, the
   // shortest must have as many tiles as a head has parts)
   const int ntile_shortest = (a.len_shortest + QAQ_TT - 1) / QAQ_TT;
-  const bool fused = !gqa && ntile > 0 && a.nparts <= 4 && a.nparts * a.ntc <= kFusedMaxTiles &&
-                     (!a.v.ragged || ntile_shortest >= a.nparts);
+  a.lds_logits = a.nparts * a.ntc <= kFusedMaxTiles || !a.scores;
+  const bool fused = !gqa && ntile > 0 && a.nparts <= 4 && (!a.v.ragged || ntile_shortest >= a.nparts) &&
+                     (a.lds_logits || a.nparts == 4);
   if (kernels) *kernels = ntile > 0 ? (fused ? 1 : 2) : 0;
   if (static_scratch && !fused) {
     if ((size_t)BQ * (size_t)(a.nparts > 0 ? a.nparts : 1) * (a.v.D + 4) * sizeof(float) > kStaticScratchBytes) {
@@ -1634,8 +1647,8 @@ hipError_t qaq_launch_attention(const QaqAttnArgs& a_in, hipStream_t s, hipEvent
       else hipExtLaunchKernelGGL((k_attn_gqa<64, 0>), grid, block, 0, s, e0, e1, 0, a);
     }
   } else if (ntile > 0) {
-    const int fp = fused ? a.nparts : 0;
-    const size_t lds = fused && a.scores ? (size_t)a.nparts * a.ntc * QAQ_TT * sizeof(float) : 0;
+    const int fp = fused ? (a.lds_logits ? a.nparts : 5) : 0;
+    const size_t lds = fused && a.scores && a.lds_logits ? (size_t)a.nparts * a.ntc * QAQ_TT * sizeof(float) : 0;
     if (a.v.D == 128) launch_tile<128>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
     else launch_tile<64>(a, fp, BQ, lds, s, ev ? ev[0] : nullptr, ev ? ev[1] : nullptr);
   }

@@ -145,6 +145,7 @@ struct QaqAttnArgs {
   int ntc;                // most tiles any workgroup of the tile kernel gets (set by the launcher)
   int nparts;             // partials per (sequence, query head)
   int len_shortest;       // cached tokens of the shortest sequence (= len unless the sequences differ in length)
+  int lds_logits;         // fused form: the head's raw logits fit the workgroup's LDS (set by the launcher); else they wait in the score buffer
   float* partial;         // two-kernel form: [B*Hq][part_stride][D+4] partial results (max, sum, X) of the parts
   int part_stride;        // partials reserved per (sequence, query head)
 };

@@ -229,6 +229,41 @@ def test_attention_with_two_and_three_parts_per_head(batch, parts):
         assert ex.max() < TOL and es.max() < TOL
 
 
+def test_one_kernel_attention_with_more_tiles_than_lds_holds_logits_for():
+    """256 query heads and 36 tiles each: four parts per head in one workgroup, but the head's raw
+    logits (36 KB) do not fit next to the parts' working blocks, so they wait in the score buffer until
+    the workgroup has merged its parts.  Sampled units against the oracle, all heads against
+    the properties that hold at any size, and the output again without the scores."""
+    sh = W.shape(3, batch=8, n_q_heads=32, n_kv_heads=32, head_dim=64, context=9000)
+    _log(f"one kernel, logits in the score buffer: {sh}")
+    K, V = W.make_kv(3, sh)
+    rng = np.random.default_rng(411)
+    widths = np.array([2, 3, 4, 8], np.uint8)
+    bk = rng.choice(widths, size=K.shape[:3], p=(0.5, 0.4, 0.07, 0.03))
+    bv = rng.choice(widths, size=K.shape[:3], p=(0.8, 0.15, 0.03, 0.02))
+    qn = np.full(sh.n_kv_heads, 0.02, F32)
+    gc = qaq.Cache(qaq.make_config(sh.batch, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.context + 1, qn.tolist()))
+    gc.quantize_append(dev(K), dev(V), dev(bk), dev(bv))
+    q = W.make_queries(3, sh)[0]
+    kn, vn = W.make_new_token(3, sh)
+    gc.profile_begin(1)
+    X, S = gc.decode_attention(dev(q), dev(kn), dev(vn), want_scores=True)
+    t_tile, t_merge = gc.profile_read()
+    gc.profile_begin(0)
+    assert t_merge == [0.0], "the call was expected to run as one kernel"
+    _global_properties(X, S, V, vn)
+    Xg, Sg = X.cpu().numpy(), S.cpu().numpy()
+    X2, _ = gc.decode_attention(dev(q), dev(kn), dev(vn))
+    np.testing.assert_array_equal(X2.cpu().numpy(), Xg)
+    for b, h in _sample_units(sh, 4, 77):
+        oc, G = _unit_oracle(sh, qn, b, h)
+        oc.append(K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], bk[b:b + 1, h:h + 1], bv[b:b + 1, h:h + 1])
+        Xo, So = oc.decode_attention(q[b:b + 1, h * G:(h + 1) * G], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1])
+        ex, es = attention_errors(Xg[b:b + 1, h * G:(h + 1) * G], Sg[b:b + 1, h * G:(h + 1) * G], Xo, So)
+        _log(f"  unit b={b} h={h}: max rel err X {ex.max():.2e}, S {es.max():.2e}")
+        assert ex.max() < TOL and es.max() < TOL
+
+
 def test_full_size_decode_update_across_a_tile_border():
     """Config 2 at full size through the call the benchmark times for the second half of a
     step: qaq_decode_update on all 256 (sequence, head) units at once, four consecutive decode
