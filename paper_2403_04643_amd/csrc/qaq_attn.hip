@@ -359,6 +359,49 @@ struct KeyRegs {
     const uint32_t off8 = s8 < n_tok - c.n1 && 8 * (tid & 15) < D ? rK.r8 + (uint32_t)(s8 - first8) * (uint32_t)KRec<D, 8>::REC + 8u * (uint32_t)(tid & 15) : 0u;
     if (c.n8 > 0) gload_dwords<2>(ubase + off8, k8);      // uniform over the workgroup
   }
+  // The first tile of a part, in two steps, so that its bytes are on their way while the class counts
+  // are: `head` asks for what can be addressed without the counts -- the slot's metadata and the 2-bit
+  // field record of slot `tid`, which is where the record of a 2- or 3-bit token is -- and `tail`, once
+  // the counts are known, for the rest (and for the first word group again where the tile has 4-bit
+  // tokens, whose records are elsewhere: rare, and uniform over the workgroup).
+  __device__ __forceinline__ void load_head(const QaqView& v, int len, int b, int h, int tile, int tid) {
+    n_tok = min(len - tile * QAQ_TT, QAQ_TT);
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
+    mm = gload32(uniform_ptr(v.mm[0] + gi0), 4u * slot);
+    pos = gload32(uniform_ptr(v.perm[0] + gi0), slot & ~3u);
+    o.load(v, 0, gi0, slot, v.no2);
+    gload_dwords<HALF>(uniform_ptr(qaq_tile_codes(v, 0, b, h, tile)) + (uint32_t)tid * (uint32_t)KRec<D, 2>::REC, ka);
+  }
+  template <bool H1>
+  __device__ __forceinline__ void load_tail(const QaqView& v, int b, int h, int tile, const QaqCounts& ck, int tid) {
+    c = ck;
+    const QaqKRegions rK = qaq_k_regions(c, D);
+    const int n32 = c.n32();
+    const bool is3 = tid < c.n3, is23 = tid < n32, is4 = !is23 && tid < n32 + c.n4;
+    const uint32_t rec4 = rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
+    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : is4 ? rec4 : 0u;
+    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    if (H1 && c.n1 > 0 && tid >= c.first1())
+      off_b0 = rK.r1b + (uint32_t)min(tid - c.first1(), c.n1 - 1) * (uint32_t)KRec<D, 1>::REC;
+    const uint32_t off_b1 = is4 ? rec4 + 4u * HALF + 2u * HALF : 0u;
+    const gbytes_t ubase = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
+    if (c.n4 > 0) {            // (into other registers first: a load into registers that an earlier load is still on its way to is held back until that one has arrived)
+      uint32_t t[HALF];
+      gload_dwords<HALF>(ubase + off_a, t);
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) ka[i] = t[i];
+    }
+    uint32_t b0[HALF / 2], b1[HALF / 2];
+    gload_dwords<HALF / 2>(ubase + off_b0, b0);
+    gload_dwords<HALF / 2>(ubase + off_b1, b1);
+#pragma unroll
+    for (int i = 0; i < HALF / 2; ++i) { kb[i] = b0[i]; kb[HALF / 2 + i] = b1[i]; }
+    const int first8 = n32 + c.n4;
+    const int s8 = max(first8, tid & ~63) + ((tid & 63) >> 4);
+    const uint32_t off8 = s8 < n_tok - c.n1 && 8 * (tid & 15) < D ? rK.r8 + (uint32_t)(s8 - first8) * (uint32_t)KRec<D, 8>::REC + 8u * (uint32_t)(tid & 15) : 0u;
+    if (c.n8 > 0) gload_dwords<2>(ubase + off8, k8);
+  }
 };
 
 template <int D, int NO2>
@@ -402,6 +445,47 @@ struct ValRegs {
       const int lane = tid & 63;
       v8 = gload32(ubase, c.n8 > 0 ? rV.r8 + (uint32_t)min(lane / (D / 16), c.n8 - 1) * D + (D / 4) * wave + 4 * (lane % (D / 16)) : 0u);
     }
+    const int nu1 = (c.n3 + 15) >> 4;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk)
+      if (blk * 4 < nu1)
+        vw1[blk] = *(const uint32_t*)(base + rV.r1 + (uint32_t)min(blk * 4 + g, nu1 - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+    if (H1) {
+      const int nb3 = (nu1 + 3) >> 2, nu1b = (c.n1 + 15) >> 4;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+        if (blk * 4 < nu1b && 3 - blk >= nb3)
+          vw1[3 - blk] = *(const uint32_t*)(base + rV.r1b + (uint32_t)min(blk * 4 + g, nu1b - 1) * (2u * D) + (uint32_t)nn * (NCG * 2) + 4u * ((CGW * wave) >> 1));
+    }
+  }
+  // the first tile of a part in two steps, as for the keys: the 2-bit field units start the tile side
+  template <bool H1>
+  __device__ __forceinline__ void load_head(const QaqView& v, int len, int b, int h, int tile, int tid, int wave, int nn, int g) {
+    const int n_tok = min(len - tile * QAQ_TT, QAQ_TT);
+    const gbytes_t ubase = uniform_ptr(qaq_tile_codes(v, 1, b, h, tile));
+    const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
+    const uint32_t slot = (uint32_t)min(tid, n_tok - 1);
+    mm = gload32(uniform_ptr(v.mm[1] + gi0), 4u * slot);
+    pos = gload32(uniform_ptr(v.perm[1] + gi0), slot & ~3u);
+    o.load(v, 1, gi0, slot, v.no2);
+    if (!H1) {
+      const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);
+    }
+  }
+  template <bool H1>
+  __device__ __forceinline__ void load_tail(const QaqView& v, int b, int h, int tile, const QaqCounts& cv, int wave, int nn, int g) {
+    c = cv;
+    const uint8_t* base = qaq_tile_codes(v, 1, b, h, tile);
+    if (H1) {
+      const gbytes_t ubase = uniform_ptr(base);
+      const uint32_t voff = (uint32_t)g * (4u * D) + (uint32_t)nn * (NCG * 4) + 4u * CGW * wave;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+        if (blk * 64 < c.n32()) gload_dwords<CGW>(ubase + voff + (uint32_t)blk * (16u * D), vw2[blk]);
+    }
+    const QaqVRegions rV = qaq_v_regions(c, D);
     const int nu1 = (c.n3 + 15) >> 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
@@ -478,12 +562,25 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
   const int no2 = v.no2;
   const v4i zero4 = {0, 0, 0, 0};
 
-  const float qv = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) : 0.0f;
+  // (no load of the prologue sits behind a branch: the compiler places its waits by counting the loads
+  // issued after the one it waits for, and where that number depends on a branch it waits for all of them
+  // -- here for the first tile's codes, before the barrier that everything else is behind)
+  const __half q_raw = a.q[(size_t)bq * D + min(tid, D - 1)];
   // class counts of all tiles of the chunk -> LDS (one 16-byte load per tile), so that the
   // tile loop needs no dependent global load to place its 1-bit regions
+  const int my_tile = tile_begin + min(tid, tile_end - tile_begin - 1);
+  const uint4 cnt_raw = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + my_tile) * 2) * 4);
+  const float vb_raw = v.vbound[qaq_bh(v, b, h) * v.NT + my_tile];
+  asm volatile("" ::: "memory");      // these first: what follows is the bulk, and loads come back in the order of issue
+  // the first tile: what its class counts are not needed for is requested at once
+  KeyRegs<D, NO2> kr;
+  ValRegs<D, NO2> vr;
+  kr.load_head(v, len, b, h, tile_begin, ktid);
+  vr.template load_head<H1>(v, len, b, h, tile_begin, tid, wave, nn, g);
+  const float qv = tid < D ? __half2float(q_raw) : 0.0f;
   if (tid < tile_end - tile_begin) {
-    *(uint4*)&S.cnt[tid][0] = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + tile_begin + tid) * 2) * 4);
-    S.vb[tid] = v.vbound[qaq_bh(v, b, h) * v.NT + tile_begin + tid];
+    *(uint4*)&S.cnt[tid][0] = cnt_raw;
+    S.vb[tid] = vb_raw;
   }
 
   // ---- query: fixed point, signed base-256 digits, one table per spreading format ------------
@@ -496,7 +593,7 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
   S.zrow[tid] = 0;
   for (int e = tid; e < D * 16; e += kThreads) (&S.xc[0][0])[e] = 0;
   lds_barrier();
-  // the first tile's codes and metadata are requested before the query digits are made
+  // the rest of the first tile is requested before the query digits are made
   auto counts_of = [&](int t, int side) {
     const uint2 c = *(const uint2*)&S.cnt[t - tile_begin][4 * side];
     const uint32_t lo = __builtin_amdgcn_readfirstlane(c.x), hi = __builtin_amdgcn_readfirstlane(c.y);
@@ -505,10 +602,8 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
     r.n1 = H1 ? min(len - t * QAQ_TT, QAQ_TT) - (r.n3 + r.n2 + r.n4 + r.n8) : 0;      // the 1-bit class is the rest of the tile
     return r;
   };
-  KeyRegs<D, NO2> kr;
-  ValRegs<D, NO2> vr;
-  kr.template load<H1>(v, len, b, h, tile_begin, counts_of(tile_begin, 0), ktid);
-  vr.template load<H1>(v, len, b, h, tile_begin, counts_of(tile_begin, 1), tid, wave, nn, g);
+  kr.template load_tail<H1>(v, b, h, tile_begin, counts_of(tile_begin, 0), ktid);
+  vr.template load_tail<H1>(v, b, h, tile_begin, counts_of(tile_begin, 1), wave, nn, g);
   const float qmax = KS == 1 ? S.red[0] : fmaxf(S.red[0], S.red[1]);
   const float sumq = KS == 1 ? S.red[4] : S.red[4] + S.red[5];
   int qexp = 0;

@@ -70,6 +70,77 @@ __device__ __forceinline__ void qaq_ring_store(const QaqView& v, size_t i, float
   else if (v.ring_half == 2) ((uint16_t*)v.ring)[i] = qaq_bf16_bits(s);
   else ((float*)v.ring)[i] = s;
 }
+// What the value rule is applied to (Section 4.2, the attention window): the largest score of position t
+// over this step's row -- the maximum over the G query heads of the KV head, rows row0 .. row0+G-1 of
+// `scores`, `stride` floats apart, GB of them loaded at a time, rounded to what the window stores;
+// returned in *s_row -- and the window's stored rows other than `skip`.  With GB = 0 there is no row of
+// this step (*s_row = 0).
+// All loads are issued before the first is used: a loop that folds each value in as it arrives pays one
+// memory round trip per row.  For that the loads carry no condition at all (a load under a branch is
+// waited for where the branch ends): the row count is a template argument, the row that is left out is
+// replaced by another one (read twice, folded once), a query head past the last one reads the last one
+// again, and every row of the ring is allocated for every position -- what a row does not cover is left
+// out of the maximum, not out of the loads.  ri = index of (sequence, KV head, t) inside a row.
+template <int W, typename RAW, int GB>
+__device__ __forceinline__ float qaq_predicted_w(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+                                                 const float* scores, size_t row0, int G, size_t stride, float* s_row) {
+  const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
+  const int other = skip == 0 ? (W > 1 ? 1 : 0) : 0;
+  RAW raw[W];
+#pragma unroll
+  for (int r = 0; r < W; ++r) raw[r] = ((const RAW*)v.ring)[(size_t)(r == skip ? other : r) * ring_row + ri];
+  float s = 0.0f;
+  if (GB > 0) {
+    float x[GB > 0 ? GB : 1];
+#pragma unroll
+    for (int j = 0; j < GB; ++j) x[j] = scores[(row0 + min(j, G - 1)) * stride + t];
+#pragma unroll
+    for (int j = 0; j < GB; ++j) s = fmaxf(s, x[j]);         // probabilities: >= 0
+    for (int g0 = GB; g0 < G; g0 += GB) {
+#pragma unroll
+      for (int j = 0; j < GB; ++j) x[j] = scores[(row0 + min(g0 + j, G - 1)) * stride + t];
+#pragma unroll
+      for (int j = 0; j < GB; ++j) s = fmaxf(s, x[j]);
+    }
+    s = v.ring_half == 1 ? __half2float(__float2half_rn(s)) : v.ring_half == 2 ? __uint_as_float((uint32_t)qaq_bf16_bits(s) << 16) : s;
+  }
+  *s_row = s;
+  float m = s;
+#pragma unroll
+  for (int r = 0; r < W; ++r) {
+    const float x = sizeof(RAW) == 4 ? __uint_as_float((uint32_t)raw[r])
+                  : v.ring_half == 1 ? __half2float(__ushort_as_half((unsigned short)raw[r])) : __uint_as_float((uint32_t)raw[r] << 16);
+    if (r != skip && t < qaq_seq_len(v, b, row_len[r])) m = fmaxf(m, x);
+  }
+  return m;
+}
+template <typename RAW, int GB>
+__device__ __forceinline__ float qaq_predicted_t(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+                                                 const float* scores, size_t row0, int G, size_t stride, float* s_row) {
+  switch (v.window) {
+    case 1: return qaq_predicted_w<1, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 2: return qaq_predicted_w<2, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 3: return qaq_predicted_w<3, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 4: return qaq_predicted_w<4, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 5: return qaq_predicted_w<5, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 6: return qaq_predicted_w<6, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 7: return qaq_predicted_w<7, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    default: return qaq_predicted_w<8, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+  }
+}
+template <bool SCORES>
+__device__ __forceinline__ float qaq_predicted(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+                                               const float* scores, size_t row0, int G, size_t stride, float* s_row) {
+  // query heads per batch of loads: none, one (no grouped-query attention), four
+  if (!SCORES)
+    return v.ring_half ? qaq_predicted_t<uint16_t, 0>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
+                       : qaq_predicted_t<uint32_t, 0>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+  if (G == 1)
+    return v.ring_half ? qaq_predicted_t<uint16_t, 1>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
+                       : qaq_predicted_t<uint32_t, 1>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+  return v.ring_half ? qaq_predicted_t<uint16_t, 4>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
+                     : qaq_predicted_t<uint32_t, 4>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+}
 __device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, int b, int h, int tile) {
   return v.codes[side] + ((qaq_bh(v, b, h) * v.NT + tile) * (size_t)v.cap[side]);
 }

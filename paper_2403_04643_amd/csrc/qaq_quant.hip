@@ -806,15 +806,10 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     const int t = t0 + tid;
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
-    float s = 0.0f;
-    if (a.mode == 2)
-      for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
-    s = qaq_ring_value(v, s);
-    pred = s;
-    for (int r = 0; r < v.window; ++r) {
-      if (r == ru.new_row) continue;
-      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
-    }
+    float s;
+    const size_t row0 = (size_t)b * v.Hq + h * ru.G;
+    pred = a.mode == 2 ? qaq_predicted<true>(v, ru.row_len, ru.new_row, b, t, ri, ru.scores, row0, ru.G, ru.score_stride, &s)
+                       : qaq_predicted<false>(v, ru.row_len, ru.new_row, b, t, ri, nullptr, 0, 0, 0, &s);
     if (a.mode == 2) qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
   }
   if (a.mode == 1) {
@@ -1400,9 +1395,9 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
 
   // ---- everything whose address is known up front ------------------------------------------------
   uint8_t* base = qaq_tile_codes(v, side, b, h, tile);
-  QaqCounts c_old;
-  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = c_old.n1 = 0;
-  if (n_before > 0) { c_old = qaq_load_counts(v, side, b, h, tile, n_before); c_old.n1 = 0; }
+  // (the stored class counts are asked for with the rest and decoded behind the barrier: made wavefront
+  // constants on the spot, they would be waited for before any other load is issued)
+  const uint2 counts_raw = *(const uint2*)(v.counts + (tile_id * 2 + side) * 4);
   const size_t gi0 = qaq_slot_index(v, b, h, tile, 0);
   // thread t is token t: the cached token in old slot t, or (t == n_before) the appended one
   uint32_t mm = 0, oi = 0, ov = 0;
@@ -1417,14 +1412,8 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     const int t = t0 + tid;
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
-    float s = 0.0f;
-    for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
-    s = qaq_ring_value(v, s);
-    float pred = s;
-    for (int r = 0; r < v.window; ++r) {
-      if (r == ru.new_row) continue;
-      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
-    }
+    float s;
+    const float pred = qaq_predicted<true>(v, ru.row_len, ru.new_row, b, t, ri, ru.scores, (size_t)b * v.Hq + h * ru.G, ru.G, ru.score_stride, &s);
     qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
     L.pred[tid] = pred;
   }
@@ -1477,6 +1466,13 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     }
   }
   __syncthreads();
+  QaqCounts c_old;
+  c_old.n3 = c_old.n2 = c_old.n4 = c_old.n8 = c_old.n1 = 0;
+  if (n_before > 0) {
+    const uint32_t c01 = (uint32_t)__builtin_amdgcn_readfirstlane((int)counts_raw.x), c23 = (uint32_t)__builtin_amdgcn_readfirstlane((int)counts_raw.y);
+    static_assert(QC3 == 0 && QC2 == 1 && QC4 == 2 && QC8 == 3, "order of the stored counts");
+    c_old.n3 = (int)(c01 & 0xffffu); c_old.n2 = (int)(c01 >> 16); c_old.n4 = (int)(c23 & 0xffffu); c_old.n8 = (int)(c23 >> 16);
+  }
   const bool is_new = has_new && tid == n_before;
   if (is_new) { mm = L.new_mm; oi = L.new_oi; ov = L.new_ov; pos = n_before; }
 
@@ -1827,16 +1823,9 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
     const size_t gi = qaq_slot_index(v, b, h, tile, tid);
     const uint32_t mk = v.mm[0][gi], mv = v.mm[1][gi];
     const int pk = v.perm[0][gi], pv = v.perm[1][gi];
-    float s = 0.0f;
-    if (a.scores) {
-      for (int g = 0; g < a.G; ++g) s = fmaxf(s, a.scores[((size_t)b * v.Hq + (h * a.G + g)) * a.len + t]);
-      s = qaq_ring_value(v, s);
-      pred = s;
-    }
-    for (int r = 0; r < v.window; ++r) {
-      if (a.scores && r == a.new_row) continue;
-      if (t < qaq_seq_len(v, b, a.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
-    }
+    float s;
+    pred = a.scores ? qaq_predicted<true>(v, a.row_len, a.new_row, b, t, ri, a.scores, (size_t)b * v.Hq + h * a.G, a.G, (size_t)a.len, &s)
+                    : qaq_predicted<false>(v, a.row_len, -1, b, t, ri, nullptr, 0, 0, 0, &s);
     if (a.scores) qaq_ring_store(v, (size_t)a.new_row * ring_row + ri, s);
     rk[pk] = h2f((uint16_t)(mk >> 16)) - h2f((uint16_t)(mk & 0xffffu));
     rv[pv] = h2f((uint16_t)(mv >> 16)) - h2f((uint16_t)(mv & 0xffffu));
