@@ -208,6 +208,7 @@ struct TileLds {
                                         // 16-byte reads of their copies start in different banks.
   float red[16];
   float part[D + 4];                    // fused form: this part's partial (output, then max, sum)
+  float newv[D];                        // fused form, first part: the new token's value row (fetched in the prologue)
 };
 
 // 64 key records through the matrix unit, one per lane.  Lane (n, g) of the wavefront
@@ -571,6 +572,12 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
   const int my_tile = tile_begin + min(tid, tile_end - tile_begin - 1);
   const uint4 cnt_raw = *(const uint4*)(v.counts + ((qaq_bh(v, b, h) * v.NT + my_tile) * 2) * 4);
   const float vb_raw = v.vbound[qaq_bh(v, b, h) * v.NT + my_tile];
+  // fused form: the new token's key and value rows are needed at the very end, by the first part; asked for
+  // there, each would be a memory round trip with nothing left to hide it behind
+  // (where they are not needed, the query row is read again instead: no load behind a branch)
+  const bool new_here = P && chunk == 0 && a.k_new;
+  const __half kn_raw = (new_here ? a.k_new + ((size_t)b * v.Hkv + h) * D : a.q + (size_t)bq * D)[min(tid, D - 1)];
+  const __half vn_raw = (new_here ? a.v_new + ((size_t)b * v.Hkv + h) * D : a.q + (size_t)bq * D)[min(tid, D - 1)];
   asm volatile("" ::: "memory");      // these first: what follows is the bulk, and loads come back in the order of issue
   // the first tile: what its class counts are not needed for is requested at once
   KeyRegs<D, NO2> kr;
@@ -578,6 +585,11 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
   kr.load_head(v, len, b, h, tile_begin, ktid);
   vr.template load_head<H1>(v, len, b, h, tile_begin, tid, wave, nn, g);
   const float qv = tid < D ? __half2float(q_raw) : 0.0f;
+  if (new_here) {
+    const float qk = wave_sum(tid < D ? __half2float(q_raw) * __half2float(kn_raw) : 0.0f);
+    if (lane == 0) S.red[12 + wave] = qk;
+    if (tid < D) S.newv[tid] = __half2float(vn_raw);
+  }
   if (tid < tile_end - tile_begin) {
     *(uint4*)&S.cnt[tid][0] = cnt_raw;
     S.vb[tid] = vb_raw;
@@ -971,11 +983,6 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
     if (lane == 0) { S.red[wave] = ls; S.red[4 + wave] = bs; }
     if (kwave < KS) S.xcorr[ktid] = c_run;
   }
-  if (P && chunk == 0 && a.k_new) {      // fused form: the logit of the unquantized new token, by the first part
-    float qk = tid < D ? __half2float(a.q[(size_t)bq * D + tid]) * __half2float(a.k_new[((size_t)b * v.Hkv + h) * D + tid]) : 0.0f;
-    qk = wave_sum(qk);
-    if (lane == 0) S.red[8 + wave] = qk;
-  }
   lds_barrier();
   const float lsum = (S.red[0] + S.red[1]) + (S.red[2] + S.red[3]);
   const float bias = (S.red[4] + S.red[5]) + (S.red[6] + S.red[7]);
@@ -991,7 +998,7 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
   lds_barrier();
   const TileLds<D>& S0 = S_all[0];
   float a_new = -INFINITY;
-  if (a.k_new) a_new = ((S0.red[8] + S0.red[9]) + (S0.red[10] + S0.red[11])) / sqrtf((float)D);
+  if (a.k_new) a_new = ((S0.red[12] + S0.red[13]) + (S0.red[14] + S0.red[15])) / sqrtf((float)D);   // the unquantized new token's logit
   float Mx = a_new;
 #pragma unroll
   for (int p = 0; p < (P ? P : 1); ++p) Mx = fmaxf(Mx, S_all[p].part[D]);
@@ -1006,7 +1013,7 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
     float x = 0.0f;
 #pragma unroll
     for (int p = 0; p < (P ? P : 1); ++p) x += fac[p] * S_all[p].part[tid];
-    if (a.k_new) x += e_new * __half2float(a.v_new[((size_t)b * v.Hkv + h) * D + tid]);
+    if (a.k_new) x += e_new * S0.newv[tid];
     if (a.out_is_fp32) ((float*)a.out)[(size_t)bq * D + tid] = x * inv;
     else ((__half*)a.out)[(size_t)bq * D + tid] = __float2half_rn(x * inv);
   }
