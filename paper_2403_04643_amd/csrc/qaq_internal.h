@@ -80,9 +80,19 @@ __device__ __forceinline__ void qaq_ring_store(const QaqView& v, size_t i, float
 // waited for where the branch ends): the row count is a template argument, the row that is left out is
 // replaced by another one (read twice, folded once), a query head past the last one reads the last one
 // again, and every row of the ring is allocated for every position -- what a row does not cover is left
-// out of the maximum, not out of the loads.  ri = index of (sequence, KV head, t) inside a row.
+// out of the maximum, not out of the loads.  ri = index of (sequence, KV head, t) inside a row; bit r of
+// `covered` says whether row r covers position t (qaq_rows_covering).
+// bit r: window row r holds a score of position t of sequence b (row_len: tokens each row covers, by the
+// longest sequence's count).  Constant indices only, so that the table stays where the kernel arguments are.
+__device__ __forceinline__ uint32_t qaq_rows_covering(const QaqView& v, const int (&row_len)[QAQ_MAX_WINDOW], int b, int t) {
+  uint32_t m = 0u;
+#pragma unroll
+  for (int r = 0; r < QAQ_MAX_WINDOW; ++r)
+    if (t < qaq_seq_len(v, b, row_len[r])) m |= 1u << r;
+  return m;
+}
 template <int W, typename RAW, int GB>
-__device__ __forceinline__ float qaq_predicted_w(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+__device__ __forceinline__ float qaq_predicted_w(const QaqView& v, uint32_t covered, int skip, size_t ri, int t,
                                                  const float* scores, size_t row0, int G, size_t stride, float* s_row) {
   const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
   const int other = skip == 0 ? (W > 1 ? 1 : 0) : 0;
@@ -110,36 +120,36 @@ __device__ __forceinline__ float qaq_predicted_w(const QaqView& v, const int* ro
   for (int r = 0; r < W; ++r) {
     const float x = sizeof(RAW) == 4 ? __uint_as_float((uint32_t)raw[r])
                   : v.ring_half == 1 ? __half2float(__ushort_as_half((unsigned short)raw[r])) : __uint_as_float((uint32_t)raw[r] << 16);
-    if (r != skip && t < qaq_seq_len(v, b, row_len[r])) m = fmaxf(m, x);
+    if (r != skip && ((covered >> r) & 1u)) m = fmaxf(m, x);
   }
   return m;
 }
 template <typename RAW, int GB>
-__device__ __forceinline__ float qaq_predicted_t(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+__device__ __forceinline__ float qaq_predicted_t(const QaqView& v, uint32_t covered, int skip, size_t ri, int t,
                                                  const float* scores, size_t row0, int G, size_t stride, float* s_row) {
   switch (v.window) {
-    case 1: return qaq_predicted_w<1, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 2: return qaq_predicted_w<2, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 3: return qaq_predicted_w<3, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 4: return qaq_predicted_w<4, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 5: return qaq_predicted_w<5, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 6: return qaq_predicted_w<6, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    case 7: return qaq_predicted_w<7, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-    default: return qaq_predicted_w<8, RAW, GB>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    case 1: return qaq_predicted_w<1, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 2: return qaq_predicted_w<2, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 3: return qaq_predicted_w<3, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 4: return qaq_predicted_w<4, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 5: return qaq_predicted_w<5, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 6: return qaq_predicted_w<6, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    case 7: return qaq_predicted_w<7, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+    default: return qaq_predicted_w<8, RAW, GB>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
   }
 }
 template <bool SCORES>
-__device__ __forceinline__ float qaq_predicted(const QaqView& v, const int* row_len, int skip, int b, int t, size_t ri,
+__device__ __forceinline__ float qaq_predicted(const QaqView& v, uint32_t covered, int skip, size_t ri, int t,
                                                const float* scores, size_t row0, int G, size_t stride, float* s_row) {
   // query heads per batch of loads: none, one (no grouped-query attention), four
   if (!SCORES)
-    return v.ring_half ? qaq_predicted_t<uint16_t, 0>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
-                       : qaq_predicted_t<uint32_t, 0>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    return v.ring_half ? qaq_predicted_t<uint16_t, 0>(v, covered, skip, ri, t, scores, row0, G, stride, s_row)
+                       : qaq_predicted_t<uint32_t, 0>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
   if (G == 1)
-    return v.ring_half ? qaq_predicted_t<uint16_t, 1>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
-                       : qaq_predicted_t<uint32_t, 1>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
-  return v.ring_half ? qaq_predicted_t<uint16_t, 4>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row)
-                     : qaq_predicted_t<uint32_t, 4>(v, row_len, skip, b, t, ri, scores, row0, G, stride, s_row);
+    return v.ring_half ? qaq_predicted_t<uint16_t, 1>(v, covered, skip, ri, t, scores, row0, G, stride, s_row)
+                       : qaq_predicted_t<uint32_t, 1>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
+  return v.ring_half ? qaq_predicted_t<uint16_t, 4>(v, covered, skip, ri, t, scores, row0, G, stride, s_row)
+                     : qaq_predicted_t<uint32_t, 4>(v, covered, skip, ri, t, scores, row0, G, stride, s_row);
 }
 __device__ __forceinline__ uint8_t* qaq_tile_codes(const QaqView& v, int side, int b, int h, int tile) {
   return v.codes[side] + ((qaq_bh(v, b, h) * v.NT + tile) * (size_t)v.cap[side]);

@@ -806,10 +806,16 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     const int t = t0 + tid;
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
-    float s;
-    const size_t row0 = (size_t)b * v.Hq + h * ru.G;
-    pred = a.mode == 2 ? qaq_predicted<true>(v, ru.row_len, ru.new_row, b, t, ri, ru.scores, row0, ru.G, ru.score_stride, &s)
-                       : qaq_predicted<false>(v, ru.row_len, ru.new_row, b, t, ri, nullptr, 0, 0, 0, &s);
+    // (row by row: this is the general kernel; the decode-step kernel asks for all rows at once)
+    float s = 0.0f;
+    if (a.mode == 2)
+      for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
+    s = qaq_ring_value(v, s);
+    pred = s;
+    for (int r = 0; r < v.window; ++r) {
+      if (r == ru.new_row) continue;
+      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
+    }
     if (a.mode == 2) qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
   }
   if (a.mode == 1) {
@@ -1413,7 +1419,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
     float s;
-    const float pred = qaq_predicted<true>(v, ru.row_len, ru.new_row, b, t, ri, ru.scores, (size_t)b * v.Hq + h * ru.G, ru.G, ru.score_stride, &s);
+    const float pred = qaq_predicted<true>(v, qaq_rows_covering(v, ru.row_len, b, t), ru.new_row, ri, t, ru.scores, (size_t)b * v.Hq + h * ru.G, ru.G, ru.score_stride, &s);
     qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
     L.pred[tid] = pred;
   }
@@ -1824,8 +1830,9 @@ __global__ __launch_bounds__(kThreads) void k_select(QaqSelectArgs a) {
     const uint32_t mk = v.mm[0][gi], mv = v.mm[1][gi];
     const int pk = v.perm[0][gi], pv = v.perm[1][gi];
     float s;
-    pred = a.scores ? qaq_predicted<true>(v, a.row_len, a.new_row, b, t, ri, a.scores, (size_t)b * v.Hq + h * a.G, a.G, (size_t)a.len, &s)
-                    : qaq_predicted<false>(v, a.row_len, -1, b, t, ri, nullptr, 0, 0, 0, &s);
+    const uint32_t covered = qaq_rows_covering(v, a.row_len, b, t);
+    pred = a.scores ? qaq_predicted<true>(v, covered, a.new_row, ri, t, a.scores, (size_t)b * v.Hq + h * a.G, a.G, (size_t)a.len, &s)
+                    : qaq_predicted<false>(v, covered, -1, ri, t, nullptr, 0, 0, 0, &s);
     if (a.scores) qaq_ring_store(v, (size_t)a.new_row * ring_row + ri, s);
     rk[pk] = h2f((uint16_t)(mk >> 16)) - h2f((uint16_t)(mk & 0xffffu));
     rv[pv] = h2f((uint16_t)(mv >> 16)) - h2f((uint16_t)(mv & 0xffffu));
