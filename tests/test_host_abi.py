@@ -105,3 +105,86 @@ def test_layout_is_a_bijection(side, D):
             # at most one partly filled group per region: keys 15 records of D/4 + D/8 + D/2 + D/8
             # bytes, values 15/16 of a 4D- and of two 2D-byte units and 7/8 of a 4D-byte half-unit
             assert pad <= 8 * (15 * D)
+
+
+# ---- code objects in the built library: the kernels on the decode path keep their working set in registers ----
+
+def _gfx950_code_objects(path):
+    """The gfx950 code objects inside the library's .hip_fatbin section (one offload bundle per source file;
+    bundle layout: magic, u64 entry count, then per entry u64 offset, u64 size, u64 triple length, triple)."""
+    import struct
+    import subprocess
+    import tempfile
+    objcopy = "/opt/rocm/llvm/bin/llvm-objcopy"
+    if not os.path.exists(objcopy):
+        pytest.skip("llvm-objcopy not found")
+    with tempfile.TemporaryDirectory() as d:
+        fat = os.path.join(d, "fat.bin")
+        subprocess.run([objcopy, f"--dump-section=.hip_fatbin={fat}", path, os.path.join(d, "unused")], check=True)
+        blob = open(fat, "rb").read()
+    magic = b"__CLANG_OFFLOAD_BUNDLE__"
+    out = []
+    at = blob.find(magic)
+    while at >= 0:
+        p = at + len(magic)
+        (n,) = struct.unpack_from("<Q", blob, p)
+        p += 8
+        for _ in range(n):
+            off, size, tl = struct.unpack_from("<QQQ", blob, p)
+            triple = blob[p + 24:p + 24 + tl].decode()
+            p += 24 + tl
+            if "gfx950" in triple:
+                out.append(blob[at + off:at + off + size])
+        at = blob.find(magic, at + len(magic))
+    return out
+
+
+def _kernel_metadata(code_object):
+    """name -> metadata map of every kernel of one code object (the msgpack document of the NT_AMDGPU_METADATA note)."""
+    import struct
+    import msgpack
+    e = code_object
+    assert e[:4] == b"\x7fELF" and e[4] == 2
+    shoff, = struct.unpack_from("<Q", e, 0x28)
+    shentsize, shnum = struct.unpack_from("<HH", e, 0x3A)
+    kernels = {}
+    for i in range(shnum):
+        sh = shoff + i * shentsize
+        sh_type, = struct.unpack_from("<I", e, sh + 4)
+        off, size = struct.unpack_from("<QQ", e, sh + 0x18)
+        if sh_type != 7:       # SHT_NOTE
+            continue
+        p = off
+        while p + 12 <= off + size:
+            namesz, descsz, ntype = struct.unpack_from("<III", e, p)
+            name = e[p + 12:p + 12 + namesz]
+            desc_at = p + 12 + ((namesz + 3) & ~3)
+            if name.rstrip(b"\0") == b"AMDGPU" and ntype == 32:
+                doc = msgpack.unpackb(e[desc_at:desc_at + descsz], raw=False, strict_map_key=False)
+                for k in doc.get("amdhsa.kernels", []):
+                    kernels[k[".name"]] = k
+            p = desc_at + ((descsz + 3) & ~3)
+    return kernels
+
+
+def test_decode_path_kernels_do_not_spill():
+    """A change elsewhere in a source file can push a kernel over its register budget or make the compiler call
+    its helpers out of line; both show as private (scratch) memory in the kernel's metadata long before a test of
+    the results notices anything.  The kernels of a decode step and of the bulk quantization at the benchmark's
+    shape (head_dim 128, one outlier per end, no 1-bit width) are held to none."""
+    if not os.path.exists(qaq.LIB_PATH):
+        pytest.skip("library not built")
+    kernels = {}
+    for co in _gfx950_code_objects(qaq.LIB_PATH):
+        kernels.update(_kernel_metadata(co))
+    assert kernels, "no gfx950 code object found in the library"
+    held = {"k_attn_tileILi128ELi2ELi4ELb0": 128, "k_attn_tileILi128ELi2ELi0ELb0": 128, "k_updateILi128": 64,
+            "k_selectE": 128, "k_buildILi128ELb1ELb0": 128, "k_attn_combineILi128": 128}
+    seen = set()
+    for name, k in kernels.items():
+        for key, max_vgpr in held.items():
+            if key in name:
+                seen.add(key)
+                assert k[".private_segment_fixed_size"] == 0, (name, k[".private_segment_fixed_size"])
+                assert k[".vgpr_count"] <= max_vgpr, (name, k[".vgpr_count"])
+    assert seen == set(held), set(held) - seen
