@@ -341,12 +341,16 @@ struct KeyRegs {
     const QaqKRegions rK = qaq_k_regions(c, D);
     const int n32 = c.n32();
     const bool is3 = tid < c.n3, is23 = tid < n32, is4 = !is23 && tid < n32 + c.n4;
-    const uint32_t rec4 = rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
-    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : is4 ? rec4 : 0u;
-    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    const bool is8 = !is23 && !is4 && tid < n_tok - c.n1;
+    // a 4-bit record, or the first half of an 8-bit one (the other half is fetched where it is used)
+    const uint32_t rec4 = is8 ? rK.r8 + (uint32_t)(tid - n32 - c.n4) * (uint32_t)KRec<D, 8>::REC
+                              : rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
+    const bool wide = is4 || is8;
+    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : wide ? rec4 : 0u;
+    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : wide ? rec4 + 4u * HALF : 0u;
     if (H1 && c.n1 > 0 && tid >= c.first1())          // a 1-bit token's record (lanes past the tile's tokens: the last one)
       off_b0 = rK.r1b + (uint32_t)min(tid - c.first1(), c.n1 - 1) * (uint32_t)KRec<D, 1>::REC;
-    const uint32_t off_b1 = is4 ? rec4 + 4u * HALF + 2u * HALF : 0u;
+    const uint32_t off_b1 = wide ? rec4 + 4u * HALF + 2u * HALF : 0u;
     const gbytes_t ubase = uniform_ptr(base);
     gload_dwords<HALF>(ubase + off_a, ka);
     uint32_t b0[HALF / 2], b1[HALF / 2];
@@ -380,14 +384,18 @@ struct KeyRegs {
     const QaqKRegions rK = qaq_k_regions(c, D);
     const int n32 = c.n32();
     const bool is3 = tid < c.n3, is23 = tid < n32, is4 = !is23 && tid < n32 + c.n4;
-    const uint32_t rec4 = rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
-    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : is4 ? rec4 : 0u;
-    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : is4 ? rec4 + 4u * HALF : 0u;
+    const bool is8 = !is23 && !is4 && tid < n_tok - c.n1;
+    // a 4-bit record, or the first half of an 8-bit one (the other half is fetched where it is used)
+    const uint32_t rec4 = is8 ? rK.r8 + (uint32_t)(tid - n32 - c.n4) * (uint32_t)KRec<D, 8>::REC
+                              : rK.r4 + (uint32_t)(tid - n32) * (uint32_t)KRec<D, 4>::REC;
+    const bool wide = is4 || is8;
+    const uint32_t off_a = is23 ? (uint32_t)tid * (uint32_t)KRec<D, 2>::REC : wide ? rec4 : 0u;
+    uint32_t off_b0 = is3 ? rK.r1 + (uint32_t)tid * (uint32_t)KRec<D, 1>::REC : wide ? rec4 + 4u * HALF : 0u;
     if (H1 && c.n1 > 0 && tid >= c.first1())
       off_b0 = rK.r1b + (uint32_t)min(tid - c.first1(), c.n1 - 1) * (uint32_t)KRec<D, 1>::REC;
-    const uint32_t off_b1 = is4 ? rec4 + 4u * HALF + 2u * HALF : 0u;
+    const uint32_t off_b1 = wide ? rec4 + 4u * HALF + 2u * HALF : 0u;
     const gbytes_t ubase = uniform_ptr(qaq_tile_codes(v, 0, b, h, tile));
-    if (c.n4 > 0) {            // (into other registers first: a load into registers that an earlier load is still on its way to is held back until that one has arrived)
+    if (c.n4 + c.n8 > 0) {     // (into other registers first: a load into registers that an earlier load is still on its way to is held back until that one has arrived)
       uint32_t t[HALF];
       gload_dwords<HALF>(ubase + off_a, t);
 #pragma unroll
@@ -746,16 +754,32 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
         for (int d = lane; d < D; d += 64) sq += (int)S.ql[2][0][d] + 256 * (int)S.ql[2][1][d] + 65536 * (int)S.ql[2][2][d];
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) sq += __shfl_xor(sq, o);
-        // the record in pieces of two slices (eight registers at a time: the whole record in
-        // registers would make every tile of every call pay for this path with spills)
+        // The first half of a lane's record came with the tile (where a narrower token has its code
+        // words); the second half is fetched here in pieces of two slices, the first piece before the
+        // arithmetic on the first half, the next into registers that arithmetic has freed: the whole
+        // record in registers would make every tile of every call pay for this path with spills.
+        // (Lanes of other classes feed what they hold; their results are not used.)
         const uint32_t rec = rK.r8 + (uint32_t)min(max(ktid - first8K, 0), cK.n8 - 1) * (uint32_t)D;
         v4i cc = zero4;
-#pragma unroll 1
-        for (int q2 = 0; q2 < D / 32; ++q2) {
-          uint32_t w[8];
-          gload_dwords<8>(baseK + (rec + 32u * (uint32_t)q2), w);
-          cc = mma(*(const v4i*)(abase2 + 32 * q2), spread<8>(&w[0], 0), cc);
-          cc = mma(*(const v4i*)(abase2 + 32 * q2 + 16), spread<8>(&w[4], 0), cc);
+        uint32_t w[8];
+        gload_dwords<8>(baseK + (rec + (uint32_t)(D / 2)), w);
+        if constexpr (D == 128) {
+          cc = mma(*(const v4i*)(abase2), spread<8>(&kr.ka[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 16), spread<8>(&kr.ka[4], 0), cc);
+          asm volatile("" ::: "memory");      // (not earlier: four pieces in flight at once do not fit the registers)
+          gload_dwords<8>(baseK + (rec + 96u), kr.ka);
+          cc = mma(*(const v4i*)(abase2 + 32), spread<8>(&kr.kb[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 48), spread<8>(&kr.kb[4], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 64), spread<8>(&w[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 80), spread<8>(&w[4], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 96), spread<8>(&kr.ka[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 112), spread<8>(&kr.ka[4], 0), cc);
+        } else {
+          static_assert(D == 64, "head_dim");
+          cc = mma(*(const v4i*)(abase2), spread<8>(&kr.ka[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 16), spread<8>(&kr.kb[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 32), spread<8>(&w[0], 0), cc);
+          cc = mma(*(const v4i*)(abase2 + 48), spread<8>(&w[4], 0), cc);
         }
         if (ktid >= first8K) dotq = ((((float)cc[2] * 65536.0f + (float)cc[1] * 256.0f) + (float)cc[0]) + 128.0f * (float)sq) * qscale;
       }
@@ -930,27 +954,35 @@ __global__ __launch_bounds__((PP == 5 ? 4 : PP ? PP : 1) * kThreads, 4) void k_a
       constexpr int TPW = 64 / LPT8;       // tokens per pass
       float a8[4] = {0.f, 0.f, 0.f, 0.f};
       const int sub = lane / LPT8, ch4 = lane % LPT8;
-      if (sub < cV.n8) {                  // a tile of a cache the rules shaped rarely has more than these rows
-        const float w8 = S.w8[sub];
-        const uint32_t dw = gload32(baseV, rV.r8 + (uint32_t)sub * D + (D / 4) * wave + 4 * ch4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw >> (8 * j)) & 255u);
-      }
-      // the others: four rows requested at a time (a row past the end repeats the last one and gets weight 0)
+      // rows sub, sub + TPW, ...: the first one and a batch of four are requested at once, and every further
+      // batch while the one before it is summed (a row past the end repeats the last one and gets weight 0);
+      // a tile of a cache the rules shaped rarely has more rows than the first covers
       constexpr int UB = 4;
+      const uint32_t lane8 = (D / 4) * wave + 4 * ch4;
+      auto row8 = [&](int i8) { return gload32(baseV, rV.r8 + (uint32_t)min(i8, cV.n8 - 1) * D + lane8); };
+      const uint32_t dw0 = row8(sub);
+      uint32_t cur[UB];
+#pragma unroll
+      for (int u = 0; u < UB; ++u) cur[u] = row8(sub + (1 + u) * TPW);
+      {
+        const float w8 = sub < cV.n8 ? S.w8[sub] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw0 >> (8 * j)) & 255u);
+      }
 #pragma unroll 1
       for (int i0 = sub + TPW; i0 < cV.n8; i0 += UB * TPW) {
-        uint32_t dw[UB];
+        uint32_t nxt[UB];
 #pragma unroll
-        for (int u = 0; u < UB; ++u)
-          dw[u] = gload32(baseV, rV.r8 + (uint32_t)min(i0 + u * TPW, cV.n8 - 1) * D + (D / 4) * wave + 4 * ch4);
+        for (int u = 0; u < UB; ++u) nxt[u] = row8(i0 + (UB + u) * TPW);
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
           const int i8 = i0 + u * TPW;
           const float w8 = i8 < cV.n8 ? S.w8[min(i8, QAQ_TT - 1)] : 0.0f;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((dw[u] >> (8 * j)) & 255u);
+          for (int j = 0; j < 4; ++j) a8[j] += w8 * (float)((cur[u] >> (8 * j)) & 255u);
         }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) cur[u] = nxt[u];
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
