@@ -166,6 +166,47 @@ __device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side,
   return c;
 }
 
+#if defined(__HIPCC__)
+// ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----
+// One instruction per step: the DPP form of the arithmetic instruction itself (the compiler
+// would emit a move with the lane pattern, a NaN-quieting max of each input and the max).
+// A VGPR written by a vector instruction needs two wait states before a DPP read.
+#define QAQ_DPP_STEP(op, pat) "s_nop 1\n\t" op " %0, %0, %0 " pat "\n\t"
+__device__ __forceinline__ float wave_max(float x) {
+  asm volatile(QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_bcast:15 row_mask:0xa bank_mask:0xf")      // into rows 1 and 3
+               QAQ_DPP_STEP("v_max_f32_dpp", "row_bcast:31 row_mask:0xc bank_mask:0xf")      // into rows 2 and 3
+               "s_nop 1"
+               : "+v"(x));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  asm volatile(QAQ_DPP_STEP("v_add_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_bcast:15 row_mask:0xa bank_mask:0xf")
+               QAQ_DPP_STEP("v_add_f32_dpp", "row_bcast:31 row_mask:0xc bank_mask:0xf")
+               "s_nop 1"
+               : "+v"(x));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+__device__ __forceinline__ float wave_min(float x) {
+  asm volatile(QAQ_DPP_STEP("v_min_f32_dpp", "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_min_f32_dpp", "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_min_f32_dpp", "row_half_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_min_f32_dpp", "row_mirror row_mask:0xf bank_mask:0xf")
+               QAQ_DPP_STEP("v_min_f32_dpp", "row_bcast:15 row_mask:0xa bank_mask:0xf")      // into rows 1 and 3
+               QAQ_DPP_STEP("v_min_f32_dpp", "row_bcast:31 row_mask:0xc bank_mask:0xf")      // into rows 2 and 3
+               "s_nop 1"
+               : "+v"(x));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+#endif
+
 // What the width rules need (Section 4.1 written as comparisons, Section 4.2 window).
 struct QaqRuleArgs {
   int G;                   // query heads per KV head

@@ -1530,8 +1530,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
         bnd = fmaxf(bnd, fmaxf(fabsf(o - mxf), fabsf(o - mnf)) + range);
       }
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) bnd = fmaxf(bnd, __shfl_xor(bnd, o));
+    bnd = wave_max(bnd);
     if (lane == 0) L.wave_bound[wave] = bnd;
   } else {
     float lo = 0.0f, hi = INFINITY;
@@ -1542,8 +1541,7 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
       if (nb < ru.bit_set[ru.nbits - 1]) lo = ldexpf(range, -nb);
       if (narrower > 0) hi = ldexpf(range, -narrower);
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) { lo = fmaxf(lo, __shfl_xor(lo, o)); hi = fminf(hi, __shfl_xor(hi, o)); }
+    lo = wave_max(lo); hi = wave_min(hi);
     if (lane == 0) { L.wave_bound[wave] = lo; L.wave_bound2[wave] = hi; }
   }
   __syncthreads();
