@@ -1292,6 +1292,7 @@ struct UpdLds {
   int wave_cnt[4][4], wave_need[4][4], wave_free[4][4];
   int wave_moved[4];
   int wave_wide[4];                        // widenings asked for, per wavefront
+  int wave_any[4];                         // a token of the wavefront changes width or arrives
   float wave_bound[4], wave_bound2[4];
   uint32_t new_mm, new_oi, new_ov;         // the appended token: min | max, outlier channels, outlier values
   uint32_t newrow[D / 4];                  // ... its codes at the widest width, byte d = channel d
@@ -1506,7 +1507,12 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   }
   const bool served = a.orig[side] != nullptr;
   note_widenings(L.wave_wide, wider);
-  if (!__syncthreads_or(changed ? 1 : 0)) {          // nothing moves and nothing is appended
+  // (one ballot per wavefront, one barrier, four flags: the library's workgroup OR is a reduction
+  // across lanes and three barriers)
+  const unsigned long long bal_changed = __ballot(changed);
+  if (lane == 0) L.wave_any[wave] = bal_changed != 0ull ? 1 : 0;
+  __syncthreads();
+  if (!(L.wave_any[0] | L.wave_any[1] | L.wave_any[2] | L.wave_any[3])) {          // nothing moves and nothing is appended
     if (tid == 0) add_widenings(v, tile_id * 2 + side, L.wave_wide, served);
     return;
   }
