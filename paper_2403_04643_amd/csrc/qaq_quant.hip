@@ -1507,17 +1507,8 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
   }
   const bool served = a.orig[side] != nullptr;
   note_widenings(L.wave_wide, wider);
-  // (one ballot per wavefront, one barrier, four flags: the library's workgroup OR is a reduction
-  // across lanes and three barriers)
-  const unsigned long long bal_changed = __ballot(changed);
-  if (lane == 0) L.wave_any[wave] = bal_changed != 0ull ? 1 : 0;
-  __syncthreads();
-  if (!(L.wave_any[0] | L.wave_any[1] | L.wave_any[2] | L.wave_any[3])) {          // nothing moves and nothing is appended
-    if (tid == 0) add_widenings(v, tile_id * 2 + side, L.wave_wide, served);
-    return;
-  }
-
-  // ---- new class counts; what the attention kernel and the next step's skip test need of the tile ------
+  // ---- new class counts; what the attention kernel and the next step's skip test need of the tile
+  // (ahead of the test whether the tile side has work at all, so that one barrier serves both) ------------
   const int cls = tid < n_after ? qaq_class_of_bits(nb) : -1;
   const int ocls = (tid < n_before) ? qaq_class_of_bits(ob) : -1;
 #pragma unroll
@@ -1550,7 +1541,16 @@ __global__ __launch_bounds__(kThreads, 8) void k_update(QaqBuildArgs a) {
     lo = wave_max(lo); hi = wave_min(hi);
     if (lane == 0) { L.wave_bound[wave] = lo; L.wave_bound2[wave] = hi; }
   }
+  // (one ballot per wavefront, one barrier, four flags: the library's workgroup OR is a reduction
+  // across lanes and three barriers)
+  const unsigned long long bal_changed = __ballot(changed);
+  if (lane == 0) L.wave_any[wave] = bal_changed != 0ull ? 1 : 0;
   __syncthreads();
+  if (!(L.wave_any[0] | L.wave_any[1] | L.wave_any[2] | L.wave_any[3])) {          // nothing moves and nothing is appended
+    if (tid == 0) add_widenings(v, tile_id * 2 + side, L.wave_wide, served);
+    return;
+  }
+
   QaqCounts cn;
   cn.n3 = L.wave_cnt[QC3][0] + L.wave_cnt[QC3][1] + L.wave_cnt[QC3][2] + L.wave_cnt[QC3][3];
   cn.n2 = L.wave_cnt[QC2][0] + L.wave_cnt[QC2][1] + L.wave_cnt[QC2][2] + L.wave_cnt[QC2][3];
