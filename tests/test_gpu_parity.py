@@ -429,6 +429,43 @@ def test_decode_update_in_one_call():
     assert gc.stats().refused_upgrades == gc3.stats().refused_upgrades == oc.refused
 
 
+@pytest.mark.parametrize("window,store,G", [(1, None, 1), (2, None, 2), (4, "window_fp16", 1), (6, None, 1),
+                                            (7, "window_bf16", 2), (8, None, 8)])
+def test_decode_steps_with_every_window_length(window, store, G):
+    """The window's rows are read by code that is specialised on their number (1 to 8), on how they are
+    stored and on whether one or several query heads share a KV head: more decode steps than the window
+    has rows, alternating the fused call and the separate calls, widths and cache bit-exact."""
+    sh = W.shape(3, batch=2, n_q_heads=2 * G, n_kv_heads=2, context=300)
+    steps = window + 3
+    _log(f"window lengths: window={window} store={store} G={G} shape={sh}")
+    K, V = W.make_kv(3, sh)
+    qn = O.query_norm_statistic(W.make_queries(3, sh, n=64, seed_offset=9), sh.head_dim)
+    kw = dict(max_tokens=sh.context + steps, window=window, sigma_s_max=4e-4, sigma_x_max=6e-3)
+    if store:
+        kw[store] = True
+    oc, gc = make_pair(sh, qn, **kw)
+    oc.append(K, V); gc.quantize_append(dev(K), dev(V))
+    Korig, Vorig = K.copy(), V.copy()
+    qs = W.make_queries(3, sh, n=steps)
+    for s in range(steps):
+        kn, vn = W.make_new_token(3, sh, step=s)
+        _, S = gc.decode_attention(dev(qs[s]), dev(kn), dev(vn), want_scores=True)
+        Korig = np.concatenate([Korig, kn[:, :, None]], 2); Vorig = np.concatenate([Vorig, vn[:, :, None]], 2)
+        oc.append(kn[:, :, None], vn[:, :, None])
+        oc.observe(S.cpu().numpy())
+        bk_o, bv_o = oc.select_bits()
+        oc.requantize(bk_o, bv_o, Korig, Vorig)
+        if s % 2 == 0:
+            bk_g, bv_g = gc.decode_update(S, dev(kn), dev(vn), dev(Korig), dev(Vorig), want_bits=True)
+        else:
+            gc.quantize_append(dev(kn[:, :, None]), dev(vn[:, :, None]))
+            bk_g, bv_g = gc.select_bits(S)
+            gc.requantize(bk_g, bv_g, dev(Korig), dev(Vorig))
+        np.testing.assert_array_equal(bk_g.cpu().numpy(), bk_o, err_msg=f"key widths, step {s}")
+        np.testing.assert_array_equal(bv_g.cpu().numpy(), bv_o, err_msg=f"value widths, step {s}")
+    compare_canonical(oc, gc, f"window {window}")
+
+
 def test_decode_update_skips_unchanged_key_tiles():
     """qaq_decode_update without the width outputs leaves key-side tiles alone when the
     threshold of this step lies inside the interval the tile recorded when it was built.
