@@ -203,6 +203,10 @@ def oc_bits(oc, side):
     (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=256), (0.0, 1.0, 0.0, 0.0)),
     (2, dict(batch=1, n_q_heads=2, n_kv_heads=2, context=40), (0.0, 0.0, 1.0, 0.0)),
     (5, dict(batch=2, n_q_heads=16, n_kv_heads=2, context=333), (0.4, 0.3, 0.2, 0.1)),
+    # mostly 8-bit: records split between what comes with the tile and what is fetched in the key phase,
+    # class borders inside a wavefront's quarter, both head dimensions
+    (1, dict(context=600), (0.1, 0.1, 0.2, 0.6)),
+    (2, dict(batch=1, n_q_heads=4, n_kv_heads=4, context=700), (0.15, 0.05, 0.2, 0.6)),
 ])
 def test_decode_attention_matches_oracle(cfgno, shape_kw, p_bits):
     sh = W.shape(cfgno, **shape_kw)
