@@ -166,6 +166,29 @@ __device__ __forceinline__ QaqCounts qaq_load_counts(const QaqView& v, int side,
   return c;
 }
 
+// The window's part of qaq_predicted in a compact form for the general build kernel (no variants by
+// row count: always QAQ_MAX_WINDOW loads, a row that does not count replaced by one that does or by row 0):
+// the largest stored score of position t over the rows in `covered` other than `skip`, at least `start`.
+__device__ __forceinline__ float qaq_window_max_compact(const QaqView& v, uint32_t covered, int skip, size_t ri, float start) {
+  const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
+  uint32_t raw[QAQ_MAX_WINDOW];
+  if (v.ring_half) {
+#pragma unroll
+    for (int r = 0; r < QAQ_MAX_WINDOW; ++r) raw[r] = ((const uint16_t*)v.ring)[(size_t)(r < v.window && r != skip ? r : 0) * ring_row + ri];
+  } else {
+#pragma unroll
+    for (int r = 0; r < QAQ_MAX_WINDOW; ++r) raw[r] = ((const uint32_t*)v.ring)[(size_t)(r < v.window && r != skip ? r : 0) * ring_row + ri];
+  }
+  float m = start;
+#pragma unroll
+  for (int r = 0; r < QAQ_MAX_WINDOW; ++r) {
+    const float x = v.ring_half == 1 ? __half2float(__ushort_as_half((unsigned short)raw[r]))
+                  : v.ring_half == 2 ? __uint_as_float(raw[r] << 16) : __uint_as_float(raw[r]);
+    if (r < v.window && r != skip && ((covered >> r) & 1u)) m = fmaxf(m, x);
+  }
+  return m;
+}
+
 #if defined(__HIPCC__)
 // ---- wavefront reductions on the data-parallel-primitive path (no LDS round trips) -----
 // One instruction per step: the DPP form of the arithmetic instruction itself (the compiler

@@ -806,16 +806,13 @@ __device__ __forceinline__ void build_tile(const QaqBuildArgs& a, const int bh, 
     const int t = t0 + tid;
     const size_t ring_row = (size_t)v.B * v.Hkv * v.Tmax;
     const size_t ri = qaq_bh(v, b, h) * v.Tmax + t;
-    // (row by row: this is the general kernel; the decode-step kernel asks for all rows at once)
+    // (the scores row by row, the window's rows at once, in the compact form: the decode-step kernel's
+    // form with its variants by row count makes this kernel call its helpers out of line)
     float s = 0.0f;
     if (a.mode == 2)
       for (int g = 0; g < ru.G; ++g) s = fmaxf(s, ru.scores[((size_t)b * v.Hq + (h * ru.G + g)) * ru.score_stride + t]);
     s = qaq_ring_value(v, s);
-    pred = s;
-    for (int r = 0; r < v.window; ++r) {
-      if (r == ru.new_row) continue;
-      if (t < qaq_seq_len(v, b, ru.row_len[r])) pred = fmaxf(pred, qaq_ring_load(v, (size_t)r * ring_row + ri));
-    }
+    pred = qaq_window_max_compact(v, qaq_rows_covering(v, ru.row_len, b, t), ru.new_row, ri, s);
     if (a.mode == 2) qaq_ring_store(v, (size_t)ru.new_row * ring_row + ri, s);
   }
   if (a.mode == 1) {
